@@ -1,0 +1,708 @@
+// C ABI of libdqn (see include/dqn.h): host-side bookkeeping, workspace layout
+// and the launch schedule of the training step.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/dqn.h"
+#include "gemm_fp32.h"
+#include "kernels_misc.h"
+#include "net.h"
+
+namespace {
+
+thread_local std::string g_err;  // errors without a context
+
+constexpr int MAX_WSPLIT = 64;   // most reduction splits of a conv weight gradient
+
+struct Workspace {
+    // minibatch staging (replay mode)
+    uint8_t *stack5;
+    int32_t *b_idx, *b_a;
+    float *b_w, *b_r, *td_abs, *loss_j, *loss_slot;
+    uint8_t *b_done;
+    // activations, channel-last, rows = samples of all passes
+    float *act1, *act2, *act3, *f1part, *h_s;
+    // backward
+    float *dA, *dh, *d3, *d2, *d1;
+    // gradient partial sums per layer, [split][W..., b...]
+    float *gp1, *gp2, *gp3, *gp4, *gp5;
+    size_t total;
+};
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int fc1_splits(long M) { return M <= 192 ? 14 : M <= 512 ? 7 : M <= 1536 ? 2 : 1; }
+
+Workspace carve(const dqn_config &c, uint8_t *base)
+{
+    Workspace w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        uint8_t *p = base ? base + off : nullptr;
+        off += align_up(bytes, 256);
+        return p;
+    };
+    const size_t MB = (size_t)c.max_batch;
+    const size_t rows = std::max<size_t>(3 * MB, (size_t)c.max_act_batch);
+    const size_t R = (size_t)c.num_actions + (c.dueling ? 1 : 0);
+    w.stack5 = take(MB * 5 * net::FRAME);
+    w.b_idx = (int32_t *)take(MB * 4);
+    w.b_a = (int32_t *)take(MB * 4);
+    w.b_w = (float *)take(MB * 4);
+    w.b_r = (float *)take(MB * 4);
+    w.td_abs = (float *)take(MB * 4);
+    w.loss_j = (float *)take(MB * 4);
+    w.loss_slot = (float *)take(256);
+    w.b_done = take(MB);
+    w.act1 = (float *)take(rows * net::A1 * 4);
+    w.act2 = (float *)take(rows * net::A2 * 4);
+    w.act3 = (float *)take(rows * net::A3 * 4);
+    size_t f1rows = std::max({std::min<size_t>(rows, 192) * 14, std::min<size_t>(rows, 512) * 7,
+                              std::min<size_t>(rows, 1536) * 2, rows});
+    w.f1part = (float *)take(f1rows * net::HID * 4);
+    w.h_s = (float *)take(MB * net::HID * 4);
+    w.dA = (float *)take(MB * R * 4);
+    w.dh = (float *)take(MB * net::HID * 4);
+    w.d3 = (float *)take(MB * net::A3 * 4);
+    w.d2 = (float *)take(MB * net::A2 * 4);
+    w.d1 = (float *)take(MB * net::A1 * 4);
+    w.gp1 = (float *)take((size_t)MAX_WSPLIT * net::L1N * 4);
+    w.gp2 = (float *)take((size_t)MAX_WSPLIT * net::L2N * 4);
+    w.gp3 = (float *)take((size_t)MAX_WSPLIT * net::L3N * 4);
+    w.gp4 = (float *)take((size_t)net::L4N * 4);
+    w.gp5 = (float *)take((size_t)net::head_count(c.num_actions, c.dueling) * 4);
+    w.total = off;
+    return w;
+}
+
+struct ProfRec {
+    const char *name;
+    hipEvent_t e0, e1;
+};
+
+}  // namespace
+
+struct dqn_ctx {
+    dqn_config cfg;
+    dqn_buffers buf;
+    dqn_sizes sz;
+    Workspace ws;
+    int64_t n;       // parameters per network
+    int R;           // head rows
+    long L;          // tree leaves (power of two)
+    int levels;      // log2(L)
+    long stored;     // transitions with a priority
+    float *theta, *theta_t, *rms_v, *rms_m, *grads;
+    int32_t *meta_a;
+    float *meta_r;
+    uint8_t *meta_done;
+    float *tree;
+    bool prof = false;
+    std::vector<ProfRec> recs;
+    std::string err;
+};
+
+namespace {
+
+int32_t fail(dqn_ctx *c, int32_t code, const std::string &msg)
+{
+    if (c) c->err = msg;
+    else g_err = msg;
+    return code;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+const char *check_config(const dqn_config &c)
+{
+    if (c.num_actions < 1 || c.num_actions > 64) return "num_actions must be in 1..64";
+    if (c.dueling < 0 || c.dueling > 1 || c.double_q < 0 || c.double_q > 1) return "dueling/double_q must be 0 or 1";
+    if (c.precision < 0 || c.precision > 1) return "precision must be 0 (fp32) or 1 (bf16)";
+    if (c.loss_kind < 0 || c.loss_kind > 1) return "loss_kind must be 0 or 1";
+    if (!(c.huber_delta > 0.f)) return "huber_delta must be > 0";
+    if (!(c.gamma >= 0.f && c.gamma <= 1.f)) return "gamma must be in [0,1]";
+    if (!(c.lr >= 0.f) || !(c.rms_decay >= 0.f && c.rms_decay < 1.f) || !(c.rms_eps > 0.f))
+        return "lr >= 0, 0 <= rms_decay < 1, rms_eps > 0 required";
+    if (c.rms_centered < 0 || c.rms_centered > 1) return "rms_centered must be 0 or 1";
+    if (c.max_batch < 1 || c.max_batch > 1024) return "max_batch must be in 1..1024";
+    if (c.max_act_batch < 1 || c.max_act_batch > 8192) return "max_act_batch must be in 1..8192";
+    if (c.per_stratified < 0 || c.per_stratified > 1) return "per_stratified must be 0 or 1";
+    if (c.replay_capacity < 0 || c.replay_capacity > (1ll << 30)) return "replay_capacity out of range";
+    if (c.replay_capacity > 0 && c.replay_capacity < 5) return "replay_capacity must be 0 or >= 5";
+    if (c.replay_capacity > 0 && (!(c.per_alpha >= 0.f) || !(c.per_eps > 0.f))) return "per_alpha >= 0 and per_eps > 0 required";
+    return nullptr;
+}
+
+long tree_leaves(int64_t cap)
+{
+    long L = 1;
+    while (L < cap) L <<= 1;
+    return L;
+}
+
+template <class F>
+void launch(dqn_ctx *c, const char *name, hipStream_t st, F &&f)
+{
+    if (c->prof) {
+        ProfRec r{name, nullptr, nullptr};
+        if (hipEventCreate(&r.e0) == hipSuccess && hipEventCreate(&r.e1) == hipSuccess) {
+            (void)hipEventRecord(r.e0, st);
+            f();
+            (void)hipEventRecord(r.e1, st);
+            c->recs.push_back(r);
+            return;
+        }
+    }
+    f();
+}
+
+int32_t hip_status(dqn_ctx *c, const char *where)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, DQN_ERR_HIP, std::string(where) + ": " + hipGetErrorString(e));
+    return DQN_OK;
+}
+
+dim3 grid1(long n, int block) { return dim3((unsigned)((n + block - 1) / block)); }
+
+// ----- host-side initial weights: uniform in +-sqrt(6/fan_in), biases 0 -----
+void he_uniform_host(std::vector<float> &blob, int K, int dueling, uint64_t seed)
+{
+    struct T { int64_t count; int fan_in; };
+    std::vector<T> spec = {{8192, 256}, {32, 0}, {32768, 512}, {64, 0}, {36864, 576}, {64, 0},
+                           {1605632, 3136}, {512, 0}};
+    if (dueling) { spec.push_back({512, 512}); spec.push_back({1, 0}); }
+    spec.push_back({(int64_t)K * 512, 512});
+    spec.push_back({K, 0});
+    int64_t e = 0;
+    for (const T &t : spec) {
+        float bound = t.fan_in ? (float)std::sqrt(6.0 / (double)t.fan_in) : 0.f;
+        for (int64_t i = 0; i < t.count; ++i, ++e) {
+            float centred = 2.0f * misc::draw_u24(seed, (uint64_t)e) - 1.0f;
+            blob[(size_t)e] = t.fan_in ? centred * bound : 0.f;
+        }
+    }
+}
+
+void permute(dqn_ctx *c, const float *src, float *dst, int dir, hipStream_t st)
+{
+    launch(c, "permute", st, [&] { misc::k_permute<<<grid1(c->n, 256), 256, 0, st>>>(src, dst, c->n, dir); });
+}
+
+float *which_buffer(dqn_ctx *c, int which)
+{
+    switch (which) {
+    case 0: return c->theta;
+    case 1: return c->theta_t;
+    case 2: return c->grads;
+    case 3: return c->rms_v;
+    case 4: return c->rms_m;
+    default: return nullptr;
+    }
+}
+
+// ----- forward of up to three passes through conv1..fc1 -----
+struct Pass {
+    const uint8_t *x;   // uint8 states
+    long xs;            // bytes between samples
+    const float *theta; // parameter blob used
+    int n;              // samples
+};
+
+int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
+                      hipStream_t st)
+{
+    using namespace g32;
+    const Workspace &w = c->ws;
+    long row0[3];
+    long rows = 0;
+    for (int i = 0; i < npass; ++i) { row0[i] = rows; rows += pass[i].n; }
+
+    auto build = [&](FwdArgs &A, int BM, int P, auto xptr, auto xstride, int64_t woff, int64_t boff,
+                     float *ybase, long ystride, bool with_bias) {
+        int tile = 0;
+        A.nseg = npass;
+        for (int i = 0; i < npass; ++i) {
+            FwdSeg &S = A.seg[i];
+            S.x = xptr(i);
+            S.xs = xstride(i);
+            S.w = pass[i].theta + woff;
+            S.bias = with_bias ? pass[i].theta + boff : nullptr;
+            S.y = ybase + row0[i] * ystride;
+            S.M = pass[i].n * P;
+            S.tile_begin = tile;
+            tile += (S.M + BM - 1) / BM;
+        }
+        for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
+        return tile;
+    };
+
+    {  // conv1
+        FwdArgs A{};
+        int tiles = build(A, 128, 400, [&](int i) { return (const void *)pass[i].x; },
+                          [&](int i) { return pass[i].xs; }, net::C1W, net::C1B, w.act1, net::A1, true);
+        A.klen = GConv1::K; A.split_stride = 0; A.scale = 1.0f / 255.0f;
+        launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 128, 32><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+    }
+    const bool small = rows * 81 < 64 * 512;  // few rows: smaller tiles, more workgroups
+    {  // conv2
+        FwdArgs A{};
+        int BM = small ? 32 : 64;
+        int tiles = build(A, BM, 81, [&](int i) { return (const void *)(w.act1 + row0[i] * net::A1); },
+                          [&](int) { return (long)net::A1; }, net::C2W, net::C2B, w.act2, net::A2, true);
+        A.klen = GConv2::K; A.split_stride = 0; A.scale = 1.0f;
+        if (small) launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 32, 64><<<dim3(tiles, 1, 1), 128, 0, st>>>(A); });
+        else launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 64, 64><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+    }
+    {  // conv3
+        FwdArgs A{};
+        int BM = small ? 32 : 64;
+        int tiles = build(A, BM, 49, [&](int i) { return (const void *)(w.act2 + row0[i] * net::A2); },
+                          [&](int) { return (long)net::A2; }, net::C3W, net::C3B, w.act3, net::A3, true);
+        A.klen = GConv3::K; A.split_stride = 0; A.scale = 1.0f;
+        if (small) launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 32, 64><<<dim3(tiles, 1, 1), 128, 0, st>>>(A); });
+        else launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 64, 64><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+    }
+    {  // fc1: raw partial sums per reduction split; the head kernels finish it
+        FwdArgs A{};
+        const int ns = fc1_splits(rows);
+        int tiles = build(A, 32, 1, [&](int i) { return (const void *)(w.act3 + row0[i] * net::A3); },
+                          [&](int) { return (long)net::A3; }, net::F1W, net::F1B, w.f1part, net::HID, false);
+        A.klen = GFc1::K / ns; A.split_stride = rows * net::HID; A.scale = 1.0f;
+        launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 32, 64><<<dim3(tiles, 8, ns), 128, 0, st>>>(A); });
+        *nsplit_out = ns;
+        *split_stride_out = rows * net::HID;
+    }
+    return hip_status(c, "forward");
+}
+
+int wgrad_splits(long M, int tiles)
+{
+    long want = std::max<long>(1, 512 / tiles);
+    long by_rows = std::max<long>(1, M / 64);
+    return (int)std::min<long>({want, by_rows, (long)MAX_WSPLIT});
+}
+
+}  // namespace
+
+// ============================================================================
+extern "C" {
+
+const char *dqn_last_error(const dqn_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+int32_t dqn_query_sizes(const dqn_config *cfg, dqn_sizes *out)
+{
+    if (!cfg || !out) return fail(nullptr, DQN_ERR_INVALID_ARG, "dqn_query_sizes: NULL argument");
+    if (const char *m = check_config(*cfg)) return fail(nullptr, DQN_ERR_INVALID_ARG, m);
+    dqn_sizes s{};
+    const int64_t n = net::param_count(cfg->num_actions, cfg->dueling);
+    s.param_count = n;
+    s.params = align_up((size_t)n * 4, 256);
+    s.opt_state = s.params * (cfg->rms_centered ? 2 : 1);
+    s.shadow_bf16 = cfg->precision == 1 ? 2 * align_up((size_t)n * 2, 256) : 0;
+    s.grads = s.params;
+    const int64_t cap = cfg->replay_capacity;
+    s.replay_frames = (size_t)cap * net::FRAME;
+    s.replay_meta = cap ? align_up((size_t)cap * 4, 256) * 2 + align_up((size_t)cap, 256) : 0;
+    s.tree_leaves = cap ? tree_leaves(cap) : 0;
+    s.tree = cap ? ((size_t)2 * s.tree_leaves + 64) * 4 : 0;
+    s.workspace = carve(*cfg, nullptr).total;
+    *out = s;
+    return DQN_OK;
+}
+
+int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, void *stream)
+{
+    if (!out || !cfg || !b) return fail(nullptr, DQN_ERR_INVALID_ARG, "dqn_init: NULL argument");
+    *out = nullptr;
+    dqn_sizes sz;
+    int32_t rc = dqn_query_sizes(cfg, &sz);
+    if (rc) return rc;
+    const void *req[] = {b->online, b->target, b->opt_state, b->grads, b->workspace};
+    for (const void *p : req)
+        if (!p || !aligned(p, 256)) return fail(nullptr, DQN_ERR_INVALID_ARG, "dqn_init: a required buffer is NULL or not 256-byte aligned");
+    if (cfg->precision == 1 && (!b->shadow_bf16 || !aligned(b->shadow_bf16, 256)))
+        return fail(nullptr, DQN_ERR_INVALID_ARG, "dqn_init: shadow_bf16 buffer required for precision 1");
+    if (cfg->replay_capacity > 0) {
+        const void *rp[] = {b->replay_frames, b->replay_meta, b->tree};
+        for (const void *p : rp)
+            if (!p || !aligned(p, 256)) return fail(nullptr, DQN_ERR_INVALID_ARG, "dqn_init: replay buffers are NULL or not 256-byte aligned");
+    }
+    dqn_ctx *c = new (std::nothrow) dqn_ctx();
+    if (!c) return fail(nullptr, DQN_ERR_OOM, "dqn_init: out of host memory");
+    c->cfg = *cfg;
+    c->buf = *b;
+    c->sz = sz;
+    c->n = sz.param_count;
+    c->R = cfg->num_actions + (cfg->dueling ? 1 : 0);
+    c->ws = carve(*cfg, (uint8_t *)b->workspace);
+    c->theta = (float *)b->online;
+    c->theta_t = (float *)b->target;
+    c->rms_v = (float *)b->opt_state;
+    c->rms_m = cfg->rms_centered ? (float *)((uint8_t *)b->opt_state + sz.params) : nullptr;
+    c->grads = (float *)b->grads;
+    c->L = sz.tree_leaves;
+    c->levels = 0;
+    while ((1l << c->levels) < c->L) ++c->levels;
+    c->stored = 0;
+    if (cfg->replay_capacity > 0) {
+        size_t stride = align_up((size_t)cfg->replay_capacity * 4, 256);
+        c->meta_a = (int32_t *)b->replay_meta;
+        c->meta_r = (float *)((uint8_t *)b->replay_meta + stride);
+        c->meta_done = (uint8_t *)b->replay_meta + 2 * stride;
+        c->tree = (float *)b->tree;
+    }
+    hipStream_t st = (hipStream_t)stream;
+
+    std::vector<float> blob;
+    try {
+        blob.resize((size_t)c->n);
+    } catch (...) {
+        delete c;
+        return fail(nullptr, DQN_ERR_OOM, "dqn_init: out of host memory");
+    }
+    for (int net_i = 0; net_i < 2; ++net_i) {
+        he_uniform_host(blob, cfg->num_actions, cfg->dueling, net_i ? cfg->target_seed : cfg->seed);
+        // the gradient buffer doubles as the staging area for the canonical blob
+        if (hipMemcpyAsync(c->grads, blob.data(), (size_t)c->n * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess) {
+            std::string m = std::string("dqn_init: upload failed: ") + hipGetErrorString(hipGetLastError());
+            delete c;
+            return fail(nullptr, DQN_ERR_HIP, m);
+        }
+        permute(c, c->grads, net_i ? c->theta_t : c->theta, 0, st);
+    }
+    long nopt = (long)(sz.opt_state / 4);
+    misc::k_fill<<<grid1(nopt, 256), 256, 0, st>>>(c->rms_v, 0.f, nopt);
+    misc::k_fill<<<grid1(c->n, 256), 256, 0, st>>>(c->grads, 0.f, c->n);
+    if (cfg->replay_capacity > 0) {
+        long nt = 2 * c->L + 64;
+        misc::k_fill<<<grid1(nt, 256), 256, 0, st>>>(c->tree, 0.f, nt);
+        misc::k_fill<<<1, 64, 0, st>>>(c->tree + 2 * c->L, 1.0f, 1);  // maximal priority starts at 1
+    }
+    if (cfg->precision == 1) {
+        __hip_bfloat16 *sh = (__hip_bfloat16 *)b->shadow_bf16;
+        size_t half = align_up((size_t)c->n * 2, 256) / 2;
+        misc::k_to_bf16<<<grid1(c->n, 256), 256, 0, st>>>(c->theta, sh, c->n);
+        misc::k_to_bf16<<<grid1(c->n, 256), 256, 0, st>>>(c->theta_t, sh + half, c->n);
+    }
+    if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
+        delete c;
+        return fail(nullptr, DQN_ERR_HIP, "dqn_init: device initialisation failed");
+    }
+    *out = c;
+    return DQN_OK;
+}
+
+int32_t dqn_destroy(dqn_ctx *ctx)
+{
+    if (!ctx) return DQN_OK;
+    for (ProfRec &r : ctx->recs) {
+        (void)hipEventDestroy(r.e0);
+        (void)hipEventDestroy(r.e1);
+    }
+    delete ctx;
+    return DQN_OK;
+}
+
+int32_t dqn_profile_begin(dqn_ctx *c)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    c->prof = true;
+    return DQN_OK;
+}
+
+int32_t dqn_profile_end(dqn_ctx *c, int32_t cap, const char **names, int64_t *counts, double *total_ms)
+{
+    if (!c || cap < 0 || (cap > 0 && (!names || !counts || !total_ms))) return DQN_ERR_INVALID_ARG;
+    c->prof = false;
+    if (hipDeviceSynchronize() != hipSuccess) return fail(c, DQN_ERR_HIP, "dqn_profile_end: synchronise failed");
+    int32_t distinct = 0;
+    for (ProfRec &r : c->recs) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, r.e0, r.e1);
+        int32_t k = 0;
+        for (; k < distinct && k < cap; ++k)
+            if (names[k] == r.name || std::strcmp(names[k], r.name) == 0) break;
+        if (k == distinct) {
+            if (k < cap) { names[k] = r.name; counts[k] = 0; total_ms[k] = 0.0; }
+            ++distinct;
+        }
+        if (k < cap) { counts[k] += 1; total_ms[k] += ms; }
+        (void)hipEventDestroy(r.e0);
+        (void)hipEventDestroy(r.e1);
+    }
+    c->recs.clear();
+    return distinct;
+}
+
+int32_t dqn_get_params(dqn_ctx *c, int32_t which, float *dst, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    float *src = which_buffer(c, which);
+    if (!src) return fail(c, which == 4 ? DQN_ERR_STATE : DQN_ERR_INVALID_ARG, "dqn_get_params: no such buffer");
+    if (!dst || !aligned(dst, 16)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_get_params: dst is NULL or misaligned");
+    permute(c, src, dst, 1, (hipStream_t)stream);
+    return hip_status(c, "dqn_get_params");
+}
+
+int32_t dqn_set_params(dqn_ctx *c, int32_t which, const float *src, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    float *dst = which_buffer(c, which);
+    if (!dst) return fail(c, which == 4 ? DQN_ERR_STATE : DQN_ERR_INVALID_ARG, "dqn_set_params: no such buffer");
+    if (!src || !aligned(src, 16)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_set_params: src is NULL or misaligned");
+    hipStream_t st = (hipStream_t)stream;
+    permute(c, src, dst, 0, st);
+    if (c->cfg.precision == 1 && which <= 1) {
+        __hip_bfloat16 *sh = (__hip_bfloat16 *)c->buf.shadow_bf16;
+        size_t half = align_up((size_t)c->n * 2, 256) / 2;
+        misc::k_to_bf16<<<grid1(c->n, 256), 256, 0, st>>>(dst, sh + (which ? half : 0), c->n);
+    }
+    return hip_status(c, "dqn_set_params");
+}
+
+int32_t dqn_sync_target(dqn_ctx *c, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(c->theta_t, c->theta, (size_t)c->n * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(c, DQN_ERR_HIP, "dqn_sync_target: copy failed");
+    if (c->cfg.precision == 1) {
+        __hip_bfloat16 *sh = (__hip_bfloat16 *)c->buf.shadow_bf16;
+        size_t half = align_up((size_t)c->n * 2, 256) / 2;
+        if (hipMemcpyAsync(sh + half, sh, (size_t)c->n * 2, hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return fail(c, DQN_ERR_HIP, "dqn_sync_target: copy failed");
+    }
+    return DQN_OK;
+}
+
+// ------------------------------------------------------------ replay
+int32_t per_fill(dqn_ctx *c, const float *priorities, int64_t n, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (c->cfg.replay_capacity <= 0) return fail(c, DQN_ERR_STATE, "per_fill: context has no replay");
+    if (n < 0 || n > c->cfg.replay_capacity) return fail(c, DQN_ERR_INVALID_ARG, "per_fill: n out of range");
+    if (n > 0 && (!priorities || !aligned(priorities, 16))) return fail(c, DQN_ERR_INVALID_ARG, "per_fill: priorities NULL or misaligned");
+    hipStream_t st = (hipStream_t)stream;
+    const long L = c->L;
+    launch(c, "tree_leaves", st, [&] {
+        misc::k_tree_leaves<<<grid1(L, 256), 256, 0, st>>>(c->tree, L, priorities, n, c->cfg.per_alpha);
+    });
+    for (long first = L >> 1; first >= 1; first >>= 1)
+        launch(c, "tree_level", st, [&] { misc::k_tree_level<<<grid1(first, 256), 256, 0, st>>>(c->tree, first, first); });
+    c->stored = n;
+    return hip_status(c, "per_fill");
+}
+
+int32_t per_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, int32_t *idx, float *is_w, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (c->cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "per_sample: nothing stored");
+    if (B < 1 || B > 1024) return fail(c, DQN_ERR_INVALID_ARG, "per_sample: B must be in 1..1024");
+    if (!idx || !is_w || !aligned(idx, 4) || !aligned(is_w, 4)) return fail(c, DQN_ERR_INVALID_ARG, "per_sample: NULL or misaligned output");
+    if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "per_sample: beta must be >= 0");
+    hipStream_t st = (hipStream_t)stream;
+    const int block = (B + 63) / 64 * 64;
+    launch(c, "per_sample", st, [&] {
+        misc::k_per_sample<<<1, block, 0, st>>>(c->tree, c->L, c->stored, B, beta, draw_seed,
+                                                c->cfg.per_stratified, idx, is_w);
+    });
+    return hip_status(c, "per_sample");
+}
+
+int32_t per_update(dqn_ctx *c, const int32_t *idx, const float *td_abs, int32_t n, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (c->cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "per_update: nothing stored");
+    if (n < 1 || n > 1024) return fail(c, DQN_ERR_INVALID_ARG, "per_update: n must be in 1..1024");
+    if (!idx || !td_abs) return fail(c, DQN_ERR_INVALID_ARG, "per_update: NULL argument");
+    hipStream_t st = (hipStream_t)stream;
+    const int block = (n + 63) / 64 * 64;
+    launch(c, "per_update", st, [&] {
+        misc::k_per_update<<<1, block, 0, st>>>(c->tree, c->L, c->levels, c->stored, idx, td_abs, n,
+                                                c->cfg.per_alpha, c->cfg.per_eps);
+    });
+    return hip_status(c, "per_update");
+}
+
+int32_t dqn_replay_write(dqn_ctx *c, int64_t slot0, int64_t n, const uint8_t *frames, const int32_t *a,
+                         const float *r, const uint8_t *done, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    const int64_t cap = c->cfg.replay_capacity;
+    if (cap <= 0) return fail(c, DQN_ERR_STATE, "dqn_replay_write: context has no replay");
+    if (slot0 < 0 || slot0 >= cap || n < 1 || n > cap) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_write: slot range out of bounds");
+    if (!frames || !aligned(frames, 16)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_write: frames NULL or not 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    launch(c, "replay_write", st, [&] {
+        misc::k_replay_write<<<dim3((unsigned)n), 256, 0, st>>>((uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r,
+                                                                c->meta_done, cap, slot0, frames, a, r, done);
+    });
+    return hip_status(c, "dqn_replay_write");
+}
+
+int32_t dqn_replay_gather(dqn_ctx *c, const int32_t *idx, int32_t n, uint8_t *s, uint8_t *s_next, int32_t *a,
+                          float *r, uint8_t *done, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (c->cfg.replay_capacity <= 0) return fail(c, DQN_ERR_STATE, "dqn_replay_gather: context has no replay");
+    if (n < 1 || n > c->cfg.max_batch || !idx) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_gather: n out of range or idx NULL");
+    if ((s && !aligned(s, 16)) || (s_next && !aligned(s_next, 16))) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_gather: outputs must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    misc::GatherArgs G{(const uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r, c->meta_done,
+                       (long)c->cfg.replay_capacity, idx, nullptr, s, s_next, a, r, done};
+    launch(c, "gather", st, [&] { misc::k_gather<<<dim3(n, 5), 256, 0, st>>>(G); });
+    return hip_status(c, "dqn_replay_gather");
+}
+
+// ------------------------------------------------------------ acting
+int32_t dqn_act(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64_t draw_seed, int32_t *actions,
+                float *q_opt, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (E < 1 || E > c->cfg.max_act_batch) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act: E out of range");
+    if (!obs || !actions || !aligned(obs, 16)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act: NULL or misaligned argument");
+    if (!(epsilon >= 0.f && epsilon <= 1.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act: epsilon must be in [0,1]");
+    if (c->cfg.precision != 0) return fail(c, DQN_ERR_UNSUPPORTED, "dqn_act: bf16 path not built yet");
+    hipStream_t st = (hipStream_t)stream;
+    Pass p{obs, net::STATE, c->theta, E};
+    int ns;
+    long ss;
+    int32_t rc = forward_trunk(c, &p, 1, &ns, &ss, st);
+    if (rc) return rc;
+    misc::HeadActArgs H{c->ws.f1part, ns, ss, E, c->cfg.num_actions, c->cfg.dueling, c->theta + net::F1B,
+                        c->theta + net::HEAD, epsilon, draw_seed, actions, q_opt};
+    launch(c, "head_act", st, [&] { misc::k_head_act<<<E, 256, 0, st>>>(H); });
+    return hip_status(c, "dqn_act");
+}
+
+// ------------------------------------------------------------ training
+int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta, uint64_t draw_seed,
+                       const dqn_step_out *out, void *stream)
+{
+    using namespace g32;
+    if (!c) return DQN_ERR_INVALID_ARG;
+    const dqn_config &cfg = c->cfg;
+    if (B < 1 || B > cfg.max_batch) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: B out of range");
+    if (cfg.precision != 0) return fail(c, DQN_ERR_UNSUPPORTED, "dqn_train_step: bf16 path not built yet");
+    hipStream_t st = (hipStream_t)stream;
+    const Workspace &w = c->ws;
+    dqn_step_out O{};
+    if (out) O = *out;
+
+    const uint8_t *s, *sn;
+    long xs;
+    const int32_t *a;
+    const float *r, *isw;
+    const uint8_t *done;
+    if (batch) {
+        if (!batch->s || !batch->s_next || !batch->a || !batch->r || !batch->done)
+            return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: batch has a NULL member");
+        if (!aligned(batch->s, 16) || !aligned(batch->s_next, 16))
+            return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: states must be 16-byte aligned");
+        s = batch->s; sn = batch->s_next; xs = net::STATE;
+        a = batch->a; r = batch->r; done = batch->done; isw = batch->w;
+    } else {
+        if (cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "dqn_train_step: replay is empty");
+        if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: beta must be >= 0");
+        int32_t rc = per_sample(c, B, beta, draw_seed, w.b_idx, w.b_w, stream);
+        if (rc) return rc;
+        misc::GatherArgs G{(const uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r, c->meta_done,
+                           (long)cfg.replay_capacity, w.b_idx, w.stack5, nullptr, nullptr, w.b_a, w.b_r, w.b_done};
+        launch(c, "gather", st, [&] { misc::k_gather<<<dim3(B, 5), 256, 0, st>>>(G); });
+        s = w.stack5; sn = w.stack5 + net::FRAME; xs = 5 * net::FRAME;
+        a = w.b_a; r = w.b_r; done = w.b_done; isw = w.b_w;
+        if (O.idx && hipMemcpyAsync(O.idx, w.b_idx, (size_t)B * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return fail(c, DQN_ERR_HIP, "dqn_train_step: copy failed");
+    }
+
+    // forward: online(s), online(s'), target(s') in one launch per layer
+    Pass passes[3] = {{s, xs, c->theta, B}, {sn, xs, c->theta, B}, {sn, xs, c->theta_t, B}};
+    int ns;
+    long ss;
+    int32_t rc = forward_trunk(c, passes, 3, &ns, &ss, st);
+    if (rc) return rc;
+
+    misc::HeadArgs H{};
+    H.part = w.f1part; H.nsplit = ns; H.split_stride = ss;
+    H.B = B; H.K = cfg.num_actions; H.dueling = cfg.dueling; H.double_q = cfg.double_q; H.loss_kind = cfg.loss_kind;
+    H.kappa = cfg.huber_delta; H.gamma = cfg.gamma;
+    H.f1b_on = c->theta + net::F1B; H.f1b_tg = c->theta_t + net::F1B;
+    H.head_on = c->theta + net::HEAD; H.head_tg = c->theta_t + net::HEAD;
+    H.a = a; H.r = r; H.done = done; H.w = isw;
+    H.h_s = w.h_s; H.dh = w.dh; H.dA = w.dA; H.td_abs = w.td_abs; H.loss_j = w.loss_j;
+    H.q_s = O.q_s; H.q_no = O.q_next_online; H.q_nt = O.q_next_target; H.y = O.y; H.td = O.td;
+    H.a_star = O.a_star; H.is_w = O.is_w;
+    launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 256, 0, st>>>(H); });
+
+    misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
+    launch(c, "head_wgrad", st, [&] { misc::k_head_wgrad<<<c->R, 512, 0, st>>>(HW); });
+
+    // backward through fc1, conv3, conv2, conv1 (no input gradient for conv1)
+    const bool small = B <= 128;
+    {
+        DgradArgs D{w.dh, c->theta + net::F1W, w.act3, w.d3, B};
+        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
+        WgradArgs G{w.dh, w.act3, w.gp4, B, B, net::A3, 0, 1.0f};
+        launch(c, "fc1_wgrad", st, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, st>>>(G); });
+    }
+    int ns3, ns2, ns1;
+    {
+        DgradArgs D{w.d3, c->theta + net::C3W, w.act2, w.d2, B};
+        long M = (long)B * 81;
+        if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 64><<<dim3((M + 31) / 32, 1, 1), 128, 0, st>>>(D); });
+        else launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
+        long Mr = (long)B * 49;
+        ns3 = wgrad_splits(Mr, 9);
+        int rps = (int)((Mr + ns3 - 1) / ns3 + 31) / 32 * 32;
+        ns3 = (int)((Mr + rps - 1) / rps);
+        WgradArgs G{w.d3, w.act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
+        launch(c, "conv3_wgrad", st, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, ns3), 256, 0, st>>>(G); });
+    }
+    {
+        DgradArgs D{w.d2, c->theta + net::C2W, w.act1, w.d1, B};
+        long M = (long)B * 100;
+        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
+        long Mr = (long)B * 81;
+        ns2 = wgrad_splits(Mr, 8);
+        int rps = (int)((Mr + ns2 - 1) / ns2 + 31) / 32 * 32;
+        ns2 = (int)((Mr + rps - 1) / rps);
+        WgradArgs G{w.d2, w.act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
+        launch(c, "conv2_wgrad", st, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, ns2), 256, 0, st>>>(G); });
+    }
+    {
+        long Mr = (long)B * 400;
+        ns1 = wgrad_splits(Mr, 4);
+        int rps = (int)((Mr + ns1 - 1) / ns1 + 31) / 32 * 32;
+        ns1 = (int)((Mr + rps - 1) / rps);
+        WgradArgs G{w.d1, s, w.gp1, B, rps, xs, net::L1N, 1.0f / 255.0f};
+        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 64><<<dim3(4, 1, ns1), 128, 0, st>>>(G); });
+    }
+
+    misc::RmsArgs RA{};
+    RA.seg[0] = {net::C1W, net::L1N, w.gp1, ns1, net::L1N};
+    RA.seg[1] = {net::C2W, net::L2N, w.gp2, ns2, net::L2N};
+    RA.seg[2] = {net::C3W, net::L3N, w.gp3, ns3, net::L3N};
+    RA.seg[3] = {net::F1W, net::L4N, w.gp4, 1, 0};
+    RA.seg[4] = {net::HEAD, net::head_count(cfg.num_actions, cfg.dueling), w.gp5, 1, 0};
+    RA.theta = c->theta; RA.v = c->rms_v; RA.m = c->rms_m; RA.g = c->grads; RA.shadow = nullptr;
+    RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps; RA.n = c->n;
+    launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<grid1(c->n, 256), 256, 0, st>>>(RA); });
+
+    if (!batch) {
+        rc = per_update(c, w.b_idx, w.td_abs, B, stream);
+        if (rc) return rc;
+    }
+    return hip_status(c, "dqn_train_step");
+}
+
+}  // extern "C"

@@ -1,0 +1,421 @@
+// fp32 implicit-GEMM kernels on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32).
+//
+// Three kernel shapes cover the whole network (Section 3; the forward /
+// backward / calculateGradient split of the paper's Layer class is kept as
+// three kernel families):
+//   k_fwd   : Y[m][n]  = sum_k  A(m,k) * W[n][k]            (conv1-3, fc1 forward)
+//   k_dgrad : dX[m][c] = sum_(tap,o) dY(m,tap,o) * W[o][tap][c]   (input gradients)
+//   k_wgrad : dW[o][k] = sum_m  dY[m][o] * A(m,k)           (weight gradients)
+// A(m,k) is the im2col view of a channel-last activation tensor, formed on the
+// fly while staging tiles in LDS; it never exists in memory.
+//
+// MFMA 32x32x2 operand layout (64-lane wave, lane = 32*h + i):
+//   a-operand: A[i][k=h]     b-operand: B[k=h][j=i]
+//   result   : acc[r] = D[8*(r/4) + 4*h + r%4][i]
+// The reduction order inside a tile is free as long as both operands agree, so
+// a lane that reads LDS along k takes 4 consecutive k (one 128-bit read) and
+// feeds them to 4 MFMAs: MFMA t pairs k = 4*h + t of both operands.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+namespace g32 {
+
+constexpr int BK = 32;      // reduction elements staged per iteration
+constexpr int LDK = BK + 4; // LDS row stride of a k-contiguous tile (floats)
+
+__device__ __forceinline__ v16f mfma(float a, float b, v16f c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ v4f ld4(const float *p) { return *reinterpret_cast<const v4f *>(p); }
+__device__ __forceinline__ v4f ld4(const uint8_t *p)
+{
+    uint32_t u = *reinterpret_cast<const uint32_t *>(p);
+    v4f r;
+    r.x = (float)(u & 0xFFu);
+    r.y = (float)((u >> 8) & 0xFFu);
+    r.z = (float)((u >> 16) & 0xFFu);
+    r.w = (float)(u >> 24);
+    return r;
+}
+
+// ---------------------------------------------------------------------------
+// Forward geometries: row m = (sample, out_y, out_x); k = position inside the
+// receptive field in the order the weights are stored.
+// ---------------------------------------------------------------------------
+struct GConv1 {  // 8x8 stride 4, uint8 CHW input, k = (c, p, q)
+    using in_t = uint8_t;
+    static constexpr int K = 256, N = 32, P = 400;
+    static __device__ __forceinline__ long row_off(int m, long xs)
+    {
+        int n = m / 400, r = m % 400, i = r / 20, j = r % 20;
+        return (long)n * xs + (i * 4) * 84 + j * 4;
+    }
+    static __device__ __forceinline__ int k_off(int k) { return (k >> 6) * 7056 + ((k >> 3) & 7) * 84 + (k & 7); }
+};
+struct GConv2 {  // 4x4 stride 2 over 20x20x32, k = (p, q, c)
+    using in_t = float;
+    static constexpr int K = 512, N = 64, P = 81;
+    static __device__ __forceinline__ long row_off(int m, long xs)
+    {
+        int n = m / 81, r = m % 81, i = r / 9, j = r % 9;
+        return (long)n * xs + ((i * 2) * 20 + j * 2) * 32;
+    }
+    static __device__ __forceinline__ int k_off(int k) { return (k >> 7) * 640 + (k & 127); }
+};
+struct GConv3 {  // 3x3 stride 1 over 9x9x64, k = (p, q, c)
+    using in_t = float;
+    static constexpr int K = 576, N = 64, P = 49;
+    static __device__ __forceinline__ long row_off(int m, long xs)
+    {
+        int n = m / 49, r = m % 49, i = r / 7, j = r % 7;
+        return (long)n * xs + (i * 9 + j) * 64;
+    }
+    static __device__ __forceinline__ int k_off(int k) { return (k / 192) * 576 + (k % 192); }
+};
+struct GFc1 {  // dense 3136 -> 512 on the flattened conv3 output
+    using in_t = float;
+    static constexpr int K = 3136, N = 512, P = 1;
+    static __device__ __forceinline__ long row_off(int m, long xs) { return (long)m * xs; }
+    static __device__ __forceinline__ int k_off(int k) { return k; }
+};
+
+// One launch serves up to three independent (input, weights, output) row
+// ranges: the online net on s, the online net on s' and the target net on s'.
+struct FwdSeg {
+    const void *x;      // input activations (uint8 for conv1, float otherwise)
+    const float *w;     // [N][K]
+    const float *bias;  // [N] or nullptr (raw partial sums, no activation)
+    float *y;           // [M][N] (+ z*split_stride per reduction split)
+    int M;              // rows
+    int tile_begin;     // first blockIdx.x of this segment
+    long xs;            // elements between consecutive samples of x
+};
+struct FwdArgs {
+    FwdSeg seg[3];
+    int nseg;
+    int klen;           // reduction elements per blockIdx.z
+    long split_stride;  // elements between the outputs of consecutive splits
+    float scale;        // multiplies the accumulated sum (1/255 for conv1)
+};
+
+template <class G, int BM, int BN>
+__global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_fwd(FwdArgs A)
+{
+    constexpr int T = (BM / 32) * (BN / 32) * 64;
+    constexpr int NA = BM * 8 / T, NB = BN * 8 / T;
+    static_assert(NA * T == BM * 8 && NB * T == BN * 8, "tile/threads mismatch");
+    using in_t = typename G::in_t;
+    __shared__ __attribute__((aligned(16))) float As[BM * LDK];
+    __shared__ __attribute__((aligned(16))) float Bs[BN * LDK];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bx = blockIdx.x;
+    FwdSeg S = A.seg[0];
+    if (A.nseg > 1 && bx >= A.seg[1].tile_begin) S = A.seg[1];
+    if (A.nseg > 2 && bx >= A.seg[2].tile_begin) S = A.seg[2];
+    const int m0 = (bx - S.tile_begin) * BM, n0 = blockIdx.y * BN;
+    const int kbeg = blockIdx.z * A.klen, kend = kbeg + A.klen;
+    const in_t *x = static_cast<const in_t *>(S.x);
+
+    const int lr = tid >> 3, kq = (tid & 7) * 4;
+    long aoff[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        int m = m0 + lr + i * (T / 8);
+        aoff[i] = m < S.M ? G::row_off(m, S.xs) : -1;
+    }
+    v4f ra[NA], rb[NB];
+    auto gload = [&](int k0) {
+        const int ko = G::k_off(k0 + kq);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ra[i] = aoff[i] >= 0 ? ld4(x + aoff[i] + ko) : v4f{0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+            rb[i] = ld4(S.w + (long)(n0 + lr + i * (T / 8)) * G::K + k0 + kq);
+    };
+    auto sstore = [&]() {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<v4f *>(&As[(lr + i * (T / 8)) * LDK + kq]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) *reinterpret_cast<v4f *>(&Bs[(lr + i * (T / 8)) * LDK + kq]) = rb[i];
+    };
+
+    const int wm = wave % (BM / 32), wn = wave / (BM / 32);
+    const int li = lane & 31, h = lane >> 5;
+    const float *ap = &As[(wm * 32 + li) * LDK + 4 * h];
+    const float *bp = &Bs[(wn * 32 + li) * LDK + 4 * h];
+    v16f acc = {0};
+
+    gload(kbeg);
+    sstore();
+    __syncthreads();
+    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+        const bool more = k0 + BK < kend;
+        if (more) gload(k0 + BK);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 8) {
+            v4f a = ld4(ap + kk), b = ld4(bp + kk);
+            acc = mfma(a.x, b.x, acc);
+            acc = mfma(a.y, b.y, acc);
+            acc = mfma(a.z, b.z, acc);
+            acc = mfma(a.w, b.w, acc);
+        }
+        __syncthreads();
+        if (more) {
+            sstore();
+            __syncthreads();
+        }
+    }
+
+    float *y = S.y + (long)blockIdx.z * A.split_stride;
+    const int col = n0 + wn * 32 + li;
+    const float bias = S.bias ? S.bias[col] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int m = m0 + wm * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+        if (m < S.M) {
+            float v = acc[r] * A.scale;
+            if (S.bias) v = fmaxf(v + bias, 0.f);
+            y[(long)m * G::N + col] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Input gradient.  For a stride-S convolution the input pixels fall into S*S
+// parity classes (h mod S, w mod S); a pixel of class (a,b) only meets the
+// kernel taps p = a + S*u, q = b + S*v, so each class is its own dense GEMM
+// over (KH/S)*(KW/S) taps with no multiplications by structural zeros:
+//   dX[n][S*h'+a][S*w'+b][c] = sum_{u,v,o} dY[n][h'-u][w'-v][o] * W[o][a+S*u][b+S*v][c]
+// (out-of-range dY positions contribute 0).  The result is multiplied by the
+// ReLU mask of the layer below (its stored output > 0).
+// ---------------------------------------------------------------------------
+template <int S_, int TH_, int TW_, int OH_, int OW_, int HP_, int WP_, int CO_, int CI_, int KH_,
+          int KW_, int H_, int W_>
+struct DGeom {
+    static constexpr int S = S_, TH = TH_, TW = TW_, OH = OH_, OW = OW_, HP = HP_, WP = WP_,
+                         CO = CO_, CI = CI_, KH = KH_, KW = KW_, H = H_, W = W_;
+    static constexpr int K = TH * TW * CO;  // reduction length per class
+    static constexpr int PP = HP * WP;      // rows per sample per class
+};
+using DConv2 = DGeom<2, 2, 2, 9, 9, 10, 10, 64, 32, 4, 4, 20, 20>;
+using DConv3 = DGeom<1, 3, 3, 7, 7, 9, 9, 64, 64, 3, 3, 9, 9>;
+using DFc1 = DGeom<1, 1, 1, 1, 1, 1, 1, 512, 3136, 1, 1, 1, 1>;
+
+struct DgradArgs {
+    const float *dy;    // [B][OH][OW][CO] gradient w.r.t. this layer's pre-activation
+    const float *w;     // [CO][KH][KW][CI]
+    const float *xact;  // [B][H][W][CI] this layer's input (ReLU output of the layer below)
+    float *dx;          // [B][H][W][CI] gradient w.r.t. the pre-activation of the layer below
+    int B;
+};
+
+template <class D, int BM, int BN>
+__global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_dgrad(DgradArgs A)
+{
+    constexpr int T = (BM / 32) * (BN / 32) * 64;
+    constexpr int NA = BM * 8 / T;
+    constexpr int LDB = BN + 4;            // LDS row stride of the [k][c] weight tile
+    constexpr int BROWS = T / (BN / 4);    // weight-tile rows filled per pass
+    constexpr int NBL = BK / BROWS;
+    static_assert(NA * T == BM * 8 && NBL * BROWS == BK, "tile/threads mismatch");
+    __shared__ __attribute__((aligned(16))) float As[BM * LDK];
+    __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int ca = blockIdx.z / D::S, cb = blockIdx.z % D::S;
+    const int Mc = A.B * D::PP;
+
+    const int lr = tid >> 3, kq = (tid & 7) * 4;
+    int rn[NA], rh[NA], rw[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        int m = m0 + lr + i * (T / 8);
+        if (m < Mc) {
+            rn[i] = m / D::PP;
+            int r = m % D::PP;
+            rh[i] = r / D::WP;
+            rw[i] = r % D::WP;
+        } else {
+            rn[i] = -1; rh[i] = 0; rw[i] = 0;
+        }
+    }
+    const int br = tid / (BN / 4), bc = (tid % (BN / 4)) * 4;
+    v4f ra[NA], rb[NBL];
+    auto gload = [&](int k0) {
+        const int tap = k0 / D::CO, o0 = k0 % D::CO;
+        const int u = tap / D::TW, v = tap % D::TW;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            int ii = rh[i] - u, jj = rw[i] - v;
+            bool ok = rn[i] >= 0 && ii >= 0 && ii < D::OH && jj >= 0 && jj < D::OW;
+            ra[i] = ok ? ld4(A.dy + ((long)(rn[i] * D::OH + ii) * D::OW + jj) * D::CO + o0 + kq)
+                       : v4f{0, 0, 0, 0};
+        }
+        const int p = ca + D::S * u, q = cb + D::S * v;
+#pragma unroll
+        for (int i = 0; i < NBL; ++i) {
+            int o = o0 + br + i * BROWS;
+            rb[i] = ld4(A.w + ((long)(o * D::KH + p) * D::KW + q) * D::CI + n0 + bc);
+        }
+    };
+    auto sstore = [&]() {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<v4f *>(&As[(lr + i * (T / 8)) * LDK + kq]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < NBL; ++i) *reinterpret_cast<v4f *>(&Bs[(br + i * BROWS) * LDB + bc]) = rb[i];
+    };
+
+    const int wm = wave % (BM / 32), wn = wave / (BM / 32);
+    const int li = lane & 31, h = lane >> 5;
+    const float *ap = &As[(wm * 32 + li) * LDK + 4 * h];
+    const float *bp = &Bs[(4 * h) * LDB + wn * 32 + li];
+    v16f acc = {0};
+
+    gload(0);
+    sstore();
+    __syncthreads();
+    for (int k0 = 0; k0 < D::K; k0 += BK) {
+        const bool more = k0 + BK < D::K;
+        if (more) gload(k0 + BK);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 8) {
+            v4f a = ld4(ap + kk);
+            acc = mfma(a.x, bp[(kk + 0) * LDB], acc);
+            acc = mfma(a.y, bp[(kk + 1) * LDB], acc);
+            acc = mfma(a.z, bp[(kk + 2) * LDB], acc);
+            acc = mfma(a.w, bp[(kk + 3) * LDB], acc);
+        }
+        __syncthreads();
+        if (more) {
+            sstore();
+            __syncthreads();
+        }
+    }
+
+    const int col = n0 + wn * 32 + li;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int m = m0 + wm * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+        if (m < Mc) {
+            int n = m / D::PP, rr = m % D::PP;
+            int hh = D::S * (rr / D::WP) + ca, ww = D::S * (rr % D::WP) + cb;
+            long off = ((long)(n * D::H + hh) * D::W + ww) * D::CI + col;
+            A.dx[off] = A.xact[off] > 0.f ? acc[r] : 0.f;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Weight gradient: dW[o][k] = sum_m dY[m][o] * A(m,k), db[o] = sum_m dY[m][o].
+// The reduction runs over all output positions of all samples; it is cut into
+// blockIdx.z splits of consecutive rows, each writing its own partial result
+// ([W..., b...] per split), which the optimizer kernel adds up in a fixed order
+// (no floating-point atomics, so results are reproducible).
+// ---------------------------------------------------------------------------
+struct WgradArgs {
+    const float *dy;   // [B*P][N]
+    const void *x;     // layer input (uint8 for conv1)
+    float *part;       // [splits][N*K + N]
+    int B;
+    int rps;           // reduction rows (output positions) per split, a multiple of 32
+    long xs;           // elements between consecutive samples of x
+    long part_stride;  // elements between consecutive splits
+    float scale;       // multiplies dW (1/255 for conv1)
+};
+
+template <class G, int BMO, int BNK>
+__global__ __launch_bounds__((BMO / 32) * (BNK / 32) * 64) void k_wgrad(WgradArgs A)
+{
+    constexpr int T = (BMO / 32) * (BNK / 32) * 64;
+    constexpr int LDY = BMO + 4, LDX = BNK + 4;
+    constexpr int YR = T / (BMO / 4), XR = T / (BNK / 4);  // tile rows filled per pass
+    constexpr int NY = (BK + YR - 1) / YR, NX = (BK + XR - 1) / XR;
+    using in_t = typename G::in_t;
+    __shared__ __attribute__((aligned(16))) float Ys[BK * LDY];
+    __shared__ __attribute__((aligned(16))) float Xs[BK * LDX];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int kc0 = blockIdx.x * BNK, o0 = blockIdx.y * BMO;
+    const int mbeg = blockIdx.z * A.rps;
+    const int mend = min(mbeg + A.rps, A.B * G::P);
+    const in_t *x = static_cast<const in_t *>(A.x);
+
+    const int yr = tid / (BMO / 4), yc = (tid % (BMO / 4)) * 4;
+    const int xr = tid / (BNK / 4), xc = (tid % (BNK / 4)) * 4;
+    const int xko = G::k_off(kc0 + xc);
+    v4f ry[NY], rx[NX];
+    auto gload = [&](int mb) {
+#pragma unroll
+        for (int i = 0; i < NY; ++i) {
+            int r = yr + i * YR, m = mb + r;
+            ry[i] = (r < BK && m < mend) ? ld4(A.dy + (long)m * G::N + o0 + yc) : v4f{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            int r = xr + i * XR, m = mb + r;
+            rx[i] = (r < BK && m < mend) ? ld4(x + G::row_off(m, A.xs) + xko) : v4f{0, 0, 0, 0};
+        }
+    };
+    auto sstore = [&]() {
+#pragma unroll
+        for (int i = 0; i < NY; ++i) {
+            int r = yr + i * YR;
+            if (r < BK) *reinterpret_cast<v4f *>(&Ys[r * LDY + yc]) = ry[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            int r = xr + i * XR;
+            if (r < BK) *reinterpret_cast<v4f *>(&Xs[r * LDX + xc]) = rx[i];
+        }
+    };
+
+    const int wo = wave % (BMO / 32), wk = wave / (BMO / 32);
+    const int li = lane & 31, h = lane >> 5;
+    const float *yp = &Ys[(4 * h) * LDY + wo * 32 + li];
+    const float *xp = &Xs[(4 * h) * LDX + wk * 32 + li];
+    const bool do_bias = blockIdx.x == 0 && wk == 0;
+    v16f acc = {0}, accb = {0};
+
+    if (mbeg < mend) {
+        gload(mbeg);
+        sstore();
+    }
+    __syncthreads();
+    for (int mb = mbeg; mb < mend; mb += BK) {
+        const bool more = mb + BK < mend;
+        if (more) gload(mb + BK);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 8) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float a = yp[(kk + t) * LDY], b = xp[(kk + t) * LDX];
+                acc = mfma(a, b, acc);
+                if (do_bias) accb = mfma(a, 1.0f, accb);
+            }
+        }
+        __syncthreads();
+        if (more) {
+            sstore();
+            __syncthreads();
+        }
+    }
+
+    float *part = A.part + (long)blockIdx.z * A.part_stride;
+    const int col = kc0 + wk * 32 + li;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int o = o0 + wo * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+        part[(long)o * G::K + col] = acc[r] * A.scale;
+        if (do_bias && li == 0) part[(long)G::N * G::K + o] = accb[r];
+    }
+}
+
+}  // namespace g32

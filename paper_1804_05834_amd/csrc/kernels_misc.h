@@ -1,0 +1,507 @@
+// Everything around the GEMMs: the head (dueling combine, argmax, Bellman
+// target, Huber loss and their gradients), RMSProp, the sum-tree, the
+// frame-stack gather, epsilon-greedy selection and layout permutations.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+
+#include "net.h"
+
+namespace misc {
+
+// ----------------------------------------------------------------- draws
+// 64-bit counter mixer (SplitMix64 output function on seed + (ctr+1)*gamma);
+// a uniform in [0,1) is its top 24 bits times 2^-24.
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t seed, uint64_t ctr)
+{
+    uint64_t z = seed + (ctr + 1ull) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__host__ __device__ __forceinline__ float draw_u24(uint64_t seed, uint64_t ctr)
+{
+    return (float)(mix64(seed, ctr) >> 40) * (1.0f / 16777216.0f);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ------------------------------------------------------------------ head
+// Rows of the head: dueling -> row 0 is the state value V, rows 1..K the
+// advantages (Eq.13); plain -> rows 0..K-1 are the Q outputs.  Offsets are
+// relative to the head section of the parameter blob.
+__device__ __forceinline__ int head_w_off(int r, int K, int dueling)
+{
+    if (!dueling) return r * net::HID;
+    return r == 0 ? 0 : net::HID + 1 + (r - 1) * net::HID;
+}
+__device__ __forceinline__ int head_b_off(int r, int K, int dueling)
+{
+    if (!dueling) return K * net::HID + r;
+    return r == 0 ? net::HID : net::HID + 1 + K * net::HID + (r - 1);
+}
+
+constexpr int MAXR = 65;  // up to 64 actions + V
+
+// hidden[i] = relu(bias[i] + sum over reduction splits of the fc1 partial sums)
+__device__ __forceinline__ float hidden_unit(const float *part, int nsplit, long split_stride,
+                                             long row, int i, const float *bias)
+{
+    float acc = 0.f;
+    for (int s = 0; s < nsplit; ++s) acc += part[s * split_stride + row * net::HID + i];
+    return fmaxf(acc + bias[i], 0.f);
+}
+
+// raw[r] = b[r] + <W[r], hid>, one wave per row in turn
+__device__ __forceinline__ void head_rows(const float *hid /*LDS*/, const float *head, int K,
+                                          int dueling, float *raw /*LDS*/, int tid, int nthreads)
+{
+    const int R = K + (dueling ? 1 : 0);
+    const int wave = tid >> 6, lane = tid & 63, nw = nthreads >> 6;
+    for (int r = wave; r < R; r += nw) {
+        const float *w = head + head_w_off(r, K, dueling);
+        float acc = 0.f;
+        for (int i = lane; i < net::HID; i += 64) acc += w[i] * hid[i];
+        acc = wave_sum(acc);
+        if (lane == 0) raw[r] = acc + head[head_b_off(r, K, dueling)];
+    }
+}
+
+// Q_a = V + (A_a - mean A) (Eq.13) or the raw outputs; serial, K <= 64
+__device__ __forceinline__ void combine_q(const float *raw, int K, int dueling, float *q)
+{
+    if (dueling) {
+        float mean = 0.f;
+        for (int a = 0; a < K; ++a) mean += raw[1 + a];
+        mean /= (float)K;
+        for (int a = 0; a < K; ++a) q[a] = raw[0] + (raw[1 + a] - mean);
+    } else {
+        for (int a = 0; a < K; ++a) q[a] = raw[a];
+    }
+}
+__device__ __forceinline__ int argmax_low(const float *q, int K)
+{
+    int best = 0;
+    for (int a = 1; a < K; ++a)
+        if (q[a] > q[best]) best = a;
+    return best;
+}
+
+struct HeadArgs {
+    const float *part;  // fc1 partial sums [nsplit][3B][512]: rows s | s' online | s' target
+    int nsplit;
+    long split_stride;
+    int B, K, dueling, double_q, loss_kind;
+    float kappa, gamma;
+    const float *f1b_on, *f1b_tg;    // fc1 biases
+    const float *head_on, *head_tg;  // head sections of the two parameter blobs
+    const int32_t *a;
+    const float *r;
+    const uint8_t *done;
+    const float *w;  // may be nullptr
+    float *h_s;      // [B][512] hidden layer of the online net on s
+    float *dh;       // [B][512] gradient w.r.t. the fc1 pre-activation
+    float *dA;       // [B][R]   gradient w.r.t. the head rows
+    float *td_abs;   // [B]
+    float *loss_j;   // [B] w_j * l(td_j)
+    float *q_s, *q_no, *q_nt, *y, *td;  // optional outputs
+    int32_t *a_star;
+    float *is_w;
+};
+
+// One workgroup per minibatch row: finishes fc1 (split reduction, bias, ReLU)
+// for the three passes, evaluates the head three times, forms the target
+// (Eq.8 / Eq.9), the TD error, the loss term and the gradient w.r.t. the
+// head rows, and back-propagates through the head into the hidden layer.
+__global__ __launch_bounds__(256) void k_head_train(HeadArgs A)
+{
+    __shared__ float hid[3][net::HID];
+    __shared__ float raw[3][MAXR];
+    __shared__ float q[3][64];
+    __shared__ float dA[MAXR];
+    const int j = blockIdx.x, tid = threadIdx.x;
+    const int K = A.K, R = K + (A.dueling ? 1 : 0);
+
+    for (int i = tid; i < net::HID; i += 256) {
+        float hs = hidden_unit(A.part, A.nsplit, A.split_stride, j, i, A.f1b_on);
+        hid[0][i] = hs;
+        hid[1][i] = hidden_unit(A.part, A.nsplit, A.split_stride, (long)A.B + j, i, A.f1b_on);
+        hid[2][i] = hidden_unit(A.part, A.nsplit, A.split_stride, 2L * A.B + j, i, A.f1b_tg);
+        A.h_s[(long)j * net::HID + i] = hs;
+    }
+    __syncthreads();
+    head_rows(hid[0], A.head_on, K, A.dueling, raw[0], tid, 256);
+    head_rows(hid[1], A.head_on, K, A.dueling, raw[1], tid, 256);
+    head_rows(hid[2], A.head_tg, K, A.dueling, raw[2], tid, 256);
+    __syncthreads();
+    if (tid < 3) combine_q(raw[tid], K, A.dueling, q[tid]);
+    __syncthreads();
+    if (tid == 0) {
+        const int aj = A.a[j];
+        const int as = argmax_low(A.double_q ? q[1] : q[2], K);
+        const float boot = A.done[j] ? 0.f : A.gamma * q[2][as];
+        const float y = A.r[j] + boot;
+        const float d = y - q[0][aj];
+        const float w = A.w ? A.w[j] : 1.f;
+        float l, dl;
+        if (A.loss_kind == 1 && fabsf(d) > A.kappa) {
+            l = A.kappa * (fabsf(d) - 0.5f * A.kappa);
+            dl = d > 0.f ? A.kappa : -A.kappa;
+        } else {
+            l = 0.5f * d * d;
+            dl = d;
+        }
+        const float g = -w * dl / (float)A.B;  // dL/dQ(s_j, a_j)
+        if (A.dueling) {
+            dA[0] = g;
+            for (int a = 0; a < K; ++a) dA[1 + a] = (a == aj ? g : 0.f) - g / (float)K;
+        } else {
+            for (int a = 0; a < K; ++a) dA[a] = a == aj ? g : 0.f;
+        }
+        A.td_abs[j] = fabsf(d);
+        A.loss_j[j] = w * l;
+        if (A.y) A.y[j] = y;
+        if (A.td) A.td[j] = d;
+        if (A.a_star) A.a_star[j] = as;
+        if (A.is_w) A.is_w[j] = w;
+    }
+    if (A.q_s && tid >= 64 && tid < 64 + K) A.q_s[(long)j * K + tid - 64] = q[0][tid - 64];
+    if (A.q_no && tid >= 128 && tid < 128 + K) A.q_no[(long)j * K + tid - 128] = q[1][tid - 128];
+    if (A.q_nt && tid >= 192 && tid < 192 + K) A.q_nt[(long)j * K + tid - 192] = q[2][tid - 192];
+    __syncthreads();
+    if (tid < R) A.dA[(long)j * R + tid] = dA[tid];
+    for (int i = tid; i < net::HID; i += 256) {
+        float acc = 0.f;
+        for (int r = 0; r < R; ++r) acc += dA[r] * A.head_on[head_w_off(r, K, A.dueling) + i];
+        A.dh[(long)j * net::HID + i] = hid[0][i] > 0.f ? acc : 0.f;
+    }
+}
+
+struct HeadWgradArgs {
+    const float *dA;      // [B][R]
+    const float *h_s;     // [B][512]
+    const float *loss_j;  // [B]
+    float *ghead;         // head section of the gradient partial buffer
+    float *loss_out;      // optional
+    float *loss_slot;     // always written
+    int B, K, dueling;
+};
+
+// Head weight gradient: dW[r][i] = sum_j dA[j][r] h[j][i], db[r] = sum_j dA[j][r];
+// block 0 also folds the per-row loss terms into L = (1/B) sum_j w_j l_j.
+__global__ __launch_bounds__(512) void k_head_wgrad(HeadWgradArgs A)
+{
+    const int r = blockIdx.x, i = threadIdx.x;
+    const int R = A.K + (A.dueling ? 1 : 0);
+    float acc = 0.f, accb = 0.f;
+    for (int j = 0; j < A.B; ++j) {
+        float d = A.dA[(long)j * R + r];
+        acc += d * A.h_s[(long)j * net::HID + i];
+        accb += d;
+    }
+    A.ghead[head_w_off(r, A.K, A.dueling) + i] = acc;
+    if (i == 0) A.ghead[head_b_off(r, A.K, A.dueling)] = accb;
+    if (r == 0 && i == 0) {
+        float s = 0.f;
+        for (int j = 0; j < A.B; ++j) s += A.loss_j[j];
+        s /= (float)A.B;
+        *A.loss_slot = s;
+        if (A.loss_out) *A.loss_out = s;
+    }
+}
+
+struct HeadActArgs {
+    const float *part;
+    int nsplit;
+    long split_stride;
+    int E, K, dueling;
+    const float *f1b, *head;
+    float epsilon;
+    uint64_t seed;
+    int32_t *actions;
+    float *q_out;  // optional [E][K]
+};
+
+// Acting (Alg.1 action lines): finish fc1, evaluate the head, pick the action.
+__global__ __launch_bounds__(256) void k_head_act(HeadActArgs A)
+{
+    __shared__ float hid[net::HID];
+    __shared__ float raw[MAXR];
+    __shared__ float q[64];
+    const int e = blockIdx.x, tid = threadIdx.x;
+    for (int i = tid; i < net::HID; i += 256)
+        hid[i] = hidden_unit(A.part, A.nsplit, A.split_stride, e, i, A.f1b);
+    __syncthreads();
+    head_rows(hid, A.head, A.K, A.dueling, raw, tid, 256);
+    __syncthreads();
+    if (tid == 0) {
+        combine_q(raw, A.K, A.dueling, q);
+        int act;
+        float u = draw_u24(A.seed, 2ull * (uint64_t)e);
+        if (u < A.epsilon) {
+            float u2 = draw_u24(A.seed, 2ull * (uint64_t)e + 1ull);
+            act = min((int)floorf(u2 * (float)A.K), A.K - 1);
+        } else {
+            act = argmax_low(q, A.K);
+        }
+        A.actions[e] = act;
+    }
+    __syncthreads();
+    if (A.q_out && tid < A.K) A.q_out[(long)e * A.K + tid] = q[tid];
+}
+
+// --------------------------------------------------------------- RMSProp
+// g = sum of the reduction splits (fixed order); v <- rho v + (1-rho) g^2;
+// theta <- theta - lr g / sqrt(v + eps)   [centered: sqrt(v - m^2 + eps)].
+struct RmsSeg {
+    long begin, count;  // range of the blob
+    const float *part;  // [nsplit][count]
+    int nsplit;
+    long stride;
+};
+struct RmsArgs {
+    RmsSeg seg[5];
+    float *theta, *v, *m, *g;
+    __hip_bfloat16 *shadow;  // bf16 copy of theta (same order) or nullptr
+    float lr, rho, eps;
+    long n;
+};
+
+__global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
+{
+    long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= A.n) return;
+    int s = 0;
+#pragma unroll
+    for (int t = 1; t < 5; ++t)
+        if (i >= A.seg[t].begin) s = t;
+    RmsSeg S = A.seg[0];
+    if (s == 1) S = A.seg[1];
+    if (s == 2) S = A.seg[2];
+    if (s == 3) S = A.seg[3];
+    if (s == 4) S = A.seg[4];
+    const long o = i - S.begin;
+    float g = 0.f;
+    for (int t = 0; t < S.nsplit; ++t) g += S.part[t * S.stride + o];
+    float v = A.rho * A.v[i] + (1.f - A.rho) * g * g;
+    float denom;
+    if (A.m) {
+        float m = A.rho * A.m[i] + (1.f - A.rho) * g;
+        A.m[i] = m;
+        denom = sqrtf(v - m * m + A.eps);
+    } else {
+        denom = sqrtf(v + A.eps);
+    }
+    float th = A.theta[i] - A.lr * g / denom;
+    A.v[i] = v;
+    A.theta[i] = th;
+    A.g[i] = g;
+    if (A.shadow) A.shadow[i] = __float2bfloat16(th);
+}
+
+// fp32 -> bf16 copy (round to nearest even)
+__global__ void k_to_bf16(const float *src, __hip_bfloat16 *dst, long n)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = __float2bfloat16(src[i]);
+}
+
+// ------------------------------------------------- layout permutations
+// canonical blob <-> internal blob (see net.h).  dir 0: dst(internal) from
+// src(canonical); dir 1: dst(canonical) from src(internal).
+__global__ void k_permute(const float *src, float *dst, long n, int dir)
+{
+    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;  // canonical index
+    if (e >= n) return;
+    long in = e;
+    if (e >= net::C2W && e < net::C2B) {  // [o][c][p][q] -> [o][p][q][c]
+        long t = e - net::C2W;
+        int q = t % 4, p = (t / 4) % 4, c = (t / 16) % 32, o = t / 512;
+        in = net::C2W + ((o * 4 + p) * 4 + q) * 32 + c;
+    } else if (e >= net::C3W && e < net::C3B) {
+        long t = e - net::C3W;
+        int q = t % 3, p = (t / 3) % 3, c = (t / 9) % 64, o = t / 576;
+        in = net::C3W + ((o * 3 + p) * 3 + q) * 64 + c;
+    } else if (e >= net::F1W && e < net::F1B) {  // [o][c*49 + hw] -> [o][hw*64 + c]
+        long t = e - net::F1W;
+        int k = t % 3136, o = t / 3136;
+        int c = k / 49, hw = k % 49;
+        in = net::F1W + (long)o * 3136 + hw * 64 + c;
+    }
+    if (dir == 0) dst[in] = src[e];
+    else dst[e] = src[in];
+}
+
+__global__ void k_fill(float *p, float v, long n)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ------------------------------------------------------------- sum-tree
+// Heap layout: tree[1] root, children of i at 2i and 2i+1, leaves at
+// tree[L..2L); tree[2L] holds the running maximum priority.
+__global__ void k_tree_leaves(float *tree, long L, const float *p, long n, float alpha)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= L) return;
+    tree[L + i] = i < n ? (float)pow((double)p[i], (double)alpha) : 0.f;
+    if (i == 0) tree[0] = 0.f;
+}
+__global__ void k_tree_level(float *tree, long first, long count)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    long node = first + i;
+    tree[node] = tree[2 * node] + tree[2 * node + 1];
+}
+
+__device__ __forceinline__ float block_max_1024(float v, float *sh /*16*/)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float r = sh[0];
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r = fmaxf(r, sh[w]);
+    return r;
+}
+
+// Proportional sampling (Eq.10, Eq.12): one thread per draw, single workgroup.
+__global__ __launch_bounds__(1024) void k_per_sample(const float *tree, long L, long size, int B,
+                                                     float beta, uint64_t seed, int stratified,
+                                                     int32_t *idx, float *is_w)
+{
+    __shared__ float sh[16];
+    const int j = threadIdx.x;
+    const float total = tree[1];
+    float wr = 0.f;
+    long slot = 0;
+    if (j < B) {
+        const float u = draw_u24(seed, (uint64_t)j);
+        float z = stratified ? __fmul_rn((float)j + u, total / (float)B) : __fmul_rn(u, total);
+        long node = 1;
+        while (node < L) {
+            float left = tree[2 * node];
+            if (z < left) {
+                node = 2 * node;
+            } else {
+                z = z - left;
+                node = 2 * node + 1;
+            }
+        }
+        slot = node - L;
+        if (slot > size - 1) slot = size - 1;
+        double P = (double)tree[L + slot] / (double)total;
+        wr = (float)pow((double)size * P, -(double)beta);
+    }
+    const float wmax = block_max_1024(wr, sh);
+    if (j < B) {
+        idx[j] = (int32_t)slot;
+        is_w[j] = wr / wmax;
+    }
+}
+
+// Priority update (Eq.11): single workgroup, one thread per entry; the tree is
+// repaired level by level with a barrier between levels, so no atomics.
+__global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int levels, long size,
+                                                     const int32_t *idx, const float *td_abs, int n,
+                                                     float alpha, float eps)
+{
+    __shared__ int sidx[1024];
+    __shared__ float sh[16];
+    const int j = threadIdx.x;
+    int my = -1;
+    float p = 0.f;
+    if (j < n) {
+        int v = idx[j];
+        if (v >= 0 && v < size) my = v;
+        p = (float)((double)fabsf(td_abs[j]) + (double)eps);
+    }
+    sidx[j] = my;
+    __syncthreads();
+    const bool valid = my >= 0;
+    bool writer = valid;
+    if (valid)
+        for (int t = j + 1; t < n; ++t)
+            if (sidx[t] == my) { writer = false; break; }
+    if (writer) tree[L + my] = (float)pow((double)p, (double)alpha);
+    const float pmax = block_max_1024(valid ? p : 0.f, sh);
+    if (j == 0) tree[2 * L] = fmaxf(tree[2 * L], pmax);
+    long node = L + (valid ? my : 0);
+    __syncthreads();
+    for (int l = 0; l < levels; ++l) {
+        node >>= 1;
+        if (valid) tree[node] = tree[2 * node] + tree[2 * node + 1];
+        __syncthreads();
+    }
+}
+
+// --------------------------------------------------------------- replay
+struct GatherArgs {
+    const uint8_t *frames;  // ring [cap][7056]
+    const int32_t *meta_a;
+    const float *meta_r;
+    const uint8_t *meta_done;
+    long cap;
+    const int32_t *idx;  // [n]
+    uint8_t *stack5;     // [n][5][7056] or nullptr
+    uint8_t *s, *s_next; // [n][4][7056] or nullptr
+    int32_t *a;
+    float *r;
+    uint8_t *done;
+};
+
+// Frame-stack gather: transition i reads ring slots i-3 .. i+1 (mod cap);
+// grid (n, 5), 16 bytes per thread per trip.
+__global__ __launch_bounds__(256) void k_gather(GatherArgs A)
+{
+    const int j = blockIdx.x, k = blockIdx.y;
+    long i = A.idx[j];
+    i = i < 0 ? 0 : (i >= A.cap ? A.cap - 1 : i);  // keeps every access inside the ring
+    long slot = (i - 3 + k) % A.cap;
+    if (slot < 0) slot += A.cap;
+    const uint4 *src = reinterpret_cast<const uint4 *>(A.frames + slot * net::FRAME);
+    uint4 *d0 = A.stack5 ? reinterpret_cast<uint4 *>(A.stack5 + ((long)j * 5 + k) * net::FRAME) : nullptr;
+    uint4 *d1 = (A.s && k < 4) ? reinterpret_cast<uint4 *>(A.s + ((long)j * 4 + k) * net::FRAME) : nullptr;
+    uint4 *d2 = (A.s_next && k > 0) ? reinterpret_cast<uint4 *>(A.s_next + ((long)j * 4 + k - 1) * net::FRAME) : nullptr;
+    for (int t = threadIdx.x; t < net::FRAME / 16; t += 256) {
+        uint4 v = src[t];
+        if (d0) d0[t] = v;
+        if (d1) d1[t] = v;
+        if (d2) d2[t] = v;
+    }
+    if (k == 0 && threadIdx.x == 0) {
+        if (A.a) A.a[j] = A.meta_a[i];
+        if (A.r) A.r[j] = A.meta_r[i];
+        if (A.done) A.done[j] = A.meta_done[i];
+    }
+}
+
+// Ring store: n frames into slots slot0.. (mod cap); grid (n).
+__global__ __launch_bounds__(256) void k_replay_write(uint8_t *frames, int32_t *meta_a, float *meta_r,
+                                                      uint8_t *meta_done, long cap, long slot0,
+                                                      const uint8_t *src, const int32_t *a,
+                                                      const float *r, const uint8_t *done)
+{
+    const long j = blockIdx.x;
+    const long slot = (slot0 + j) % cap;
+    const uint4 *s = reinterpret_cast<const uint4 *>(src + j * net::FRAME);
+    uint4 *d = reinterpret_cast<uint4 *>(frames + slot * net::FRAME);
+    for (int t = threadIdx.x; t < net::FRAME / 16; t += 256) d[t] = s[t];
+    if (threadIdx.x == 0) {
+        if (a) meta_a[slot] = a[j];
+        if (r) meta_r[slot] = r[j];
+        if (done) meta_done[slot] = done[j];
+    }
+}
+
+}  // namespace misc

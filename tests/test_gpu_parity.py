@@ -1,0 +1,321 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Tolerance (fp32 path): per tensor X, max|X_gpu - X_ref| / max|X_ref| <= 1e-4, applied to the
+Q-values, targets, TD errors, loss, gradients, the parameter step and the optimizer state.
+Integer results (argmax actions, sampled indices, tree nodes) are compared bit-exactly, except
+where the oracle's own top-2 gap or distance to a bucket boundary is inside that tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_1804_05834_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def dq():
+    from paper_1804_05834_amd import dqn
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    dqn.lib()
+    return dqn
+
+
+def relerr(x, ref):
+    x = np.asarray(x, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    assert x.shape == ref.shape, (x.shape, ref.shape)
+    return float(np.abs(x - ref).max() / max(np.abs(ref).max(), 1e-12))
+
+
+def check_argmax(a_gpu, q_ref, tol=TOL):
+    a_ref = q_ref.argmax(axis=1)
+    bad = np.flatnonzero(a_gpu != a_ref)
+    for j in bad:
+        top2 = np.sort(q_ref[j])[-2:]
+        assert top2[1] - top2[0] <= tol * np.abs(q_ref[j]).max(), (j, a_gpu[j], a_ref[j], q_ref[j])
+
+
+def dev(t):
+    return t.cuda() if isinstance(t, torch.Tensor) else torch.from_numpy(np.ascontiguousarray(t)).cuda()
+
+
+# ------------------------------------------------------------------ parameters
+@pytest.mark.parametrize("K,dueling", [(4, 0), (18, 1)])
+def test_init_and_param_roundtrip(dq, K, dueling):
+    print("case init/roundtrip", K, dueling, flush=True)
+    m = dq.Dqn(dq.make_config(num_actions=K, dueling=dueling, seed=1804, target_seed=5834))
+    assert np.array_equal(m.get_params(0).cpu().numpy(), synth.he_uniform_params(1804, K, dueling))
+    assert np.array_equal(m.get_params(1).cpu().numpy(), synth.he_uniform_params(5834, K, dueling))
+    assert float(m.get_params(3).abs().max()) == 0.0
+    p = synth.he_uniform_params(77, K, dueling, bias_scale=0.05)
+    m.set_params(0, torch.from_numpy(p))
+    assert np.array_equal(m.get_params(0).cpu().numpy(), p)
+    m.sync_target()
+    assert np.array_equal(m.get_params(1).cpu().numpy(), p)
+    m.close()
+
+
+# ------------------------------------------------------------------ acting / forward
+@pytest.mark.parametrize("K,dueling,E", [(4, 0, 37), (18, 1, 70), (1, 1, 3), (64, 0, 5)])
+def test_act_forward_parity(dq, orc, K, dueling, E):
+    print("case act", K, dueling, E, flush=True)
+    m = dq.Dqn(dq.make_config(num_actions=K, dueling=dueling, max_act_batch=128))
+    p = synth.he_uniform_params(3 + K, K, dueling, bias_scale=0.05)
+    m.set_params(0, torch.from_numpy(p))
+    obs = synth.states(31, E)
+    q_ref = orc.forward(p, K, dueling, obs.numpy())
+    a0, q = m.act(dev(obs), 0.0, 99, want_q=True)
+    assert relerr(q.cpu().numpy(), q_ref) <= TOL
+    check_argmax(a0.cpu().numpy(), q_ref)
+    # epsilon = 1: every action is the specified random draw
+    a1 = m.act(dev(obs), 1.0, 99).cpu().numpy()
+    ref1, _ = orc.act(p, K, dueling, obs.numpy(), 1.0, 99)
+    assert np.array_equal(a1, ref1)
+    # mixed: explore decisions follow the draw stream exactly; greedy ones follow argmax
+    a5 = m.act(dev(obs), 0.5, 1234).cpu().numpy()
+    ref5, _ = orc.act(p, K, dueling, obs.numpy(), 0.5, 1234)
+    explore = synth.u24(1234, 2 * torch.arange(E)).numpy() < 0.5
+    assert np.array_equal(a5[explore], ref5[explore])
+    check_argmax(a5[~explore], q_ref[~explore])
+    m.close()
+
+
+# ------------------------------------------------------------------ training step
+def _oracle_step(orc, cfgd, p, pt, batch_np, w):
+    cfg = orc.make_config(cfgd["num_actions"], cfgd["dueling"], cfgd["double_q"], cfgd["loss_kind"],
+                          lr=cfgd.get("lr", 2.5e-4), rms_centered=cfgd.get("rms_centered", 0))
+    theta = p.copy(); v = np.zeros_like(p)
+    mm = np.zeros_like(p) if cfgd.get("rms_centered", 0) else None
+    out = orc.train_step(cfg, theta, pt, v, *batch_np, w, rms_m=mm)
+    out["theta"] = theta; out["v"] = v; out["m"] = mm
+    return out
+
+
+def _check_step(orc, out, ref, p, m, K, dueling, tol=TOL):
+    g = {k: v.cpu().numpy() for k, v in out.items()}
+    errs = {}
+    for k in ("q_s", "q_next_online", "q_next_target", "y", "td"):
+        errs[k] = relerr(g[k], ref[k])
+    errs["loss"] = abs(float(g["loss"][0]) - ref["loss"]) / max(abs(ref["loss"]), 1e-12)
+    sel = ref["q_next_online"] if m.cfg.double_q else ref["q_next_target"]
+    check_argmax(g["a_star"], sel, tol)
+    grads = m.get_params(2).cpu().numpy()
+    theta = m.get_params(0).cpu().numpy()
+    v = m.get_params(3).cpu().numpy()
+    for name, (o, shp) in orc.param_slices(K, dueling).items():
+        n = int(np.prod(shp))
+        sl = slice(o, o + n)
+        errs["g:" + name] = relerr(grads[sl], ref["grads"][sl])
+        errs["dtheta:" + name] = relerr(theta[sl].astype(np.float64) - p[sl], ref["theta"][sl].astype(np.float64) - p[sl])
+        errs["v:" + name] = relerr(v[sl], ref["v"][sl])
+    errs["theta"] = relerr(theta, ref["theta"])
+    bad = {k: e for k, e in errs.items() if not e <= tol}
+    assert not bad, bad
+    return errs
+
+
+CONFIGS = {
+    # vanilla DQN, plain head, K=4 (first configuration)
+    "dqn": dict(num_actions=4, dueling=0, double_q=0, loss_kind=1),
+    # Double DQN + dueling head, K=18 (second configuration)
+    "dueling_ddqn": dict(num_actions=18, dueling=1, double_q=1, loss_kind=1),
+    # squared loss of Eq.7, and a centered RMSProp
+    "squared_centered": dict(num_actions=6, dueling=1, double_q=0, loss_kind=0, rms_centered=1),
+}
+
+
+@pytest.mark.parametrize("name,B", [("dqn", 32), ("dueling_ddqn", 32), ("dueling_ddqn", 5),
+                                    ("dueling_ddqn", 67), ("squared_centered", 33), ("dqn", 1)])
+def test_train_step_explicit_batch(dq, orc, name, B):
+    print("case train_step", name, B, flush=True)
+    cfgd = CONFIGS[name]
+    K, dueling = cfgd["num_actions"], cfgd["dueling"]
+    m = dq.Dqn(dq.make_config(max_batch=max(B, 32), seed=1804, target_seed=5834, **cfgd))
+    p = synth.he_uniform_params(1804, K, dueling, bias_scale=0.02)
+    pt = synth.he_uniform_params(5834, K, dueling, bias_scale=0.02)
+    m.set_params(0, torch.from_numpy(p)); m.set_params(1, torch.from_numpy(pt))
+    s, sn, a, r, d = synth.batch(11, B, K)
+    w = (0.25 + 0.75 * synth.u24(19, torch.arange(B))) if name != "dqn" else None
+    batch = tuple(dev(t) for t in (s, sn, a, r, d)) + ((dev(w),) if w is not None else ())
+    out = m.train_step(B, batch)
+    ref = _oracle_step(orc, cfgd, p, pt, (s.numpy(), sn.numpy(), a.numpy(), r.numpy(), d.numpy()),
+                       None if w is None else w.numpy())
+    errs = _check_step(orc, out, ref, p, m, K, dueling)
+    print("  worst:", max(errs.items(), key=lambda kv: kv[1]), flush=True)
+    if cfgd.get("rms_centered"):
+        assert relerr(m.get_params(4).cpu().numpy(), ref["m"]) <= TOL
+    # the target network is not touched by a step
+    assert np.array_equal(m.get_params(1).cpu().numpy(), pt)
+    m.close()
+
+
+def test_three_step_chain(dq, orc):
+    print("case chain", flush=True)
+    cfgd = CONFIGS["dueling_ddqn"]
+    K, dueling, B = 18, 1, 16
+    m = dq.Dqn(dq.make_config(max_batch=32, **cfgd))
+    p = synth.he_uniform_params(1804, K, dueling)
+    pt = synth.he_uniform_params(5834, K, dueling)
+    m.set_params(0, torch.from_numpy(p)); m.set_params(1, torch.from_numpy(pt))
+    cfg = orc.make_config(K, dueling, 1, 1)
+    theta = p.copy(); v = np.zeros_like(p)
+    for step in range(3):
+        s, sn, a, r, d = synth.batch(100 + 10 * step, B, K)
+        out = m.train_step(B, tuple(dev(t) for t in (s, sn, a, r, d)))
+        ref = orc.train_step(cfg, theta, pt, v, s.numpy(), sn.numpy(), a.numpy(), r.numpy(), d.numpy())
+        assert relerr(out["td"].cpu().numpy(), ref["td"]) <= 3 * TOL
+        assert abs(float(out["loss"][0]) - ref["loss"]) <= 3 * TOL * abs(ref["loss"])
+    assert relerr(m.get_params(0).cpu().numpy() - p.astype(np.float64), theta.astype(np.float64) - p) <= 3 * TOL
+    assert relerr(m.get_params(3).cpu().numpy(), v) <= 3 * TOL
+    m.close()
+
+
+# ------------------------------------------------------------------ prioritized replay
+def _fill_replay(m, cap, seed_frames=21, seed_meta=40, K=18, chunk=20000):
+    for s0 in range(0, cap, chunk):
+        n = min(chunk, cap - s0)
+        fr = synth.frames(seed_frames, torch.arange(s0, s0 + n, device="cuda"), device="cuda")
+        a = synth.actions(seed_meta, n, K, "cuda", first=s0)
+        r = synth.rewards(seed_meta + 1, n, "cuda", first=s0)
+        d = synth.dones(seed_meta + 2, n, 0.01, "cuda", first=s0)
+        m.replay_write(s0, fr, a, r, d)
+    torch.cuda.synchronize()
+
+
+def _check_indices(orc, idx_gpu, tree_ref, size, B, beta, seed, stratified=False):
+    idx_ref, w_ref, z = orc.per_sample(tree_ref, size, B, beta, seed, stratified)
+    bad = np.flatnonzero(idx_gpu != idx_ref)
+    if bad.size:
+        _, dist = orc.per_sample_cumsum(tree_ref, size, z)
+        assert np.all(dist[bad] <= TOL * tree_ref[1]), (bad, dist[bad])
+    return idx_ref, w_ref
+
+
+@pytest.mark.parametrize("cap,n,B,strat", [(1000, 1000, 32, 0), (1000, 613, 512, 0), (5000, 5000, 64, 1),
+                                           (37, 37, 1024, 0), (5, 1, 7, 0)])
+def test_tree_fill_sample_update(dq, orc, cap, n, B, strat):
+    print("case tree", cap, n, B, strat, flush=True)
+    alpha, eps = np.float32(0.6), np.float32(1e-6)
+    m = dq.Dqn(dq.make_config(replay_capacity=cap, per_stratified=strat, max_batch=32))
+    p = synth.exp_priorities(9, n)
+    m.per_fill(dev(p))
+    L = m.L
+    tree_ref = orc.tree_build(p.numpy(), L, float(alpha))
+    assert np.array_equal(m.tree.cpu().numpy()[1:], tree_ref[1:])           # every node, bit for bit
+    idx, w = m.per_sample(B, 0.4, 4242)
+    idx = idx.cpu().numpy(); w = w.cpu().numpy()
+    idx_ref, w_ref = _check_indices(orc, idx, tree_ref, n, B, 0.4, 4242, bool(strat))
+    same = idx == idx_ref
+    assert same.mean() > 0.99
+    assert relerr(w[same], w_ref[same]) <= TOL and idx.min() >= 0 and idx.max() < n
+    # priority update with repeated indices (last one wins) and an out-of-range entry (skipped)
+    nu = min(B, 40)
+    uidx = idx[:nu].copy()
+    if nu > 3:
+        uidx[3] = uidx[0]
+    td = (synth.u24(5, torch.arange(nu)) * 3).numpy()
+    m.per_update(dev(uidx.astype(np.int32)), dev(td.astype(np.float32)))
+    mp = orc.per_update(tree_ref, n, uidx.astype(np.int32), td.astype(np.float32), float(alpha), float(eps), 1.0)
+    assert np.array_equal(m.tree.cpu().numpy()[1:], tree_ref[1:])
+    assert float(m.max_priority) == np.float32(mp)
+    m.close()
+
+
+def test_replay_gather(dq, orc):
+    print("case gather", flush=True)
+    cap, K = 300, 18
+    m = dq.Dqn(dq.make_config(replay_capacity=cap, max_batch=64))
+    _fill_replay(m, cap, K=K)
+    idx = np.array([0, 1, 2, 3, 150, 298, 299, 77], np.int32)
+    s, sn, a, r, d = m.replay_gather(dev(idx))
+    fr = synth.frames(21, torch.arange(cap)).numpy()
+    s_ref, sn_ref = orc.gather(fr, idx)
+    assert np.array_equal(s.cpu().numpy(), s_ref) and np.array_equal(sn.cpu().numpy(), sn_ref)
+    assert np.array_equal(a.cpu().numpy(), synth.actions(40, cap, K).numpy()[idx])
+    assert np.array_equal(r.cpu().numpy(), synth.rewards(41, cap).numpy()[idx])
+    assert np.array_equal(d.cpu().numpy(), synth.dones(42, cap).numpy()[idx])
+    m.close()
+
+
+def _replay_step_case(dq, orc, cap, B):
+    """Third configuration: PER sample + gather + dueling Double-DQN step + priority update."""
+    K, dueling = 18, 1
+    cfgd = CONFIGS["dueling_ddqn"]
+    m = dq.Dqn(dq.make_config(replay_capacity=cap, max_batch=B, **cfgd))
+    p = synth.he_uniform_params(1804, K, dueling)
+    pt = synth.he_uniform_params(5834, K, dueling)
+    m.set_params(0, torch.from_numpy(p)); m.set_params(1, torch.from_numpy(pt))
+    _fill_replay(m, cap, K=K)
+    pri = synth.exp_priorities(9, cap, "cuda")
+    m.per_fill(pri)
+    tree_ref = orc.tree_build(pri.cpu().numpy(), m.L, float(np.float32(0.6)))
+    out = m.train_step(B, None, beta=0.4, draw_seed=7)
+    idx = out["idx"].cpu().numpy()
+    idx_ref, w_ref = _check_indices(orc, idx, tree_ref, cap, B, 0.4, 7)
+    assert np.array_equal(idx, idx_ref), "a draw fell on a bucket boundary; pick another draw_seed"
+    assert relerr(out["is_w"].cpu().numpy(), w_ref) <= TOL
+    # the oracle regenerates only the frames it needs
+    slots = (idx_ref[:, None].astype(np.int64) - 3 + np.arange(5)[None, :]) % cap
+    fr = synth.frames(21, torch.from_numpy(slots.reshape(-1))).numpy().reshape(B, 5, 84, 84)
+    s, sn = fr[:, :4], fr[:, 1:]
+    ii = torch.from_numpy(idx_ref.astype(np.int64))
+    a = synth.u24(40, ii); a = torch.clamp((a * K).floor().to(torch.int32), max=K - 1).numpy()
+    r = (torch.clamp((synth.u24(41, ii) * 3).floor(), max=2.0) - 1.0).numpy()
+    d = (synth.u24(42, ii) < 0.01).to(torch.uint8).numpy()
+    ref = _oracle_step(orc, cfgd, p, pt, (np.ascontiguousarray(s), np.ascontiguousarray(sn), a, r, d), w_ref)
+    errs = _check_step(orc, out, ref, p, m, K, dueling)
+    # priorities written back from |td|
+    td_abs = np.abs(out["td"].cpu().numpy()).astype(np.float32)
+    orc.per_update(tree_ref, cap, idx_ref, td_abs, float(np.float32(0.6)), float(np.float32(1e-6)), 1.0)
+    tree_gpu = m.tree.cpu().numpy()
+    leaves_same = tree_gpu[m.L + idx_ref] == tree_ref[m.L + idx_ref]
+    # |td| itself carries the fp32 tolerance, so leaves agree to that tolerance and the rest of
+    # the tree must be consistent with its own leaves bit for bit
+    assert relerr(tree_gpu[m.L + idx_ref], tree_ref[m.L + idx_ref]) <= TOL, leaves_same.mean()
+    lv = tree_gpu[m.L:2 * m.L].copy()
+    chk = orc.tree_build(np.ones(0, np.float32), m.L, 1.0)
+    chk[m.L:] = lv
+    for i in range(m.L - 1, 0, -1):
+        chk[i] = chk[2 * i] + chk[2 * i + 1]
+    assert np.array_equal(tree_gpu[1:], chk[1:])
+    m.close()
+    return errs
+
+
+def test_replay_train_step_small_ring(dq, orc):
+    print("case replay step small", flush=True)
+    _replay_step_case(dq, orc, cap=4096, B=32)
+
+
+# ------------------------------------------------------------------ error paths
+def test_error_paths_on_device(dq):
+    print("case errors", flush=True)
+    m = dq.Dqn(dq.make_config(replay_capacity=100, max_batch=8, max_act_batch=8))
+    with pytest.raises(dq.DqnError) as e:
+        m.per_sample(4, 0.4, 1)                      # nothing stored yet
+    assert e.value.code == dq.ERR_STATE
+    with pytest.raises(dq.DqnError) as e:
+        m.train_step(4, None)
+    assert e.value.code == dq.ERR_STATE
+    with pytest.raises(dq.DqnError) as e:
+        m.train_step(9, tuple(dev(t) for t in synth.batch(1, 9, 18)))
+    assert e.value.code == dq.ERR_INVALID_ARG
+    with pytest.raises(dq.DqnError) as e:
+        m.act(dev(synth.states(1, 9)), 0.0, 1)
+    assert e.value.code == dq.ERR_INVALID_ARG
+    with pytest.raises(dq.DqnError) as e:
+        m.act(dev(synth.states(1, 2)), 1.5, 1)
+    assert e.value.code == dq.ERR_INVALID_ARG
+    with pytest.raises(dq.DqnError) as e:
+        m.per_fill(dev(synth.exp_priorities(1, 101)))
+    assert e.value.code == dq.ERR_INVALID_ARG
+    with pytest.raises(dq.DqnError):
+        m.get_params(4)                              # not centered
+    m2 = dq.Dqn(dq.make_config())
+    with pytest.raises(dq.DqnError) as e:
+        m2.per_fill(dev(synth.exp_priorities(1, 4)))  # context without replay
+    assert e.value.code == dq.ERR_STATE
+    m.close(); m2.close()
