@@ -28,7 +28,7 @@ class OrcConfig(C.Structure):
         ("loss_kind", C.c_int32),
         ("huber_delta", C.c_double), ("gamma", C.c_double), ("lr", C.c_double),
         ("rms_decay", C.c_double), ("rms_eps", C.c_double),
-        ("rms_centered", C.c_int32), ("pad_", C.c_int32),
+        ("rms_centered", C.c_int32), ("quant", C.c_int32),
     ]
 
 
@@ -50,9 +50,11 @@ def lib():
         L.orc_param_count.argtypes = [C.c_int32, C.c_int32]
         L.orc_param_offsets.restype = None
         L.orc_param_offsets.argtypes = [C.c_int32, C.c_int32, C.c_void_p]
-        L.orc_forward.restype = C.c_int32
-        L.orc_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
-                                  C.c_void_p, C.c_void_p]
+        L.orc_forward_q.restype = C.c_int32
+        L.orc_forward_q.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
+                                    C.c_void_p, C.c_void_p]
+        L.orc_round_bf16.restype = C.c_double
+        L.orc_round_bf16.argtypes = [C.c_double]
         L.orc_target_loss.restype = C.c_int32
         L.orc_target_loss.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double,
                                       C.c_double] + [C.c_void_p] * 12
@@ -64,8 +66,8 @@ def lib():
         L.orc_train_step.restype = C.c_int32
         L.orc_train_step.argtypes = [C.POINTER(OrcConfig), C.c_int32] + [C.c_void_p] * 18
         L.orc_act.restype = C.c_int32
-        L.orc_act.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_double,
-                              C.c_uint64, C.c_void_p, C.c_void_p]
+        L.orc_act.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
+                              C.c_double, C.c_uint64, C.c_void_p, C.c_void_p]
         L.orc_tree_build.restype = None
         L.orc_tree_build.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_double, C.c_void_p]
         L.orc_per_sample.restype = C.c_int32
@@ -135,14 +137,18 @@ def param_slices(K, dueling):
     return out
 
 
-def forward(params, K, dueling, states, want_hidden=False):
+def round_bf16(x):
+    return float(lib().orc_round_bf16(float(x)))
+
+
+def forward(params, K, dueling, states, want_hidden=False, quant=0):
     params = _chk(params, np.float32)
     states = _chk(states, np.uint8)
     n = states.shape[0]
     assert states.shape[1:] == (4, 84, 84) and params.size == param_count(K, dueling)
     q = np.zeros((n, K), dtype=np.float64)
     h = np.zeros((n, 512), dtype=np.float64) if want_hidden else None
-    rc = lib().orc_forward(_p(params), K, int(dueling), _p(states), n, _p(q), _p(h))
+    rc = lib().orc_forward_q(_p(params), K, int(dueling), int(quant), _p(states), n, _p(q), _p(h))
     assert rc == 0, rc
     return (q, h) if want_hidden else q
 
@@ -169,9 +175,10 @@ def rmsprop(theta, v, g, *, lr, rho, eps, m=None):
 
 
 def make_config(K, dueling, double_q, loss_kind=1, huber_delta=1.0, gamma=0.99, lr=2.5e-4,
-                rms_decay=0.95, rms_eps=0.01, rms_centered=0):
+                rms_decay=0.95, rms_eps=0.01, rms_centered=0, quant=0):
+    """quant=1: the reduced-precision mode (bf16 weights / activations, see dqn_oracle.c)."""
     return OrcConfig(K, int(dueling), int(double_q), int(loss_kind), huber_delta, gamma, lr,
-                     rms_decay, rms_eps, int(rms_centered), 0)
+                     rms_decay, rms_eps, int(rms_centered), int(quant))
 
 
 def _batch(s, s_next, a, r, done, w):
@@ -219,12 +226,12 @@ def train_step(cfg, theta, theta_target, rms_v, s, s_next, a, r, done, w=None, r
     return out
 
 
-def act(params, K, dueling, obs, epsilon, draw_seed):
+def act(params, K, dueling, obs, epsilon, draw_seed, quant=0):
     params = _chk(params, np.float32); obs = _chk(obs, np.uint8)
     E = obs.shape[0]
     actions = np.zeros(E, np.int32); q = np.zeros((E, K))
-    rc = lib().orc_act(_p(params), K, int(dueling), _p(obs), E, epsilon, C.c_uint64(draw_seed),
-                       _p(actions), _p(q))
+    rc = lib().orc_act(_p(params), K, int(dueling), int(quant), _p(obs), E, epsilon,
+                       C.c_uint64(draw_seed), _p(actions), _p(q))
     assert rc == 0, rc
     return actions, q
 

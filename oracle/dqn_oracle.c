@@ -19,6 +19,16 @@
  *                   then  plain head : out.W[K][512] out.b[K]
  *                   or    dueling    : V.W[1][512] V.b[1] A.W[K][512] A.b[K]
  *
+ * Reduced-precision mode (quant = 1): the throughput configuration computes with
+ * "bf16 weights/activations, fp32 accumulation and fp32 master weights".  A ReLU
+ * mask is a yes/no decision taken on a rounded number, so to compare gradients the
+ * checker has to take those decisions on the same numbers: in this mode the conv
+ * and fc1 weight matrices, the outputs of conv1-3 and the activation gradients
+ * that flow back through fc1 and the convolutions are rounded to bf16
+ * (round-to-nearest-even from the fp32 value); biases, the 512-unit hidden layer,
+ * the head, all sums and the master parameters keep full precision.  Gradients
+ * are taken at the rounded weights and applied to the master weights.
+ *
  * Pins (tests/test_oracle_*.py): Eq.1 closed form, a brute-forced tabular MDP
  * for the targets, the Eq.13 identities, finite differences and an independent
  * autograd for the gradients, closed forms for RMSProp, exact integer
@@ -51,6 +61,27 @@
 #define C3_H 7
 #define FC_IN (C3_O * C3_H * C3_H) /* 3136 */
 #define FC_OUT 512
+
+/* ------------------------------------------------------------------ */
+/* bf16 rounding: the value is first an fp32 number (what an fp32 accumulator
+ * holds), then rounded to the nearest bf16 (8 significant bits), ties to even. */
+/* ------------------------------------------------------------------ */
+double orc_round_bf16(double x)
+{
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (double)f; /* inf / nan unchanged */
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+static void round_array_bf16(double *x, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) x[i] = orc_round_bf16(x[i]);
+}
 
 /* ------------------------------------------------------------------ */
 /* Counter-based draws.  A 64-bit mixer (the SplitMix64 output function
@@ -217,13 +248,16 @@ typedef struct {
 /* Forward of one sample (Section 3 layer list; ReLU after conv1-3 and fc1,
  * linear output; Eq.13 for the dueling head with both streams reading the
  * same 512-unit hidden layer).                                         */
-static void net_forward_one(const float *P, const orc_layout *L, int K, int dueling,
+static void net_forward_one(const float *P, const orc_layout *L, int K, int dueling, int quant,
                             const uint8_t *s, orc_acts *A, double *q)
 {
     for (int i = 0; i < IN_C * IN_H * IN_W; ++i) A->x0[i] = (double)s[i] / 255.0;
     conv_fwd(A->x0, IN_C, IN_H, IN_W, P + L->c1w, P + L->c1b, C1_O, C1_K, C1_S, 1, A->a1);
+    if (quant) round_array_bf16(A->a1, C1_O * C1_H * C1_H);
     conv_fwd(A->a1, C1_O, C1_H, C1_H, P + L->c2w, P + L->c2b, C2_O, C2_K, C2_S, 1, A->a2);
+    if (quant) round_array_bf16(A->a2, C2_O * C2_H * C2_H);
     conv_fwd(A->a2, C2_O, C2_H, C2_H, P + L->c3w, P + L->c3b, C3_O, C3_K, C3_S, 1, A->a3);
+    if (quant) round_array_bf16(A->a3, FC_IN);
     fc_fwd(A->a3, FC_IN, P + L->f1w, P + L->f1b, FC_OUT, 1, A->h);
     fc_fwd(A->h, FC_OUT, P + L->aw, P + L->ab, K, 0, A->adv);
     if (dueling) {
@@ -238,22 +272,47 @@ static void net_forward_one(const float *P, const orc_layout *L, int K, int duel
     }
 }
 
-/* Q-values of n states.  q: double [n][K].  hidden (may be NULL): [n][512]. */
-int32_t orc_forward(const float *params, int32_t K, int32_t dueling, const uint8_t *states,
-                    int64_t n, double *q, double *hidden)
+/* Copy of a parameter blob with the conv1-3 and fc1 weight matrices rounded to
+ * bf16 (reduced-precision mode); biases and the head are copied unchanged.   */
+static float *quantized_copy(const float *P, const orc_layout *L)
+{
+    float *Q = (float *)malloc(sizeof(float) * (size_t)L->total);
+    if (!Q) return NULL;
+    memcpy(Q, P, sizeof(float) * (size_t)L->total);
+    const int64_t beg[4] = {L->c1w, L->c2w, L->c3w, L->f1w};
+    const int64_t end[4] = {L->c1b, L->c2b, L->c3b, L->f1b};
+    for (int t = 0; t < 4; ++t)
+        for (int64_t i = beg[t]; i < end[t]; ++i) Q[i] = (float)orc_round_bf16((double)P[i]);
+    return Q;
+}
+
+/* Q-values of n states.  q: double [n][K].  hidden (may be NULL): [n][512].
+ * quant: 0 full precision / 1 reduced-precision mode (see the file header).  */
+int32_t orc_forward_q(const float *params, int32_t K, int32_t dueling, int32_t quant,
+                      const uint8_t *states, int64_t n, double *q, double *hidden)
 {
     if (K < 1 || K > 64) return -1;
     orc_layout L = make_layout(K, dueling);
+    float *Pq = quant ? quantized_copy(params, &L) : NULL;
+    if (quant && !Pq) return -2;
+    if (quant) params = Pq;
     int fail = 0;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t j = 0; j < n; ++j) {
         orc_acts *A = (orc_acts *)malloc(sizeof(orc_acts));
         if (!A) { fail = 1; continue; }
-        net_forward_one(params, &L, K, dueling, states + j * (IN_C * IN_H * IN_W), A, q + j * K);
+        net_forward_one(params, &L, K, dueling, quant, states + j * (IN_C * IN_H * IN_W), A, q + j * K);
         if (hidden) memcpy(hidden + j * FC_OUT, A->h, sizeof(double) * FC_OUT);
         free(A);
     }
+    free(Pq);
     return fail ? -2 : 0;
+}
+
+int32_t orc_forward(const float *params, int32_t K, int32_t dueling, const uint8_t *states,
+                    int64_t n, double *q, double *hidden)
+{
+    return orc_forward_q(params, K, dueling, 0, states, n, q, hidden);
 }
 
 /* argmax with the lowest index winning ties */
@@ -345,7 +404,8 @@ void orc_rmsprop(int64_t n, float *theta, float *v, float *m, const double *g, d
 typedef struct {
     int32_t num_actions, dueling, double_q, loss_kind;
     double huber_delta, gamma, lr, rms_decay, rms_eps;
-    int32_t rms_centered, pad_;
+    int32_t rms_centered;
+    int32_t quant; /* 0 full precision / 1 reduced-precision mode (see the file header) */
 } orc_config;
 
 /* Gradient of L w.r.t. all online parameters: forward on s (online),
@@ -367,18 +427,25 @@ int32_t orc_loss_grad(const orc_config *cfg, int32_t B, const float *theta,
     orc_acts *acts = (orc_acts *)malloc(sizeof(orc_acts) * (size_t)B);
     if (!qs || !acts) { free(qs); free(acts); return -2; }
     double *qno = qs + (size_t)B * K, *qnt = qno + (size_t)B * K, *dq = qnt + (size_t)B * K;
+    /* the weights the network computes with: the parameters themselves, or
+     * their bf16-rounded copies in reduced-precision mode */
+    const int quant = cfg->quant;
+    float *Wq = quant ? quantized_copy(theta, &L) : NULL;
+    float *Wtq = quant ? quantized_copy(theta_target, &L) : NULL;
+    if (quant && (!Wq || !Wtq)) { free(qs); free(acts); free(Wq); free(Wtq); return -2; }
+    const float *W = quant ? Wq : theta, *Wt = quant ? Wtq : theta_target;
 
 #pragma omp parallel for schedule(dynamic, 1)
     for (int j = 0; j < B; ++j) {
         orc_acts *tmp = (orc_acts *)malloc(sizeof(orc_acts));
-        net_forward_one(theta, &L, K, due, s + j * SS, &acts[j], qs + (int64_t)j * K);
-        net_forward_one(theta, &L, K, due, s_next + j * SS, tmp, qno + (int64_t)j * K);
-        net_forward_one(theta_target, &L, K, due, s_next + j * SS, tmp, qnt + (int64_t)j * K);
+        net_forward_one(W, &L, K, due, quant, s + j * SS, &acts[j], qs + (int64_t)j * K);
+        net_forward_one(W, &L, K, due, quant, s_next + j * SS, tmp, qno + (int64_t)j * K);
+        net_forward_one(Wt, &L, K, due, quant, s_next + j * SS, tmp, qnt + (int64_t)j * K);
         free(tmp);
     }
     int32_t rc = orc_target_loss(B, K, cfg->double_q, cfg->loss_kind, cfg->huber_delta, cfg->gamma,
                                  qs, qno, qnt, a, r, done, w, a_star, y, td, loss, dq);
-    if (rc) { free(qs); free(acts); return rc; }
+    if (rc) { free(qs); free(acts); free(Wq); free(Wtq); return rc; }
     if (q_s) memcpy(q_s, qs, sizeof(double) * (size_t)B * K);
     if (q_next_online) memcpy(q_next_online, qno, sizeof(double) * (size_t)B * K);
     if (q_next_target) memcpy(q_next_target, qnt, sizeof(double) * (size_t)B * K);
@@ -393,7 +460,7 @@ int32_t orc_loss_grad(const orc_config *cfg, int32_t B, const float *theta,
         if (nthreads > B) nthreads = B;
 #endif
         double *priv = (double *)calloc((size_t)nthreads * (size_t)L.total, sizeof(double));
-        if (!priv) { free(qs); free(acts); return -2; }
+        if (!priv) { free(qs); free(acts); free(Wq); free(Wtq); return -2; }
 #pragma omp parallel num_threads(nthreads)
         {
             int tid = 0;
@@ -421,25 +488,29 @@ int32_t orc_loss_grad(const orc_config *cfg, int32_t B, const float *theta,
                 } else {
                     for (int k = 0; k < K; ++k) dadv[k] = dqj[k];
                 }
-                fc_bwd(A->h, FC_OUT, theta + L.aw, K, dadv, dh, G + L.aw, G + L.ab);
+                fc_bwd(A->h, FC_OUT, W + L.aw, K, dadv, dh, G + L.aw, G + L.ab);
                 if (due) {
-                    fc_bwd(A->h, FC_OUT, theta + L.vw, 1, &dv, dh2, G + L.vw, G + L.vb);
+                    fc_bwd(A->h, FC_OUT, W + L.vw, 1, &dv, dh2, G + L.vw, G + L.vb);
                     for (int i = 0; i < FC_OUT; ++i) dh[i] += dh2[i];
                 }
                 for (int i = 0; i < FC_OUT; ++i)
                     if (A->h[i] <= 0.0) dh[i] = 0.0;
-                fc_bwd(A->a3, FC_IN, theta + L.f1w, FC_OUT, dh, d3, G + L.f1w, G + L.f1b);
+                if (quant) round_array_bf16(dh, FC_OUT);
+                fc_bwd(A->a3, FC_IN, W + L.f1w, FC_OUT, dh, d3, G + L.f1w, G + L.f1b);
                 for (int i = 0; i < FC_IN; ++i)
                     if (A->a3[i] <= 0.0) d3[i] = 0.0;
-                conv_bwd(A->a2, C2_O, C2_H, C2_H, theta + L.c3w, C3_O, C3_K, C3_S, d3, d2,
+                if (quant) round_array_bf16(d3, FC_IN);
+                conv_bwd(A->a2, C2_O, C2_H, C2_H, W + L.c3w, C3_O, C3_K, C3_S, d3, d2,
                          G + L.c3w, G + L.c3b);
                 for (int i = 0; i < C2_O * C2_H * C2_H; ++i)
                     if (A->a2[i] <= 0.0) d2[i] = 0.0;
-                conv_bwd(A->a1, C1_O, C1_H, C1_H, theta + L.c2w, C2_O, C2_K, C2_S, d2, d1,
+                if (quant) round_array_bf16(d2, C2_O * C2_H * C2_H);
+                conv_bwd(A->a1, C1_O, C1_H, C1_H, W + L.c2w, C2_O, C2_K, C2_S, d2, d1,
                          G + L.c2w, G + L.c2b);
                 for (int i = 0; i < C1_O * C1_H * C1_H; ++i)
                     if (A->a1[i] <= 0.0) d1[i] = 0.0;
-                conv_bwd(A->x0, IN_C, IN_H, IN_W, theta + L.c1w, C1_O, C1_K, C1_S, d1, NULL,
+                if (quant) round_array_bf16(d1, C1_O * C1_H * C1_H);
+                conv_bwd(A->x0, IN_C, IN_H, IN_W, W + L.c1w, C1_O, C1_K, C1_S, d1, NULL,
                          G + L.c1w, G + L.c1b);
             }
             free(dh); free(dh2); free(d3); free(d2); free(d1);
@@ -452,6 +523,8 @@ int32_t orc_loss_grad(const orc_config *cfg, int32_t B, const float *theta,
     }
     free(qs);
     free(acts);
+    free(Wq);
+    free(Wtq);
     return 0;
 }
 
@@ -479,12 +552,12 @@ int32_t orc_train_step(const orc_config *cfg, int32_t B, float *theta, const flo
  *   u = draw(seed, 2e); if u < epsilon: a = floor(draw(seed, 2e+1) * K)
  *   else a = argmax_a Q(obs_e, a), lowest index on ties.               */
 /* ------------------------------------------------------------------ */
-int32_t orc_act(const float *params, int32_t K, int32_t dueling, const uint8_t *obs, int64_t E,
-                double epsilon, uint64_t draw_seed, int32_t *actions, double *q)
+int32_t orc_act(const float *params, int32_t K, int32_t dueling, int32_t quant, const uint8_t *obs,
+                int64_t E, double epsilon, uint64_t draw_seed, int32_t *actions, double *q)
 {
     double *qq = q ? q : (double *)malloc(sizeof(double) * (size_t)E * K);
     if (!qq) return -2;
-    int32_t rc = orc_forward(params, K, dueling, obs, E, qq, NULL);
+    int32_t rc = orc_forward_q(params, K, dueling, quant, obs, E, qq, NULL);
     if (rc == 0) {
         for (int64_t e = 0; e < E; ++e) {
             float u = orc_draw_u24(draw_seed, 2u * (uint64_t)e);

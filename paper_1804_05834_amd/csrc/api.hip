@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/dqn.h"
+#include "gemm_bf16.h"
 #include "gemm_fp32.h"
 #include "kernels_misc.h"
 #include "net.h"
@@ -20,7 +21,8 @@ namespace {
 
 thread_local std::string g_err;  // errors without a context
 
-constexpr int MAX_WSPLIT = 64;   // most reduction splits of a conv weight gradient
+constexpr int MAX_WSPLIT = 64;   // most reduction splits of a conv2/conv3 weight gradient
+constexpr int MAX_WSPLIT1 = 256; // ... of the conv1 weight gradient (one output tile only)
 
 struct Workspace {
     // minibatch staging (replay mode)
@@ -28,10 +30,12 @@ struct Workspace {
     int32_t *b_idx, *b_a;
     float *b_w, *b_r, *td_abs, *loss_j, *loss_slot;
     uint8_t *b_done;
-    // activations, channel-last, rows = samples of all passes
-    float *act1, *act2, *act3, *f1part, *h_s;
-    // backward
-    float *dA, *dh, *d3, *d2, *d1;
+    // activations, channel-last, rows = samples of all passes (fp32 or bf16 by precision)
+    void *act1, *act2, *act3;
+    float *f1part, *h_s;
+    // backward (dh, d3, d2, d1: fp32 or bf16 by precision)
+    float *dA;
+    void *dh, *d3, *d2, *d1;
     // gradient partial sums per layer, [split][W..., b...]
     float *gp1, *gp2, *gp3, *gp4, *gp5;
     size_t total;
@@ -39,7 +43,12 @@ struct Workspace {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-int fc1_splits(long M) { return M <= 192 ? 14 : M <= 512 ? 7 : M <= 1536 ? 2 : 1; }
+// reduction splits of the fc1 forward GEMM (3136 = 98*32 = 49*64 reduction elements)
+int fc1_splits(long M, int precision)
+{
+    if (precision == 1) return M <= 2048 ? 7 : 1;
+    return M <= 192 ? 14 : M <= 512 ? 7 : M <= 1536 ? 2 : 1;
+}
 
 Workspace carve(const dqn_config &c, uint8_t *base)
 {
@@ -62,19 +71,21 @@ Workspace carve(const dqn_config &c, uint8_t *base)
     w.loss_j = (float *)take(MB * 4);
     w.loss_slot = (float *)take(256);
     w.b_done = take(MB);
-    w.act1 = (float *)take(rows * net::A1 * 4);
-    w.act2 = (float *)take(rows * net::A2 * 4);
-    w.act3 = (float *)take(rows * net::A3 * 4);
+    const size_t es = c.precision == 1 ? 2 : 4;  // bytes per activation element
+    w.act1 = take(rows * net::A1 * es);
+    w.act2 = take(rows * net::A2 * es);
+    w.act3 = take(rows * net::A3 * es);
     size_t f1rows = std::max({std::min<size_t>(rows, 192) * 14, std::min<size_t>(rows, 512) * 7,
                               std::min<size_t>(rows, 1536) * 2, rows});
+    if (c.precision == 1) f1rows = std::max(f1rows, std::min<size_t>(rows, 2048) * 7);
     w.f1part = (float *)take(f1rows * net::HID * 4);
     w.h_s = (float *)take(MB * net::HID * 4);
     w.dA = (float *)take(MB * R * 4);
-    w.dh = (float *)take(MB * net::HID * 4);
-    w.d3 = (float *)take(MB * net::A3 * 4);
-    w.d2 = (float *)take(MB * net::A2 * 4);
-    w.d1 = (float *)take(MB * net::A1 * 4);
-    w.gp1 = (float *)take((size_t)MAX_WSPLIT * net::L1N * 4);
+    w.dh = take(MB * net::HID * es);
+    w.d3 = take(MB * net::A3 * es);
+    w.d2 = take(MB * net::A2 * es);
+    w.d1 = take(MB * net::A1 * es);
+    w.gp1 = (float *)take((size_t)MAX_WSPLIT1 * net::L1N * 4);
     w.gp2 = (float *)take((size_t)MAX_WSPLIT * net::L2N * 4);
     w.gp3 = (float *)take((size_t)MAX_WSPLIT * net::L3N * 4);
     w.gp4 = (float *)take((size_t)net::L4N * 4);
@@ -213,15 +224,23 @@ float *which_buffer(dqn_ctx *c, int which)
 struct Pass {
     const uint8_t *x;   // uint8 states
     long xs;            // bytes between samples
-    const float *theta; // parameter blob used
+    int net;            // 0 online / 1 target parameters
     int n;              // samples
 };
 
-int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
-                      hipStream_t st)
+const float *theta_of(dqn_ctx *c, int net) { return net ? c->theta_t : c->theta; }
+const gbf::bf16_t *shadow_of(dqn_ctx *c, int net)
+{
+    const gbf::bf16_t *sh = (const gbf::bf16_t *)c->buf.shadow_bf16;
+    return sh + (net ? align_up((size_t)c->n * 2, 256) / 2 : 0);
+}
+
+int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
+                          hipStream_t st)
 {
     using namespace g32;
     const Workspace &w = c->ws;
+    float *act1 = (float *)w.act1, *act2 = (float *)w.act2, *act3 = (float *)w.act3;
     long row0[3];
     long rows = 0;
     for (int i = 0; i < npass; ++i) { row0[i] = rows; rows += pass[i].n; }
@@ -232,10 +251,11 @@ int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, 
         A.nseg = npass;
         for (int i = 0; i < npass; ++i) {
             FwdSeg &S = A.seg[i];
+            const float *theta = theta_of(c, pass[i].net);
             S.x = xptr(i);
             S.xs = xstride(i);
-            S.w = pass[i].theta + woff;
-            S.bias = with_bias ? pass[i].theta + boff : nullptr;
+            S.w = theta + woff;
+            S.bias = with_bias ? theta + boff : nullptr;
             S.y = ybase + row0[i] * ystride;
             S.M = pass[i].n * P;
             S.tile_begin = tile;
@@ -248,7 +268,7 @@ int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, 
     {  // conv1
         FwdArgs A{};
         int tiles = build(A, 128, 400, [&](int i) { return (const void *)pass[i].x; },
-                          [&](int i) { return pass[i].xs; }, net::C1W, net::C1B, w.act1, net::A1, true);
+                          [&](int i) { return pass[i].xs; }, net::C1W, net::C1B, act1, net::A1, true);
         A.klen = GConv1::K; A.split_stride = 0; A.scale = 1.0f / 255.0f;
         launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 128, 32><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
     }
@@ -256,8 +276,8 @@ int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, 
     {  // conv2
         FwdArgs A{};
         int BM = small ? 32 : 64;
-        int tiles = build(A, BM, 81, [&](int i) { return (const void *)(w.act1 + row0[i] * net::A1); },
-                          [&](int) { return (long)net::A1; }, net::C2W, net::C2B, w.act2, net::A2, true);
+        int tiles = build(A, BM, 81, [&](int i) { return (const void *)(act1 + row0[i] * net::A1); },
+                          [&](int) { return (long)net::A1; }, net::C2W, net::C2B, act2, net::A2, true);
         A.klen = GConv2::K; A.split_stride = 0; A.scale = 1.0f;
         if (small) launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 32, 64><<<dim3(tiles, 1, 1), 128, 0, st>>>(A); });
         else launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 64, 64><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
@@ -265,16 +285,16 @@ int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, 
     {  // conv3
         FwdArgs A{};
         int BM = small ? 32 : 64;
-        int tiles = build(A, BM, 49, [&](int i) { return (const void *)(w.act2 + row0[i] * net::A2); },
-                          [&](int) { return (long)net::A2; }, net::C3W, net::C3B, w.act3, net::A3, true);
+        int tiles = build(A, BM, 49, [&](int i) { return (const void *)(act2 + row0[i] * net::A2); },
+                          [&](int) { return (long)net::A2; }, net::C3W, net::C3B, act3, net::A3, true);
         A.klen = GConv3::K; A.split_stride = 0; A.scale = 1.0f;
         if (small) launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 32, 64><<<dim3(tiles, 1, 1), 128, 0, st>>>(A); });
         else launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 64, 64><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
     }
     {  // fc1: raw partial sums per reduction split; the head kernels finish it
         FwdArgs A{};
-        const int ns = fc1_splits(rows);
-        int tiles = build(A, 32, 1, [&](int i) { return (const void *)(w.act3 + row0[i] * net::A3); },
+        const int ns = fc1_splits(rows, 0);
+        int tiles = build(A, 32, 1, [&](int i) { return (const void *)(act3 + row0[i] * net::A3); },
                           [&](int) { return (long)net::A3; }, net::F1W, net::F1B, w.f1part, net::HID, false);
         A.klen = GFc1::K / ns; A.split_stride = rows * net::HID; A.scale = 1.0f;
         launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 32, 64><<<dim3(tiles, 8, ns), 128, 0, st>>>(A); });
@@ -284,11 +304,164 @@ int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, 
     return hip_status(c, "forward");
 }
 
-int wgrad_splits(long M, int tiles)
+int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
+                           hipStream_t st)
+{
+    using namespace gbf;
+    const Workspace &w = c->ws;
+    bf16_t *act1 = (bf16_t *)w.act1, *act2 = (bf16_t *)w.act2, *act3 = (bf16_t *)w.act3;
+    long row0[3];
+    long rows = 0;
+    for (int i = 0; i < npass; ++i) { row0[i] = rows; rows += pass[i].n; }
+
+    auto build = [&](FwdArgs &A, int BM, int P, auto xptr, auto xstride, int64_t woff, int64_t boff,
+                     auto yptr, bool with_bias) {
+        int tile = 0;
+        A.nseg = npass;
+        for (int i = 0; i < npass; ++i) {
+            FwdSeg &S = A.seg[i];
+            S.x = xptr(i);
+            S.xs = xstride(i);
+            S.w = shadow_of(c, pass[i].net) + woff;
+            S.bias = with_bias ? theta_of(c, pass[i].net) + boff : nullptr;
+            S.y = yptr(i);
+            S.M = pass[i].n * P;
+            S.tile_begin = tile;
+            tile += (S.M + BM - 1) / BM;
+        }
+        for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
+        return tile;
+    };
+
+    {
+        FwdArgs A{};
+        int tiles = build(A, 256, 400, [&](int i) { return (const void *)pass[i].x; },
+                          [&](int i) { return pass[i].xs; }, net::C1W, net::C1B,
+                          [&](int i) { return (void *)(act1 + row0[i] * net::A1); }, true);
+        A.klen = GConv1::K; A.split_stride = 0; A.scale = 1.0f / 255.0f;
+        launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 256, 32, 2, 1, false><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+    }
+    {
+        FwdArgs A{};
+        int tiles = build(A, 128, 81, [&](int i) { return (const void *)(act1 + row0[i] * net::A1); },
+                          [&](int) { return (long)net::A1; }, net::C2W, net::C2B,
+                          [&](int i) { return (void *)(act2 + row0[i] * net::A2); }, true);
+        A.klen = GConv2::K; A.split_stride = 0; A.scale = 1.0f;
+        launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 128, 64, 2, 1, false><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+    }
+    {
+        FwdArgs A{};
+        int tiles = build(A, 128, 49, [&](int i) { return (const void *)(act2 + row0[i] * net::A2); },
+                          [&](int) { return (long)net::A2; }, net::C3W, net::C3B,
+                          [&](int i) { return (void *)(act3 + row0[i] * net::A3); }, true);
+        A.klen = GConv3::K; A.split_stride = 0; A.scale = 1.0f;
+        launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 128, 64, 2, 1, false><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+    }
+    {
+        FwdArgs A{};
+        const int ns = fc1_splits(rows, 1);
+        int tiles = build(A, 64, 1, [&](int i) { return (const void *)(act3 + row0[i] * net::A3); },
+                          [&](int) { return (long)net::A3; }, net::F1W, net::F1B,
+                          [&](int i) { return (void *)(w.f1part + row0[i] * net::HID); }, false);
+        A.klen = GFc1::K / ns; A.split_stride = rows * net::HID; A.scale = 1.0f;
+        launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 64, 128, 1, 2, true><<<dim3(tiles, 4, ns), 256, 0, st>>>(A); });
+        *nsplit_out = ns;
+        *split_stride_out = rows * net::HID;
+    }
+    return hip_status(c, "forward");
+}
+
+int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *ns, long *ss, hipStream_t st)
+{
+    return c->cfg.precision == 1 ? forward_trunk_bf16(c, pass, npass, ns, ss, st)
+                                 : forward_trunk_f32(c, pass, npass, ns, ss, st);
+}
+
+// reduction rows per split (a multiple of `unit`) and the resulting number of splits
+void split_rows(long M, int tiles, int cap, int unit, int *rps, int *ns)
 {
     long want = std::max<long>(1, 512 / tiles);
     long by_rows = std::max<long>(1, M / 64);
-    return (int)std::min<long>({want, by_rows, (long)MAX_WSPLIT});
+    long n = std::min<long>({want, by_rows, (long)cap});
+    long r = ((M + n - 1) / n + unit - 1) / unit * unit;
+    *rps = (int)r;
+    *ns = (int)((M + r - 1) / r);
+}
+
+// ----- backward through fc1, conv3, conv2, conv1 (no input gradient for conv1) -----
+void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st)
+{
+    using namespace g32;
+    const Workspace &w = c->ws;
+    float *act1 = (float *)w.act1, *act2 = (float *)w.act2, *act3 = (float *)w.act3;
+    float *dh = (float *)w.dh, *d3 = (float *)w.d3, *d2 = (float *)w.d2, *d1 = (float *)w.d1;
+    const bool small = B <= 128;
+    int rps;
+    {
+        DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
+        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
+        WgradArgs G{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
+        launch(c, "fc1_wgrad", st, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, st>>>(G); });
+    }
+    {
+        DgradArgs D{d3, c->theta + net::C3W, act2, d2, B};
+        long M = (long)B * 81;
+        if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 64><<<dim3((M + 31) / 32, 1, 1), 128, 0, st>>>(D); });
+        else launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
+        split_rows((long)B * 49, 9, MAX_WSPLIT, 32, &rps, ns3);
+        WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
+        launch(c, "conv3_wgrad", st, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, *ns3), 256, 0, st>>>(G); });
+    }
+    {
+        DgradArgs D{d2, c->theta + net::C2W, act1, d1, B};
+        long M = (long)B * 100;
+        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
+        split_rows((long)B * 81, 8, MAX_WSPLIT, 32, &rps, ns2);
+        WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
+        launch(c, "conv2_wgrad", st, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, st>>>(G); });
+    }
+    {
+        split_rows((long)B * 400, 1, MAX_WSPLIT1, 32, &rps, ns1);
+        WgradArgs G{d1, s, w.gp1, B, rps, xs, net::L1N, 1.0f / 255.0f};
+        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256><<<dim3(1, 1, *ns1), 512, 0, st>>>(G); });
+    }
+}
+
+void backward_bf16(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st)
+{
+    using namespace gbf;
+    const Workspace &w = c->ws;
+    bf16_t *act1 = (bf16_t *)w.act1, *act2 = (bf16_t *)w.act2, *act3 = (bf16_t *)w.act3;
+    bf16_t *dh = (bf16_t *)w.dh, *d3 = (bf16_t *)w.d3, *d2 = (bf16_t *)w.d2, *d1 = (bf16_t *)w.d1;
+    const bf16_t *sh = shadow_of(c, 0);
+    int rps;
+    {
+        DgradArgs D{dh, sh + net::F1W, act3, d3, B};
+        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 64, 64, 1, 1><<<dim3((B + 63) / 64, 49, 1), 256, 0, st>>>(D); });
+        WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
+        launch(c, "fc1_wgrad", st, [&] { k_wgrad<GFc1, 64, 64, 1, 1><<<dim3(49, 8, 1), 256, 0, st>>>(G); });
+    }
+    {
+        DgradArgs D{d3, sh + net::C3W, act2, d2, B};
+        long M = (long)B * 81;
+        launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 128, 64, 2, 1><<<dim3((M + 127) / 128, 1, 1), 256, 0, st>>>(D); });
+        split_rows((long)B * 49, 9, MAX_WSPLIT, 64, &rps, ns3);
+        WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
+        launch(c, "conv3_wgrad", st, [&] { k_wgrad<GConv3, 64, 64, 1, 1><<<dim3(9, 1, *ns3), 256, 0, st>>>(G); });
+    }
+    {
+        DgradArgs D{d2, sh + net::C2W, act1, d1, B};
+        long M = (long)B * 100;
+        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 256, 32, 2, 1><<<dim3((M + 255) / 256, 1, 4), 256, 0, st>>>(D); });
+        split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
+        WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
+        launch(c, "conv2_wgrad", st, [&] { k_wgrad<GConv2, 64, 64, 1, 1><<<dim3(8, 1, *ns2), 256, 0, st>>>(G); });
+    }
+    {
+        split_rows((long)B * 400, 1, MAX_WSPLIT1, 64, &rps, ns1);
+        WgradArgs G{d1, s, w.gp1, B, rps, xs, net::L1N, 1.0f / 255.0f};
+        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256, 1, 1><<<dim3(1, 1, *ns1), 512, 0, st>>>(G); });
+    }
 }
 
 }  // namespace
@@ -526,9 +699,8 @@ int32_t per_update(dqn_ctx *c, const int32_t *idx, const float *td_abs, int32_t 
     if (n < 1 || n > 1024) return fail(c, DQN_ERR_INVALID_ARG, "per_update: n must be in 1..1024");
     if (!idx || !td_abs) return fail(c, DQN_ERR_INVALID_ARG, "per_update: NULL argument");
     hipStream_t st = (hipStream_t)stream;
-    const int block = (n + 63) / 64 * 64;
     launch(c, "per_update", st, [&] {
-        misc::k_per_update<<<1, block, 0, st>>>(c->tree, c->L, c->levels, c->stored, idx, td_abs, n,
+        misc::k_per_update<<<1, 1024, 0, st>>>(c->tree, c->L, c->levels, c->stored, idx, td_abs, n,
                                                 c->cfg.per_alpha, c->cfg.per_eps);
     });
     return hip_status(c, "per_update");
@@ -572,9 +744,8 @@ int32_t dqn_act(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64
     if (E < 1 || E > c->cfg.max_act_batch) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act: E out of range");
     if (!obs || !actions || !aligned(obs, 16)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act: NULL or misaligned argument");
     if (!(epsilon >= 0.f && epsilon <= 1.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act: epsilon must be in [0,1]");
-    if (c->cfg.precision != 0) return fail(c, DQN_ERR_UNSUPPORTED, "dqn_act: bf16 path not built yet");
     hipStream_t st = (hipStream_t)stream;
-    Pass p{obs, net::STATE, c->theta, E};
+    Pass p{obs, net::STATE, 0, E};
     int ns;
     long ss;
     int32_t rc = forward_trunk(c, &p, 1, &ns, &ss, st);
@@ -589,11 +760,9 @@ int32_t dqn_act(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64
 int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta, uint64_t draw_seed,
                        const dqn_step_out *out, void *stream)
 {
-    using namespace g32;
     if (!c) return DQN_ERR_INVALID_ARG;
     const dqn_config &cfg = c->cfg;
     if (B < 1 || B > cfg.max_batch) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: B out of range");
-    if (cfg.precision != 0) return fail(c, DQN_ERR_UNSUPPORTED, "dqn_train_step: bf16 path not built yet");
     hipStream_t st = (hipStream_t)stream;
     const Workspace &w = c->ws;
     dqn_step_out O{};
@@ -626,7 +795,7 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     }
 
     // forward: online(s), online(s'), target(s') in one launch per layer
-    Pass passes[3] = {{s, xs, c->theta, B}, {sn, xs, c->theta, B}, {sn, xs, c->theta_t, B}};
+    Pass passes[3] = {{s, xs, 0, B}, {sn, xs, 0, B}, {sn, xs, 1, B}};
     int ns;
     long ss;
     int32_t rc = forward_trunk(c, passes, 3, &ns, &ss, st);
@@ -639,64 +808,35 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     H.f1b_on = c->theta + net::F1B; H.f1b_tg = c->theta_t + net::F1B;
     H.head_on = c->theta + net::HEAD; H.head_tg = c->theta_t + net::HEAD;
     H.a = a; H.r = r; H.done = done; H.w = isw;
-    H.h_s = w.h_s; H.dh = w.dh; H.dA = w.dA; H.td_abs = w.td_abs; H.loss_j = w.loss_j;
+    H.h_s = w.h_s; H.dh = w.dh; H.dh_bf16 = cfg.precision == 1; H.dA = w.dA; H.td_abs = w.td_abs; H.loss_j = w.loss_j;
     H.q_s = O.q_s; H.q_no = O.q_next_online; H.q_nt = O.q_next_target; H.y = O.y; H.td = O.td;
     H.a_star = O.a_star; H.is_w = O.is_w;
-    launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 256, 0, st>>>(H); });
+    launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 512, 0, st>>>(H); });
 
     misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
-    launch(c, "head_wgrad", st, [&] { misc::k_head_wgrad<<<c->R, 512, 0, st>>>(HW); });
+    launch(c, "head_wgrad", st, [&] { misc::k_head_wgrad<<<dim3(c->R, 4), 512, 0, st>>>(HW); });
 
-    // backward through fc1, conv3, conv2, conv1 (no input gradient for conv1)
-    const bool small = B <= 128;
-    {
-        DgradArgs D{w.dh, c->theta + net::F1W, w.act3, w.d3, B};
-        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
-        WgradArgs G{w.dh, w.act3, w.gp4, B, B, net::A3, 0, 1.0f};
-        launch(c, "fc1_wgrad", st, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, st>>>(G); });
-    }
-    int ns3, ns2, ns1;
-    {
-        DgradArgs D{w.d3, c->theta + net::C3W, w.act2, w.d2, B};
-        long M = (long)B * 81;
-        if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 64><<<dim3((M + 31) / 32, 1, 1), 128, 0, st>>>(D); });
-        else launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
-        long Mr = (long)B * 49;
-        ns3 = wgrad_splits(Mr, 9);
-        int rps = (int)((Mr + ns3 - 1) / ns3 + 31) / 32 * 32;
-        ns3 = (int)((Mr + rps - 1) / rps);
-        WgradArgs G{w.d3, w.act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
-        launch(c, "conv3_wgrad", st, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, ns3), 256, 0, st>>>(G); });
-    }
-    {
-        DgradArgs D{w.d2, c->theta + net::C2W, w.act1, w.d1, B};
-        long M = (long)B * 100;
-        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
-        long Mr = (long)B * 81;
-        ns2 = wgrad_splits(Mr, 8);
-        int rps = (int)((Mr + ns2 - 1) / ns2 + 31) / 32 * 32;
-        ns2 = (int)((Mr + rps - 1) / rps);
-        WgradArgs G{w.d2, w.act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
-        launch(c, "conv2_wgrad", st, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, ns2), 256, 0, st>>>(G); });
-    }
-    {
-        long Mr = (long)B * 400;
-        ns1 = wgrad_splits(Mr, 4);
-        int rps = (int)((Mr + ns1 - 1) / ns1 + 31) / 32 * 32;
-        ns1 = (int)((Mr + rps - 1) / rps);
-        WgradArgs G{w.d1, s, w.gp1, B, rps, xs, net::L1N, 1.0f / 255.0f};
-        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 64><<<dim3(4, 1, ns1), 128, 0, st>>>(G); });
-    }
+    int ns1, ns2, ns3;
+    if (cfg.precision == 1) backward_bf16(c, B, s, xs, &ns1, &ns2, &ns3, st);
+    else backward_f32(c, B, s, xs, &ns1, &ns2, &ns3, st);
 
     misc::RmsArgs RA{};
-    RA.seg[0] = {net::C1W, net::L1N, w.gp1, ns1, net::L1N};
-    RA.seg[1] = {net::C2W, net::L2N, w.gp2, ns2, net::L2N};
-    RA.seg[2] = {net::C3W, net::L3N, w.gp3, ns3, net::L3N};
-    RA.seg[3] = {net::F1W, net::L4N, w.gp4, 1, 0};
-    RA.seg[4] = {net::HEAD, net::head_count(cfg.num_actions, cfg.dueling), w.gp5, 1, 0};
-    RA.theta = c->theta; RA.v = c->rms_v; RA.m = c->rms_m; RA.g = c->grads; RA.shadow = nullptr;
-    RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps; RA.n = c->n;
-    launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<grid1(c->n, 256), 256, 0, st>>>(RA); });
+    {
+        const long cnt[5] = {net::L1N, net::L2N, net::L3N, net::L4N, net::head_count(cfg.num_actions, cfg.dueling)};
+        const long beg[5] = {net::C1W, net::C2W, net::C3W, net::F1W, net::HEAD};
+        const float *part[5] = {w.gp1, w.gp2, w.gp3, w.gp4, w.gp5};
+        const int nsp[5] = {ns1, ns2, ns3, 1, 1};
+        int blk = 0;
+        for (int i = 0; i < 5; ++i) {
+            RA.seg[i] = {beg[i], cnt[i], part[i], nsp[i], nsp[i] > 1 ? cnt[i] : 0, blk};
+            const long per = nsp[i] > 1 ? 64 : 256;
+            blk += (int)((cnt[i] + per - 1) / per);
+        }
+        RA.theta = c->theta; RA.v = c->rms_v; RA.m = c->rms_m; RA.g = c->grads;
+        RA.shadow = cfg.precision == 1 ? (__hip_bfloat16 *)c->buf.shadow_bf16 : nullptr;
+        RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps;
+        launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
+    }
 
     if (!batch) {
         rc = per_update(c, w.b_idx, w.td_abs, B, stream);

@@ -54,6 +54,7 @@ __device__ __forceinline__ float hidden_unit(const float *part, int nsplit, long
                                              long row, int i, const float *bias)
 {
     float acc = 0.f;
+#pragma unroll 7
     for (int s = 0; s < nsplit; ++s) acc += part[s * split_stride + row * net::HID + i];
     return fmaxf(acc + bias[i], 0.f);
 }
@@ -106,7 +107,8 @@ struct HeadArgs {
     const uint8_t *done;
     const float *w;  // may be nullptr
     float *h_s;      // [B][512] hidden layer of the online net on s
-    float *dh;       // [B][512] gradient w.r.t. the fc1 pre-activation
+    void *dh;        // [B][512] gradient w.r.t. the fc1 pre-activation (fp32, or bf16 if dh_bf16)
+    int dh_bf16;
     float *dA;       // [B][R]   gradient w.r.t. the head rows
     float *td_abs;   // [B]
     float *loss_j;   // [B] w_j * l(td_j)
@@ -119,7 +121,7 @@ struct HeadArgs {
 // for the three passes, evaluates the head three times, forms the target
 // (Eq.8 / Eq.9), the TD error, the loss term and the gradient w.r.t. the
 // head rows, and back-propagates through the head into the hidden layer.
-__global__ __launch_bounds__(256) void k_head_train(HeadArgs A)
+__global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
 {
     __shared__ float hid[3][net::HID];
     __shared__ float raw[3][MAXR];
@@ -128,7 +130,8 @@ __global__ __launch_bounds__(256) void k_head_train(HeadArgs A)
     const int j = blockIdx.x, tid = threadIdx.x;
     const int K = A.K, R = K + (A.dueling ? 1 : 0);
 
-    for (int i = tid; i < net::HID; i += 256) {
+    {
+        const int i = tid;  // one hidden unit per thread
         float hs = hidden_unit(A.part, A.nsplit, A.split_stride, j, i, A.f1b_on);
         hid[0][i] = hs;
         hid[1][i] = hidden_unit(A.part, A.nsplit, A.split_stride, (long)A.B + j, i, A.f1b_on);
@@ -136,9 +139,9 @@ __global__ __launch_bounds__(256) void k_head_train(HeadArgs A)
         A.h_s[(long)j * net::HID + i] = hs;
     }
     __syncthreads();
-    head_rows(hid[0], A.head_on, K, A.dueling, raw[0], tid, 256);
-    head_rows(hid[1], A.head_on, K, A.dueling, raw[1], tid, 256);
-    head_rows(hid[2], A.head_tg, K, A.dueling, raw[2], tid, 256);
+    head_rows(hid[0], A.head_on, K, A.dueling, raw[0], tid, 512);
+    head_rows(hid[1], A.head_on, K, A.dueling, raw[1], tid, 512);
+    head_rows(hid[2], A.head_tg, K, A.dueling, raw[2], tid, 512);
     __syncthreads();
     if (tid < 3) combine_q(raw[tid], K, A.dueling, q[tid]);
     __syncthreads();
@@ -176,10 +179,14 @@ __global__ __launch_bounds__(256) void k_head_train(HeadArgs A)
     if (A.q_nt && tid >= 192 && tid < 192 + K) A.q_nt[(long)j * K + tid - 192] = q[2][tid - 192];
     __syncthreads();
     if (tid < R) A.dA[(long)j * R + tid] = dA[tid];
-    for (int i = tid; i < net::HID; i += 256) {
+    {
+        const int i = tid;
         float acc = 0.f;
+#pragma unroll 4
         for (int r = 0; r < R; ++r) acc += dA[r] * A.head_on[head_w_off(r, K, A.dueling) + i];
-        A.dh[(long)j * net::HID + i] = hid[0][i] > 0.f ? acc : 0.f;
+        const float gmask = hid[0][i] > 0.f ? acc : 0.f;
+        if (A.dh_bf16) static_cast<__hip_bfloat16 *>(A.dh)[(long)j * net::HID + i] = __float2bfloat16(gmask);
+        else static_cast<float *>(A.dh)[(long)j * net::HID + i] = gmask;
     }
 }
 
@@ -193,26 +200,41 @@ struct HeadWgradArgs {
     int B, K, dueling;
 };
 
-// Head weight gradient: dW[r][i] = sum_j dA[j][r] h[j][i], db[r] = sum_j dA[j][r];
-// block 0 also folds the per-row loss terms into L = (1/B) sum_j w_j l_j.
+// Head weight gradient: dW[r][i] = sum_j dA[j][r] h[j][i], db[r] = sum_j dA[j][r].
+// grid (R, 4): block (r, c) owns hidden units [128c, 128c+128); its 512 threads split the
+// minibatch four ways and combine through LDS in a fixed order.  Block (0,0) also folds the
+// per-row loss terms into L = (1/B) sum_j w_j l_j.
 __global__ __launch_bounds__(512) void k_head_wgrad(HeadWgradArgs A)
 {
-    const int r = blockIdx.x, i = threadIdx.x;
+    __shared__ float red[4][128];
+    __shared__ float redb[4];
+    const int r = blockIdx.x, il = threadIdx.x & 127, jg = threadIdx.x >> 7;
+    const int i = blockIdx.y * 128 + il;
     const int R = A.K + (A.dueling ? 1 : 0);
     float acc = 0.f, accb = 0.f;
-    for (int j = 0; j < A.B; ++j) {
+#pragma unroll 4
+    for (int j = jg; j < A.B; j += 4) {
         float d = A.dA[(long)j * R + r];
         acc += d * A.h_s[(long)j * net::HID + i];
         accb += d;
     }
-    A.ghead[head_w_off(r, A.K, A.dueling) + i] = acc;
-    if (i == 0) A.ghead[head_b_off(r, A.K, A.dueling)] = accb;
-    if (r == 0 && i == 0) {
+    red[jg][il] = acc;
+    if (il == 0) redb[jg] = accb;
+    __syncthreads();
+    if (jg == 0) {
+        A.ghead[head_w_off(r, A.K, A.dueling) + i] = (red[0][il] + red[1][il]) + (red[2][il] + red[3][il]);
+        if (il == 0 && blockIdx.y == 0)
+            A.ghead[head_b_off(r, A.K, A.dueling)] = (redb[0] + redb[1]) + (redb[2] + redb[3]);
+    }
+    if (r == 0 && blockIdx.y == 0 && threadIdx.x >= 448) {  // the last wave sums the loss terms
+        const int lane = threadIdx.x & 63;
         float s = 0.f;
-        for (int j = 0; j < A.B; ++j) s += A.loss_j[j];
-        s /= (float)A.B;
-        *A.loss_slot = s;
-        if (A.loss_out) *A.loss_out = s;
+        for (int j = lane; j < A.B; j += 64) s += A.loss_j[j];
+        s = wave_sum(s) / (float)A.B;
+        if (lane == 0) {
+            *A.loss_slot = s;
+            if (A.loss_out) *A.loss_out = s;
+        }
     }
 }
 
@@ -259,36 +281,26 @@ __global__ __launch_bounds__(256) void k_head_act(HeadActArgs A)
 // --------------------------------------------------------------- RMSProp
 // g = sum of the reduction splits (fixed order); v <- rho v + (1-rho) g^2;
 // theta <- theta - lr g / sqrt(v + eps)   [centered: sqrt(v - m^2 + eps)].
+// Each layer is a segment with its own block range.  A segment whose gradient
+// arrives in several splits uses 64 parameters x 4 split-groups per block, so
+// the split sum is spread over four times the threads and combined in LDS;
+// a single-split segment (fc1, head) is a plain 256-parameters-per-block sweep.
 struct RmsSeg {
     long begin, count;  // range of the blob
     const float *part;  // [nsplit][count]
     int nsplit;
     long stride;
+    int block_begin;    // first blockIdx.x of this segment
 };
 struct RmsArgs {
     RmsSeg seg[5];
     float *theta, *v, *m, *g;
     __hip_bfloat16 *shadow;  // bf16 copy of theta (same order) or nullptr
     float lr, rho, eps;
-    long n;
 };
 
-__global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
+__device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g)
 {
-    long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= A.n) return;
-    int s = 0;
-#pragma unroll
-    for (int t = 1; t < 5; ++t)
-        if (i >= A.seg[t].begin) s = t;
-    RmsSeg S = A.seg[0];
-    if (s == 1) S = A.seg[1];
-    if (s == 2) S = A.seg[2];
-    if (s == 3) S = A.seg[3];
-    if (s == 4) S = A.seg[4];
-    const long o = i - S.begin;
-    float g = 0.f;
-    for (int t = 0; t < S.nsplit; ++t) g += S.part[t * S.stride + o];
     float v = A.rho * A.v[i] + (1.f - A.rho) * g * g;
     float denom;
     if (A.m) {
@@ -303,6 +315,37 @@ __global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
     A.theta[i] = th;
     A.g[i] = g;
     if (A.shadow) A.shadow[i] = __float2bfloat16(th);
+}
+
+__global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
+{
+    __shared__ float red[4][64];
+    const int bx = blockIdx.x, tid = threadIdx.x;
+    int s = 0;
+#pragma unroll
+    for (int t = 1; t < 5; ++t)
+        if (bx >= A.seg[t].block_begin) s = t;
+    RmsSeg S = A.seg[0];
+    if (s == 1) S = A.seg[1];
+    if (s == 2) S = A.seg[2];
+    if (s == 3) S = A.seg[3];
+    if (s == 4) S = A.seg[4];
+    if (S.nsplit > 1) {
+        const int pl = tid & 63, sg = tid >> 6;
+        const long o = (long)(bx - S.block_begin) * 64 + pl;
+        float g = 0.f;
+        if (o < S.count) {
+#pragma unroll 4
+            for (int t = sg; t < S.nsplit; t += 4) g += S.part[t * S.stride + o];
+        }
+        red[sg][pl] = g;
+        __syncthreads();
+        if (sg == 0 && o < S.count)
+            rms_update(A, S.begin + o, (red[0][pl] + red[1][pl]) + (red[2][pl] + red[3][pl]));
+    } else {
+        const long o = (long)(bx - S.block_begin) * 256 + tid;
+        if (o < S.count) rms_update(A, S.begin + o, S.part[o]);
+    }
 }
 
 // fp32 -> bf16 copy (round to nearest even)
@@ -410,14 +453,23 @@ __global__ __launch_bounds__(1024) void k_per_sample(const float *tree, long L, 
     }
 }
 
-// Priority update (Eq.11): single workgroup, one thread per entry; the tree is
-// repaired level by level with a barrier between levels, so no atomics.
+// Priority update (Eq.11): single workgroup of 1024 threads, one thread per
+// entry; the tree is repaired level by level with a barrier between levels.
+//  * "last occurrence wins": every entry first stamps its leaf with -1, then
+//    with the integer maximum of the entry numbers that name the leaf (an
+//    integer max has one result whatever the order); the entry that reads its
+//    own number back is the writer.
+//  * Every node a thread will need (the children of all its ancestors) is
+//    requested up front so the dependent chain later runs out of cache.
+//  * The top PU_TOP levels are rebuilt in LDS from the 2^PU_TOP nodes below
+//    them (recomputing an untouched node as left+right reproduces its bits).
+constexpr int PU_TOP = 13;
 __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int levels, long size,
                                                      const int32_t *idx, const float *td_abs, int n,
                                                      float alpha, float eps)
 {
-    __shared__ int sidx[1024];
     __shared__ float sh[16];
+    __shared__ float top[2 << PU_TOP];
     const int j = threadIdx.x;
     int my = -1;
     float p = 0.f;
@@ -426,23 +478,42 @@ __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int le
         if (v >= 0 && v < size) my = v;
         p = (float)((double)fabsf(td_abs[j]) + (double)eps);
     }
-    sidx[j] = my;
-    __syncthreads();
     const bool valid = my >= 0;
-    bool writer = valid;
-    if (valid)
-        for (int t = j + 1; t < n; ++t)
-            if (sidx[t] == my) { writer = false; break; }
-    if (writer) tree[L + my] = (float)pow((double)p, (double)alpha);
-    const float pmax = block_max_1024(valid ? p : 0.f, sh);
+    int *leaf_i = reinterpret_cast<int *>(tree + L + (valid ? my : 0));
+    float warm = 0.f;
+    if (valid) {
+        long nd = (L + my) >> 1;
+#pragma unroll
+        for (int l = 0; l < 32; ++l, nd >>= 1)  // fixed trip count: all loads issue back to back
+            if (l < levels) warm += tree[2 * nd] + tree[2 * nd + 1];
+        *leaf_i = -1;
+    }
+    const float leaf = (float)pow((double)p, (double)alpha);
+    __syncthreads();
+    if (valid) atomicMax(leaf_i, j);
+    const float pmax = block_max_1024(valid ? p : 0.f, sh);  // contains barriers
     if (j == 0) tree[2 * L] = fmaxf(tree[2 * L], pmax);
+    if (warm == -1.2345e38f) tree[0] = warm;  // never true for sums of priorities; keeps the loads
+    const bool writer = valid && __hip_atomic_load(leaf_i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == j;
+    __syncthreads();
+    if (writer) tree[L + my] = leaf;
     long node = L + (valid ? my : 0);
     __syncthreads();
-    for (int l = 0; l < levels; ++l) {
+    const int ltop = levels < PU_TOP ? levels : PU_TOP;  // levels rebuilt in LDS
+    for (int l = 0; l < levels - ltop; ++l) {
         node >>= 1;
         if (valid) tree[node] = tree[2 * node] + tree[2 * node + 1];
         __syncthreads();
     }
+    // tree level `ltop` (2^ltop nodes, heap index 2^ltop + t) is now final: rebuild above it
+    const int wtop = 1 << ltop;
+    for (int t = j; t < wtop; t += blockDim.x) top[wtop + t] = tree[wtop + t];
+    __syncthreads();
+    for (int wdt = wtop >> 1; wdt >= 1; wdt >>= 1) {
+        for (int t = j; t < wdt; t += blockDim.x) top[wdt + t] = top[2 * (wdt + t)] + top[2 * (wdt + t) + 1];
+        __syncthreads();
+    }
+    for (int t = j; t < wtop - 1; t += blockDim.x) tree[1 + t] = top[1 + t];
 }
 
 // --------------------------------------------------------------- replay
