@@ -70,17 +70,19 @@ def test_act_forward_parity(dq, orc, K, dueling, E, prec):
     p = synth.he_uniform_params(3 + K, K, dueling, bias_scale=0.05)
     m.set_params(0, torch.from_numpy(p))
     obs = synth.states(31, E)
-    q_ref = orc.forward(p, K, dueling, obs.numpy())
+    q_ref = orc.forward(p, K, dueling, obs.numpy(), quant=prec)
     a0, q = m.act(dev(obs), 0.0, 99, want_q=True)
+    if prec:   # and within the stated tolerance of the full-precision Q-values
+        assert relerr(q.cpu().numpy(), orc.forward(p, K, dueling, obs.numpy())) <= TOL
     assert relerr(q.cpu().numpy(), q_ref) <= TOL
     check_argmax(a0.cpu().numpy(), q_ref, TOL)
     # epsilon = 1: every action is the specified random draw
     a1 = m.act(dev(obs), 1.0, 99).cpu().numpy()
-    ref1, _ = orc.act(p, K, dueling, obs.numpy(), 1.0, 99)
+    ref1, _ = orc.act(p, K, dueling, obs.numpy(), 1.0, 99, quant=prec)
     assert np.array_equal(a1, ref1)
     # mixed: explore decisions follow the draw stream exactly; greedy ones follow argmax
     a5 = m.act(dev(obs), 0.5, 1234).cpu().numpy()
-    ref5, _ = orc.act(p, K, dueling, obs.numpy(), 0.5, 1234)
+    ref5, _ = orc.act(p, K, dueling, obs.numpy(), 0.5, 1234, quant=prec)
     explore = synth.u24(1234, 2 * torch.arange(E)).numpy() < 0.5
     assert np.array_equal(a5[explore], ref5[explore])
     check_argmax(a5[~explore], q_ref[~explore], TOL)
@@ -88,9 +90,9 @@ def test_act_forward_parity(dq, orc, K, dueling, E, prec):
 
 
 # ------------------------------------------------------------------ training step
-def _oracle_step(orc, cfgd, p, pt, batch_np, w):
+def _oracle_step(orc, cfgd, p, pt, batch_np, w, quant=0):
     cfg = orc.make_config(cfgd["num_actions"], cfgd["dueling"], cfgd["double_q"], cfgd["loss_kind"],
-                          lr=cfgd.get("lr", 2.5e-4), rms_centered=cfgd.get("rms_centered", 0))
+                          lr=cfgd.get("lr", 2.5e-4), rms_centered=cfgd.get("rms_centered", 0), quant=quant)
     theta = p.copy(); v = np.zeros_like(p)
     mm = np.zeros_like(p) if cfgd.get("rms_centered", 0) else None
     out = orc.train_step(cfg, theta, pt, v, *batch_np, w, rms_m=mm)
@@ -101,16 +103,19 @@ def _oracle_step(orc, cfgd, p, pt, batch_np, w):
 def _check_step(orc, out, ref, p, m, K, dueling, tol=TOL):
     """Compares every output of one step taken from parameters p and zero optimizer state.
 
-    fp32 path: everything directly at `tol` (the parameter step gets one extra ulp of the
-    parameter, because theta is stored in fp32 on both sides).
-    bf16 path: Q-values, targets, TD errors, loss, gradients and the updated weights directly at
-    `tol`.  RMSProp divides by sqrt(v + eps), so an error dg in a gradient moves the step by up to
-    lr/sqrt(eps) * dg while the largest step of a tensor saturates near lr/sqrt(1-rho): relative
-    to the largest step the optimizer may legitimately amplify the gradient tolerance.  The step
-    is therefore checked twice: (a) against the oracle's RMSProp applied to the GPU's own
-    gradient, at the fp32 tolerance (the optimizer arithmetic itself), and (b) against the
-    oracle's step within the propagated bound lr/sqrt(eps) * tol * max|g|; v = (1-rho) g^2 gets
-    2*tol (d(g^2) = 2 g dg).
+    fp32 path: every tensor in the max norm at `tol`; the parameter step gets one extra ulp of
+    the parameter (theta is stored in fp32 on both sides, each within half an ulp of its own
+    unrounded value).
+
+    bf16 path: `ref` comes from the oracle's reduced-precision mode, so both sides round the same
+    numbers; what remains are sums that land on opposite sides of a bf16 rounding boundary
+    (about 2e-4 of the activations, one bf16 ulp each) and, downstream of those, a few ReLU masks
+    per step that flip.  A flipped mask moves single gradient entries by one sample's
+    contribution, which the max norm sees in full at small batch sizes.  Gradients are therefore
+    held to `tol` in the relative L2 norm per tensor and to 3*tol in the max norm; the optimizer
+    is checked exactly, by applying the oracle's RMSProp to the GPU's own gradient (fp32
+    tolerance), because RMSProp's division by sqrt(v + eps) would otherwise amplify a gradient
+    difference in small entries relative to the largest (saturated) step of the tensor.
     """
     g = {k: v.cpu().numpy() for k, v in out.items()}
     errs = {}
@@ -123,34 +128,55 @@ def _check_step(orc, out, ref, p, m, K, dueling, tol=TOL):
     theta = m.get_params(0).cpu().numpy()
     v = m.get_params(3).cpu().numpy()
     exact = tol <= TOL
-    lr, rho, eps = float(m.cfg.lr), float(m.cfg.rms_decay), float(m.cfg.rms_eps)
-    if not exact:   # the oracle's optimizer on the GPU's gradient
-        th_own = p.copy(); v_own = np.zeros_like(p)
+    th_ref, v_ref = ref["theta"], ref["v"]
+    if not exact:
+        th_ref = p.copy(); v_ref = np.zeros_like(p)
         m_own = np.zeros_like(p) if m.cfg.rms_centered else None
-        orc.rmsprop(th_own, v_own, grads.astype(np.float64), lr=lr, rho=rho, eps=eps, m=m_own)
+        orc.rmsprop(th_ref, v_ref, grads.astype(np.float64), lr=float(m.cfg.lr), rho=float(m.cfg.rms_decay),
+                    eps=float(m.cfg.rms_eps), m=m_own)
+    scale = 1.0 if exact else tol / TOL      # optimizer checks stay at the fp32 tolerance
     for name, (o, shp) in orc.param_slices(K, dueling).items():
         n = int(np.prod(shp))
         sl = slice(o, o + n)
-        errs["g:" + name] = relerr(grads[sl], ref["grads"][sl])
-        dth_g = theta[sl].astype(np.float64) - p[sl]
-        dth_r = ref["theta"][sl].astype(np.float64) - p[sl]
-        ulp = float(np.spacing(np.float32(np.abs(p[sl]).max())))
         if exact:
-            slack = max(np.abs(dth_g - dth_r).max() - ulp, 0.0)
-            errs["dtheta:" + name] = slack / max(np.abs(dth_r).max(), 1e-12)
-            errs["v:" + name] = relerr(v[sl], ref["v"][sl])
+            errs["g:" + name] = relerr(grads[sl], ref["grads"][sl])
         else:
-            dth_o = th_own[sl].astype(np.float64) - p[sl]
-            slack = max(np.abs(dth_g - dth_o).max() - ulp, 0.0)
-            errs["dtheta_own:" + name] = slack / max(np.abs(dth_o).max(), 1e-12) * (tol / TOL)
-            errs["v_own:" + name] = relerr(v[sl], v_own[sl]) * (tol / TOL)
-            bound = lr / np.sqrt(eps) * tol * np.abs(ref["grads"][sl]).max() + ulp
-            errs["dtheta:" + name] = np.abs(dth_g - dth_r).max() / bound * tol
-            errs["v:" + name] = relerr(v[sl], ref["v"][sl]) / 2
+            errs["g_l2:" + name] = float(np.linalg.norm(grads[sl] - ref["grads"][sl]) /
+                                         max(np.linalg.norm(ref["grads"][sl]), 1e-30))
+            errs["g_max:" + name] = relerr(grads[sl], ref["grads"][sl]) / 3
+        dth_g = theta[sl].astype(np.float64) - p[sl]
+        dth_r = th_ref[sl].astype(np.float64) - p[sl]
+        ulp = float(np.spacing(np.float32(np.abs(p[sl]).max())))
+        slack = max(np.abs(dth_g - dth_r).max() - ulp, 0.0)
+        errs["dtheta:" + name] = slack / max(np.abs(dth_r).max(), 1e-12) * scale
+        errs["v:" + name] = relerr(v[sl], v_ref[sl]) * scale
     errs["theta"] = relerr(theta, ref["theta"])
-    bad = {k: float(e) for k, e in errs.items() if not e <= tol}
+    bad = sorted((k, float(e)) for k, e in errs.items() if not e <= tol)
     assert not bad, bad
     return errs
+
+
+def _check_against_full_precision(out, ref64, theta_gpu, double_q, tol):
+    """bf16 path vs the full-precision oracle, on the quantities the tolerance is stated for:
+    Q-values, targets, TD errors, loss and the updated weights.  Where the full-precision
+    Q-values have a near-tie (top-2 gap inside the tolerance) the bf16 argmax may pick the other
+    action; the Double-DQN target of such a row is discontinuous there, so its y and td (and then
+    the loss, an average over all rows) are compared on the remaining rows only."""
+    g = {k: v.cpu().numpy() for k, v in out.items()}
+    errs = {k: relerr(g[k], ref64[k]) for k in ("q_s", "q_next_online", "q_next_target")}
+    sel = ref64["q_next_online"] if double_q else ref64["q_next_target"]
+    check_argmax(g["a_star"], sel, tol)
+    keep = g["a_star"] == ref64["a_star"]
+    assert keep.mean() > 0.9
+    errs["y"] = relerr(g["y"][keep], ref64["y"][keep])
+    # td = y - Q is a difference of the two: its error is bounded by theirs, relative to them
+    errs["td"] = float(np.abs(g["td"] - ref64["td"])[keep].max() /
+                       max(np.abs(ref64["q_s"]).max(), np.abs(ref64["y"]).max()))
+    if keep.all():
+        errs["loss"] = abs(float(g["loss"][0]) - ref64["loss"]) / max(abs(ref64["loss"]), 1e-12)
+    errs["theta"] = relerr(theta_gpu, ref64["theta"])
+    bad = sorted((k, float(e)) for k, e in errs.items() if not e <= tol)
+    assert not bad, bad
 
 
 CONFIGS = {
@@ -180,9 +206,14 @@ def test_train_step_explicit_batch(dq, orc, name, B, prec):
     w = (0.25 + 0.75 * synth.u24(19, torch.arange(B))) if name != "dqn" else None
     batch = tuple(dev(t) for t in (s, sn, a, r, d)) + ((dev(w),) if w is not None else ())
     out = m.train_step(B, batch)
-    ref = _oracle_step(orc, cfgd, p, pt, (s.numpy(), sn.numpy(), a.numpy(), r.numpy(), d.numpy()),
-                       None if w is None else w.numpy())
+    bnp = (s.numpy(), sn.numpy(), a.numpy(), r.numpy(), d.numpy())
+    # bf16 path: every decision (ReLU masks, argmax) is compared against the oracle taking it on
+    # the same rounded numbers; the stated quantities also against the full-precision oracle
+    ref = _oracle_step(orc, cfgd, p, pt, bnp, None if w is None else w.numpy(), quant=prec)
     errs = _check_step(orc, out, ref, p, m, K, dueling, tol)
+    if prec:
+        ref64 = _oracle_step(orc, cfgd, p, pt, bnp, None if w is None else w.numpy())
+        _check_against_full_precision(out, ref64, m.get_params(0).cpu().numpy(), m.cfg.double_q, tol)
     print("  worst:", max(errs.items(), key=lambda kv: kv[1]), flush=True)
     if cfgd.get("rms_centered"):
         assert relerr(m.get_params(4).cpu().numpy(), ref["m"]) <= tol
@@ -307,8 +338,13 @@ def _replay_step_case(dq, orc, cap, B, m=None, draw_seed=7, tol=TOL):
     a = synth.u24(40, ii); a = torch.clamp((a * K).floor().to(torch.int32), max=K - 1).numpy()
     r = (torch.clamp((synth.u24(41, ii) * 3).floor(), max=2.0) - 1.0).numpy()
     d = (synth.u24(42, ii) < 0.01).to(torch.uint8).numpy()
-    ref = _oracle_step(orc, cfgd, p, pt, (np.ascontiguousarray(s), np.ascontiguousarray(sn), a, r, d), w_ref)
+    bnp = (np.ascontiguousarray(s), np.ascontiguousarray(sn), a, r, d)
+    prec = int(m.cfg.precision)
+    ref = _oracle_step(orc, cfgd, p, pt, bnp, w_ref, quant=prec)
     errs = _check_step(orc, out, ref, p, m, K, dueling, tol)
+    if prec:
+        ref64 = _oracle_step(orc, cfgd, p, pt, bnp, w_ref)
+        _check_against_full_precision(out, ref64, m.get_params(0).cpu().numpy(), m.cfg.double_q, tol)
     # priorities written back from |td|
     td_abs = np.abs(out["td"].cpu().numpy()).astype(np.float32)
     orc.per_update(tree_ref, cap, idx_ref, td_abs, float(np.float32(0.6)), float(np.float32(1e-6)), 1.0)
