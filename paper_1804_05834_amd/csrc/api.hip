@@ -116,6 +116,10 @@ struct dqn_ctx {
     float *meta_r;
     uint8_t *meta_done;
     float *tree;
+    // side stream: kernels off the critical chain (weight gradients, priority update) overlap
+    // the input-gradient chain of the backward pass
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_join = nullptr;
     bool prof = false;
     std::vector<ProfRec> recs;
     std::string err;
@@ -388,8 +392,20 @@ void split_rows(long M, int tiles, int cap, int unit, int *rps, int *ns)
     *ns = (int)((M + r - 1) / r);
 }
 
+// fork/join between the caller's stream and the side stream (no-ops when they are the same)
+void ev_record(hipEvent_t e, hipStream_t on, hipStream_t other)
+{
+    if (on != other) (void)hipEventRecord(e, on);
+}
+void ev_wait(hipStream_t waiter, hipEvent_t e, hipStream_t other)
+{
+    if (waiter != other) (void)hipStreamWaitEvent(waiter, e, 0);
+}
+
 // ----- backward through fc1, conv3, conv2, conv1 (no input gradient for conv1) -----
-void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st)
+// The input-gradient chain runs on st; the weight gradients of fc1, conv3 and conv2 run on sd.
+void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st,
+                  hipStream_t sd)
 {
     using namespace g32;
     const Workspace &w = c->ws;
@@ -400,17 +416,20 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     {
         DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
         launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
+        ev_record(c->ev_a, st, sd);
         WgradArgs G{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
-        launch(c, "fc1_wgrad", st, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, st>>>(G); });
+        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
     }
     {
         DgradArgs D{d3, c->theta + net::C3W, act2, d2, B};
         long M = (long)B * 81;
         if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 64><<<dim3((M + 31) / 32, 1, 1), 128, 0, st>>>(D); });
         else launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
+        ev_record(c->ev_b, st, sd);
         split_rows((long)B * 49, 9, MAX_WSPLIT, 32, &rps, ns3);
         WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
-        launch(c, "conv3_wgrad", st, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, *ns3), 256, 0, st>>>(G); });
+        ev_wait(sd, c->ev_a, st);
+        launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G); });
     }
     {
         DgradArgs D{d2, c->theta + net::C2W, act1, d1, B};
@@ -418,7 +437,8 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
         launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
         split_rows((long)B * 81, 8, MAX_WSPLIT, 32, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
-        launch(c, "conv2_wgrad", st, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, st>>>(G); });
+        ev_wait(sd, c->ev_b, st);
+        launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
     }
     {
         split_rows((long)B * 400, 1, MAX_WSPLIT1, 32, &rps, ns1);
@@ -427,7 +447,8 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     }
 }
 
-void backward_bf16(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st)
+void backward_bf16(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st,
+                  hipStream_t sd)
 {
     using namespace gbf;
     const Workspace &w = c->ws;
@@ -438,16 +459,19 @@ void backward_bf16(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *
     {
         DgradArgs D{dh, sh + net::F1W, act3, d3, B};
         launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 64, 64, 1, 1><<<dim3((B + 63) / 64, 49, 1), 256, 0, st>>>(D); });
+        ev_record(c->ev_a, st, sd);
         WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
-        launch(c, "fc1_wgrad", st, [&] { k_wgrad<GFc1, 64, 64, 1, 1><<<dim3(49, 8, 1), 256, 0, st>>>(G); });
+        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64, 1, 1><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
     }
     {
         DgradArgs D{d3, sh + net::C3W, act2, d2, B};
         long M = (long)B * 81;
         launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 128, 64, 2, 1><<<dim3((M + 127) / 128, 1, 1), 256, 0, st>>>(D); });
+        ev_record(c->ev_b, st, sd);
         split_rows((long)B * 49, 9, MAX_WSPLIT, 64, &rps, ns3);
         WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
-        launch(c, "conv3_wgrad", st, [&] { k_wgrad<GConv3, 64, 64, 1, 1><<<dim3(9, 1, *ns3), 256, 0, st>>>(G); });
+        ev_wait(sd, c->ev_a, st);
+        launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64, 1, 1><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G); });
     }
     {
         DgradArgs D{d2, sh + net::C2W, act1, d1, B};
@@ -455,7 +479,8 @@ void backward_bf16(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *
         launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 256, 32, 2, 1><<<dim3((M + 255) / 256, 1, 4), 256, 0, st>>>(D); });
         split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
-        launch(c, "conv2_wgrad", st, [&] { k_wgrad<GConv2, 64, 64, 1, 1><<<dim3(8, 1, *ns2), 256, 0, st>>>(G); });
+        ev_wait(sd, c->ev_b, st);
+        launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64, 1, 1><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
     }
     {
         split_rows((long)B * 400, 1, MAX_WSPLIT1, 64, &rps, ns1);
@@ -571,6 +596,15 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
         delete c;
         return fail(nullptr, DQN_ERR_HIP, "dqn_init: device initialisation failed");
     }
+    // side stream at the default priority; if anything fails the step simply runs on one stream
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) c->side = nullptr;
+    hipEvent_t *evs[4] = {&c->ev_fork, &c->ev_a, &c->ev_b, &c->ev_join};
+    for (hipEvent_t *e : evs)
+        if (c->side && hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) {
+            (void)hipStreamDestroy(c->side);
+            c->side = nullptr;
+        }
+    (void)hipGetLastError();
     *out = c;
     return DQN_OK;
 }
@@ -582,6 +616,12 @@ int32_t dqn_destroy(dqn_ctx *ctx)
         (void)hipEventDestroy(r.e0);
         (void)hipEventDestroy(r.e1);
     }
+    if (ctx->side) {
+        (void)hipStreamSynchronize(ctx->side);
+        (void)hipStreamDestroy(ctx->side);
+    }
+    for (hipEvent_t e : {ctx->ev_fork, ctx->ev_a, ctx->ev_b, ctx->ev_join})
+        if (e) (void)hipEventDestroy(e);
     delete ctx;
     return DQN_OK;
 }
@@ -813,12 +853,22 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     H.a_star = O.a_star; H.is_w = O.is_w;
     launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 512, 0, st>>>(H); });
 
+    // fork: head weight gradient, priority update and the weight gradients leave the chain
+    hipStream_t sd = c->side ? c->side : st;
+    ev_record(c->ev_fork, st, sd);
+    ev_wait(sd, c->ev_fork, st);
     misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
-    launch(c, "head_wgrad", st, [&] { misc::k_head_wgrad<<<dim3(c->R, 4), 512, 0, st>>>(HW); });
+    launch(c, "head_wgrad", sd, [&] { misc::k_head_wgrad<<<dim3(c->R, 4), 512, 0, sd>>>(HW); });
+    if (!batch) {
+        rc = per_update(c, w.b_idx, w.td_abs, B, (void *)sd);
+        if (rc) return rc;
+    }
 
     int ns1, ns2, ns3;
-    if (cfg.precision == 1) backward_bf16(c, B, s, xs, &ns1, &ns2, &ns3, st);
-    else backward_f32(c, B, s, xs, &ns1, &ns2, &ns3, st);
+    if (cfg.precision == 1) backward_bf16(c, B, s, xs, &ns1, &ns2, &ns3, st, sd);
+    else backward_f32(c, B, s, xs, &ns1, &ns2, &ns3, st, sd);
+    ev_record(c->ev_join, sd, st);
+    ev_wait(st, c->ev_join, sd);
 
     misc::RmsArgs RA{};
     {
@@ -836,11 +886,6 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
         RA.shadow = cfg.precision == 1 ? (__hip_bfloat16 *)c->buf.shadow_bf16 : nullptr;
         RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps;
         launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
-    }
-
-    if (!batch) {
-        rc = per_update(c, w.b_idx, w.td_abs, B, stream);
-        if (rc) return rc;
     }
     return hip_status(c, "dqn_train_step");
 }
