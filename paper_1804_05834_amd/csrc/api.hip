@@ -118,6 +118,7 @@ struct dqn_ctx {
     float *tree;
     // side stream: kernels off the critical chain (weight gradients, priority update) overlap
     // the input-gradient chain of the backward pass
+    int num_cu = 256;  // compute units of the device
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_join = nullptr;
     bool prof = false;
@@ -226,10 +227,12 @@ float *which_buffer(dqn_ctx *c, int which)
 
 // ----- forward of up to three passes through conv1..fc1 -----
 struct Pass {
-    const uint8_t *x;   // uint8 states
-    long xs;            // bytes between samples
-    int net;            // 0 online / 1 target parameters
-    int n;              // samples
+    const uint8_t *x;    // uint8 states, or the replay ring when idx is set
+    long xs;             // bytes between samples (states)
+    int net;             // 0 online / 1 target parameters
+    int n;               // samples
+    const int32_t *idx;  // ring mode (bf16 path): sampled slots; frames are read from the ring
+    int shift;           // ring mode: 0 = s (frames i-3..i), 1 = s' (frames i-2..i+1)
 };
 
 const float *theta_of(dqn_ctx *c, int net) { return net ? c->theta_t : c->theta; }
@@ -337,21 +340,33 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         return tile;
     };
 
-    {
-        FwdArgs A{};
-        int tiles = build(A, 256, 400, [&](int i) { return (const void *)pass[i].x; },
-                          [&](int i) { return pass[i].xs; }, net::C1W, net::C1B,
-                          [&](int i) { return (void *)(act1 + row0[i] * net::A1); }, true);
-        A.klen = GConv1::K; A.split_stride = 0; A.scale = 1.0f / 255.0f;
-        launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 256, 32, 2, 1, false><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+    {  // conv1: one workgroup per sample, frames staged in LDS (read from the ring in ring mode)
+        c1::FwdArgs A{};
+        A.nseg = npass;
+        int first = 0;
+        for (int i = 0; i < npass; ++i) {
+            c1::FwdSeg &S = A.seg[i];
+            S.src = c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift};
+            S.w = shadow_of(c, pass[i].net) + net::C1W;
+            S.bias = theta_of(c, pass[i].net) + net::C1B;
+            S.y = act1 + row0[i] * net::A1;
+            S.n = pass[i].n;
+            S.first = first;
+            first += pass[i].n;
+        }
+        for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
+        A.total = first;
+        const int grid = std::min(first, c->num_cu);  // one persistent workgroup per CU measured fastest
+        launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd<<<dim3(grid), 512, 0, st>>>(A); });
     }
-    {
+    {  // 8 waves per workgroup, one 32x32 block each: the short reduction loops of these layers
+       // are latency-bound, and more resident waves hide more of it than bigger per-wave tiles
         FwdArgs A{};
         int tiles = build(A, 128, 81, [&](int i) { return (const void *)(act1 + row0[i] * net::A1); },
                           [&](int) { return (long)net::A1; }, net::C2W, net::C2B,
                           [&](int i) { return (void *)(act2 + row0[i] * net::A2); }, true);
         A.klen = GConv2::K; A.split_stride = 0; A.scale = 1.0f;
-        launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 128, 64, 2, 1, false><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+        launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 128, 64, 1, 1, false><<<dim3(tiles, 1, 1), 512, 0, st>>>(A); });
     }
     {
         FwdArgs A{};
@@ -359,7 +374,7 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
                           [&](int) { return (long)net::A2; }, net::C3W, net::C3B,
                           [&](int i) { return (void *)(act3 + row0[i] * net::A3); }, true);
         A.klen = GConv3::K; A.split_stride = 0; A.scale = 1.0f;
-        launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 128, 64, 2, 1, false><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+        launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 128, 64, 1, 1, false><<<dim3(tiles, 1, 1), 512, 0, st>>>(A); });
     }
     {
         FwdArgs A{};
@@ -447,8 +462,8 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     }
 }
 
-void backward_bf16(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st,
-                  hipStream_t sd)
+void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *ns3, hipStream_t st,
+                   hipStream_t sd)
 {
     using namespace gbf;
     const Workspace &w = c->ws;
@@ -466,7 +481,7 @@ void backward_bf16(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *
     {
         DgradArgs D{d3, sh + net::C3W, act2, d2, B};
         long M = (long)B * 81;
-        launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 128, 64, 2, 1><<<dim3((M + 127) / 128, 1, 1), 256, 0, st>>>(D); });
+        launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64, 1, 1><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_b, st, sd);
         split_rows((long)B * 49, 9, MAX_WSPLIT, 64, &rps, ns3);
         WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
@@ -476,16 +491,16 @@ void backward_bf16(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *
     {
         DgradArgs D{d2, sh + net::C2W, act1, d1, B};
         long M = (long)B * 100;
-        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 256, 32, 2, 1><<<dim3((M + 255) / 256, 1, 4), 256, 0, st>>>(D); });
+        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32, 1, 1><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
         split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
         ev_wait(sd, c->ev_b, st);
         launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64, 1, 1><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
     }
-    {
-        split_rows((long)B * 400, 1, MAX_WSPLIT1, 64, &rps, ns1);
-        WgradArgs G{d1, s, w.gp1, B, rps, xs, net::L1N, 1.0f / 255.0f};
-        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256, 1, 1><<<dim3(1, 1, *ns1), 512, 0, st>>>(G); });
+    {  // conv1: one workgroup per split of samples, frames staged in LDS
+        *ns1 = std::min(B, MAX_WSPLIT1);
+        c1::WgradArgs G{c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift}, d1, w.gp1, B, *ns1};
+        launch(c, "conv1_wgrad", st, [&] { c1::k_conv1_wgrad<<<dim3(*ns1, 2), 256, 0, st>>>(G); });
     }
 }
 
@@ -595,6 +610,12 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
     if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
         delete c;
         return fail(nullptr, DQN_ERR_HIP, "dqn_init: device initialisation failed");
+    }
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            c->num_cu = cus;
     }
     // side stream at the default priority; if anything fails the step simply runs on one stream
     if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) c->side = nullptr;
@@ -727,7 +748,7 @@ int32_t per_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, int32_
     const int block = (B + 63) / 64 * 64;
     launch(c, "per_sample", st, [&] {
         misc::k_per_sample<<<1, block, 0, st>>>(c->tree, c->L, c->stored, B, beta, draw_seed,
-                                                c->cfg.per_stratified, idx, is_w);
+                                                c->cfg.per_stratified, idx, is_w, misc::MetaGather{});
     });
     return hip_status(c, "per_sample");
 }
@@ -785,7 +806,7 @@ int32_t dqn_act(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64
     if (!obs || !actions || !aligned(obs, 16)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act: NULL or misaligned argument");
     if (!(epsilon >= 0.f && epsilon <= 1.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act: epsilon must be in [0,1]");
     hipStream_t st = (hipStream_t)stream;
-    Pass p{obs, net::STATE, 0, E};
+    Pass p{obs, net::STATE, 0, E, nullptr, 0};
     int ns;
     long ss;
     int32_t rc = forward_trunk(c, &p, 1, &ns, &ss, st);
@@ -809,6 +830,7 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     if (out) O = *out;
 
     const uint8_t *s, *sn;
+    const int32_t *ring_idx = nullptr;
     long xs;
     const int32_t *a;
     const float *r, *isw;
@@ -823,19 +845,29 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     } else {
         if (cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "dqn_train_step: replay is empty");
         if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: beta must be >= 0");
-        int32_t rc = per_sample(c, B, beta, draw_seed, w.b_idx, w.b_w, stream);
-        if (rc) return rc;
-        misc::GatherArgs G{(const uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r, c->meta_done,
-                           (long)cfg.replay_capacity, w.b_idx, w.stack5, nullptr, nullptr, w.b_a, w.b_r, w.b_done};
-        launch(c, "gather", st, [&] { misc::k_gather<<<dim3(B, 5), 256, 0, st>>>(G); });
-        s = w.stack5; sn = w.stack5 + net::FRAME; xs = 5 * net::FRAME;
+        const int block = (B + 63) / 64 * 64;
+        launch(c, "per_sample", st, [&] {
+            misc::k_per_sample<<<1, block, 0, st>>>(c->tree, c->L, c->stored, B, beta, draw_seed, cfg.per_stratified,
+                                                    w.b_idx, w.b_w,
+                                                    misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done});
+        });
         a = w.b_a; r = w.b_r; done = w.b_done; isw = w.b_w;
+        if (cfg.precision == 1) {
+            // bf16 path: the conv1 kernels read the five frames of a transition straight from the ring
+            ring_idx = w.b_idx;
+            s = sn = (const uint8_t *)c->buf.replay_frames; xs = 0;
+        } else {
+            misc::GatherArgs G{(const uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r, c->meta_done,
+                               (long)cfg.replay_capacity, w.b_idx, w.stack5, nullptr, nullptr, nullptr, nullptr, nullptr};
+            launch(c, "gather", st, [&] { misc::k_gather<<<dim3(B, 5), 256, 0, st>>>(G); });
+            s = w.stack5; sn = w.stack5 + net::FRAME; xs = 5 * net::FRAME;
+        }
         if (O.idx && hipMemcpyAsync(O.idx, w.b_idx, (size_t)B * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
             return fail(c, DQN_ERR_HIP, "dqn_train_step: copy failed");
     }
 
     // forward: online(s), online(s'), target(s') in one launch per layer
-    Pass passes[3] = {{s, xs, 0, B}, {sn, xs, 0, B}, {sn, xs, 1, B}};
+    Pass passes[3] = {{s, xs, 0, B, ring_idx, 0}, {sn, xs, 0, B, ring_idx, 1}, {sn, xs, 1, B, ring_idx, 1}};
     int ns;
     long ss;
     int32_t rc = forward_trunk(c, passes, 3, &ns, &ss, st);
@@ -865,7 +897,7 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     }
 
     int ns1, ns2, ns3;
-    if (cfg.precision == 1) backward_bf16(c, B, s, xs, &ns1, &ns2, &ns3, st, sd);
+    if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, sd);
     else backward_f32(c, B, s, xs, &ns1, &ns2, &ns3, st, sd);
     ev_record(c->ev_join, sd, st);
     ev_wait(st, c->ev_join, sd);

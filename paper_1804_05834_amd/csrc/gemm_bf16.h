@@ -16,6 +16,12 @@
 //
 // MFMA 32x32x16 operand layout (lane = 32*h + i): a-operand A[i][8h..8h+7],
 // b-operand B[8h..8h+7][i], result acc[r] = D[8*(r/4) + 4*h + r%4][i].
+//
+// Kernels whose output is channel-last ([position][channel]) feed the WEIGHT
+// fragment as the a-operand and the activation fragment as the b-operand, i.e.
+// they compute the transposed tile: a lane then owns one output position and 4
+// groups of 4 consecutive channels, which it stores as 8-byte pieces (instead of
+// sixteen 2-byte stores at a 64-byte row stride).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -38,9 +44,14 @@ __device__ __forceinline__ v16f mfma(v8bf a, v8bf b, v16f c)
 
 __device__ __forceinline__ bf16_t f2bf(float f)  // round to nearest even
 {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+    return __builtin_bit_cast(bf16_t, (__bf16)f);
+}
+// four floats -> four bf16 in 8 bytes
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d)
+{
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    v2bf lo = {(__bf16)a, (__bf16)b}, hi = {(__bf16)c, (__bf16)d};
+    return uint2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
 }
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
@@ -59,6 +70,13 @@ __device__ __forceinline__ uint4 ld8(const uint8_t *p)  // 8 pixels -> 8 bf16 (e
     r.z = pack2_u8(b & 0xFFu, (b >> 8) & 0xFFu);
     r.w = pack2_u8((b >> 16) & 0xFFu, b >> 24);
     return r;
+}
+
+// Barrier that orders LDS traffic only: global loads and stores issued earlier stay in flight
+// across it (__syncthreads() would wait for all of them first).
+__device__ __forceinline__ void sync_lds()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 __device__ __forceinline__ v8bf frag_k(const bf16_t *p)  // 8 consecutive k of one row
@@ -177,7 +195,7 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_fw
 #pragma unroll
             for (int a = 0; a < WM; ++a)
 #pragma unroll
-                for (int b = 0; b < WN; ++b) acc[a][b] = mfma(fa[a], fb[b], acc[a][b]);
+                for (int b = 0; b < WN; ++b) acc[a][b] = mfma(fb[b], fa[a], acc[a][b]);  // transposed tile
         }
         __syncthreads();
         if (more) {
@@ -186,23 +204,25 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_fw
         }
     }
 
+    // acc[a][b][4g + j] = Y[row m = block a, lane li][channel = block b, 8g + 4h + j]
 #pragma unroll
-    for (int b = 0; b < WN; ++b) {
-        const int col = n0 + (wn * WN + b) * 32 + li;
-        const float bias = (!RAW && S.bias) ? S.bias[col] : 0.f;
+    for (int a = 0; a < WM; ++a) {
+        const int m = m0 + (wm * WM + a) * 32 + li;
+        if (m >= S.M) continue;
 #pragma unroll
-        for (int a = 0; a < WM; ++a) {
+        for (int b = 0; b < WN; ++b) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int m = m0 + (wm * WM + a) * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                if (m < S.M) {
-                    float v = acc[a][b][r] * A.scale;
-                    if (RAW) {
-                        (static_cast<float *>(S.y) + (long)blockIdx.z * A.split_stride)[(long)m * G::N + col] = v;
-                    } else {
-                        v = fmaxf(v + bias, 0.f);
-                        static_cast<bf16_t *>(S.y)[(long)m * G::N + col] = f2bf(v);
-                    }
+            for (int g = 0; g < 4; ++g) {
+                const int col = n0 + (wn * WN + b) * 32 + 8 * g + 4 * h;
+                float v0 = acc[a][b][4 * g] * A.scale, v1 = acc[a][b][4 * g + 1] * A.scale;
+                float v2 = acc[a][b][4 * g + 2] * A.scale, v3 = acc[a][b][4 * g + 3] * A.scale;
+                if (RAW) {
+                    float *y = static_cast<float *>(S.y) + (long)blockIdx.z * A.split_stride;
+                    *reinterpret_cast<v4f *>(y + (long)m * G::N + col) = v4f{v0, v1, v2, v3};
+                } else {
+                    const v4f bv = *reinterpret_cast<const v4f *>(S.bias + col);
+                    *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(S.y) + (long)m * G::N + col) =
+                        pack4(fmaxf(v0 + bv.x, 0.f), fmaxf(v1 + bv.y, 0.f), fmaxf(v2 + bv.z, 0.f), fmaxf(v3 + bv.w, 0.f));
                 }
             }
         }
@@ -310,7 +330,7 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
 #pragma unroll
             for (int a = 0; a < WM; ++a)
 #pragma unroll
-                for (int b = 0; b < WN; ++b) acc[a][b] = mfma(fa[a], fb[b], acc[a][b]);
+                for (int b = 0; b < WN; ++b) acc[a][b] = mfma(fb[b], fa[a], acc[a][b]);  // transposed tile
         }
         __syncthreads();
         if (more) {
@@ -319,20 +339,26 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
         }
     }
 
+    // acc[a][b][4g + j] = dX[position m = block a, lane li][channel = block b, 8g + 4h + j]
 #pragma unroll
-    for (int b = 0; b < WN; ++b) {
-        const int col = n0 + (wn * WN + b) * 32 + li;
+    for (int a = 0; a < WM; ++a) {
+        const int m = m0 + (wm * WM + a) * 32 + li;
+        if (m >= Mc) continue;
+        const int n = m / D::PP, rr = m % D::PP;
+        const int hh = D::S * (rr / D::WP) + ca, ww = D::S * (rr % D::WP) + cb;
+        const long base = ((long)(n * D::H + hh) * D::W + ww) * D::CI;
 #pragma unroll
-        for (int a = 0; a < WM; ++a) {
+        for (int b = 0; b < WN; ++b) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int m = m0 + (wm * WM + a) * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                if (m < Mc) {
-                    int n = m / D::PP, rr = m % D::PP;
-                    int hh = D::S * (rr / D::WP) + ca, ww = D::S * (rr % D::WP) + cb;
-                    long off = ((long)(n * D::H + hh) * D::W + ww) * D::CI + col;
-                    A.dx[off] = (int16_t)A.xact[off] > 0 ? f2bf(acc[a][b][r]) : (bf16_t)0;
-                }
+            for (int g = 0; g < 4; ++g) {
+                const long off = base + n0 + (wn * WN + b) * 32 + 8 * g + 4 * h;
+                const uint2 xa = *reinterpret_cast<const uint2 *>(A.xact + off);
+                // ReLU mask of the layer below: its stored output is > 0
+                const float v0 = (int16_t)(xa.x & 0xFFFFu) > 0 ? acc[a][b][4 * g] : 0.f;
+                const float v1 = (int16_t)(xa.x >> 16) > 0 ? acc[a][b][4 * g + 1] : 0.f;
+                const float v2 = (int16_t)(xa.y & 0xFFFFu) > 0 ? acc[a][b][4 * g + 2] : 0.f;
+                const float v3 = (int16_t)(xa.y >> 16) > 0 ? acc[a][b][4 * g + 3] : 0.f;
+                *reinterpret_cast<uint2 *>(A.dx + off) = pack4(v0, v1, v2, v3);
             }
         }
     }
@@ -459,4 +485,287 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
     }
 }
 
+
+
+// ===========================================================================
+// conv1 (8x8 stride 4 over the uint8 frame stack), specialised.
+//
+// The generic kernels gather conv1's im2col rows from global memory in 4/8-byte
+// pieces at 84-byte strides, which is address-bound.  Here one workgroup owns
+// one sample: its four 84x84 frames are read once with 16-byte loads -- from a
+// materialised state, or straight from the replay ring through the sampled
+// slot (the frame-stack gather fused into the loader) -- converted to bf16 and
+// kept in LDS as [4][84][84].  Every operand of the 8x8/4 convolution is then
+// an LDS read at a computed address:
+//   forward : pixel row of A = 8 consecutive q for one (c,p): 16 bytes;
+//             all of W (32x256 bf16) sits in registers as 16 b-operands;
+//   wgrad   : 8 consecutive pixels of one im2col column, fetched with the LDS
+//             transpose load, whose lanes each supply their own address.
+// ===========================================================================
+namespace c1 {
+constexpr int FR = 84 * 84;       // elements per frame
+constexpr int XIN = 4 * FR;       // staged state, elements
+
+struct Src {                      // where the four frames of sample n come from
+    const uint8_t *x;             // explicit states [n][4][84][84] (idx == nullptr) or the ring
+    long xs;                      // bytes between samples (explicit)
+    const int32_t *idx;           // sampled slots (ring mode)
+    long cap;                     // ring capacity
+    int shift;                    // 0: frames i-3..i (s), 1: frames i-2..i+1 (s')
+};
+
+__device__ __forceinline__ const uint8_t *frame_ptr(const Src &S, int n, int k)
+{
+    if (!S.idx) return S.x + (long)n * S.xs + (long)k * FR;
+    long i = S.idx[n];
+    i = i < 0 ? 0 : (i >= S.cap ? S.cap - 1 : i);
+    long slot = i - 3 + k + S.shift;  // within [-3, cap+1]: one wrap at most (cap >= 5)
+    if (slot < 0) slot += S.cap;
+    if (slot >= S.cap) slot -= S.cap;
+    return S.x + slot * FR;
+}
+
+// Staging of frames k0 .. k0+NF-1 of sample n as bf16 into xin[(k-k0)*FR ...], in two halves so
+// that the global loads of the next sample can be in flight while the current one is computed:
+// stage_load issues every 16-byte load of a thread, stage_store converts (16 pixels -> 16 bf16)
+// and writes two 16-byte LDS stores per load.
+template <int T, int NF> struct Staged {
+    static constexpr int CH = FR / 8, TOT = NF * CH, NL = (TOT + T - 1) / T;
+    uint2 raw[NL];
+};
+template <int T, int NF>
+__device__ __forceinline__ void stage_load(Staged<T, NF> &R, const Src &S, int n, int k0, int tid)
+{
+    using ST = Staged<T, NF>;
+    // the (workgroup-uniform) frame addresses first, so that the slot lookup does not sit
+    // between the frame loads and serialise them
+    const uint8_t *f[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k] = frame_ptr(S, n, k0 + (k < NF ? k : 0));
+#pragma unroll
+    for (int i = 0; i < ST::NL; ++i) {
+        const int t = tid + i * T;
+        if (t < ST::TOT) {
+            const int k = t / ST::CH;
+            const uint8_t *fp = k == 0 ? f[0] : k == 1 ? f[1] : k == 2 ? f[2] : f[3];
+            R.raw[i] = *reinterpret_cast<const uint2 *>(fp + (t % ST::CH) * 8);
+        }
+    }
+}
+// 8 pixels -> 8 bf16 -> one 16-byte LDS store; consecutive lanes write consecutive 16 bytes
+template <int T, int NF>
+__device__ __forceinline__ void stage_store(bf16_t *xin, const Staged<T, NF> &R, int tid)
+{
+    using ST = Staged<T, NF>;
+#pragma unroll
+    for (int i = 0; i < ST::NL; ++i) {
+        const int t = tid + i * T;
+        if (t < ST::TOT) {
+            const uint2 r = R.raw[i];
+            uint4 o;
+            o.x = pack2_u8(r.x & 0xFFu, (r.x >> 8) & 0xFFu);
+            o.y = pack2_u8((r.x >> 16) & 0xFFu, r.x >> 24);
+            o.z = pack2_u8(r.y & 0xFFu, (r.y >> 8) & 0xFFu);
+            o.w = pack2_u8((r.y >> 16) & 0xFFu, r.y >> 24);
+            *reinterpret_cast<uint4 *>(xin + t * 8) = o;  // frames are contiguous in xin: (t/CH)*FR + (t%CH)*8 == t*8
+        }
+    }
+}
+
+struct FwdSeg {
+    Src src;
+    const bf16_t *w;    // [32][256] bf16
+    const float *bias;  // [32]
+    bf16_t *y;          // [n][400][32]
+    int n;              // samples
+    int first;          // index of the segment's first sample in the launch-wide sample list
+};
+struct FwdArgs {
+    FwdSeg seg[3];
+    int nseg;
+    int total;          // samples of all segments
+};
+
+// Persistent workgroups: workgroup b owns samples [b*total/G, (b+1)*total/G) of the launch-wide
+// list, keeps the weights in registers while the segment does not change, and loads the frames
+// of its next sample while it computes the current one.
+__global__ __launch_bounds__(512) void k_conv1_fwd(FwdArgs A)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t xin[XIN];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, h = lane >> 5;
+    const int g0 = (int)((long)blockIdx.x * A.total / gridDim.x);
+    const int g1 = (int)((long)(blockIdx.x + 1) * A.total / gridDim.x);
+    if (g0 >= g1) return;
+
+    auto seg_of = [&](int g) {
+        int s = 0;
+        if (A.nseg > 1 && g >= A.seg[1].first) s = 1;
+        if (A.nseg > 2 && g >= A.seg[2].first) s = 2;
+        return s;
+    };
+    auto pick = [&](int s) {
+        FwdSeg S = A.seg[0];
+        if (s == 1) S = A.seg[1];
+        if (s == 2) S = A.seg[2];
+        return S;
+    };
+
+    Staged<512, 4> R;
+    {
+        FwdSeg S = pick(seg_of(g0));
+        stage_load<512, 4>(R, S.src, g0 - S.first, 0, tid);
+    }
+    v8bf wb[16];
+    int loaded = -1;
+    for (int g = g0; g < g1; ++g) {
+        const int sg = seg_of(g);
+        const FwdSeg S = pick(sg);
+        if (sg != loaded) {
+            // Weight fragments for the 16 reduction steps.  MFMA row i carries output channel
+            // ch(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3), so that the 16 results of a lane
+            // (rows 8g + 4h + j) are the 16 consecutive channels 16h + 4g + j of its pixel.
+            const int ch = 16 * ((li >> 2) & 1) + 4 * (li >> 3) + (li & 3);
+#pragma unroll
+            for (int t = 0; t < 16; ++t)
+                wb[t] = __builtin_bit_cast(v8bf, ld8(S.w + ch * 256 + 16 * t + 8 * h));
+            loaded = sg;
+        }
+        sync_lds();  // the previous sample is no longer read
+        stage_store<512, 4>(xin, R, tid);
+        sync_lds();
+        if (g + 1 < g1) {
+            FwdSeg Sn = pick(seg_of(g + 1));
+            stage_load<512, 4>(R, Sn.src, g + 1 - Sn.first, 0, tid);
+        }
+        bf16_t *y = S.y + (long)(g - S.first) * (400 * 32);
+        // 13 blocks of 32 output pixels (the last one half empty).  Wave w takes blocks w and
+        // w+8 together: two independent accumulator chains hide the LDS latency of each other.
+        {
+            const bool two = wave + 8 < 13;
+            int m0 = wave * 32 + li, m1 = (wave + 8) * 32 + li;
+            if (m1 > 399) m1 = 399;  // rows past the end read a valid pixel and are not stored
+            const bf16_t *px0 = xin + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20);
+            const bf16_t *px1 = xin + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20);
+            v16f acc0 = {0}, acc1 = {0};
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                const int c = t >> 2, p = (2 * t) & 7;  // k = 16t + 8h: channel t/4, kernel row (2t+h)%8
+                const int off = c * FR + (p + h) * 84;
+                const uint2 *q0 = reinterpret_cast<const uint2 *>(px0 + off);
+                uint4 v0 = {q0[0].x, q0[0].y, q0[1].x, q0[1].y};
+                acc0 = mfma(wb[t], __builtin_bit_cast(v8bf, v0), acc0);  // transposed tile
+                if (two) {
+                    const uint2 *q1 = reinterpret_cast<const uint2 *>(px1 + off);
+                    uint4 v1 = {q1[0].x, q1[0].y, q1[1].x, q1[1].y};
+                    acc1 = mfma(wb[t], __builtin_bit_cast(v8bf, v1), acc1);
+                }
+            }
+            // acc[4g + j] = Y[pixel li of the block][channel 16h + 4g + j]: 32 contiguous bytes
+            {
+                constexpr float sc = 1.0f / 255.0f;
+                const float *bp = S.bias + 16 * h;
+                uint2 o0[4], o1[4];
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const v4f bv = *reinterpret_cast<const v4f *>(bp + 4 * g4);
+                    o0[g4] = pack4(fmaxf(acc0[4 * g4] * sc + bv.x, 0.f), fmaxf(acc0[4 * g4 + 1] * sc + bv.y, 0.f),
+                                   fmaxf(acc0[4 * g4 + 2] * sc + bv.z, 0.f), fmaxf(acc0[4 * g4 + 3] * sc + bv.w, 0.f));
+                    o1[g4] = pack4(fmaxf(acc1[4 * g4] * sc + bv.x, 0.f), fmaxf(acc1[4 * g4 + 1] * sc + bv.y, 0.f),
+                                   fmaxf(acc1[4 * g4 + 2] * sc + bv.z, 0.f), fmaxf(acc1[4 * g4 + 3] * sc + bv.w, 0.f));
+                }
+                uint4 *d0 = reinterpret_cast<uint4 *>(y + (wave * 32 + li) * 32 + 16 * h);
+                d0[0] = uint4{o0[0].x, o0[0].y, o0[1].x, o0[1].y};
+                d0[1] = uint4{o0[2].x, o0[2].y, o0[3].x, o0[3].y};
+                const int mm = (wave + 8) * 32 + li;
+                if (two && mm < 400) {
+                    uint4 *d1 = reinterpret_cast<uint4 *>(y + mm * 32 + 16 * h);
+                    d1[0] = uint4{o1[0].x, o1[0].y, o1[1].x, o1[1].y};
+                    d1[1] = uint4{o1[2].x, o1[2].y, o1[3].x, o1[3].y};
+                }
+            }
+        }
+    }
+}
+
+struct WgradArgs {
+    Src src;
+    const bf16_t *dy;  // [B][400][32]
+    float *part;       // [nsplit][32*256 + 32]
+    int B;
+    int nsplit;        // = gridDim.x; workgroup z sums samples z, z+nsplit, ...
+};
+
+constexpr int LDY1 = 40;  // row stride (elements) of the staged dY tile
+
+// grid (nsplit, 2): blockIdx.y selects the channel pair (frames 2y, 2y+1 = im2col columns
+// 128y .. 128y+127), so a workgroup stages half a state and two workgroups fit one CU.
+__global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t xin[2 * FR];
+    __shared__ __attribute__((aligned(16))) bf16_t dys[400 * LDY1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;  // wave = block of 32 im2col columns
+    const int li = lane & 31, h = lane >> 5, s16 = lane & 15, half = (lane >> 4) & 1;
+    const int cp = blockIdx.y;
+    typedef __attribute__((address_space(3))) v4s *lds_v4s;
+
+    // this lane's share of the transpose loads: reduction row offset s/4 (+4 for the second
+    // load), columns 16*half + 4*(s%4) .. +3 of the wave's 32-column block
+    const int rsub = 8 * h + (s16 >> 2);
+    const int kc = 32 * wave + 16 * half + 4 * (s16 & 3);       // column within the pair: (c, p, q0)
+    const int xoff = (kc >> 6) * FR + ((kc >> 3) & 7) * 84 + (kc & 7);
+    const bf16_t *yp = dys + rsub * LDY1 + 16 * half + 4 * (s16 & 3);
+
+    v16f acc = {0}, accb = {0};
+    v8bf ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+    const bool do_bias = cp == 0 && wave == 0;
+
+    Staged<256, 2> R;
+    uint4 ry[7];
+    auto load_sample = [&](int n) {
+        stage_load<256, 2>(R, A.src, n, 2 * cp, tid);
+        const bf16_t *dyn = A.dy + (long)n * (400 * 32);
+#pragma unroll
+        for (int i = 0; i < 7; ++i) {
+            const int t = tid + i * 256;
+            if (t < 1600) ry[i] = ld8(dyn + (t >> 2) * 32 + (t & 3) * 8);
+        }
+    };
+    if ((int)blockIdx.x < A.B) load_sample(blockIdx.x);
+    for (int n = blockIdx.x; n < A.B; n += A.nsplit) {
+        __syncthreads();  // the previous sample's tiles are no longer read
+        stage_store<256, 2>(xin, R, tid);
+#pragma unroll
+        for (int i = 0; i < 7; ++i) {
+            const int t = tid + i * 256;
+            if (t < 1600) *reinterpret_cast<uint4 *>(dys + (t >> 2) * LDY1 + (t & 3) * 8) = ry[i];
+        }
+        __syncthreads();
+        if (n + A.nsplit < A.B) load_sample(n + A.nsplit);  // in flight during the MFMA loop
+#pragma unroll 5
+        for (int t = 0; t < 25; ++t) {  // 16 output pixels per step
+            v8bf fa = frag_tr(yp + 16 * t * LDY1, LDY1);
+            const int m0 = 16 * t + rsub, m1 = m0 + 4;
+            const bf16_t *x0 = xin + xoff + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20);
+            const bf16_t *x1 = xin + xoff + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20);
+            v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x0);
+            v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x1);
+            typedef short v8s __attribute__((ext_vector_type(8)));
+            v8s xb = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            acc = mfma(fa, __builtin_bit_cast(v8bf, xb), acc);
+            if (do_bias) accb = mfma(fa, ones, accb);
+        }
+    }
+
+    float *part = A.part + (long)blockIdx.x * (32 * 256 + 32);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int o = 8 * (r / 4) + 4 * h + (r % 4);
+        part[o * 256 + 128 * cp + 32 * wave + li] = acc[r] * (1.0f / 255.0f);
+        if (do_bias && li == 0) part[32 * 256 + o] = accb[r];
+    }
+}
+}  // namespace c1
 }  // namespace gbf

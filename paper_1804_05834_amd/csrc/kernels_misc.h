@@ -419,9 +419,19 @@ __device__ __forceinline__ float block_max_1024(float v, float *sh /*16*/)
 }
 
 // Proportional sampling (Eq.10, Eq.12): one thread per draw, single workgroup.
+// Optional per-slot transition data to carry along with the draw.
+struct MetaGather {
+    const int32_t *meta_a;
+    const float *meta_r;
+    const uint8_t *meta_done;
+    int32_t *a;
+    float *r;
+    uint8_t *done;
+};
+
 __global__ __launch_bounds__(1024) void k_per_sample(const float *tree, long L, long size, int B,
                                                      float beta, uint64_t seed, int stratified,
-                                                     int32_t *idx, float *is_w)
+                                                     int32_t *idx, float *is_w, MetaGather G)
 {
     __shared__ float sh[16];
     const int j = threadIdx.x;
@@ -450,6 +460,11 @@ __global__ __launch_bounds__(1024) void k_per_sample(const float *tree, long L, 
     if (j < B) {
         idx[j] = (int32_t)slot;
         is_w[j] = wr / wmax;
+        if (G.a) {
+            G.a[j] = G.meta_a[slot];
+            G.r[j] = G.meta_r[slot];
+            G.done[j] = G.meta_done[slot];
+        }
     }
 }
 
