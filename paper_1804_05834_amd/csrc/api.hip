@@ -745,11 +745,11 @@ int32_t per_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, int32_
     if (!idx || !is_w || !aligned(idx, 4) || !aligned(is_w, 4)) return fail(c, DQN_ERR_INVALID_ARG, "per_sample: NULL or misaligned output");
     if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "per_sample: beta must be >= 0");
     hipStream_t st = (hipStream_t)stream;
-    const int block = (B + 63) / 64 * 64;
     launch(c, "per_sample", st, [&] {
-        misc::k_per_sample<<<1, block, 0, st>>>(c->tree, c->L, c->stored, B, beta, draw_seed,
-                                                c->cfg.per_stratified, idx, is_w, misc::MetaGather{});
+        misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(c->tree, c->L, c->levels, c->stored, B, beta, draw_seed,
+                                                        c->cfg.per_stratified, idx, is_w, misc::MetaGather{});
     });
+    launch(c, "per_normalise", st, [&] { misc::k_per_normalise<<<1, 1024, 0, st>>>(is_w, B); });
     return hip_status(c, "per_sample");
 }
 
@@ -845,11 +845,11 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     } else {
         if (cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "dqn_train_step: replay is empty");
         if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: beta must be >= 0");
-        const int block = (B + 63) / 64 * 64;
+        // raw importance weights; the head kernel divides by their maximum
         launch(c, "per_sample", st, [&] {
-            misc::k_per_sample<<<1, block, 0, st>>>(c->tree, c->L, c->stored, B, beta, draw_seed, cfg.per_stratified,
-                                                    w.b_idx, w.b_w,
-                                                    misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done});
+            misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(c->tree, c->L, c->levels, c->stored, B, beta, draw_seed,
+                                                            cfg.per_stratified, w.b_idx, w.b_w,
+                                                            misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done});
         });
         a = w.b_a; r = w.b_r; done = w.b_done; isw = w.b_w;
         if (cfg.precision == 1) {
@@ -879,7 +879,7 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     H.kappa = cfg.huber_delta; H.gamma = cfg.gamma;
     H.f1b_on = c->theta + net::F1B; H.f1b_tg = c->theta_t + net::F1B;
     H.head_on = c->theta + net::HEAD; H.head_tg = c->theta_t + net::HEAD;
-    H.a = a; H.r = r; H.done = done; H.w = isw;
+    H.a = a; H.r = r; H.done = done; H.w = isw; H.w_raw = batch ? 0 : 1;
     H.h_s = w.h_s; H.dh = w.dh; H.dh_bf16 = cfg.precision == 1; H.dA = w.dA; H.td_abs = w.td_abs; H.loss_j = w.loss_j;
     H.q_s = O.q_s; H.q_no = O.q_next_online; H.q_nt = O.q_next_target; H.y = O.y; H.td = O.td;
     H.a_star = O.a_star; H.is_w = O.is_w;

@@ -32,6 +32,19 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+__device__ __forceinline__ float block_max_1024(float v, float *sh /*16*/)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float r = sh[0];
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r = fmaxf(r, sh[w]);
+    return r;
+}
+
 // ------------------------------------------------------------------ head
 // Rows of the head: dueling -> row 0 is the state value V, rows 1..K the
 // advantages (Eq.13); plain -> rows 0..K-1 are the Q outputs.  Offsets are
@@ -106,6 +119,7 @@ struct HeadArgs {
     const float *r;
     const uint8_t *done;
     const float *w;  // may be nullptr
+    int w_raw;       // 1: w holds unnormalised importance weights; divide by their maximum here
     float *h_s;      // [B][512] hidden layer of the online net on s
     void *dh;        // [B][512] gradient w.r.t. the fc1 pre-activation (fp32, or bf16 if dh_bf16)
     int dh_bf16;
@@ -127,8 +141,15 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
     __shared__ float raw[3][MAXR];
     __shared__ float q[3][64];
     __shared__ float dA[MAXR];
+    __shared__ float shm[16];
     const int j = blockIdx.x, tid = threadIdx.x;
     const int K = A.K, R = K + (A.dueling ? 1 : 0);
+    float wnorm = 1.f;
+    if (A.w && A.w_raw) {  // maximum of the minibatch's raw importance weights (Alg.2 weighting line)
+        float m = 0.f;
+        for (int t = tid; t < A.B; t += 512) m = fmaxf(m, A.w[t]);
+        wnorm = 1.f / block_max_1024(m, shm);
+    }
 
     {
         const int i = tid;  // one hidden unit per thread
@@ -151,7 +172,7 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         const float boot = A.done[j] ? 0.f : A.gamma * q[2][as];
         const float y = A.r[j] + boot;
         const float d = y - q[0][aj];
-        const float w = A.w ? A.w[j] : 1.f;
+        const float w = A.w ? A.w[j] * wnorm : 1.f;
         float l, dl;
         if (A.loss_kind == 1 && fabsf(d) > A.kappa) {
             l = A.kappa * (fabsf(d) - 0.5f * A.kappa);
@@ -405,20 +426,7 @@ __global__ void k_tree_level(float *tree, long first, long count)
     tree[node] = tree[2 * node] + tree[2 * node + 1];
 }
 
-__device__ __forceinline__ float block_max_1024(float v, float *sh /*16*/)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    __syncthreads();
-    if (lane == 0) sh[wave] = v;
-    __syncthreads();
-    float r = sh[0];
-    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r = fmaxf(r, sh[w]);
-    return r;
-}
 
-// Proportional sampling (Eq.10, Eq.12): one thread per draw, single workgroup.
 // Optional per-slot transition data to carry along with the draw.
 struct MetaGather {
     const int32_t *meta_a;
@@ -429,43 +437,68 @@ struct MetaGather {
     uint8_t *done;
 };
 
-__global__ __launch_bounds__(1024) void k_per_sample(const float *tree, long L, long size, int B,
-                                                     float beta, uint64_t seed, int stratified,
-                                                     int32_t *idx, float *is_w, MetaGather G)
+// Proportional sampling (Eq.10, Eq.12), one WAVE per draw.  The descent is the
+// sequential rule "z < left ? go left : (z -= left, go right)" in fp32, but the
+// memory side is batched: at a node x the wave fetches the whole 6-level subtree
+// below x in one round trip (lane l reads local heap node l of levels 1..5 and
+// node l of level 6), then walks those 6 levels out of registers with lane
+// shuffles.  20 levels cost 4 dependent round trips instead of 20, and every
+// fetch is a contiguous run of the heap array.
+// is_w receives the RAW weight (N P(j))^-beta; k_per_normalise (or the consumer)
+// divides by the minibatch maximum.
+__global__ __launch_bounds__(256) void k_per_sample(const float *tree, long L, int levels, long size, int B,
+                                                    float beta, uint64_t seed, int stratified,
+                                                    int32_t *idx, float *is_w, MetaGather G)
 {
-    __shared__ float sh[16];
-    const int j = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= B) return;
     const float total = tree[1];
-    float wr = 0.f;
-    long slot = 0;
-    if (j < B) {
-        const float u = draw_u24(seed, (uint64_t)j);
-        float z = stratified ? __fmul_rn((float)j + u, total / (float)B) : __fmul_rn(u, total);
-        long node = 1;
-        while (node < L) {
-            float left = tree[2 * node];
+    const float u = draw_u24(seed, (uint64_t)j);
+    float z = stratified ? __fmul_rn((float)j + u, total / (float)B) : __fmul_rn(u, total);
+    long node = 1;
+    const int lj = lane >= 2 ? 31 - __clz(lane) : 0;  // level of local heap node `lane`
+    for (int done = 0; done < levels;) {
+        const int r = min(6, levels - done);  // levels walked in this round
+        float va = 0.f, vb = 0.f;
+        if (lane >= 2 && lane < (2 << min(r, 5))) va = tree[(node << lj) + (lane - (1 << lj))];
+        if (r == 6) vb = tree[(node << 6) + lane];
+        int cur = 1;  // local heap index
+        for (int t = 0; t < r; ++t) {
+            const int c = 2 * cur;  // left child
+            const float left = c < 64 ? __shfl(va, c, 64) : __shfl(vb, c - 64, 64);
             if (z < left) {
-                node = 2 * node;
+                cur = c;
             } else {
                 z = z - left;
-                node = 2 * node + 1;
+                cur = c + 1;
             }
         }
-        slot = node - L;
-        if (slot > size - 1) slot = size - 1;
-        double P = (double)tree[L + slot] / (double)total;
-        wr = (float)pow((double)size * P, -(double)beta);
+        node = (node << r) + (cur - (1 << r));
+        done += r;
     }
-    const float wmax = block_max_1024(wr, sh);
-    if (j < B) {
+    if (lane == 0) {
+        long slot = node - L;
+        if (slot > size - 1) slot = size - 1;
+        const double P = (double)tree[L + slot] / (double)total;
         idx[j] = (int32_t)slot;
-        is_w[j] = wr / wmax;
+        is_w[j] = (float)pow((double)size * P, -(double)beta);
         if (G.a) {
             G.a[j] = G.meta_a[slot];
             G.r[j] = G.meta_r[slot];
             G.done[j] = G.meta_done[slot];
         }
     }
+}
+
+// w_j <- w_j / max_j w_j over the minibatch (single workgroup)
+__global__ __launch_bounds__(1024) void k_per_normalise(float *is_w, int B)
+{
+    __shared__ float sh[16];
+    const int j = threadIdx.x;
+    const float w = j < B ? is_w[j] : 0.f;
+    const float wmax = block_max_1024(w, sh);
+    if (j < B) is_w[j] = w / wmax;
 }
 
 // Priority update (Eq.11): single workgroup of 1024 threads, one thread per
