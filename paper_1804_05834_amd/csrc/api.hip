@@ -120,7 +120,8 @@ struct dqn_ctx {
     // the input-gradient chain of the backward pass
     int num_cu = 256;  // compute units of the device
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_join = nullptr;
+    hipStream_t side2 = nullptr;  // the single-workgroup priority update gets a lane of its own
+    hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_join = nullptr, ev_join2 = nullptr;
     bool prof = false;
     std::vector<ProfRec> recs;
     std::string err;
@@ -619,11 +620,13 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
     }
     // side stream at the default priority; if anything fails the step simply runs on one stream
     if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) c->side = nullptr;
-    hipEvent_t *evs[4] = {&c->ev_fork, &c->ev_a, &c->ev_b, &c->ev_join};
+    if (c->side && hipStreamCreateWithFlags(&c->side2, hipStreamNonBlocking) != hipSuccess) c->side2 = nullptr;
+    hipEvent_t *evs[5] = {&c->ev_fork, &c->ev_a, &c->ev_b, &c->ev_join, &c->ev_join2};
     for (hipEvent_t *e : evs)
         if (c->side && hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) {
             (void)hipStreamDestroy(c->side);
-            c->side = nullptr;
+            if (c->side2) (void)hipStreamDestroy(c->side2);
+            c->side = c->side2 = nullptr;
         }
     (void)hipGetLastError();
     *out = c;
@@ -637,11 +640,12 @@ int32_t dqn_destroy(dqn_ctx *ctx)
         (void)hipEventDestroy(r.e0);
         (void)hipEventDestroy(r.e1);
     }
-    if (ctx->side) {
-        (void)hipStreamSynchronize(ctx->side);
-        (void)hipStreamDestroy(ctx->side);
-    }
-    for (hipEvent_t e : {ctx->ev_fork, ctx->ev_a, ctx->ev_b, ctx->ev_join})
+    for (hipStream_t sx : {ctx->side, ctx->side2})
+        if (sx) {
+            (void)hipStreamSynchronize(sx);
+            (void)hipStreamDestroy(sx);
+        }
+    for (hipEvent_t e : {ctx->ev_fork, ctx->ev_a, ctx->ev_b, ctx->ev_join, ctx->ev_join2})
         if (e) (void)hipEventDestroy(e);
     delete ctx;
     return DQN_OK;
@@ -891,9 +895,12 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     ev_wait(sd, c->ev_fork, st);
     misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
     launch(c, "head_wgrad", sd, [&] { misc::k_head_wgrad<<<dim3(c->R, 4), 512, 0, sd>>>(HW); });
+    hipStream_t sp = (c->side2 && sd != st) ? c->side2 : sd;
     if (!batch) {
-        rc = per_update(c, w.b_idx, w.td_abs, B, (void *)sd);
+        ev_wait(sp, c->ev_fork, st);
+        rc = per_update(c, w.b_idx, w.td_abs, B, (void *)sp);
         if (rc) return rc;
+        if (sp != sd) (void)hipEventRecord(c->ev_join2, sp);
     }
 
     int ns1, ns2, ns3;
@@ -919,6 +926,8 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
         RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps;
         launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
     }
+    // whatever follows on the caller's stream (the next step's sampling) sees the updated tree
+    if (!batch && sp != sd) (void)hipStreamWaitEvent(st, c->ev_join2, 0);
     return hip_status(c, "dqn_train_step");
 }
 

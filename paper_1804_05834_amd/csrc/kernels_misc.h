@@ -25,6 +25,13 @@ __host__ __device__ __forceinline__ float draw_u24(uint64_t seed, uint64_t ctr)
     return (float)(mix64(seed, ctr) >> 40) * (1.0f / 16777216.0f);
 }
 
+// Barrier that orders LDS traffic only: global loads and stores issued earlier stay in flight
+// across it (__syncthreads() would first wait for every one of them to complete).
+__device__ __forceinline__ void sync_lds()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -502,66 +509,105 @@ __global__ __launch_bounds__(1024) void k_per_normalise(float *is_w, int B)
 }
 
 // Priority update (Eq.11): single workgroup of 1024 threads, one thread per
-// entry; the tree is repaired level by level with a barrier between levels.
-//  * "last occurrence wins": every entry first stamps its leaf with -1, then
-//    with the integer maximum of the entry numbers that name the leaf (an
-//    integer max has one result whatever the order); the entry that reads its
-//    own number back is the writer.
-//  * Every node a thread will need (the children of all its ancestors) is
-//    requested up front so the dependent chain later runs out of cache.
-//  * The top PU_TOP levels are rebuilt in LDS from the 2^PU_TOP nodes below
-//    them (recomputing an untouched node as left+right reproduces its bits).
-constexpr int PU_TOP = 13;
+// entry, ONE round trip to memory.  Each thread first requests the sibling of
+// every node on its leaf-to-root path (independent loads), then the tree is
+// repaired level by level entirely on chip: at each level the threads publish
+// (node, new value) in an LDS hash table, look their sibling up there -- a hit
+// means another entry of this batch changed the sibling's subtree, a miss means
+// the preloaded value is still valid -- and form parent = left + right (fp32,
+// commutative, so bit-identical to a sequential repair).  "Last occurrence
+// wins" for repeated slots is an integer maximum over entry numbers in the
+// same table.  New node values are stored as they are produced; entries that
+// share a node store identical values.
+constexpr int PU_SLOTS = 2048;  // hash slots (at most 1024 live keys)
+__device__ __forceinline__ int pu_hash(int key) { return (int)(((unsigned)key * 2654435761u) >> 21); }
+// returns the slot of `key`; *first is set when this call created it
+__device__ __forceinline__ int pu_insert(int *keys, int key, bool *first)
+{
+    int h = pu_hash(key);
+    for (;;) {
+        const int old = atomicCAS(&keys[h], -1, key);
+        if (old == -1 || old == key) {
+            *first = old == -1;
+            return h;
+        }
+        h = (h + 1) & (PU_SLOTS - 1);
+    }
+}
+__device__ __forceinline__ int pu_find(const int *keys, int key)
+{
+    int h = pu_hash(key);
+    for (;;) {
+        const int k = keys[h];
+        if (k == key) return h;
+        if (k == -1) return -1;
+        h = (h + 1) & (PU_SLOTS - 1);
+    }
+}
+
 __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int levels, long size,
                                                      const int32_t *idx, const float *td_abs, int n,
                                                      float alpha, float eps)
 {
+    __shared__ int keys[PU_SLOTS];
+    __shared__ int ivals[PU_SLOTS];  // entry number (level 0) or float bits of a node value
+    __shared__ float leafv[1024];
     __shared__ float sh[16];
-    __shared__ float top[2 << PU_TOP];
     const int j = threadIdx.x;
     int my = -1;
     float p = 0.f;
     if (j < n) {
-        int v = idx[j];
+        const int v = idx[j];
         if (v >= 0 && v < size) my = v;
         p = (float)((double)fabsf(td_abs[j]) + (double)eps);
     }
     const bool valid = my >= 0;
-    int *leaf_i = reinterpret_cast<int *>(tree + L + (valid ? my : 0));
-    float warm = 0.f;
-    if (valid) {
-        long nd = (L + my) >> 1;
+    // siblings along the path, requested back to back (levels <= 31)
+    float sib[32];
+    {
+        long nd = L + (valid ? my : 0);
 #pragma unroll
-        for (int l = 0; l < 32; ++l, nd >>= 1)  // fixed trip count: all loads issue back to back
-            if (l < levels) warm += tree[2 * nd] + tree[2 * nd + 1];
-        *leaf_i = -1;
+        for (int l = 0; l < 32; ++l, nd >>= 1) sib[l] = (valid && l < levels) ? tree[nd ^ 1] : 0.f;
     }
-    const float leaf = (float)pow((double)p, (double)alpha);
+    leafv[j] = (float)pow((double)p, (double)alpha);
+    for (int t = j; t < PU_SLOTS; t += 1024) { keys[t] = -1; ivals[t] = -1; }
     __syncthreads();
-    if (valid) atomicMax(leaf_i, j);
+    int node = (int)L + (valid ? my : 0);
+    bool first;
+    if (valid) atomicMax(&ivals[pu_insert(keys, node, &first)], j);
     const float pmax = block_max_1024(valid ? p : 0.f, sh);  // contains barriers
     if (j == 0) tree[2 * L] = fmaxf(tree[2 * L], pmax);
-    if (warm == -1.2345e38f) tree[0] = warm;  // never true for sums of priorities; keeps the loads
-    const bool writer = valid && __hip_atomic_load(leaf_i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == j;
-    __syncthreads();
-    if (writer) tree[L + my] = leaf;
-    long node = L + (valid ? my : 0);
-    __syncthreads();
-    const int ltop = levels < PU_TOP ? levels : PU_TOP;  // levels rebuilt in LDS
-    for (int l = 0; l < levels - ltop; ++l) {
-        node >>= 1;
-        if (valid) tree[node] = tree[2 * node] + tree[2 * node + 1];
-        __syncthreads();
+    // One thread carries each distinct node upwards: at the leaves the last entry naming the
+    // slot, above them whichever thread publishes a node first.  Paths that merge retire all
+    // but one carrier, so no hash slot is ever contended by more than two threads.
+    bool active = false;
+    float v = 0.f;
+    if (valid) {
+        active = ivals[pu_find(keys, node)] == j;
+        v = leafv[j];
+        if (active) tree[node] = v;
     }
-    // tree level `ltop` (2^ltop nodes, heap index 2^ltop + t) is now final: rebuild above it
-    const int wtop = 1 << ltop;
-    for (int t = j; t < wtop; t += blockDim.x) top[wtop + t] = tree[wtop + t];
-    __syncthreads();
-    for (int wdt = wtop >> 1; wdt >= 1; wdt >>= 1) {
-        for (int t = j; t < wdt; t += blockDim.x) top[wdt + t] = top[2 * (wdt + t)] + top[2 * (wdt + t) + 1];
-        __syncthreads();
+#pragma unroll
+    for (int l = 0; l < 32; ++l) {
+        if (l < levels) {  // uniform
+            sync_lds();  // the node stores of earlier levels keep draining
+            for (int t = j; t < PU_SLOTS; t += 1024) keys[t] = -1;
+            sync_lds();  // the node stores of earlier levels keep draining
+            if (active) {
+                const int h = pu_insert(keys, node, &first);
+                if (first) ivals[h] = __float_as_int(v);
+                else active = false;  // another carrier already holds this node (same value)
+            }
+            sync_lds();  // the node stores of earlier levels keep draining
+            if (active) {
+                const int hs = pu_find(keys, node ^ 1);
+                const float vs = hs >= 0 ? __int_as_float(ivals[hs]) : sib[l];
+                v = v + vs;
+                node >>= 1;
+                tree[node] = v;
+            }
+        }
     }
-    for (int t = j; t < wtop - 1; t += blockDim.x) tree[1 + t] = top[1 + t];
 }
 
 // --------------------------------------------------------------- replay
