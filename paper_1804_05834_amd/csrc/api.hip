@@ -273,21 +273,24 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
         return tile;
     };
 
+    // Few rows (small batches): the reduction slab of every stage is sliced over extra waves
+    // (KS > 1), which shortens the dependent chain of stages per tile.
+    const bool small = rows * 81 < 64 * 512;
     {  // conv1
         FwdArgs A{};
-        int tiles = build(A, 128, 400, [&](int i) { return (const void *)pass[i].x; },
+        int tiles = build(A, small ? 64 : 128, 400, [&](int i) { return (const void *)pass[i].x; },
                           [&](int i) { return pass[i].xs; }, net::C1W, net::C1B, act1, net::A1, true);
         A.klen = GConv1::K; A.split_stride = 0; A.scale = 1.0f / 255.0f;
-        launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 128, 32><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+        if (small) launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 64, 32, 4><<<dim3(tiles, 1, 1), 512, 0, st>>>(A); });
+        else launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 128, 32><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
     }
-    const bool small = rows * 81 < 64 * 512;  // few rows: smaller tiles, more workgroups
     {  // conv2
         FwdArgs A{};
         int BM = small ? 32 : 64;
         int tiles = build(A, BM, 81, [&](int i) { return (const void *)(act1 + row0[i] * net::A1); },
                           [&](int) { return (long)net::A1; }, net::C2W, net::C2B, act2, net::A2, true);
         A.klen = GConv2::K; A.split_stride = 0; A.scale = 1.0f;
-        if (small) launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 32, 64><<<dim3(tiles, 1, 1), 128, 0, st>>>(A); });
+        if (small) launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 32, 64, 4><<<dim3(tiles, 1, 1), 512, 0, st>>>(A); });
         else launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 64, 64><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
     }
     {  // conv3
@@ -296,7 +299,7 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
         int tiles = build(A, BM, 49, [&](int i) { return (const void *)(act2 + row0[i] * net::A2); },
                           [&](int) { return (long)net::A2; }, net::C3W, net::C3B, act3, net::A3, true);
         A.klen = GConv3::K; A.split_stride = 0; A.scale = 1.0f;
-        if (small) launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 32, 64><<<dim3(tiles, 1, 1), 128, 0, st>>>(A); });
+        if (small) launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 32, 64, 3><<<dim3(tiles, 1, 1), 384, 0, st>>>(A); });
         else launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 64, 64><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
     }
     {  // fc1: raw partial sums per reduction split; the head kernels finish it
@@ -305,7 +308,8 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
         int tiles = build(A, 32, 1, [&](int i) { return (const void *)(act3 + row0[i] * net::A3); },
                           [&](int) { return (long)net::A3; }, net::F1W, net::F1B, w.f1part, net::HID, false);
         A.klen = GFc1::K / ns; A.split_stride = rows * net::HID; A.scale = 1.0f;
-        launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 32, 64><<<dim3(tiles, 8, ns), 128, 0, st>>>(A); });
+        if (ns == 14) launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 32, 32, 7><<<dim3(tiles, 16, ns), 448, 0, st>>>(A); });
+        else launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 32, 64><<<dim3(tiles, 8, ns), 128, 0, st>>>(A); });
         *nsplit_out = ns;
         *split_stride_out = rows * net::HID;
     }
@@ -431,7 +435,8 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     int rps;
     {
         DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
-        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
+        if (small) launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 32, 4><<<dim3((B + 31) / 32, 98, 1), 256, 0, st>>>(D); });
+        else launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
         ev_record(c->ev_a, st, sd);
         WgradArgs G{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
         launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
@@ -439,7 +444,7 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     {
         DgradArgs D{d3, c->theta + net::C3W, act2, d2, B};
         long M = (long)B * 81;
-        if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 64><<<dim3((M + 31) / 32, 1, 1), 128, 0, st>>>(D); });
+        if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 64, 3><<<dim3((M + 31) / 32, 1, 1), 384, 0, st>>>(D); });
         else launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_b, st, sd);
         split_rows((long)B * 49, 9, MAX_WSPLIT, 32, &rps, ns3);
@@ -450,7 +455,7 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     {
         DgradArgs D{d2, c->theta + net::C2W, act1, d1, B};
         long M = (long)B * 100;
-        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
+        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 64, 32, 4><<<dim3((M + 63) / 64, 1, 4), 512, 0, st>>>(D); });
         split_rows((long)B * 81, 8, MAX_WSPLIT, 32, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
         ev_wait(sd, c->ev_b, st);
@@ -619,7 +624,10 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
             c->num_cu = cus;
     }
     // side stream at the default priority; if anything fails the step simply runs on one stream
-    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) c->side = nullptr;
+    // (DQN_SINGLE_STREAM=1 in the environment keeps everything on the caller's stream)
+    const char *single = std::getenv("DQN_SINGLE_STREAM");
+    if ((single && single[0] == '1') || hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess)
+        c->side = nullptr;
     if (c->side && hipStreamCreateWithFlags(&c->side2, hipStreamNonBlocking) != hipSuccess) c->side2 = nullptr;
     hipEvent_t *evs[5] = {&c->ev_fork, &c->ev_a, &c->ev_b, &c->ev_join, &c->ev_join2};
     for (hipEvent_t *e : evs)

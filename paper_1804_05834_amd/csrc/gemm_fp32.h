@@ -104,15 +104,45 @@ struct FwdArgs {
     float scale;        // multiplies the accumulated sum (1/255 for conv1)
 };
 
-template <class G, int BM, int BN>
-__global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_fwd(FwdArgs A)
+// KS > 1 cuts every staged reduction slab into KS slices of 32, one per group of waves: the
+// workgroup then has KS times the threads, the same loads per thread and KS times the bytes in
+// flight, and the reduction loop is KS times shorter.  The KS partial tiles are added through
+// LDS at the end.  This is what the small-batch launches use: with few rows there are few
+// tiles, and a long dependent chain of short stages per tile is pure latency.
+template <int NWT, int KS>
+__device__ __forceinline__ void reduce_slices(v16f &acc, float *red /*LDS, (KS-1)*NWT*1024 floats*/, int ks,
+                                              int w2, int lane)
 {
-    constexpr int T = (BM / 32) * (BN / 32) * 64;
-    constexpr int NA = BM * 8 / T, NB = BN * 8 / T;
-    static_assert(NA * T == BM * 8 && NB * T == BN * 8, "tile/threads mismatch");
+    if constexpr (KS > 1) {
+        __syncthreads();  // every wave is done reading the staged tiles
+        if (ks > 0) {
+            float *dst = red + ((ks - 1) * NWT + w2) * 1024;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dst[r * 64 + lane] = acc[r];
+        }
+        __syncthreads();
+        if (ks == 0) {
+#pragma unroll
+            for (int s = 0; s < KS - 1; ++s) {
+                const float *src = red + (s * NWT + w2) * 1024;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] += src[r * 64 + lane];
+            }
+        }
+    }
+}
+
+template <class G, int BM, int BN, int KS = 1>
+__global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_fwd(FwdArgs A)
+{
+    constexpr int NWT = (BM / 32) * (BN / 32), T = NWT * KS * 64;
+    constexpr int BKS = BK * KS, LD = BKS + 4, CPR = BKS / 4, RPP = T / CPR;
+    constexpr int NA = BM * CPR / T, NB = BN * CPR / T;
+    static_assert(NA * T == BM * CPR && NB * T == BN * CPR && G::K % BKS == 0, "tile/threads mismatch");
+    static_assert((BM + BN) * LD >= (KS - 1) * NWT * 1024, "reduction scratch does not fit the tiles");
     using in_t = typename G::in_t;
-    __shared__ __attribute__((aligned(16))) float As[BM * LDK];
-    __shared__ __attribute__((aligned(16))) float Bs[BN * LDK];
+    __shared__ __attribute__((aligned(16))) float smem[(BM + BN) * LD];
+    float *As = smem, *Bs = smem + BM * LD;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bx = blockIdx.x;
@@ -123,11 +153,11 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_fwd(FwdArgs A)
     const int kbeg = blockIdx.z * A.klen, kend = kbeg + A.klen;
     const in_t *x = static_cast<const in_t *>(S.x);
 
-    const int lr = tid >> 3, kq = (tid & 7) * 4;
+    const int lr = tid / CPR, kq = (tid % CPR) * 4;
     long aoff[NA];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        int m = m0 + lr + i * (T / 8);
+        int m = m0 + lr + i * RPP;
         aoff[i] = m < S.M ? G::row_off(m, S.xs) : -1;
     }
     v4f ra[NA], rb[NB];
@@ -137,27 +167,28 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_fwd(FwdArgs A)
         for (int i = 0; i < NA; ++i) ra[i] = aoff[i] >= 0 ? ld4(x + aoff[i] + ko) : v4f{0, 0, 0, 0};
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            rb[i] = ld4(S.w + (long)(n0 + lr + i * (T / 8)) * G::K + k0 + kq);
+            rb[i] = ld4(S.w + (long)(n0 + lr + i * RPP) * G::K + k0 + kq);
     };
     auto sstore = [&]() {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) *reinterpret_cast<v4f *>(&As[(lr + i * (T / 8)) * LDK + kq]) = ra[i];
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<v4f *>(&As[(lr + i * RPP) * LD + kq]) = ra[i];
 #pragma unroll
-        for (int i = 0; i < NB; ++i) *reinterpret_cast<v4f *>(&Bs[(lr + i * (T / 8)) * LDK + kq]) = rb[i];
+        for (int i = 0; i < NB; ++i) *reinterpret_cast<v4f *>(&Bs[(lr + i * RPP) * LD + kq]) = rb[i];
     };
 
-    const int wm = wave % (BM / 32), wn = wave / (BM / 32);
+    const int ks = wave / NWT, w2 = wave % NWT;
+    const int wm = w2 % (BM / 32), wn = w2 / (BM / 32);
     const int li = lane & 31, h = lane >> 5;
-    const float *ap = &As[(wm * 32 + li) * LDK + 4 * h];
-    const float *bp = &Bs[(wn * 32 + li) * LDK + 4 * h];
+    const float *ap = &As[(wm * 32 + li) * LD + ks * BK + 4 * h];
+    const float *bp = &Bs[(wn * 32 + li) * LD + ks * BK + 4 * h];
     v16f acc = {0};
 
     gload(kbeg);
     sstore();
     __syncthreads();
-    for (int k0 = kbeg; k0 < kend; k0 += BK) {
-        const bool more = k0 + BK < kend;
-        if (more) gload(k0 + BK);
+    for (int k0 = kbeg; k0 < kend; k0 += BKS) {
+        const bool more = k0 + BKS < kend;
+        if (more) gload(k0 + BKS);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 8) {
             v4f a = ld4(ap + kk), b = ld4(bp + kk);
@@ -172,6 +203,8 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_fwd(FwdArgs A)
             __syncthreads();
         }
     }
+    reduce_slices<NWT, KS>(acc, smem, ks, w2, lane);
+    if (ks != 0) return;
 
     float *y = S.y + (long)blockIdx.z * A.split_stride;
     const int col = n0 + wn * 32 + li;
@@ -216,28 +249,30 @@ struct DgradArgs {
     int B;
 };
 
-template <class D, int BM, int BN>
-__global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_dgrad(DgradArgs A)
+template <class D, int BM, int BN, int KS = 1>
+__global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_dgrad(DgradArgs A)
 {
-    constexpr int T = (BM / 32) * (BN / 32) * 64;
-    constexpr int NA = BM * 8 / T;
+    constexpr int NWT = (BM / 32) * (BN / 32), T = NWT * KS * 64;
+    constexpr int BKS = BK * KS, LD = BKS + 4, CPR = BKS / 4, RPP = T / CPR;
+    constexpr int NA = BM * CPR / T;
     constexpr int LDB = BN + 4;            // LDS row stride of the [k][c] weight tile
     constexpr int BROWS = T / (BN / 4);    // weight-tile rows filled per pass
-    constexpr int NBL = BK / BROWS;
-    static_assert(NA * T == BM * 8 && NBL * BROWS == BK, "tile/threads mismatch");
-    __shared__ __attribute__((aligned(16))) float As[BM * LDK];
-    __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
+    constexpr int NBL = BKS / BROWS;
+    static_assert(NA * T == BM * CPR && NBL * BROWS == BKS && D::K % BKS == 0 && D::CO % 4 == 0, "tile/threads mismatch");
+    static_assert(BM * LD + BKS * LDB >= (KS - 1) * NWT * 1024, "reduction scratch does not fit the tiles");
+    __shared__ __attribute__((aligned(16))) float smem[BM * LD + BKS * LDB];
+    float *As = smem, *Bs = smem + BM * LD;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
     const int ca = blockIdx.z / D::S, cb = blockIdx.z % D::S;
     const int Mc = A.B * D::PP;
 
-    const int lr = tid >> 3, kq = (tid & 7) * 4;
+    const int lr = tid / CPR, kq = (tid % CPR) * 4;
     int rn[NA], rh[NA], rw[NA];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        int m = m0 + lr + i * (T / 8);
+        int m = m0 + lr + i * RPP;
         if (m < Mc) {
             rn[i] = m / D::PP;
             int r = m % D::PP;
@@ -250,41 +285,44 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_dgrad(DgradArgs 
     const int br = tid / (BN / 4), bc = (tid % (BN / 4)) * 4;
     v4f ra[NA], rb[NBL];
     auto gload = [&](int k0) {
-        const int tap = k0 / D::CO, o0 = k0 % D::CO;
-        const int u = tap / D::TW, v = tap % D::TW;
+        {   // a staged slab may span several kernel taps: each thread derives the tap of its chunk
+            const int k = k0 + kq, tap = k / D::CO, o = k % D::CO;
+            const int u = tap / D::TW, v = tap % D::TW;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            int ii = rh[i] - u, jj = rw[i] - v;
-            bool ok = rn[i] >= 0 && ii >= 0 && ii < D::OH && jj >= 0 && jj < D::OW;
-            ra[i] = ok ? ld4(A.dy + ((long)(rn[i] * D::OH + ii) * D::OW + jj) * D::CO + o0 + kq)
-                       : v4f{0, 0, 0, 0};
+            for (int i = 0; i < NA; ++i) {
+                int ii = rh[i] - u, jj = rw[i] - v;
+                bool ok = rn[i] >= 0 && ii >= 0 && ii < D::OH && jj >= 0 && jj < D::OW;
+                ra[i] = ok ? ld4(A.dy + ((long)(rn[i] * D::OH + ii) * D::OW + jj) * D::CO + o)
+                           : v4f{0, 0, 0, 0};
+            }
         }
-        const int p = ca + D::S * u, q = cb + D::S * v;
 #pragma unroll
         for (int i = 0; i < NBL; ++i) {
-            int o = o0 + br + i * BROWS;
+            const int k = k0 + br + i * BROWS, tap = k / D::CO, o = k % D::CO;
+            const int p = ca + D::S * (tap / D::TW), q = cb + D::S * (tap % D::TW);
             rb[i] = ld4(A.w + ((long)(o * D::KH + p) * D::KW + q) * D::CI + n0 + bc);
         }
     };
     auto sstore = [&]() {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) *reinterpret_cast<v4f *>(&As[(lr + i * (T / 8)) * LDK + kq]) = ra[i];
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<v4f *>(&As[(lr + i * RPP) * LD + kq]) = ra[i];
 #pragma unroll
         for (int i = 0; i < NBL; ++i) *reinterpret_cast<v4f *>(&Bs[(br + i * BROWS) * LDB + bc]) = rb[i];
     };
 
-    const int wm = wave % (BM / 32), wn = wave / (BM / 32);
+    const int ks = wave / NWT, w2 = wave % NWT;
+    const int wm = w2 % (BM / 32), wn = w2 / (BM / 32);
     const int li = lane & 31, h = lane >> 5;
-    const float *ap = &As[(wm * 32 + li) * LDK + 4 * h];
-    const float *bp = &Bs[(4 * h) * LDB + wn * 32 + li];
+    const float *ap = &As[(wm * 32 + li) * LD + ks * BK + 4 * h];
+    const float *bp = &Bs[(ks * BK + 4 * h) * LDB + wn * 32 + li];
     v16f acc = {0};
 
     gload(0);
     sstore();
     __syncthreads();
-    for (int k0 = 0; k0 < D::K; k0 += BK) {
-        const bool more = k0 + BK < D::K;
-        if (more) gload(k0 + BK);
+    for (int k0 = 0; k0 < D::K; k0 += BKS) {
+        const bool more = k0 + BKS < D::K;
+        if (more) gload(k0 + BKS);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 8) {
             v4f a = ld4(ap + kk);
@@ -299,6 +337,8 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * 64) void k_dgrad(DgradArgs 
             __syncthreads();
         }
     }
+    reduce_slices<NWT, KS>(acc, smem, ks, w2, lane);
+    if (ks != 0) return;
 
     const int col = n0 + wn * 32 + li;
 #pragma unroll

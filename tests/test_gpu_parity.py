@@ -243,6 +243,27 @@ def test_three_step_chain(dq, orc):
     m.close()
 
 
+@pytest.mark.parametrize("B,prec", [(512, 0), (160, 0), (32, 0), (512, 1), (96, 1)])
+def test_step_is_run_to_run_deterministic(dq, B, prec):
+    """Every reduction has a fixed order (no floating-point atomics): the same step from the same
+    state gives the same bits, whichever tile shapes the batch size selects."""
+    print("case determinism", B, prec, flush=True)
+    cfgd = CONFIGS["dueling_ddqn"]
+    m = dq.Dqn(dq.make_config(max_batch=512, precision=prec, **cfgd))
+    p = torch.from_numpy(synth.he_uniform_params(1804, 18, 1))
+    pt = torch.from_numpy(synth.he_uniform_params(5834, 18, 1))
+    batch = tuple(dev(t) for t in synth.batch(11, B, 18))
+    runs = []
+    for rep in range(3):
+        m.set_params(0, p); m.set_params(1, pt); m.set_params(3, torch.zeros_like(p))
+        out = m.train_step(B, batch)
+        runs.append([m.get_params(2).cpu().numpy(), m.get_params(0).cpu().numpy(), out["td"].cpu().numpy()])
+    for rep in (1, 2):
+        for x, y in zip(runs[0], runs[rep]):
+            assert np.array_equal(x, y)
+    m.close()
+
+
 # ------------------------------------------------------------------ prioritized replay
 def _fill_replay(m, cap, seed_frames=21, seed_meta=40, K=18, chunk=20000):
     for s0 in range(0, cap, chunk):
