@@ -773,7 +773,7 @@ int32_t per_update(dqn_ctx *c, const int32_t *idx, const float *td_abs, int32_t 
     if (!idx || !td_abs) return fail(c, DQN_ERR_INVALID_ARG, "per_update: NULL argument");
     hipStream_t st = (hipStream_t)stream;
     launch(c, "per_update", st, [&] {
-        misc::k_per_update<<<1, 1024, 0, st>>>(c->tree, c->L, c->levels, c->stored, idx, td_abs, n,
+        misc::k_per_update<<<1, (n + 63) / 64 * 64, 0, st>>>(c->tree, c->L, c->levels, c->stored, idx, td_abs, n,
                                                 c->cfg.per_alpha, c->cfg.per_eps);
     });
     return hip_status(c, "per_update");

@@ -508,17 +508,11 @@ __global__ __launch_bounds__(1024) void k_per_normalise(float *is_w, int B)
     if (j < B) is_w[j] = w / wmax;
 }
 
-// Priority update (Eq.11): single workgroup of 1024 threads, one thread per
-// entry, ONE round trip to memory.  Each thread first requests the sibling of
-// every node on its leaf-to-root path (independent loads), then the tree is
-// repaired level by level entirely on chip: at each level the threads publish
-// (node, new value) in an LDS hash table, look their sibling up there -- a hit
-// means another entry of this batch changed the sibling's subtree, a miss means
-// the preloaded value is still valid -- and form parent = left + right (fp32,
-// commutative, so bit-identical to a sequential repair).  "Last occurrence
-// wins" for repeated slots is an integer maximum over entry numbers in the
-// same table.  New node values are stored as they are produced; entries that
-// share a node store identical values.
+// Priority update (Eq.11): a single workgroup, one thread per entry.  Repeated
+// slots are settled first ("last occurrence wins" is an integer maximum over
+// entry numbers in an LDS hash table keyed by leaf).  The surviving entries
+// then repair the tree level by level, parent = left + right in fp32; the sum
+// is commutative, so the result is bit-identical to a sequential repair.
 constexpr int PU_SLOTS = 2048;  // hash slots (at most 1024 live keys)
 __device__ __forceinline__ int pu_hash(int key) { return (int)(((unsigned)key * 2654435761u) >> 21); }
 // returns the slot of `key`; *first is set when this call created it
@@ -550,10 +544,9 @@ __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int le
                                                      float alpha, float eps)
 {
     __shared__ int keys[PU_SLOTS];
-    __shared__ int ivals[PU_SLOTS];  // entry number (level 0) or float bits of a node value
-    __shared__ float leafv[1024];
+    __shared__ int ivals[PU_SLOTS];  // largest entry number naming the slot's leaf
     __shared__ float sh[16];
-    const int j = threadIdx.x;
+    const int j = threadIdx.x, nt = blockDim.x;
     int my = -1;
     float p = 0.f;
     if (j < n) {
@@ -562,50 +555,33 @@ __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int le
         p = (float)((double)fabsf(td_abs[j]) + (double)eps);
     }
     const bool valid = my >= 0;
-    // siblings along the path, requested back to back (levels <= 31)
-    float sib[32];
-    {
-        long nd = L + (valid ? my : 0);
-#pragma unroll
-        for (int l = 0; l < 32; ++l, nd >>= 1) sib[l] = (valid && l < levels) ? tree[nd ^ 1] : 0.f;
-    }
-    leafv[j] = (float)pow((double)p, (double)alpha);
-    for (int t = j; t < PU_SLOTS; t += 1024) { keys[t] = -1; ivals[t] = -1; }
+    for (int t = j; t < PU_SLOTS; t += nt) { keys[t] = -1; ivals[t] = -1; }
     __syncthreads();
     int node = (int)L + (valid ? my : 0);
     bool first;
-    if (valid) atomicMax(&ivals[pu_insert(keys, node, &first)], j);
+    int slot = 0;
+    if (valid) {
+        slot = pu_insert(keys, node, &first);
+        atomicMax(&ivals[slot], j);
+    }
     const float pmax = block_max_1024(valid ? p : 0.f, sh);  // contains barriers
     if (j == 0) tree[2 * L] = fmaxf(tree[2 * L], pmax);
-    // One thread carries each distinct node upwards: at the leaves the last entry naming the
-    // slot, above them whichever thread publishes a node first.  Paths that merge retire all
-    // but one carrier, so no hash slot is ever contended by more than two threads.
-    bool active = false;
-    float v = 0.f;
-    if (valid) {
-        active = ivals[pu_find(keys, node)] == j;
-        v = leafv[j];
-        if (active) tree[node] = v;
-    }
-#pragma unroll
-    for (int l = 0; l < 32; ++l) {
-        if (l < levels) {  // uniform
-            sync_lds();  // the node stores of earlier levels keep draining
-            for (int t = j; t < PU_SLOTS; t += 1024) keys[t] = -1;
-            sync_lds();  // the node stores of earlier levels keep draining
-            if (active) {
-                const int h = pu_insert(keys, node, &first);
-                if (first) ivals[h] = __float_as_int(v);
-                else active = false;  // another carrier already holds this node (same value)
-            }
-            sync_lds();  // the node stores of earlier levels keep draining
-            if (active) {
-                const int hs = pu_find(keys, node ^ 1);
-                const float vs = hs >= 0 ? __int_as_float(ivals[hs]) : sib[l];
-                v = v + vs;
-                node >>= 1;
-                tree[node] = v;
-            }
+    // One thread per distinct leaf (the last entry naming it) walks to the root.  A level is one
+    // exchange through memory: every walker publishes its node, the workgroup meets, every
+    // walker reads its sibling as it now stands.  Walkers whose paths have merged hold the same
+    // value and store it to the same word.
+    const bool walk = valid && ivals[slot] == j;
+    float v = (float)pow((double)p, (double)alpha);
+    // All walkers sit on one compute unit, so workgroup scope is enough: a store is complete
+    // before the barrier and the load after it sees it.
+    if (walk) __hip_atomic_store(&tree[node], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    for (int l = 0; l < levels; ++l) {
+        __syncthreads();
+        if (walk) {
+            const float vs = __hip_atomic_load(&tree[node ^ 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            v = v + vs;
+            node >>= 1;
+            __hip_atomic_store(&tree[node], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
 }
