@@ -10,7 +10,8 @@ shapes) and already resident in HBM when the timed region starts.
 Prints ONE JSON line.  `value` is train steps/s of the headline workload; `roofline` describes
 the kernel that takes the most time in that workload (timed live with HIP events on the
 launch stream); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same
-workload; `also` carries the batch-32 fp32 configuration of the same metric.
+workload; `kernels` lists every kernel of the step against its own roofline; `also` carries
+the batch-32 fp32 configuration of the same metric and the acting + training loop.
 """
 import argparse
 import json
@@ -38,12 +39,31 @@ def flops_per_launch(B, R):
     }
 
 
-def bytes_per_launch(B, n_params, bf16):
-    """Algorithmic HBM bytes of the bandwidth-bound kernels."""
+def bytes_per_launch(B, n_params, bf16, levels=20):
+    """Algorithmic HBM bytes of the kernels that move data rather than multiply."""
     return {
         "gather": B * 5 * 7056 * 2,                       # read 5 ring frames, write the 5-stack
         "rmsprop": n_params * (22 if bf16 else 20),       # r/w theta, v; read g (+ bf16 copy)
+        "per_sample": B * levels * 4,                     # one useful node per level and draw
+        "per_update": B * levels * 12,                    # read sibling, write node (+ leaf) per level
     }
+
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each
+# scaled by what the same counter shows for the ring-fill copy kernel of known size in the same
+# run (fetch x1.949, write x0.9875).  Keyed by (kernel, batch, precision); the figures and the
+# commands are in profiles/train_step_b512_bf16_hbm_traffic.md.
+MEASURED_TRAFFIC = {
+    ("conv1_fwd", 512, "bf16"): 42.8e6 + 38.8e6,
+    ("conv2_fwd", 512, "bf16"): 52.3e6 + 15.8e6,
+    ("conv3_fwd", 512, "bf16"): 18.0e6 + 9.5e6,
+    ("fc1_fwd", 512, "bf16"): 66.8e6 + 22.1e6,
+    ("conv2_dgrad", 512, "bf16"): 19.3e6 + 20.9e6,
+    ("conv2_wgrad", 512, "bf16"): 82.9e6 + 7.7e6,
+    ("conv3_wgrad", 512, "bf16"): 51.7e6 + 8.2e6,
+    ("conv1_wgrad", 512, "bf16"): 27.1e6 + 8.3e6,
+    ("rmsprop", 512, "bf16"): 43.4e6 + 23.4e6,
+}
 
 
 def step_flops(B, R):
@@ -57,6 +77,11 @@ def build_model(dqn, synth, torch, B, precision, capacity, K=18):
                           max_batch=B, max_act_batch=32, replay_capacity=capacity, per_alpha=0.6,
                           per_eps=1e-6, seed=1804, target_seed=5834)
     m = dqn.Dqn(cfg)
+    fill_ring(m, synth, torch, capacity, K)
+    return m
+
+
+def fill_ring(m, synth, torch, capacity, K):
     chunk = 25000
     for s0 in range(0, capacity, chunk):
         n = min(chunk, capacity - s0)
@@ -67,10 +92,10 @@ def build_model(dqn, synth, torch, B, precision, capacity, K=18):
         del fr
     m.per_fill(synth.exp_priorities(9, capacity, "cuda"))
     torch.cuda.synchronize()
-    return m
 
 
 def time_steps(m, torch, B, steps, warmup, seed0=0):
+    """Returns (wall seconds, device seconds, host seconds spent enqueueing) for `steps` steps."""
     for i in range(warmup):
         m.train_step(B, None, beta=0.4, draw_seed=seed0 + i, outputs=False)
     torch.cuda.synchronize()
@@ -80,9 +105,44 @@ def time_steps(m, torch, B, steps, warmup, seed0=0):
     for i in range(steps):
         m.train_step(B, None, beta=0.4, draw_seed=seed0 + warmup + i, outputs=False)
     e1.record()
+    t_enq = time.perf_counter() - t0
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    return wall, e0.elapsed_time(e1) / 1e3
+    return wall, e0.elapsed_time(e1) / 1e3, t_enq
+
+
+def time_act_train(dqn, synth, torch, capacity, iters, warmup, E=2048, B=256, K=18):
+    """Acting on E environments (epsilon 0.05) interleaved with batch-B bf16 train steps.  The
+    observations rotate among four pre-generated sets so they are not cache-resident; the acted
+    frames are not written back into the ring."""
+    cfg = dqn.make_config(num_actions=K, dueling=1, double_q=1, precision=1, loss_kind=1,
+                          huber_delta=1.0, gamma=0.99, lr=2.5e-4, rms_decay=0.95, rms_eps=0.01,
+                          max_batch=B, max_act_batch=E, replay_capacity=capacity, per_alpha=0.6,
+                          per_eps=1e-6, seed=1804, target_seed=5834)
+    m = dqn.Dqn(cfg)
+    fill_ring(m, synth, torch, capacity, K)
+    obs = [synth.states(31 + i, E, device="cuda") for i in range(4)]
+    for i in range(warmup):
+        m.act(obs[i % 4], 0.05, i)
+        m.train_step(B, None, beta=0.4, draw_seed=i, outputs=False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(iters):
+        m.act(obs[i % 4], 0.05, warmup + i)
+        m.train_step(B, None, beta=0.4, draw_seed=warmup + i, outputs=False)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t1 = time.perf_counter()
+    for i in range(iters):
+        m.act(obs[i % 4], 0.05, warmup + i)
+    torch.cuda.synchronize()
+    act_only = time.perf_counter() - t1
+    m.close()
+    act_flops = E * (F_CONV1 + F_CONV2 + F_CONV3 + F_FC1 + 2 * 512 * 19)
+    return {"workload": "act on %d environments (epsilon 0.05) + train step batch %d, bf16, alternating" % (E, B),
+            "value": iters / wall, "unit": "act+train iterations/s", "ms_per_iteration": wall / iters * 1e3,
+            "env_steps_per_s": E * iters / wall, "act_only_ms": act_only / iters * 1e3,
+            "act_only_mfma_frac": act_flops * iters / act_only / PEAK["bf16"]}
 
 
 def profile_kernels(m, torch, B, steps, seed0):
@@ -90,6 +150,25 @@ def profile_kernels(m, torch, B, steps, seed0):
     for i in range(steps):
         m.train_step(B, None, beta=0.4, draw_seed=seed0 + i, outputs=False)
     return m.profile_end()
+
+
+def kernel_table(prof, B, R, n_params, precision):
+    """Per kernel: live HIP-event average duration, the roofline that bounds it, what it achieves."""
+    fl = flops_per_launch(B, R)
+    by = bytes_per_launch(B, n_params, precision == "bf16")
+    out = {}
+    for k, (cnt, tot_ms) in prof.items():
+        avg_s = tot_ms / cnt / 1e3
+        if k in fl:
+            e = {"bound": "mfma", "achieved": fl[k] / avg_s / 1e12, "peak": PEAK[precision] / 1e12, "unit": "TFLOP/s"}
+        else:
+            e = {"bound": "hbm", "achieved": by.get(k, 0) / avg_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
+        e["frac"] = e["achieved"] / e["peak"]
+        e["avg_us"] = round(avg_s * 1e6, 2)
+        e["achieved"] = round(e["achieved"], 3)
+        e["frac"] = round(e["frac"], 5)
+        out[k] = e
+    return dict(sorted(out.items(), key=lambda kv: -kv[1]["avg_us"]))
 
 
 def check_health(m, torch, B):
@@ -139,7 +218,7 @@ def main():
     ap.add_argument("--precision", choices=["fp32", "bf16"], default="bf16")
     ap.add_argument("--capacity", type=int, default=1_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-also", action="store_true", help="skip the batch-32 fp32 side measurement")
+    ap.add_argument("--no-also", action="store_true", help="skip the batch-32 fp32 and the act+train side measurements")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a one-GPU training step (no collectives, no sharding); "
@@ -154,27 +233,21 @@ def main():
     B, K, R = args.batch, 18, 19
     prec = 1 if args.precision == "bf16" else 0
     m = build_model(dqn, synth, torch, B, prec, args.capacity)
-    wall, dev_s = time_steps(m, torch, B, args.steps, args.warmup)
+    wall, dev_s, enq_s = time_steps(m, torch, B, args.steps, args.warmup)
     ms_per_step = wall / args.steps * 1e3
     value = args.steps / wall
 
     prof = profile_kernels(m, torch, B, min(args.steps, 100), seed0=10_000_000)
     loss = check_health(m, torch, B)
-    fl = flops_per_launch(B, R)
-    by = bytes_per_launch(B, m.n, prec == 1)
-    name = max(prof, key=lambda k: prof[k][1])
-    cnt, tot_ms = prof[name]
-    avg_s = tot_ms / cnt / 1e3
-    if name in fl:
-        roof = {"kernel": name, "bound": "mfma", "achieved": fl[name] / avg_s / 1e12,
-                "peak": PEAK[args.precision] / 1e12, "unit": "TFLOP/s"}
-    else:
-        roof = {"kernel": name, "bound": "hbm", "achieved": by.get(name, 0) / avg_s / 1e9,
-                "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
-    roof["avg_us"] = avg_s * 1e6
-    kernels = {k: round(v[1] / v[0] * 1e3, 2) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
+    table = kernel_table(prof, B, R, m.n, args.precision)
+    # the dominant kernel: the largest total time among the kernels of the step (the tree
+    # kernels are listed in the table too; they are bound by dependent-load latency, not by a
+    # throughput roofline, and per_update runs beside the backward pass on a stream of its own)
+    ranked = [k for k in sorted(table, key=lambda k: -table[k]["avg_us"]) if k not in ("per_update", "per_sample")]
+    name = ranked[0]
+    roof = {"kernel": name, "bound": table[name]["bound"], "achieved": table[name]["achieved"],
+            "peak": table[name]["peak"], "unit": table[name]["unit"], "frac": table[name]["frac"],
+            "traffic": MEASURED_TRAFFIC.get((name, B, args.precision)), "avg_us": table[name]["avg_us"]}
 
     res = {
         "metric": "DQN train steps/s (84x84x4, dueling Double-DQN + PER, 1M-frame replay)",
@@ -187,22 +260,29 @@ def main():
                    "batch": B, "num_actions": K},
         "mfma_frac_step": step_flops(B, R) * value / PEAK[args.precision],
         "device_ms_per_step": dev_s / args.steps * 1e3,
+        "host_enqueue_ms_per_step": enq_s / args.steps * 1e3,
         "final_loss": loss,
-        "kernel_avg_us": kernels,
         "roofline": roof,
+        "kernels": table,
     }
     m.close()
     del m
     torch.cuda.empty_cache()
 
-    if not args.no_also and not (B == 32 and prec == 0):
-        m32 = build_model(dqn, synth, torch, 32, 0, args.capacity)
-        w32, d32 = time_steps(m32, torch, 32, args.steps, args.warmup)
-        res["also"] = {"workload": "same step, batch 32, fp32", "value": args.steps / w32,
-                       "unit": "train steps/s", "ms_per_step": w32 / args.steps * 1e3,
-                       "device_ms_per_step": d32 / args.steps * 1e3,
-                       "mfma_frac_step": step_flops(32, R) * args.steps / w32 / PEAK["fp32"]}
-        m32.close()
+    if not args.no_also:
+        also = []
+        if not (B == 32 and prec == 0):
+            m32 = build_model(dqn, synth, torch, 32, 0, args.capacity)
+            w32, d32, _ = time_steps(m32, torch, 32, args.steps, args.warmup)
+            also.append({"workload": "same step, batch 32, fp32", "value": args.steps / w32,
+                         "unit": "train steps/s", "ms_per_step": w32 / args.steps * 1e3,
+                         "device_ms_per_step": d32 / args.steps * 1e3,
+                         "mfma_frac_step": step_flops(32, R) * args.steps / w32 / PEAK["fp32"]})
+            m32.close()
+            del m32
+            torch.cuda.empty_cache()
+        also.append(time_act_train(dqn, synth, torch, args.capacity, max(50, args.steps // 5), 10))
+        res["also"] = also
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(torch, synth, B, min(B, 64))
     print(json.dumps(res))
