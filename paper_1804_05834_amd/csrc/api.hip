@@ -38,10 +38,15 @@ struct Workspace {
     void *dh, *d3, *d2, *d1;
     // gradient partial sums per layer, [split][W..., b...]
     float *gp1, *gp2, *gp3, *gp4, *gp5;
+    // step outputs staged here when the step is replayed from a recording
+    float *o_loss, *o_q, *o_y, *o_td, *o_isw;  // o_q: [3][max_batch][K]
+    int32_t *o_astar;
     size_t total;
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+constexpr size_t MAX_STEP_GRAPHS = 16;  // recorded steps kept per context (one per batch size)
 
 // reduction splits of the fc1 forward GEMM (3136 = 98*32 = 49*64 reduction elements)
 int fc1_splits(long M, int precision)
@@ -90,6 +95,12 @@ Workspace carve(const dqn_config &c, uint8_t *base)
     w.gp3 = (float *)take((size_t)MAX_WSPLIT * net::L3N * 4);
     w.gp4 = (float *)take((size_t)net::L4N * 4);
     w.gp5 = (float *)take((size_t)net::head_count(c.num_actions, c.dueling) * 4);
+    w.o_loss = (float *)take(256);
+    w.o_q = (float *)take(3 * MB * (size_t)c.num_actions * 4);
+    w.o_y = (float *)take(MB * 4);
+    w.o_td = (float *)take(MB * 4);
+    w.o_isw = (float *)take(MB * 4);
+    w.o_astar = (int32_t *)take(MB * 4);
     w.total = off;
     return w;
 }
@@ -125,6 +136,18 @@ struct dqn_ctx {
     bool prof = false;
     std::vector<ProfRec> recs;
     std::string err;
+    // Optional: the replay-mode training step (everything after the sampling kernel, whose
+    // arguments change every step) is recorded once per batch size into a HIP graph and replayed.
+    // Recording happens on `cap`, so the caller may pass the legacy default stream, which
+    // cannot be captured.  Recordings live until dqn_destroy.
+    hipStream_t cap = nullptr;
+    bool graph_off = true;   // cleared by DQN_GRAPH=1; set again after a failed recording
+    struct StepGraph {
+        int32_t B;
+        hipGraph_t graph;
+        hipGraphExec_t exec;
+    };
+    std::vector<StepGraph> graphs;
 };
 
 namespace {
@@ -137,6 +160,15 @@ int32_t fail(dqn_ctx *c, int32_t code, const std::string &msg)
 }
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+void drop_graphs(dqn_ctx *c)
+{
+    for (dqn_ctx::StepGraph &g : c->graphs) {
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+        if (g.graph) (void)hipGraphDestroy(g.graph);
+    }
+    c->graphs.clear();
+}
 
 const char *check_config(const dqn_config &c)
 {
@@ -629,6 +661,12 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
     if ((single && single[0] == '1') || hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess)
         c->side = nullptr;
     if (c->side && hipStreamCreateWithFlags(&c->side2, hipStreamNonBlocking) != hipSuccess) c->side2 = nullptr;
+    // DQN_GRAPH=1 replays the step from a recorded HIP graph.  Off by default: on this runtime a
+    // graph launch costs the host about as much as the plain launches it replaces and the
+    // step is bound by the device either way.
+    const char *graph = std::getenv("DQN_GRAPH");
+    c->graph_off = !(graph && graph[0] == '1');
+    if (!c->graph_off && hipStreamCreateWithFlags(&c->cap, hipStreamNonBlocking) != hipSuccess) c->cap = nullptr;
     hipEvent_t *evs[5] = {&c->ev_fork, &c->ev_a, &c->ev_b, &c->ev_join, &c->ev_join2};
     for (hipEvent_t *e : evs)
         if (c->side && hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) {
@@ -648,7 +686,9 @@ int32_t dqn_destroy(dqn_ctx *ctx)
         (void)hipEventDestroy(r.e0);
         (void)hipEventDestroy(r.e1);
     }
-    for (hipStream_t sx : {ctx->side, ctx->side2})
+    if (!ctx->graphs.empty()) (void)hipDeviceSynchronize();  // no recording is destroyed while it may still run
+    drop_graphs(ctx);
+    for (hipStream_t sx : {ctx->side, ctx->side2, ctx->cap})
         if (sx) {
             (void)hipStreamSynchronize(sx);
             (void)hipStreamDestroy(sx);
@@ -830,13 +870,23 @@ int32_t dqn_act(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64
 }
 
 // ------------------------------------------------------------ training
-int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta, uint64_t draw_seed,
-                       const dqn_step_out *out, void *stream)
+static void enqueue_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, hipStream_t st)
 {
-    if (!c) return DQN_ERR_INVALID_ARG;
+    const Workspace &w = c->ws;
+    // raw importance weights; the head kernel divides by their maximum
+    launch(c, "per_sample", st, [&] {
+        misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(c->tree, c->L, c->levels, c->stored, B, beta, draw_seed,
+                                                        c->cfg.per_stratified, w.b_idx, w.b_w,
+                                                        misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done});
+    });
+}
+
+// Enqueues every kernel of one training step on st (and on the side streams, which fork from
+// st and join it again before the function returns).  In replay mode the sampling kernel has
+// been enqueued by the caller.
+static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const dqn_step_out *out, hipStream_t st)
+{
     const dqn_config &cfg = c->cfg;
-    if (B < 1 || B > cfg.max_batch) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: B out of range");
-    hipStream_t st = (hipStream_t)stream;
     const Workspace &w = c->ws;
     dqn_step_out O{};
     if (out) O = *out;
@@ -855,14 +905,6 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
         s = batch->s; sn = batch->s_next; xs = net::STATE;
         a = batch->a; r = batch->r; done = batch->done; isw = batch->w;
     } else {
-        if (cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "dqn_train_step: replay is empty");
-        if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: beta must be >= 0");
-        // raw importance weights; the head kernel divides by their maximum
-        launch(c, "per_sample", st, [&] {
-            misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(c->tree, c->L, c->levels, c->stored, B, beta, draw_seed,
-                                                            cfg.per_stratified, w.b_idx, w.b_w,
-                                                            misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done});
-        });
         a = w.b_a; r = w.b_r; done = w.b_done; isw = w.b_w;
         if (cfg.precision == 1) {
             // bf16 path: the conv1 kernels read the five frames of a transition straight from the ring
@@ -897,25 +939,31 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     H.a_star = O.a_star; H.is_w = O.is_w;
     launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 512, 0, st>>>(H); });
 
-    // fork: head weight gradient, priority update and the weight gradients leave the chain
-    hipStream_t sd = c->side ? c->side : st;
+    // fork: the weight gradients of the trunk go to one side stream, the head weight gradient
+    // and the priority update to another; both join again before the optimizer
+    // (a small batch stays on one stream: its kernels are too short to repay the hand-overs)
+    hipStream_t sd = (c->side && B > 64) ? c->side : st;
+    hipStream_t sp = (c->side2 && sd != st) ? c->side2 : sd;
     ev_record(c->ev_fork, st, sd);
     ev_wait(sd, c->ev_fork, st);
+    if (sp != sd) ev_wait(sp, c->ev_fork, st);
     misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
-    launch(c, "head_wgrad", sd, [&] { misc::k_head_wgrad<<<dim3(c->R, 4), 512, 0, sd>>>(HW); });
-    hipStream_t sp = (c->side2 && sd != st) ? c->side2 : sd;
+    launch(c, "head_wgrad", sp, [&] { misc::k_head_wgrad<<<dim3(c->R, 4), 512, 0, sp>>>(HW); });
     if (!batch) {
-        ev_wait(sp, c->ev_fork, st);
-        rc = per_update(c, w.b_idx, w.td_abs, B, (void *)sp);
-        if (rc) return rc;
-        if (sp != sd) (void)hipEventRecord(c->ev_join2, sp);
+        // the indices come from the sampling kernel, so the ring capacity bounds them
+        launch(c, "per_update", sp, [&] {
+            misc::k_per_update<<<1, (B + 63) / 64 * 64, 0, sp>>>(c->tree, c->L, c->levels, (long)cfg.replay_capacity,
+                                                                 w.b_idx, w.td_abs, B, cfg.per_alpha, cfg.per_eps);
+        });
     }
+    if (sp != sd) (void)hipEventRecord(c->ev_join2, sp);
 
     int ns1, ns2, ns3;
     if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, sd);
     else backward_f32(c, B, s, xs, &ns1, &ns2, &ns3, st, sd);
     ev_record(c->ev_join, sd, st);
     ev_wait(st, c->ev_join, sd);
+    if (sp != sd) (void)hipStreamWaitEvent(st, c->ev_join2, 0);
 
     misc::RmsArgs RA{};
     {
@@ -934,8 +982,81 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
         RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps;
         launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
     }
-    // whatever follows on the caller's stream (the next step's sampling) sees the updated tree
-    if (!batch && sp != sd) (void)hipStreamWaitEvent(st, c->ev_join2, 0);
+    return hip_status(c, "dqn_train_step");
+}
+
+// Records the replay-mode step for batch size B (everything after the sampling kernel, with the
+// outputs staged in the workspace); returns nullptr if this runtime cannot do it.
+static dqn_ctx::StepGraph *record_step_graph(dqn_ctx *c, int32_t B)
+{
+    const Workspace &w = c->ws;
+    const size_t BK = (size_t)c->cfg.max_batch * c->cfg.num_actions;
+    dqn_step_out O{};
+    O.loss = w.o_loss; O.q_s = w.o_q; O.q_next_online = w.o_q + BK; O.q_next_target = w.o_q + 2 * BK;
+    O.y = w.o_y; O.td = w.o_td; O.a_star = w.o_astar; O.is_w = w.o_isw;  // idx: already in b_idx
+    if (hipStreamBeginCapture(c->cap, hipStreamCaptureModeRelaxed) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    const int32_t rc = enqueue_step(c, B, nullptr, &O, c->cap);
+    hipGraph_t g = nullptr;
+    const hipError_t e = hipStreamEndCapture(c->cap, &g);
+    hipGraphExec_t x = nullptr;
+    if (rc != DQN_OK || e != hipSuccess || !g || hipGraphInstantiate(&x, g, nullptr, nullptr, 0) != hipSuccess) {
+        if (g) (void)hipGraphDestroy(g);
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    c->graphs.push_back({B, g, x});
+    return &c->graphs.back();
+}
+
+int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta, uint64_t draw_seed,
+                       const dqn_step_out *out, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (B < 1 || B > c->cfg.max_batch) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: B out of range");
+    hipStream_t st = (hipStream_t)stream;
+    if (batch) return enqueue_step(c, B, batch, out, st);
+    if (c->cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "dqn_train_step: replay is empty");
+    if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: beta must be >= 0");
+    enqueue_sample(c, B, beta, draw_seed, st);
+
+    dqn_ctx::StepGraph *g = nullptr;
+    if (!c->prof && !c->graph_off && c->cap && c->side) {
+        for (dqn_ctx::StepGraph &x : c->graphs)
+            if (x.B == B) g = &x;
+        if (!g && c->graphs.size() < MAX_STEP_GRAPHS) {
+            g = record_step_graph(c, B);
+            if (!g) c->graph_off = true;  // this runtime cannot record the step: plain launches from now on
+        }
+    }
+    if (!g) return enqueue_step(c, B, nullptr, out, st);
+
+    if (hipGraphLaunch(g->exec, st) != hipSuccess) {
+        c->graph_off = true;
+        return fail(c, DQN_ERR_HIP, std::string("dqn_train_step: graph launch: ") + hipGetErrorString(hipGetLastError()));
+    }
+    if (out) {  // hand the staged outputs to the caller
+        const Workspace &w = c->ws;
+        const size_t BK = (size_t)c->cfg.max_batch * c->cfg.num_actions;
+        const int nq = B * c->cfg.num_actions;
+        misc::CopyOutArgs A{};
+        int n = 0;
+        auto add = [&](void *dst, const void *src, int words) {
+            if (dst) A.item[n++] = {(uint32_t *)dst, (const uint32_t *)src, words};
+        };
+        add(out->loss, w.o_loss, 1);
+        add(out->q_s, w.o_q, nq);
+        add(out->q_next_online, w.o_q + BK, nq);
+        add(out->q_next_target, w.o_q + 2 * BK, nq);
+        add(out->y, w.o_y, B);
+        add(out->td, w.o_td, B);
+        add(out->a_star, w.o_astar, B);
+        add(out->idx, w.b_idx, B);
+        add(out->is_w, w.o_isw, B);
+        if (n) misc::k_copy_out<<<dim3((nq + 255) / 256, n), 256, 0, st>>>(A);
+    }
     return hip_status(c, "dqn_train_step");
 }
 

@@ -133,12 +133,14 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_fw
     __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDK];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int bx = blockIdx.x;
+    // tile order: column tiles of one row tile together, reduction splits apart
+    const int t = net::tile_of_workgroup();
+    const int by = t % (int)gridDim.y, bx = (t / (int)gridDim.y) % (int)gridDim.x, bz = t / (int)(gridDim.y * gridDim.x);
     FwdSeg S = A.seg[0];
     if (A.nseg > 1 && bx >= A.seg[1].tile_begin) S = A.seg[1];
     if (A.nseg > 2 && bx >= A.seg[2].tile_begin) S = A.seg[2];
-    const int m0 = (bx - S.tile_begin) * BM, n0 = blockIdx.y * BN;
-    const int kbeg = blockIdx.z * A.klen, kend = kbeg + A.klen;
+    const int m0 = (bx - S.tile_begin) * BM, n0 = by * BN;
+    const int kbeg = bz * A.klen, kend = kbeg + A.klen;
     const in_t *x = static_cast<const in_t *>(S.x);
 
     const int lr = tid >> 3, kq = (tid & 7) * 8;
@@ -217,7 +219,7 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_fw
                 float v0 = acc[a][b][4 * g] * A.scale, v1 = acc[a][b][4 * g + 1] * A.scale;
                 float v2 = acc[a][b][4 * g + 2] * A.scale, v3 = acc[a][b][4 * g + 3] * A.scale;
                 if (RAW) {
-                    float *y = static_cast<float *>(S.y) + (long)blockIdx.z * A.split_stride;
+                    float *y = static_cast<float *>(S.y) + (long)bz * A.split_stride;
                     *reinterpret_cast<v4f *>(y + (long)m * G::N + col) = v4f{v0, v1, v2, v3};
                 } else {
                     const v4f bv = *reinterpret_cast<const v4f *>(S.bias + col);
@@ -256,8 +258,11 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
     __shared__ __attribute__((aligned(16))) bf16_t Bs[BK * LDB];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int ca = blockIdx.z / D::S, cb = blockIdx.z % D::S;
+    // tile order: the parity classes of one row tile together, then the row tiles of one column tile
+    const int t = net::tile_of_workgroup();
+    const int bz = t % (int)gridDim.z, bx = (t / (int)gridDim.z) % (int)gridDim.x, by = t / (int)(gridDim.z * gridDim.x);
+    const int m0 = bx * BM, n0 = by * BN;
+    const int ca = bz / D::S, cb = bz % D::S;
     const int Mc = A.B * D::PP;
 
     const int lr = tid >> 3, kq = (tid & 7) * 8;
@@ -389,8 +394,17 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
     __shared__ __attribute__((aligned(16))) bf16_t Xs[BK * LDX];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int kc0 = blockIdx.x * BNK, o0 = blockIdx.y * BMO;
-    const int mbeg = blockIdx.z * A.rps;
+    // tile order: with row splits (conv layers) all tiles of one split together; without
+    // (fc1) all output tiles of one input-column tile together
+    const int t = net::tile_of_workgroup();
+    int bx, by, bz;
+    if (gridDim.z > 1) {
+        bx = t % (int)gridDim.x; by = (t / (int)gridDim.x) % (int)gridDim.y; bz = t / (int)(gridDim.x * gridDim.y);
+    } else {
+        by = t % (int)gridDim.y; bx = t / (int)gridDim.y; bz = 0;
+    }
+    const int kc0 = bx * BNK, o0 = by * BMO;
+    const int mbeg = bz * A.rps;
     const int mend = min(mbeg + A.rps, A.B * G::P);
     const in_t *x = static_cast<const in_t *>(A.x);
 
@@ -428,7 +442,7 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
     const int trow = 8 * h + (s16 >> 2), tcol = 16 * half + 4 * (s16 & 3);
     const bf16_t *yp = &Ys[trow * LDY + wo * 32 * WM + tcol];
     const bf16_t *xp = &Xs[trow * LDX + wk * 32 * WN + tcol];
-    const bool do_bias = blockIdx.x == 0 && wk == 0;
+    const bool do_bias = bx == 0 && wk == 0;
     v16f acc[WM][WN], accb[WM];
 #pragma unroll
     for (int a = 0; a < WM; ++a) {
@@ -469,7 +483,7 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
         }
     }
 
-    float *part = A.part + (long)blockIdx.z * A.part_stride;
+    float *part = A.part + (long)bz * A.part_stride;
 #pragma unroll
     for (int a = 0; a < WM; ++a) {
 #pragma unroll
@@ -698,7 +712,7 @@ struct WgradArgs {
 
 constexpr int LDY1 = 40;  // row stride (elements) of the staged dY tile
 
-// grid (nsplit, 2): blockIdx.y selects the channel pair (frames 2y, 2y+1 = im2col columns
+// grid (nsplit, 2): a workgroup takes one channel pair y (frames 2y, 2y+1 = im2col columns
 // 128y .. 128y+127), so a workgroup stages half a state and two workgroups fit one CU.
 __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
 {
@@ -706,7 +720,9 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
     __shared__ __attribute__((aligned(16))) bf16_t dys[400 * LDY1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;  // wave = block of 32 im2col columns
     const int li = lane & 31, h = lane >> 5, s16 = lane & 15, half = (lane >> 4) & 1;
-    const int cp = blockIdx.y;
+    // the two channel pairs of one sample split run next to each other: same dY, same ring slots
+    const int tile = net::tile_of_workgroup();
+    const int cp = tile & 1, split = tile >> 1;
     typedef __attribute__((address_space(3))) v4s *lds_v4s;
 
     // this lane's share of the transpose loads: reduction row offset s/4 (+4 for the second
@@ -733,8 +749,8 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
             if (t < 1600) ry[i] = ld8(dyn + (t >> 2) * 32 + (t & 3) * 8);
         }
     };
-    if ((int)blockIdx.x < A.B) load_sample(blockIdx.x);
-    for (int n = blockIdx.x; n < A.B; n += A.nsplit) {
+    if (split < A.B) load_sample(split);
+    for (int n = split; n < A.B; n += A.nsplit) {
         __syncthreads();  // the previous sample's tiles are no longer read
         stage_store<256, 2>(xin, R, tid);
 #pragma unroll
@@ -759,7 +775,7 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
         }
     }
 
-    float *part = A.part + (long)blockIdx.x * (32 * 256 + 32);
+    float *part = A.part + (long)split * (32 * 256 + 32);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int o = 8 * (r / 4) + 4 * h + (r % 4);

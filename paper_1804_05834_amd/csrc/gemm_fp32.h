@@ -19,6 +19,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "net.h"
+
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -145,12 +147,14 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_fwd(FwdArgs
     float *As = smem, *Bs = smem + BM * LD;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int bx = blockIdx.x;
+    // tile order: column tiles of one row tile together, reduction splits apart
+    const int t = net::tile_of_workgroup();
+    const int by = t % (int)gridDim.y, bx = (t / (int)gridDim.y) % (int)gridDim.x, bz = t / (int)(gridDim.y * gridDim.x);
     FwdSeg S = A.seg[0];
     if (A.nseg > 1 && bx >= A.seg[1].tile_begin) S = A.seg[1];
     if (A.nseg > 2 && bx >= A.seg[2].tile_begin) S = A.seg[2];
-    const int m0 = (bx - S.tile_begin) * BM, n0 = blockIdx.y * BN;
-    const int kbeg = blockIdx.z * A.klen, kend = kbeg + A.klen;
+    const int m0 = (bx - S.tile_begin) * BM, n0 = by * BN;
+    const int kbeg = bz * A.klen, kend = kbeg + A.klen;
     const in_t *x = static_cast<const in_t *>(S.x);
 
     const int lr = tid / CPR, kq = (tid % CPR) * 4;
@@ -206,7 +210,7 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_fwd(FwdArgs
     reduce_slices<NWT, KS>(acc, smem, ks, w2, lane);
     if (ks != 0) return;
 
-    float *y = S.y + (long)blockIdx.z * A.split_stride;
+    float *y = S.y + (long)bz * A.split_stride;
     const int col = n0 + wn * 32 + li;
     const float bias = S.bias ? S.bias[col] : 0.f;
 #pragma unroll
@@ -264,8 +268,11 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_dgrad(Dgrad
     float *As = smem, *Bs = smem + BM * LD;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int ca = blockIdx.z / D::S, cb = blockIdx.z % D::S;
+    // tile order: the parity classes of one row tile together, then the row tiles of one column tile
+    const int t = net::tile_of_workgroup();
+    const int bz = t % (int)gridDim.z, bx = (t / (int)gridDim.z) % (int)gridDim.x, by = t / (int)(gridDim.z * gridDim.x);
+    const int m0 = bx * BM, n0 = by * BN;
+    const int ca = bz / D::S, cb = bz % D::S;
     const int Mc = A.B * D::PP;
 
     const int lr = tid / CPR, kq = (tid % CPR) * 4;
@@ -383,8 +390,17 @@ __global__ __launch_bounds__((BMO / 32) * (BNK / 32) * 64) void k_wgrad(WgradArg
     __shared__ __attribute__((aligned(16))) float Xs[BK * LDX];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int kc0 = blockIdx.x * BNK, o0 = blockIdx.y * BMO;
-    const int mbeg = blockIdx.z * A.rps;
+    // tile order: with row splits (conv layers) all tiles of one split together; without
+    // (fc1) all output tiles of one input-column tile together
+    const int t = net::tile_of_workgroup();
+    int bx, by, bz;
+    if (gridDim.z > 1) {
+        bx = t % (int)gridDim.x; by = (t / (int)gridDim.x) % (int)gridDim.y; bz = t / (int)(gridDim.x * gridDim.y);
+    } else {
+        by = t % (int)gridDim.y; bx = t / (int)gridDim.y; bz = 0;
+    }
+    const int kc0 = bx * BNK, o0 = by * BMO;
+    const int mbeg = bz * A.rps;
     const int mend = min(mbeg + A.rps, A.B * G::P);
     const in_t *x = static_cast<const in_t *>(A.x);
 
@@ -421,7 +437,7 @@ __global__ __launch_bounds__((BMO / 32) * (BNK / 32) * 64) void k_wgrad(WgradArg
     const int li = lane & 31, h = lane >> 5;
     const float *yp = &Ys[(4 * h) * LDY + wo * 32 + li];
     const float *xp = &Xs[(4 * h) * LDX + wk * 32 + li];
-    const bool do_bias = blockIdx.x == 0 && wk == 0;
+    const bool do_bias = bx == 0 && wk == 0;
     v16f acc = {0}, accb = {0};
 
     if (mbeg < mend) {
@@ -448,7 +464,7 @@ __global__ __launch_bounds__((BMO / 32) * (BNK / 32) * 64) void k_wgrad(WgradArg
         }
     }
 
-    float *part = A.part + (long)blockIdx.z * A.part_stride;
+    float *part = A.part + (long)bz * A.part_stride;
     const int col = kc0 + wk * 32 + li;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {

@@ -586,6 +586,21 @@ __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int le
     }
 }
 
+// Copies up to nine short arrays of 4-byte words; grid (blocks, items).
+struct CopyOutArgs {
+    struct Item {
+        uint32_t *dst;
+        const uint32_t *src;
+        int words;
+    } item[9];
+};
+__global__ __launch_bounds__(256) void k_copy_out(CopyOutArgs A)
+{
+    const CopyOutArgs::Item it = A.item[blockIdx.y];
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < it.words) it.dst[t] = it.src[t];
+}
+
 // --------------------------------------------------------------- replay
 struct GatherArgs {
     const uint8_t *frames;  // ring [cap][7056]

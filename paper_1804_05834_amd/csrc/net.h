@@ -34,4 +34,21 @@ constexpr int64_t L4N = 1606144;        // fc1 W+b
 
 inline int64_t head_count(int K, int dueling) { return (int64_t)(K + (dueling ? 1 : 0)) * (HID + 1); }
 inline int64_t param_count(int K, int dueling) { return HEAD + head_count(K, dueling); }
+
+#ifdef __HIPCC__
+// Workgroups are handed to the eight accelerator dies of the package round-robin in dispatch
+// order (x fastest, then y, then z), and each die has an L2 of its own.  tile_of_workgroup turns
+// the dispatch-order number of this workgroup into a tile number such that every die works on
+// one contiguous range of tile numbers; the kernels number tiles that share operands next to
+// each other, so they meet in one L2 instead of fetching the operand once per die.  The map
+// is a bijection on [0, total) whatever the hardware does, so it can only change locality.
+__device__ __forceinline__ int tile_of_workgroup()
+{
+    const int total = gridDim.x * gridDim.y * gridDim.z;
+    const int id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int die = id & 7, slot = id >> 3;
+    const int q = total >> 3, r = total & 7;  // die d receives q + (d < r) workgroups
+    return die * q + (die < r ? die : r) + slot;
+}
+#endif
 }  // namespace net

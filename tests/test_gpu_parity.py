@@ -390,6 +390,61 @@ def test_replay_train_step_small_ring(dq, orc):
     _replay_step_case(dq, orc, cap=4096, B=32)
 
 
+@pytest.mark.parametrize("prec,B", [(0, 32), (1, 64)])
+def test_recorded_step_replays_match_plain_launches(dq, prec, B):
+    """With DQN_GRAPH=1 the replay-mode step is recorded into a HIP graph and replayed.  Two
+    contexts over identical state, one on the graph and one on plain launches, must agree
+    bit for bit on every replay: enqueued back to back, with other work and synchronisations
+    between the replays, with the outputs requested and not requested, after a change of batch
+    size and after the number of stored transitions has changed."""
+    import os
+    print("case graph replays", prec, B, flush=True)
+    cap = 6000
+    cfgd = dict(CONFIGS["dueling_ddqn"], max_batch=B, precision=prec, replay_capacity=cap)
+    ms = []
+    for graph in ("1", "0"):
+        os.environ["DQN_GRAPH"] = graph
+        try:
+            m = dq.Dqn(dq.make_config(**cfgd))
+        finally:
+            os.environ.pop("DQN_GRAPH", None)
+        _fill_replay(m, cap)
+        m.per_fill(synth.exp_priorities(9, cap, "cuda"))
+        ms.append(m)
+    # a run of steps enqueued back to back, nothing waited for in between
+    for m in ms:
+        for step in range(5):
+            m.train_step(B, None, beta=0.3 + 0.1 * step, draw_seed=500 + step, outputs=False)
+    for which in (0, 3):
+        assert torch.equal(ms[0].get_params(which), ms[1].get_params(which)), which
+    assert torch.equal(ms[0].tree, ms[1].tree)
+    for step in range(6):
+        beta, seed = 0.4 + 0.1 * step, 1000 + step
+        outs = [m.train_step(B, None, beta=beta, draw_seed=seed, outputs=(step % 3 == 2)) for m in ms]
+        torch.cuda.synchronize()
+        if step % 3 == 2:
+            for k in outs[0]:
+                assert torch.equal(outs[0][k], outs[1][k]), (step, k)
+        # unrelated work between replays: sampling on its own, acting, a parameter read
+        for m in ms:
+            m.per_sample(B, 0.5, 77 + step)
+            m.act(dev(synth.states(5, 3)), 0.0, 1)
+        for which in (0, 3):
+            assert torch.equal(ms[0].get_params(which), ms[1].get_params(which)), (step, which)
+        assert torch.equal(ms[0].tree, ms[1].tree), step
+    # a different batch size (a new recording) and a different number of stored transitions
+    B2 = B // 2
+    for m in ms:
+        m.train_step(B2, None, beta=0.7, draw_seed=5)
+        m.per_fill(synth.exp_priorities(10, cap - 100, "cuda"))
+        m.train_step(B2, None, beta=0.7, draw_seed=6, outputs=False)
+    torch.cuda.synchronize()
+    assert torch.equal(ms[0].get_params(0), ms[1].get_params(0))
+    assert torch.equal(ms[0].tree, ms[1].tree)
+    for m in ms:
+        m.close()
+
+
 def test_replay_train_step_full_size(dq, orc):
     """The throughput configuration as bench.py launches it: 1,000,000-frame ring, batch 512,
     then batch 32 on the same context; every output of the step is compared."""
