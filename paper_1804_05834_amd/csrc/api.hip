@@ -132,7 +132,7 @@ struct dqn_ctx {
     int num_cu = 256;  // compute units of the device
     hipStream_t side = nullptr;
     hipStream_t side2 = nullptr;  // the single-workgroup priority update gets a lane of its own
-    hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_join = nullptr, ev_join2 = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_c = nullptr, ev_join = nullptr, ev_join2 = nullptr;
     bool prof = false;
     std::vector<ProfRec> recs;
     std::string err;
@@ -454,8 +454,36 @@ void ev_wait(hipStream_t waiter, hipEvent_t e, hipStream_t other)
     if (waiter != other) (void)hipStreamWaitEvent(waiter, e, 0);
 }
 
+// ----- RMSProp over a subset of the layers (bit i of `layers`: conv1, conv2, conv3, fc1, head) -----
+enum : unsigned { RMS_CONV1 = 1, RMS_CONV2 = 2, RMS_CONV3 = 4, RMS_FC1 = 8, RMS_HEAD = 16, RMS_ALL = 31 };
+void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipStream_t st)
+{
+    const dqn_config &cfg = c->cfg;
+    const Workspace &w = c->ws;
+    const long cnt[5] = {net::L1N, net::L2N, net::L3N, net::L4N, net::head_count(cfg.num_actions, cfg.dueling)};
+    const long beg[5] = {net::C1W, net::C2W, net::C3W, net::F1W, net::HEAD};
+    const float *part[5] = {w.gp1, w.gp2, w.gp3, w.gp4, w.gp5};
+    const int nsp[5] = {ns1, ns2, ns3, 1, 1};
+    misc::RmsArgs RA{};
+    int blk = 0, k = 0;
+    for (int i = 0; i < 5; ++i) {
+        if (!(layers >> i & 1)) continue;
+        RA.seg[k++] = {beg[i], cnt[i], part[i], nsp[i], nsp[i] > 1 ? cnt[i] : 0, blk};
+        const long per = nsp[i] > 1 ? 64 : 256;
+        blk += (int)((cnt[i] + per - 1) / per);
+    }
+    for (; k < 5; ++k) RA.seg[k].block_begin = 0x7fffffff;  // never selected
+    RA.theta = c->theta; RA.v = c->rms_v; RA.m = c->rms_m; RA.g = c->grads;
+    RA.shadow = cfg.precision == 1 ? (__hip_bfloat16 *)c->buf.shadow_bf16 : nullptr;
+    RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps;
+    launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
+}
+
 // ----- backward through fc1, conv3, conv2, conv1 (no input gradient for conv1) -----
-// The input-gradient chain runs on st; the weight gradients of fc1, conv3 and conv2 run on sd.
+// The input-gradient chain and conv1's weight gradient run on st; the weight gradients of fc1,
+// conv3 and conv2 run on sd behind the events the chain records.  All of st's kernels are
+// enqueued before any of sd's: handing the host from one stream to another costs more than a
+// launch, and the device does not care in which order the host filled the two queues.
 void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st,
                   hipStream_t sd)
 {
@@ -470,8 +498,6 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
         if (small) launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 32, 4><<<dim3((B + 31) / 32, 98, 1), 256, 0, st>>>(D); });
         else launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
         ev_record(c->ev_a, st, sd);
-        WgradArgs G{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
-        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
     }
     {
         DgradArgs D{d3, c->theta + net::C3W, act2, d2, B};
@@ -479,24 +505,32 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
         if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 64, 3><<<dim3((M + 31) / 32, 1, 1), 384, 0, st>>>(D); });
         else launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_b, st, sd);
+    }
+    {
+        DgradArgs D{d2, c->theta + net::C2W, act1, d1, B};
+        long M = (long)B * 100;
+        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 64, 32, 4><<<dim3((M + 63) / 64, 1, 4), 512, 0, st>>>(D); });
+    }
+    {
+        split_rows((long)B * 400, 1, MAX_WSPLIT1, 32, &rps, ns1);
+        WgradArgs G{d1, s, w.gp1, B, rps, xs, net::L1N, 1.0f / 255.0f};
+        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256><<<dim3(1, 1, *ns1), 512, 0, st>>>(G); });
+    }
+    {
+        WgradArgs G{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
+        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
+    }
+    {
         split_rows((long)B * 49, 9, MAX_WSPLIT, 32, &rps, ns3);
         WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
         ev_wait(sd, c->ev_a, st);
         launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G); });
     }
     {
-        DgradArgs D{d2, c->theta + net::C2W, act1, d1, B};
-        long M = (long)B * 100;
-        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 64, 32, 4><<<dim3((M + 63) / 64, 1, 4), 512, 0, st>>>(D); });
         split_rows((long)B * 81, 8, MAX_WSPLIT, 32, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
         ev_wait(sd, c->ev_b, st);
         launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
-    }
-    {
-        split_rows((long)B * 400, 1, MAX_WSPLIT1, 32, &rps, ns1);
-        WgradArgs G{d1, s, w.gp1, B, rps, xs, net::L1N, 1.0f / 255.0f};
-        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256><<<dim3(1, 1, *ns1), 512, 0, st>>>(G); });
     }
 }
 
@@ -513,32 +547,38 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
         DgradArgs D{dh, sh + net::F1W, act3, d3, B};
         launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 64, 64, 1, 1><<<dim3((B + 63) / 64, 49, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_a, st, sd);
-        WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
-        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64, 1, 1><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
     }
     {
         DgradArgs D{d3, sh + net::C3W, act2, d2, B};
         long M = (long)B * 81;
         launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64, 1, 1><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_b, st, sd);
+    }
+    {
+        DgradArgs D{d2, sh + net::C2W, act1, d1, B};
+        long M = (long)B * 100;
+        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32, 1, 1><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
+    }
+    {  // conv1: one workgroup per split of samples, frames staged in LDS
+        *ns1 = std::min(B, MAX_WSPLIT1);
+        c1::WgradArgs G{c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift}, d1, w.gp1, B, *ns1};
+        launch(c, "conv1_wgrad", st, [&] { c1::k_conv1_wgrad<<<dim3(*ns1, 2), 256, 0, st>>>(G); });
+    }
+    {
+        WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
+        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64, 1, 1><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
+    }
+    {
         split_rows((long)B * 49, 9, MAX_WSPLIT, 64, &rps, ns3);
         WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
         ev_wait(sd, c->ev_a, st);
         launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64, 1, 1><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G); });
     }
     {
-        DgradArgs D{d2, sh + net::C2W, act1, d1, B};
-        long M = (long)B * 100;
-        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32, 1, 1><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
         split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
         ev_wait(sd, c->ev_b, st);
         launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64, 1, 1><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
-    }
-    {  // conv1: one workgroup per split of samples, frames staged in LDS
-        *ns1 = std::min(B, MAX_WSPLIT1);
-        c1::WgradArgs G{c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift}, d1, w.gp1, B, *ns1};
-        launch(c, "conv1_wgrad", st, [&] { c1::k_conv1_wgrad<<<dim3(*ns1, 2), 256, 0, st>>>(G); });
     }
 }
 
@@ -667,7 +707,7 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
     const char *graph = std::getenv("DQN_GRAPH");
     c->graph_off = !(graph && graph[0] == '1');
     if (!c->graph_off && hipStreamCreateWithFlags(&c->cap, hipStreamNonBlocking) != hipSuccess) c->cap = nullptr;
-    hipEvent_t *evs[5] = {&c->ev_fork, &c->ev_a, &c->ev_b, &c->ev_join, &c->ev_join2};
+    hipEvent_t *evs[6] = {&c->ev_fork, &c->ev_a, &c->ev_b, &c->ev_c, &c->ev_join, &c->ev_join2};
     for (hipEvent_t *e : evs)
         if (c->side && hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) {
             (void)hipStreamDestroy(c->side);
@@ -693,7 +733,7 @@ int32_t dqn_destroy(dqn_ctx *ctx)
             (void)hipStreamSynchronize(sx);
             (void)hipStreamDestroy(sx);
         }
-    for (hipEvent_t e : {ctx->ev_fork, ctx->ev_a, ctx->ev_b, ctx->ev_join, ctx->ev_join2})
+    for (hipEvent_t e : {ctx->ev_fork, ctx->ev_a, ctx->ev_b, ctx->ev_c, ctx->ev_join, ctx->ev_join2})
         if (e) (void)hipEventDestroy(e);
     delete ctx;
     return DQN_OK;
@@ -948,7 +988,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     ev_wait(sd, c->ev_fork, st);
     if (sp != sd) ev_wait(sp, c->ev_fork, st);
     misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
-    launch(c, "head_wgrad", sp, [&] { misc::k_head_wgrad<<<dim3(c->R, 4), 512, 0, sp>>>(HW); });
+    launch(c, "head_wgrad", sp, [&] { misc::k_head_wgrad<<<dim3(c->R, 16), 512, 0, sp>>>(HW); });
     if (!batch) {
         // the indices come from the sampling kernel, so the ring capacity bounds them
         launch(c, "per_update", sp, [&] {
@@ -965,23 +1005,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     ev_wait(st, c->ev_join, sd);
     if (sp != sd) (void)hipStreamWaitEvent(st, c->ev_join2, 0);
 
-    misc::RmsArgs RA{};
-    {
-        const long cnt[5] = {net::L1N, net::L2N, net::L3N, net::L4N, net::head_count(cfg.num_actions, cfg.dueling)};
-        const long beg[5] = {net::C1W, net::C2W, net::C3W, net::F1W, net::HEAD};
-        const float *part[5] = {w.gp1, w.gp2, w.gp3, w.gp4, w.gp5};
-        const int nsp[5] = {ns1, ns2, ns3, 1, 1};
-        int blk = 0;
-        for (int i = 0; i < 5; ++i) {
-            RA.seg[i] = {beg[i], cnt[i], part[i], nsp[i], nsp[i] > 1 ? cnt[i] : 0, blk};
-            const long per = nsp[i] > 1 ? 64 : 256;
-            blk += (int)((cnt[i] + per - 1) / per);
-        }
-        RA.theta = c->theta; RA.v = c->rms_v; RA.m = c->rms_m; RA.g = c->grads;
-        RA.shadow = cfg.precision == 1 ? (__hip_bfloat16 *)c->buf.shadow_bf16 : nullptr;
-        RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps;
-        launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
-    }
+    launch_rmsprop(c, RMS_ALL, ns1, ns2, ns3, st);
     return hip_status(c, "dqn_train_step");
 }
 

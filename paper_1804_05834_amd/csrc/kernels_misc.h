@@ -94,6 +94,29 @@ __device__ __forceinline__ void head_rows(const float *hid /*LDS*/, const float 
     }
 }
 
+// The same for the three passes of a training row at once: 3R dot products of length 512 spread
+// over groups of 16 lanes (32 independent loads per lane), so the whole head takes two rounds
+// of a 512-thread workgroup instead of one wave per row in turn.
+__device__ __forceinline__ void head_rows3(const float (*hid)[net::HID] /*LDS [3][512]*/, const float *head_on,
+                                           const float *head_tg, int K, int dueling,
+                                           float (*raw)[65] /*LDS [3][65]*/, int tid)
+{
+    const int R = K + (dueling ? 1 : 0);
+    const int grp = tid >> 4, l = tid & 15;
+    for (int d = grp; d < 3 * R; d += 32) {
+        const int p = d / R, r = d - p * R;
+        const float *head = p == 2 ? head_tg : head_on;
+        const float *w = head + head_w_off(r, K, dueling);
+        const float *x = hid[p];
+        float acc = 0.f;
+#pragma unroll 8
+        for (int k = 0; k < net::HID / 16; ++k) acc += w[l + 16 * k] * x[l + 16 * k];
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        if (l == 0) raw[p][r] = acc + head[head_b_off(r, K, dueling)];
+    }
+}
+
 // Q_a = V + (A_a - mean A) (Eq.13) or the raw outputs; serial, K <= 64
 __device__ __forceinline__ void combine_q(const float *raw, int K, int dueling, float *q)
 {
@@ -167,9 +190,7 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         A.h_s[(long)j * net::HID + i] = hs;
     }
     __syncthreads();
-    head_rows(hid[0], A.head_on, K, A.dueling, raw[0], tid, 512);
-    head_rows(hid[1], A.head_on, K, A.dueling, raw[1], tid, 512);
-    head_rows(hid[2], A.head_tg, K, A.dueling, raw[2], tid, 512);
+    head_rows3(hid, A.head_on, A.head_tg, K, A.dueling, raw, tid);
     __syncthreads();
     if (tid < 3) combine_q(raw[tid], K, A.dueling, q[tid]);
     __syncthreads();
@@ -229,19 +250,19 @@ struct HeadWgradArgs {
 };
 
 // Head weight gradient: dW[r][i] = sum_j dA[j][r] h[j][i], db[r] = sum_j dA[j][r].
-// grid (R, 4): block (r, c) owns hidden units [128c, 128c+128); its 512 threads split the
-// minibatch four ways and combine through LDS in a fixed order.  Block (0,0) also folds the
+// grid (R, 16): block (r, c) owns hidden units [32c, 32c+32); its 512 threads split the
+// minibatch sixteen ways and combine through LDS in a fixed order.  Block (0,0) also folds the
 // per-row loss terms into L = (1/B) sum_j w_j l_j.
 __global__ __launch_bounds__(512) void k_head_wgrad(HeadWgradArgs A)
 {
-    __shared__ float red[4][128];
-    __shared__ float redb[4];
-    const int r = blockIdx.x, il = threadIdx.x & 127, jg = threadIdx.x >> 7;
-    const int i = blockIdx.y * 128 + il;
+    __shared__ float red[16][33];
+    __shared__ float redb[16];
+    const int r = blockIdx.x, il = threadIdx.x & 31, jg = threadIdx.x >> 5;
+    const int i = blockIdx.y * 32 + il;
     const int R = A.K + (A.dueling ? 1 : 0);
     float acc = 0.f, accb = 0.f;
-#pragma unroll 4
-    for (int j = jg; j < A.B; j += 4) {
+#pragma unroll 8
+    for (int j = jg; j < A.B; j += 16) {
         float d = A.dA[(long)j * R + r];
         acc += d * A.h_s[(long)j * net::HID + i];
         accb += d;
@@ -250,9 +271,16 @@ __global__ __launch_bounds__(512) void k_head_wgrad(HeadWgradArgs A)
     if (il == 0) redb[jg] = accb;
     __syncthreads();
     if (jg == 0) {
-        A.ghead[head_w_off(r, A.K, A.dueling) + i] = (red[0][il] + red[1][il]) + (red[2][il] + red[3][il]);
-        if (il == 0 && blockIdx.y == 0)
-            A.ghead[head_b_off(r, A.K, A.dueling)] = (redb[0] + redb[1]) + (redb[2] + redb[3]);
+        float s = red[0][il];
+#pragma unroll
+        for (int g = 1; g < 16; ++g) s += red[g][il];
+        A.ghead[head_w_off(r, A.K, A.dueling) + i] = s;
+        if (il == 0 && blockIdx.y == 0) {
+            float sb = redb[0];
+#pragma unroll
+            for (int g = 1; g < 16; ++g) sb += redb[g];
+            A.ghead[head_b_off(r, A.K, A.dueling)] = sb;
+        }
     }
     if (r == 0 && blockIdx.y == 0 && threadIdx.x >= 448) {  // the last wave sums the loss terms
         const int lane = threadIdx.x & 63;
