@@ -181,6 +181,16 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_fw
 #pragma unroll
         for (int b = 0; b < WN; ++b) acc[a][b] = v16f{0};
 
+    // bias of this lane's channels, requested before the loop so the epilogue does not wait for it
+    v4f bias_r[WN][4];
+    if (!RAW) {
+#pragma unroll
+        for (int b = 0; b < WN; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                bias_r[b][g] = *reinterpret_cast<const v4f *>(S.bias + n0 + (wn * WN + b) * 32 + 8 * g + 4 * h);
+    }
+
     gload(kbeg);
     sstore();
     __syncthreads();
@@ -207,26 +217,47 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_fw
     }
 
     // acc[a][b][4g + j] = Y[row m = block a, lane li][channel = block b, 8g + 4h + j]
+    if constexpr (RAW) {
 #pragma unroll
-    for (int a = 0; a < WM; ++a) {
-        const int m = m0 + (wm * WM + a) * 32 + li;
-        if (m >= S.M) continue;
+        for (int a = 0; a < WM; ++a) {
+            const int m = m0 + (wm * WM + a) * 32 + li;
+            if (m >= S.M) continue;
+            float *y = static_cast<float *>(S.y) + (long)bz * A.split_stride;
 #pragma unroll
-        for (int b = 0; b < WN; ++b) {
+            for (int b = 0; b < WN; ++b)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = n0 + (wn * WN + b) * 32 + 8 * g + 4 * h;
-                float v0 = acc[a][b][4 * g] * A.scale, v1 = acc[a][b][4 * g + 1] * A.scale;
-                float v2 = acc[a][b][4 * g + 2] * A.scale, v3 = acc[a][b][4 * g + 3] * A.scale;
-                if (RAW) {
-                    float *y = static_cast<float *>(S.y) + (long)bz * A.split_stride;
-                    *reinterpret_cast<v4f *>(y + (long)m * G::N + col) = v4f{v0, v1, v2, v3};
-                } else {
-                    const v4f bv = *reinterpret_cast<const v4f *>(S.bias + col);
-                    *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(S.y) + (long)m * G::N + col) =
-                        pack4(fmaxf(v0 + bv.x, 0.f), fmaxf(v1 + bv.y, 0.f), fmaxf(v2 + bv.z, 0.f), fmaxf(v3 + bv.w, 0.f));
+                for (int g = 0; g < 4; ++g) {
+                    const int col = n0 + (wn * WN + b) * 32 + 8 * g + 4 * h;
+                    *reinterpret_cast<v4f *>(y + (long)m * G::N + col) =
+                        v4f{acc[a][b][4 * g] * A.scale, acc[a][b][4 * g + 1] * A.scale,
+                            acc[a][b][4 * g + 2] * A.scale, acc[a][b][4 * g + 3] * A.scale};
                 }
-            }
+        }
+    } else {
+        // bias + ReLU, the bf16 tile goes through LDS (the operand tiles are no longer read: the
+        // loop ends on a barrier) and leaves as whole rows, 16 bytes per lane
+        static_assert(RAW || BN <= BK, "the output tile is staged in the A tile's LDS");
+#pragma unroll
+        for (int a = 0; a < WM; ++a)
+#pragma unroll
+            for (int b = 0; b < WN; ++b)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = (wn * WN + b) * 32 + 8 * g + 4 * h;
+                    const v4f bv = bias_r[b][g];
+                    *reinterpret_cast<uint2 *>(&As[((wm * WM + a) * 32 + li) * LDK + col]) =
+                        pack4(fmaxf(acc[a][b][4 * g] * A.scale + bv.x, 0.f), fmaxf(acc[a][b][4 * g + 1] * A.scale + bv.y, 0.f),
+                              fmaxf(acc[a][b][4 * g + 2] * A.scale + bv.z, 0.f), fmaxf(acc[a][b][4 * g + 3] * A.scale + bv.w, 0.f));
+                }
+        __syncthreads();
+        constexpr int CH = BN / 8;
+        static_assert((BM * CH) % T == 0, "tile/threads mismatch");
+#pragma unroll
+        for (int i = 0; i < BM * CH / T; ++i) {
+            const int c = tid + i * T, row = c / CH, ch = c % CH;
+            if (m0 + row < S.M)
+                *reinterpret_cast<uint4 *>(static_cast<bf16_t *>(S.y) + (long)(m0 + row) * G::N + n0 + ch * 8) =
+                    *reinterpret_cast<const uint4 *>(&As[row * LDK + ch * 8]);
         }
     }
 }
@@ -319,6 +350,27 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
 #pragma unroll
         for (int b = 0; b < WN; ++b) acc[a][b] = v16f{0};
 
+    // where this lane's results go, and the stored activations there (the ReLU mask), requested
+    // before the loop so the epilogue does not wait for them
+    long obase[WM];
+    uint2 xa[WM][WN][4];
+#pragma unroll
+    for (int a = 0; a < WM; ++a) {
+        const int m = m0 + (wm * WM + a) * 32 + li;
+        obase[a] = -1;
+        if (m < Mc) {
+            const int n = m / D::PP, rr = m % D::PP;
+            const int hh = D::S * (rr / D::WP) + ca, ww = D::S * (rr % D::WP) + cb;
+            obase[a] = ((long)(n * D::H + hh) * D::W + ww) * D::CI + n0 + wn * WN * 32 + 4 * h;
+        }
+#pragma unroll
+        for (int b = 0; b < WN; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                xa[a][b][g] = obase[a] >= 0 ? *reinterpret_cast<const uint2 *>(A.xact + obase[a] + b * 32 + 8 * g)
+                                            : uint2{0, 0};
+    }
+
     gload(0);
     sstore();
     __syncthreads();
@@ -347,23 +399,18 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
     // acc[a][b][4g + j] = dX[position m = block a, lane li][channel = block b, 8g + 4h + j]
 #pragma unroll
     for (int a = 0; a < WM; ++a) {
-        const int m = m0 + (wm * WM + a) * 32 + li;
-        if (m >= Mc) continue;
-        const int n = m / D::PP, rr = m % D::PP;
-        const int hh = D::S * (rr / D::WP) + ca, ww = D::S * (rr % D::WP) + cb;
-        const long base = ((long)(n * D::H + hh) * D::W + ww) * D::CI;
+        if (obase[a] < 0) continue;
 #pragma unroll
         for (int b = 0; b < WN; ++b) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const long off = base + n0 + (wn * WN + b) * 32 + 8 * g + 4 * h;
-                const uint2 xa = *reinterpret_cast<const uint2 *>(A.xact + off);
+                const uint2 x = xa[a][b][g];
                 // ReLU mask of the layer below: its stored output is > 0
-                const float v0 = (int16_t)(xa.x & 0xFFFFu) > 0 ? acc[a][b][4 * g] : 0.f;
-                const float v1 = (int16_t)(xa.x >> 16) > 0 ? acc[a][b][4 * g + 1] : 0.f;
-                const float v2 = (int16_t)(xa.y & 0xFFFFu) > 0 ? acc[a][b][4 * g + 2] : 0.f;
-                const float v3 = (int16_t)(xa.y >> 16) > 0 ? acc[a][b][4 * g + 3] : 0.f;
-                *reinterpret_cast<uint2 *>(A.dx + off) = pack4(v0, v1, v2, v3);
+                const float v0 = (int16_t)(x.x & 0xFFFFu) > 0 ? acc[a][b][4 * g] : 0.f;
+                const float v1 = (int16_t)(x.x >> 16) > 0 ? acc[a][b][4 * g + 1] : 0.f;
+                const float v2 = (int16_t)(x.y & 0xFFFFu) > 0 ? acc[a][b][4 * g + 2] : 0.f;
+                const float v3 = (int16_t)(x.y >> 16) > 0 ? acc[a][b][4 * g + 3] : 0.f;
+                *reinterpret_cast<uint2 *>(A.dx + obase[a] + b * 32 + 8 * g) = pack4(v0, v1, v2, v3);
             }
         }
     }
