@@ -54,14 +54,18 @@ def bytes_per_launch(B, n_params, bf16, levels=20):
 # run (fetch x1.949, write x0.9875).  Keyed by (kernel, batch, precision); the figures and the
 # commands are in profiles/train_step_b512_bf16_hbm_traffic.md.
 MEASURED_TRAFFIC = {
-    ("conv1_fwd", 512, "bf16"): 42.8e6 + 38.8e6,
-    ("conv2_fwd", 512, "bf16"): 52.3e6 + 15.8e6,
-    ("conv3_fwd", 512, "bf16"): 18.0e6 + 9.5e6,
-    ("fc1_fwd", 512, "bf16"): 66.8e6 + 22.1e6,
-    ("conv2_dgrad", 512, "bf16"): 19.3e6 + 20.9e6,
-    ("conv2_wgrad", 512, "bf16"): 82.9e6 + 7.7e6,
-    ("conv3_wgrad", 512, "bf16"): 51.7e6 + 8.2e6,
-    ("conv1_wgrad", 512, "bf16"): 27.1e6 + 8.3e6,
+    ("conv1_fwd", 512, "bf16"): 42.9e6 + 38.8e6,
+    ("conv2_fwd", 512, "bf16"): 40.9e6 + 15.7e6,
+    ("conv3_fwd", 512, "bf16"): 16.2e6 + 9.5e6,
+    ("fc1_fwd", 512, "bf16"): 19.9e6 + 21.7e6,
+    ("head_train", 512, "bf16"): 22.3e6 + 1.6e6,
+    ("fc1_dgrad", 512, "bf16"): 11.4e6 + 3.2e6,
+    ("conv3_dgrad", 512, "bf16"): 8.9e6 + 5.2e6,
+    ("conv2_dgrad", 512, "bf16"): 18.5e6 + 12.9e6,
+    ("conv1_wgrad", 512, "bf16"): 27.0e6 + 8.3e6,
+    ("conv2_wgrad", 512, "bf16"): 19.5e6 + 7.7e6,
+    ("conv3_wgrad", 512, "bf16"): 8.4e6 + 8.2e6,
+    ("fc1_wgrad", 512, "bf16"): 7.7e6 + 6.3e6,
     ("rmsprop", 512, "bf16"): 43.4e6 + 23.4e6,
 }
 
