@@ -11,7 +11,8 @@ Prints ONE JSON line.  `value` is train steps/s of the headline workload; `roofl
 the kernel that takes the most time in that workload (timed live with HIP events on the
 launch stream); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same
 workload; `kernels` lists every kernel of the step against its own roofline; `also` carries
-the batch-32 fp32 configuration of the same metric and the acting + training loop.
+the batch-32 fp32 configuration of the same metric, the acting + training loop and the
+single-stream agent loop (act, store with maximal priority, train every fourth step).
 """
 import argparse
 import json
@@ -156,6 +157,50 @@ def profile_kernels(m, torch, B, steps, seed0):
     return m.profile_end()
 
 
+def time_agent_loop(dqn, synth, torch, capacity, env_steps, K=18, B=32):
+    """The loop of Alg.1 / Alg.2 around a synthetic emulator (one environment stream, as in the
+    paper): every environment step acts on one observation and stores one time step with the
+    maximal priority; every fourth step trains on a batch of 32 (fp32); the target network is
+    copied on Table 1's period; epsilon and beta follow Table 1's ramps.  The ring starts
+    full (learning start already passed)."""
+    cfg = dqn.make_config(num_actions=K, dueling=1, double_q=1, precision=0, loss_kind=1,
+                          huber_delta=1.0, gamma=0.99, lr=2.5e-4, rms_decay=0.95, rms_eps=0.01,
+                          max_batch=B, max_act_batch=32, replay_capacity=capacity, per_alpha=0.6,
+                          per_eps=1e-6, seed=1804, target_seed=5834)
+    m = dqn.Dqn(cfg)
+    fill_ring(m, synth, torch, capacity, K)
+    sc = dqn.schedule_default()
+    pool = 256
+    obs = synth.states(31, pool, device="cuda")
+    frames = synth.frames(23, torch.arange(pool, device="cuda"), device="cuda")
+    rew = synth.rewards(41, pool, "cuda")
+    don = synth.dones(42, pool, 0.01, "cuda")
+    t0 = None
+    first = sc.learning_start + 1
+    trains = 0
+    for i in range(-40, env_steps):
+        if i == 0:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        t = first + max(i, 0)
+        eps, beta, train, sync = dqn.schedule_at(sc, t)
+        k = i % pool
+        act = m.act(obs[k:k + 1], eps, t)
+        m.replay_store(frames[k:k + 1], act, rew[k:k + 1], don[k:k + 1])
+        if train:
+            m.train_step(B, None, beta=beta, draw_seed=t, outputs=False)
+            trains += i >= 0
+        if sync:
+            m.sync_target()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    m.close()
+    return {"workload": "agent loop (Alg.1/Alg.2, Table 1 schedules): act on 1 observation + store 1 time step "
+                        "per environment step, train batch %d fp32 every 4th step, synthetic emulator" % B,
+            "value": env_steps / wall, "unit": "environment steps/s", "us_per_env_step": wall / env_steps * 1e6,
+            "train_steps": trains}
+
+
 def kernel_table(prof, B, R, n_params, precision):
     """Per kernel: live HIP-event average duration, the roofline that bounds it, what it achieves."""
     fl = flops_per_launch(B, R)
@@ -286,6 +331,7 @@ def main():
             del m32
             torch.cuda.empty_cache()
         also.append(time_act_train(dqn, synth, torch, args.capacity, max(50, args.steps // 5), 10))
+        also.append(time_agent_loop(dqn, synth, torch, args.capacity, max(200, 2 * args.steps)))
         res["also"] = also
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(torch, synth, B, min(B, 64))

@@ -178,6 +178,47 @@ int32_t per_fill(dqn_ctx *ctx, const float *priorities, int64_t n, void *stream)
 int32_t dqn_replay_write(dqn_ctx *ctx, int64_t slot0, int64_t n, const uint8_t *frames,
                          const int32_t *a, const float *r, const uint8_t *done, void *stream);
 
+/* Store path (Alg.1 "store transition"; Alg.2 "store transition with maximal
+ * priority").  Appends n consecutive time steps of ONE environment stream at the
+ * write cursor (slot = stream position mod capacity): frame x_t with the action
+ * a_t taken on it, the reward r_t and the terminal flag done_t.  Transition i is
+ * read back as s = frames (i-3..i), s' = frames (i-2..i+1), so a time step
+ * completes the transition before it.  Each completed transition enters the
+ * sum-tree with the maximal priority seen so far (1 before the first update),
+ * leaf = fp32(max_p^alpha); a transition whose state stack would reach back
+ * before the start of the stream or across an episode end (done at one of the
+ * three slots before it) gets leaf 0 and is never sampled, and so do the last
+ * written slot (its transition is not complete yet) and the three slots after
+ * it, whose windows mix the newest frames with the oldest.
+ * The stored count (N of Eq.12) becomes min(time steps stored, capacity).
+ * frames: [n][84][84] device, 16-byte aligned; a, r, done: [n] device, not NULL.
+ * 1 <= n <= min(1020, capacity - 8); the ring must have at least 16 slots.
+ * per_fill sets the cursor to n mod capacity; dqn_replay_write does not move it. */
+int32_t dqn_replay_store(dqn_ctx *ctx, int64_t n, const uint8_t *frames, const int32_t *a,
+                         const float *r, const uint8_t *done, void *stream);
+
+/* Host-side view of the store path: next slot, stored count, time steps so far.
+ * Any pointer may be NULL. */
+int32_t dqn_replay_state(const dqn_ctx *ctx, int64_t *cursor, int64_t *stored, int64_t *steps);
+
+/* Schedules of Table 1 as functions of the environment step t = 1, 2, ... (host
+ * only, no device work): a value "a -> b (1 -> T steps)" is a at t = 1, b at
+ * t >= T, linear in between; train is set when t is past learning_start and
+ * t = 0 mod update_period (Alg.2 "if t = 0 mod K"); sync_target when
+ * t = 0 mod target_period (Alg.2 last line).  dqn_schedule_default fills in
+ * Table 1: learning start 50,000, update period 4, target period 30,000,
+ * epsilon 1.0 -> 0.1 over 5,000,000 steps, beta 0.4 -> 1.0 over 100,000,000. */
+typedef struct {
+    int64_t learning_start, update_period, target_period, eps_steps, beta_steps;
+    float eps_start, eps_end, beta_start, beta_end;
+} dqn_schedule;
+typedef struct {
+    float epsilon, beta;
+    int32_t train, sync_target;
+} dqn_schedule_point;
+int32_t dqn_schedule_default(dqn_schedule *s);
+int32_t dqn_schedule_at(const dqn_schedule *s, int64_t step, dqn_schedule_point *out);
+
 /* Materialises the stacks of n slots: s, s_next [n][4][84][84], a, r, done [n]
  * (any output may be NULL).  1 <= n <= max_batch. */
 int32_t dqn_replay_gather(dqn_ctx *ctx, const int32_t *idx, int32_t n, uint8_t *s, uint8_t *s_next,

@@ -32,6 +32,12 @@ class OrcConfig(C.Structure):
     ]
 
 
+class OrcSchedule(C.Structure):
+    _fields_ = [("learning_start", C.c_int64), ("update_period", C.c_int64), ("target_period", C.c_int64),
+                ("eps_steps", C.c_int64), ("beta_steps", C.c_int64), ("eps_start", C.c_double),
+                ("eps_end", C.c_double), ("beta_start", C.c_double), ("beta_end", C.c_double)]
+
+
 _lib = None
 
 
@@ -81,6 +87,12 @@ def lib():
         L.orc_per_update.restype = C.c_int32
         L.orc_per_update.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_int32, C.c_double, C.c_double, C.c_void_p]
+        L.orc_replay_store.restype = None
+        L.orc_replay_store.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_int64, C.c_double, C.c_float]
+        L.orc_schedule_at.restype = None
+        L.orc_schedule_at.argtypes = [C.POINTER(OrcSchedule), C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p]
         L.orc_gather.restype = None
         L.orc_gather.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p,
                                  C.c_void_p]
@@ -279,6 +291,43 @@ def per_update(tree, size, idx, td_abs, alpha, eps, max_p=1.0):
     if rc != 0:
         raise ValueError("orc_per_update rc=%d" % rc)
     return float(mp[0])
+
+
+class ReplayState:
+    """Host-side picture of the store path: sum-tree, done flags, write cursor, stream length."""
+
+    def __init__(self, capacity, alpha):
+        self.capacity = int(capacity)
+        self.alpha = float(alpha)
+        L = 1
+        while L < capacity:
+            L *= 2
+        self.L = L
+        self.tree = np.zeros(2 * L, np.float32)
+        self.done = np.zeros(capacity, np.uint8)
+        self.cursor = np.zeros(1, np.int64)
+        self.seq = np.zeros(1, np.int64)
+        self.max_p = 1.0
+
+    @property
+    def stored(self):
+        return int(min(self.seq[0], self.capacity))
+
+    def store(self, done_new):
+        done_new = _chk(done_new, np.uint8)
+        lib().orc_replay_store(_p(self.tree), self.L, self.capacity, _p(self.cursor), _p(self.seq),
+                               _p(self.done), _p(done_new), done_new.size, self.alpha,
+                               C.c_float(self.max_p))
+
+
+def schedule_at(t, learning_start=50000, update_period=4, target_period=30000, eps_steps=5000000,
+                beta_steps=100000000, eps_start=1.0, eps_end=0.1, beta_start=0.4, beta_end=1.0):
+    """(epsilon, beta, train, sync_target) at environment step t (Table 1 defaults)."""
+    sc = OrcSchedule(learning_start, update_period, target_period, eps_steps, beta_steps,
+                     eps_start, eps_end, beta_start, beta_end)
+    e = np.zeros(1); b = np.zeros(1); tr = np.zeros(1, np.int32); sy = np.zeros(1, np.int32)
+    lib().orc_schedule_at(C.byref(sc), int(t), _p(e), _p(b), _p(tr), _p(sy))
+    return float(e[0]), float(b[0]), int(tr[0]), int(sy[0])
 
 
 def gather(frames, idx):

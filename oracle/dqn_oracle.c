@@ -698,3 +698,77 @@ void orc_gather(const uint8_t *frames, int64_t capacity, const int32_t *idx, int
             if (k > 0) memcpy(s_next + ((int64_t)j * 4 + k - 1) * F, src, (size_t)F);
         }
 }
+
+/* ------------------------------------------------------------------ */
+/* Store path (Alg.1 "store transition"; Alg.2 "store transition ... with
+ * maximal priority").  One environment stream; time step t goes to ring slot
+ * t mod N and carries (x_t, a_t, r_t, done_t); transition i is
+ * (s = frames i-3..i, a_i, r_i, s' = frames i-2..i+1).  Only the part that
+ * decides what can be sampled is modelled here (frames themselves are a plain
+ * copy): the done flags and the sum-tree.
+ *
+ * Written out one time step at a time.  When time step q lands in slot h:
+ *   - transition h-1 becomes complete (its s' now ends in x_q).  It enters
+ *     the tree with the maximal priority seen so far, leaf = fp32(max_p^alpha),
+ *     unless its state stack would reach back before the stream's start
+ *     (q-1 < 3) or across an episode end (done at i-3, i-2 or i-1): such a
+ *     stack mixes two episodes, the paper does not say what the preprocessing
+ *     does there, and the reading taken is that it is never sampled (leaf 0).
+ *   - slot h itself (its transition waits for the next frame) and slots
+ *     h+1 .. h+3, whose five-frame windows now mix the newest frames with the
+ *     oldest: leaf 0.
+ * Every ancestor is recomputed as left + right.                            */
+/* ------------------------------------------------------------------ */
+static void set_leaf(float *tree, int64_t L, int64_t slot, float v)
+{
+    int64_t node = L + slot;
+    tree[node] = v;
+    for (node >>= 1; node >= 1; node >>= 1) tree[node] = tree[2 * node] + tree[2 * node + 1];
+}
+
+void orc_replay_store(float *tree, int64_t L, int64_t capacity, int64_t *cursor, int64_t *seq,
+                      uint8_t *done_ring, const uint8_t *done_new, int64_t n, double alpha, float max_p)
+{
+    for (int64_t t = 0; t < n; ++t) {
+        const int64_t h = *cursor, q = *seq;
+        done_ring[h] = done_new ? done_new[t] : 0;
+        if (q >= 1) {
+            const int64_t i = (h - 1 + capacity) % capacity;
+            int valid = q - 1 >= 3;
+            for (int k = 1; k <= 3 && valid; ++k)
+                if (done_ring[((i - k) % capacity + capacity) % capacity]) valid = 0;
+            set_leaf(tree, L, i, valid ? leaf_value((double)max_p, alpha) : 0.0f);
+        }
+        for (int k = 0; k < 4; ++k) set_leaf(tree, L, (h + k) % capacity, 0.0f);
+        *cursor = (h + 1) % capacity;
+        *seq = q + 1;
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Schedules of Table 1, as functions of the environment step t = 1, 2, ...:
+ * a value that goes "a -> b (1 -> T steps)" is a at t = 1, b at t >= T and
+ * linear in between; an update happens when t is past the learning start and
+ * t = 0 mod the update period (Alg.2 "if t = 0 mod K"); the target network is
+ * copied when t = 0 mod the target period.                                */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t learning_start, update_period, target_period, eps_steps, beta_steps;
+    double eps_start, eps_end, beta_start, beta_end;
+} orc_schedule;
+
+static double ramp(double a, double b, int64_t t, int64_t T)
+{
+    if (T <= 1 || t >= T) return b;
+    if (t <= 1) return a;
+    return a + (b - a) * (double)(t - 1) / (double)(T - 1);
+}
+
+void orc_schedule_at(const orc_schedule *s, int64_t t, double *epsilon, double *beta, int32_t *train,
+                     int32_t *sync_target)
+{
+    *epsilon = ramp(s->eps_start, s->eps_end, t, s->eps_steps);
+    *beta = ramp(s->beta_start, s->beta_end, t, s->beta_steps);
+    *train = t > s->learning_start && t % s->update_period == 0;
+    *sync_target = t % s->target_period == 0;
+}

@@ -133,6 +133,8 @@ struct dqn_ctx {
     hipStream_t side = nullptr;
     hipStream_t side2 = nullptr;  // the single-workgroup priority update gets a lane of its own
     hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_c = nullptr, ev_join = nullptr, ev_join2 = nullptr;
+    int64_t cursor = 0;  // next ring slot of the store path
+    int64_t seq = 0;     // time steps stored so far (stream position of the next one)
     bool prof = false;
     std::vector<ProfRec> recs;
     std::string err;
@@ -826,6 +828,8 @@ int32_t per_fill(dqn_ctx *c, const float *priorities, int64_t n, void *stream)
     for (long first = L >> 1; first >= 1; first >>= 1)
         launch(c, "tree_level", st, [&] { misc::k_tree_level<<<grid1(first, 256), 256, 0, st>>>(c->tree, first, first); });
     c->stored = n;
+    c->seq = n;
+    c->cursor = n % c->cfg.replay_capacity;
     return hip_status(c, "per_fill");
 }
 
@@ -873,6 +877,64 @@ int32_t dqn_replay_write(dqn_ctx *c, int64_t slot0, int64_t n, const uint8_t *fr
                                                                 c->meta_done, cap, slot0, frames, a, r, done);
     });
     return hip_status(c, "dqn_replay_write");
+}
+
+int32_t dqn_replay_store(dqn_ctx *c, int64_t n, const uint8_t *frames, const int32_t *a, const float *r,
+                         const uint8_t *done, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    const int64_t cap = c->cfg.replay_capacity;
+    if (cap <= 0) return fail(c, DQN_ERR_STATE, "dqn_replay_store: context has no replay");
+    if (cap < 16) return fail(c, DQN_ERR_STATE, "dqn_replay_store: needs a ring of at least 16 slots");
+    if (n < 1 || n > 1020 || n > cap - 8) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_store: n must be in 1..min(1020, capacity-8)");
+    if (!frames || !aligned(frames, 16) || !a || !r || !done)
+        return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_store: NULL argument or frames not 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t h0 = c->cursor;
+    launch(c, "replay_write", st, [&] {
+        misc::k_replay_write<<<dim3((unsigned)n), 256, 0, st>>>((uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r,
+                                                                c->meta_done, cap, h0, frames, a, r, done);
+    });
+    launch(c, "store_priorities", st, [&] {
+        misc::k_store_priorities<<<1, (int)((n + 4 + 63) / 64 * 64), 0, st>>>(c->tree, c->L, c->levels, cap, h0, c->seq,
+                                                                             (int)n, c->meta_done, c->cfg.per_alpha);
+    });
+    c->cursor = (h0 + n) % cap;
+    c->seq += n;
+    c->stored = std::min<int64_t>(c->seq, cap);
+    return hip_status(c, "dqn_replay_store");
+}
+
+int32_t dqn_replay_state(const dqn_ctx *c, int64_t *cursor, int64_t *stored, int64_t *steps)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (cursor) *cursor = c->cursor;
+    if (stored) *stored = c->stored;
+    if (steps) *steps = c->seq;
+    return DQN_OK;
+}
+
+int32_t dqn_schedule_default(dqn_schedule *s)
+{
+    if (!s) return DQN_ERR_INVALID_ARG;
+    s->learning_start = 50000; s->update_period = 4; s->target_period = 30000;
+    s->eps_steps = 5000000; s->beta_steps = 100000000;
+    s->eps_start = 1.0f; s->eps_end = 0.1f; s->beta_start = 0.4f; s->beta_end = 1.0f;
+    return DQN_OK;
+}
+
+int32_t dqn_schedule_at(const dqn_schedule *s, int64_t step, dqn_schedule_point *out)
+{
+    if (!s || !out || step < 1 || s->update_period < 1 || s->target_period < 1) return DQN_ERR_INVALID_ARG;
+    auto ramp = [](double a, double b, int64_t t, int64_t T) {
+        if (T <= 1 || t >= T) return b;
+        return a + (b - a) * (double)(t - 1) / (double)(T - 1);
+    };
+    out->epsilon = (float)ramp(s->eps_start, s->eps_end, step, s->eps_steps);
+    out->beta = (float)ramp(s->beta_start, s->beta_end, step, s->beta_steps);
+    out->train = step > s->learning_start && step % s->update_period == 0;
+    out->sync_target = step % s->target_period == 0;
+    return DQN_OK;
 }
 
 int32_t dqn_replay_gather(dqn_ctx *c, const int32_t *idx, int32_t n, uint8_t *s, uint8_t *s_next, int32_t *a,

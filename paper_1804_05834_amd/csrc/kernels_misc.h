@@ -536,6 +536,28 @@ __global__ __launch_bounds__(1024) void k_per_normalise(float *is_w, int B)
     if (j < B) is_w[j] = w / wmax;
 }
 
+// Leaf-to-root repair by the threads of ONE workgroup, each starting from its own distinct leaf
+// with the leaf's new value v: a level is one exchange through memory: every walker publishes
+// its node, the workgroup meets, every walker reads its sibling as it now stands and forms
+// parent = left + right (fp32; the sum is commutative, so walkers whose paths have merged hold
+// identical values and store them to the same word; the result is bit-identical to repairing
+// the paths one after another).  All walkers sit on one compute unit, so workgroup scope is
+// enough: a store is complete before the barrier and the load after it sees it.  Every thread
+// of the workgroup must call this (it contains barriers).
+__device__ __forceinline__ void tree_walk(float *tree, int node, float v, bool walk, int levels)
+{
+    if (walk) __hip_atomic_store(&tree[node], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    for (int l = 0; l < levels; ++l) {
+        __syncthreads();
+        if (walk) {
+            const float vs = __hip_atomic_load(&tree[node ^ 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            v = v + vs;
+            node >>= 1;
+            __hip_atomic_store(&tree[node], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    }
+}
+
 // Priority update (Eq.11): a single workgroup, one thread per entry.  Repeated
 // slots are settled first ("last occurrence wins" is an integer maximum over
 // entry numbers in an LDS hash table keyed by leaf).  The surviving entries
@@ -600,18 +622,39 @@ __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int le
     // value and store it to the same word.
     const bool walk = valid && ivals[slot] == j;
     float v = (float)pow((double)p, (double)alpha);
-    // All walkers sit on one compute unit, so workgroup scope is enough: a store is complete
-    // before the barrier and the load after it sees it.
-    if (walk) __hip_atomic_store(&tree[node], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    for (int l = 0; l < levels; ++l) {
-        __syncthreads();
-        if (walk) {
-            const float vs = __hip_atomic_load(&tree[node ^ 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            v = v + vs;
-            node >>= 1;
-            __hip_atomic_store(&tree[node], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    tree_walk(tree, node, v, walk, levels);
+}
+
+// Store path (Alg.2 "store transition with maximal priority"): n time steps have just been
+// written to ring slots h0 .. h0+n-1 (stream positions seq0 .. seq0+n-1).  Thread j settles
+// the leaf of slot h0-1+j: for j < n that transition has just become complete (its s' ends in a
+// new frame) and enters with leaf = fp32(max_p^alpha), unless its state stack would reach back
+// before the start of the stream or across an episode end (done at one of the three slots
+// before it), in which case it is never sampled (leaf 0); the last written slot (not complete
+// yet) and the three after it, whose windows mix the newest frames with the oldest (j = n ..
+// n+3), get leaf 0.
+// One workgroup, n + 4 <= 1024 distinct slots, then the same level-by-level walk as above.
+__global__ __launch_bounds__(1024) void k_store_priorities(float *tree, long L, int levels, long cap,
+                                                           long h0, long seq0, int n,
+                                                           const uint8_t *done, float alpha)
+{
+    const int j = threadIdx.x;
+    const bool walk = j < n + 4;
+    long slot = (h0 - 1 + j) % cap;
+    if (slot < 0) slot += cap;
+    float v = 0.f;
+    if (j < n) {
+        const long q = seq0 - 1 + j;  // stream position of the transition's own frame
+        bool valid = q >= 3;
+#pragma unroll
+        for (int k = 1; k <= 3; ++k) {
+            long sk = slot - k;
+            if (sk < 0) sk += cap;
+            if (done[sk]) valid = false;
         }
+        if (valid) v = (float)pow((double)tree[2 * L], (double)alpha);
     }
+    tree_walk(tree, (int)(L + slot), v, walk, levels);
 }
 
 // Copies up to nine short arrays of 4-byte words; grid (blocks, items).

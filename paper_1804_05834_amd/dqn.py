@@ -17,7 +17,8 @@ OK, ERR_INVALID_ARG, ERR_OOM, ERR_HIP, ERR_STATE, ERR_UNSUPPORTED = 0, -1, -2, -
 
 EXPORTS = ["dqn_query_sizes", "dqn_init", "dqn_act", "dqn_train_step", "per_sample", "per_update",
            "per_fill", "dqn_replay_write", "dqn_replay_gather", "dqn_sync_target", "dqn_get_params",
-           "dqn_set_params", "dqn_profile_begin", "dqn_profile_end", "dqn_last_error", "dqn_destroy"]
+           "dqn_set_params", "dqn_profile_begin", "dqn_profile_end", "dqn_last_error", "dqn_destroy",
+           "dqn_replay_store", "dqn_replay_state", "dqn_schedule_default", "dqn_schedule_at"]
 
 
 class DqnConfig(C.Structure):
@@ -52,6 +53,16 @@ class DqnBatch(C.Structure):
 class DqnStepOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("loss", "q_s", "q_next_online", "q_next_target", "y", "td",
                                           "a_star", "idx", "is_w")]
+
+
+class DqnSchedule(C.Structure):
+    _fields_ = [("learning_start", C.c_int64), ("update_period", C.c_int64), ("target_period", C.c_int64),
+                ("eps_steps", C.c_int64), ("beta_steps", C.c_int64), ("eps_start", C.c_float),
+                ("eps_end", C.c_float), ("beta_start", C.c_float), ("beta_end", C.c_float)]
+
+
+class DqnSchedulePoint(C.Structure):
+    _fields_ = [("epsilon", C.c_float), ("beta", C.c_float), ("train", C.c_int32), ("sync_target", C.c_int32)]
 
 
 class DqnError(RuntimeError):
@@ -91,6 +102,10 @@ def lib():
             "per_fill": [vp, vp, i64, vp],
             "dqn_replay_write": [vp, i64, i64, vp, vp, vp, vp, vp],
             "dqn_replay_gather": [vp, vp, i32, vp, vp, vp, vp, vp, vp],
+            "dqn_replay_store": [vp, i64, vp, vp, vp, vp, vp],
+            "dqn_replay_state": [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)],
+            "dqn_schedule_default": [C.POINTER(DqnSchedule)],
+            "dqn_schedule_at": [C.POINTER(DqnSchedule), i64, C.POINTER(DqnSchedulePoint)],
             "dqn_sync_target": [vp, vp],
             "dqn_get_params": [vp, i32, vp, vp],
             "dqn_set_params": [vp, i32, vp, vp],
@@ -243,6 +258,16 @@ class Dqn:
         self._check(lib().dqn_replay_write(self._h, slot0, frames.shape[0], _ptr(frames), _ptr(a),
                                            _ptr(r), _ptr(done), _stream()))
 
+    def replay_store(self, frames, a, r, done):
+        self._check(lib().dqn_replay_store(self._h, frames.shape[0], _ptr(frames), _ptr(a), _ptr(r), _ptr(done),
+                                           _stream()))
+
+    def replay_state(self):
+        """(next slot, stored count, time steps stored so far)"""
+        cur, st, n = C.c_int64(), C.c_int64(), C.c_int64()
+        self._check(lib().dqn_replay_state(self._h, C.byref(cur), C.byref(st), C.byref(n)))
+        return cur.value, st.value, n.value
+
     def replay_gather(self, idx):
         n, dev = idx.numel(), self.device
         s = torch.empty(n, 4, 84, 84, dtype=torch.uint8, device=dev)
@@ -277,3 +302,20 @@ class Dqn:
         ms = (C.c_double * cap)()
         n = self._check(lib().dqn_profile_end(self._h, cap, names, counts, ms))
         return {names[i].decode(): (int(counts[i]), float(ms[i])) for i in range(min(n, cap))}
+
+
+def schedule_default():
+    sc = DqnSchedule()
+    rc = lib().dqn_schedule_default(C.byref(sc))
+    if rc != 0:
+        raise DqnError(rc, "dqn_schedule_default")
+    return sc
+
+
+def schedule_at(sc, step):
+    """(epsilon, beta, train, sync_target) at environment step `step` (host only)."""
+    pt = DqnSchedulePoint()
+    rc = lib().dqn_schedule_at(C.byref(sc), int(step), C.byref(pt))
+    if rc != 0:
+        raise DqnError(rc, "dqn_schedule_at")
+    return pt.epsilon, pt.beta, pt.train, pt.sync_target

@@ -474,6 +474,62 @@ def test_replay_train_step_full_size_bf16(dq, orc):
 
 
 # ------------------------------------------------------------------ error paths
+def test_store_path_parity(dq, orc):
+    """Alg.2 store line: chunks of time steps appended at the cursor, every tree node compared
+    bit for bit with the oracle's one-step-at-a-time store, across a ring wrap, episode ends and
+    priority updates that raise the maximal priority; then the stored data drive a train step."""
+    print("case store path", flush=True)
+    cap, K, B = 3000, 18, 64
+    m = dq.Dqn(dq.make_config(max_batch=B, replay_capacity=cap, **CONFIGS["dueling_ddqn"]))
+    ref = orc.ReplayState(cap, float(np.float32(0.6)))
+    assert ref.L == m.L
+    pos = 0
+    rng = np.random.default_rng(3)
+
+    def store(n):
+        nonlocal pos
+        fr = synth.frames(21, torch.arange(pos, pos + n, device="cuda"), device="cuda")
+        a = synth.actions(40, n, K, "cuda", first=pos)
+        r = synth.rewards(41, n, "cuda", first=pos)
+        d = synth.dones(42, n, 0.05, "cuda", first=pos)
+        m.replay_store(fr, a, r, d)
+        ref.store(d.cpu().numpy())
+        pos += n
+        assert np.array_equal(m.tree.cpu().numpy()[1:], ref.tree[1:]), pos
+        assert m.replay_state() == (pos % cap, min(pos, cap), pos)
+
+    for n in (1, 1, 2, 5, 64, 1020, 333):
+        store(n)
+    # updates with known |delta| raise the maximal priority; later stores must use it
+    idx, _ = m.per_sample(B, 0.4, 17)
+    td = (0.5 + 3.0 * synth.u24(77, torch.arange(B))).cuda()
+    m.per_update(idx, td)
+    ref.max_p = orc.per_update(ref.tree, ref.stored, idx.cpu().numpy(), td.cpu().numpy(), ref.alpha,
+                               float(np.float32(1e-6)), ref.max_p)
+    assert float(m.max_priority) == np.float32(ref.max_p)
+    for n in (3, 1020, 1020, 17, 600):      # wraps the 3000-slot ring
+        store(n)
+    assert pos > cap
+    # what is drawn is whole, and reads back as the frames that were stored
+    idx, w = m.per_sample(B, 0.4, 5)
+    idx_ref, _ = _check_indices(orc, idx.cpu().numpy(), ref.tree, ref.stored, B, 0.4, 5)
+    s, sn, a, r, d = m.replay_gather(idx)
+    base = pos - cap
+    q = (idx_ref.astype(np.int64) - base % cap) % cap + base      # stream position held by each drawn slot
+    assert np.all(q + 1 < pos) and np.all(q - 3 >= base)
+    want = synth.frames(21, torch.from_numpy((q[:, None] - 3 + np.arange(5)[None, :]).reshape(-1))).reshape(B, 5, 84, 84)
+    assert torch.equal(s.cpu(), want[:, :4]) and torch.equal(sn.cpu(), want[:, 1:])
+    dn = synth.dones(42, pos, 0.05, "cpu").numpy()
+    assert not any(dn[qq - 3:qq].any() for qq in q)
+    out = m.train_step(B, None, beta=0.5, draw_seed=8)
+    assert np.isfinite(float(out["loss"][0]))
+    # error paths: too many steps in one call, NULL metadata
+    fr = synth.frames(21, torch.arange(4, device="cuda"), device="cuda")
+    with pytest.raises(dq.DqnError):
+        m.replay_store(fr, None, None, None)
+    m.close()
+
+
 def test_error_paths_on_device(dq):
     print("case errors", flush=True)
     m = dq.Dqn(dq.make_config(replay_capacity=100, max_batch=8, max_act_batch=8))
