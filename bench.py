@@ -157,6 +157,28 @@ def profile_kernels(m, torch, B, steps, seed0):
     return m.profile_end()
 
 
+def time_variants(dqn, synth, torch, capacity, steps, warmup, K=18, B=32):
+    """The four model settings of the paper's performance figure (Double DQN with a plain or a
+    dueling head, uniform replay = priority exponent 0, or prioritized replay with exponent 0.6),
+    each as the batch-32 fp32 step over the same ring."""
+    out = []
+    for name, dueling, alpha in (("double DQN", 0, 0.0), ("dueling double DQN", 1, 0.0),
+                                 ("double DQN with prioritized replay", 0, 0.6),
+                                 ("dueling double DQN with prioritized replay", 1, 0.6)):
+        cfg = dqn.make_config(num_actions=K, dueling=dueling, double_q=1, precision=0, loss_kind=1,
+                              huber_delta=1.0, gamma=0.99, lr=2.5e-4, rms_decay=0.95, rms_eps=0.01,
+                              max_batch=B, max_act_batch=32, replay_capacity=capacity, per_alpha=alpha,
+                              per_eps=1e-6, seed=1804, target_seed=5834)
+        m = dqn.Dqn(cfg)
+        fill_ring(m, synth, torch, capacity, K)
+        wall, _, _ = time_steps(m, torch, B, steps, warmup)
+        out.append({"setting": name, "value": steps / wall, "unit": "train steps/s"})
+        m.close()
+        del m
+        torch.cuda.empty_cache()
+    return {"workload": "the four model settings of the paper's performance figure, batch %d fp32" % B, "settings": out}
+
+
 def time_agent_loop(dqn, synth, torch, capacity, env_steps, K=18, B=32):
     """The loop of Alg.1 / Alg.2 around a synthetic emulator (one environment stream, as in the
     paper): every environment step acts on one observation and stores one time step with the
@@ -332,6 +354,7 @@ def main():
             torch.cuda.empty_cache()
         also.append(time_act_train(dqn, synth, torch, args.capacity, max(50, args.steps // 5), 10))
         also.append(time_agent_loop(dqn, synth, torch, args.capacity, max(200, 2 * args.steps)))
+        also.append(time_variants(dqn, synth, torch, args.capacity, max(100, args.steps // 2), args.warmup))
         res["also"] = also
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(torch, synth, B, min(B, 64))

@@ -201,6 +201,17 @@ int32_t dqn_replay_store(dqn_ctx *ctx, int64_t n, const uint8_t *frames, const i
  * Any pointer may be NULL. */
 int32_t dqn_replay_state(const dqn_ctx *ctx, int64_t *cursor, int64_t *stored, int64_t *steps);
 
+/* Frame preprocessing (Sec.3: raw palette frame -> grey-scale -> linearly
+ * interpolated to 84 x 84), batched.  raw: [n][height][width] bytes (device);
+ * grey_lut: 256 floats (device) mapping a byte to its grey level in 0..255, or
+ * NULL when the bytes already are grey levels; frames: [n][84][84] (device).
+ * Output pixel (i,j) samples the source at (i+1/2)*height/84 - 1/2,
+ * (j+1/2)*width/84 - 1/2 (clamped), blends the four neighbours bilinearly in
+ * fp32 and rounds to the nearest integer (ties to even).  Needs no context.
+ * 1 <= n <= 65535. */
+int32_t dqn_preprocess(const uint8_t *raw, int64_t n, int32_t height, int32_t width,
+                       const float *grey_lut, uint8_t *frames, void *stream);
+
 /* Schedules of Table 1 as functions of the environment step t = 1, 2, ... (host
  * only, no device work): a value "a -> b (1 -> T steps)" is a at t = 1, b at
  * t >= T, linear in between; train is set when t is past learning_start and

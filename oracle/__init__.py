@@ -93,6 +93,8 @@ def lib():
         L.orc_schedule_at.restype = None
         L.orc_schedule_at.argtypes = [C.POINTER(OrcSchedule), C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p]
+        L.orc_preprocess.restype = None
+        L.orc_preprocess.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.orc_gather.restype = None
         L.orc_gather.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p,
                                  C.c_void_p]
@@ -328,6 +330,18 @@ def schedule_at(t, learning_start=50000, update_period=4, target_period=30000, e
     e = np.zeros(1); b = np.zeros(1); tr = np.zeros(1, np.int32); sy = np.zeros(1, np.int32)
     lib().orc_schedule_at(C.byref(sc), int(t), _p(e), _p(b), _p(tr), _p(sy))
     return float(e[0]), float(b[0]), int(tr[0]), int(sy[0])
+
+
+def preprocess(raw, lut=None):
+    """raw uint8 [n][H][W] -> (uint8 [n][84][84], unrounded float64 values)."""
+    raw = _chk(raw, np.uint8)
+    n, H, W = raw.shape
+    if lut is not None:
+        lut = _chk(lut, np.float32)
+        assert lut.size == 256
+    out = np.zeros((n, 84, 84), np.uint8); val = np.zeros((n, 84, 84), np.float64)
+    lib().orc_preprocess(_p(raw), n, H, W, None if lut is None else _p(lut), _p(out), _p(val))
+    return out, val
 
 
 def gather(frames, idx):

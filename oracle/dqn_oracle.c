@@ -772,3 +772,46 @@ void orc_schedule_at(const orc_schedule *s, int64_t t, double *epsilon, double *
     *train = t > s->learning_start && t % s->update_period == 0;
     *sync_target = t % s->target_period == 0;
 }
+
+/* ------------------------------------------------------------------ */
+/* Frame preprocessing (Sec.3: palette frame -> grey-scale -> linear
+ * interpolation to 84 x 84).  raw: [n][H][W] bytes; grey(y,x) = lut[raw] if a
+ * 256-entry table is given (the emulator's palette -> luminance map, which the
+ * paper does not print), else the byte itself.  Output pixel (i,j) samples
+ * the source at the centre-aligned coordinate
+ *     sy = (i + 1/2) H/84 - 1/2,   sx = (j + 1/2) W/84 - 1/2
+ * (the convention of library "linear" resizing), clamped to the image, and
+ * blends the four neighbours bilinearly; the result is rounded to the
+ * nearest integer (ties to even) and clipped to 0..255.  val (optional)
+ * receives the unrounded value.  Pinned against a library bilinear resize
+ * and closed forms; parity with OpenCV's own fixed-point rounding (the
+ * library the paper names) is unpinned: it is not available here.       */
+/* ------------------------------------------------------------------ */
+void orc_preprocess(const uint8_t *raw, int64_t n, int32_t H, int32_t W, const float *lut, uint8_t *out,
+                    double *val)
+{
+    for (int64_t f = 0; f < n; ++f)
+        for (int i = 0; i < IN_H; ++i)
+            for (int j = 0; j < IN_W; ++j) {
+                double sy = (i + 0.5) * (double)H / IN_H - 0.5, sx = (j + 0.5) * (double)W / IN_W - 0.5;
+                if (sy < 0) sy = 0;
+                if (sx < 0) sx = 0;
+                if (sy > H - 1) sy = H - 1;
+                if (sx > W - 1) sx = W - 1;
+                int y0 = (int)floor(sy), x0 = (int)floor(sx);
+                int y1 = y0 + 1 < H ? y0 + 1 : H - 1, x1 = x0 + 1 < W ? x0 + 1 : W - 1;
+                double fy = sy - y0, fx = sx - x0;
+                const uint8_t *im = raw + f * (int64_t)H * W;
+#define GREY(y, x) (lut ? (double)lut[im[(int64_t)(y) * W + (x)]] : (double)im[(int64_t)(y) * W + (x)])
+                double top = GREY(y0, x0) * (1 - fx) + GREY(y0, x1) * fx;
+                double bot = GREY(y1, x0) * (1 - fx) + GREY(y1, x1) * fx;
+#undef GREY
+                double v = top * (1 - fy) + bot * fy;
+                double r = rint(v);
+                if (r < 0) r = 0;
+                if (r > 255) r = 255;
+                int64_t o = (f * IN_H + i) * IN_W + j;
+                out[o] = (uint8_t)r;
+                if (val) val[o] = v;
+            }
+}

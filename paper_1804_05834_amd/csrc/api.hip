@@ -914,6 +914,19 @@ int32_t dqn_replay_state(const dqn_ctx *c, int64_t *cursor, int64_t *stored, int
     return DQN_OK;
 }
 
+int32_t dqn_preprocess(const uint8_t *raw, int64_t n, int32_t height, int32_t width, const float *grey_lut,
+                       uint8_t *frames, void *stream)
+{
+    if (!raw || !frames) return fail(nullptr, DQN_ERR_INVALID_ARG, "dqn_preprocess: NULL argument");
+    if (n < 1 || n > 65535 || height < 1 || width < 1 || height > 4096 || width > 4096)
+        return fail(nullptr, DQN_ERR_INVALID_ARG, "dqn_preprocess: n must be in 1..65535, height and width in 1..4096");
+    hipStream_t st = (hipStream_t)stream;
+    misc::k_preprocess<<<dim3((net::FRAME + 255) / 256, (unsigned)n), 256, 0, st>>>(raw, height, width, grey_lut, frames);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(nullptr, DQN_ERR_HIP, std::string("dqn_preprocess: ") + hipGetErrorString(e));
+    return DQN_OK;
+}
+
 int32_t dqn_schedule_default(dqn_schedule *s)
 {
     if (!s) return DQN_ERR_INVALID_ARG;

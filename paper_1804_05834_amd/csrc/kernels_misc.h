@@ -657,6 +657,32 @@ __global__ __launch_bounds__(1024) void k_store_priorities(float *tree, long L, 
     tree_walk(tree, (int)(L + slot), v, walk, levels);
 }
 
+// Frame preprocessing (Sec.3: palette frame -> grey-scale -> linear interpolation to 84 x 84).
+// One thread per output pixel, grid (ceil(7056/256), n).  grey = lut[byte] or the byte itself;
+// centre-aligned source coordinate, clamped; bilinear blend; round to nearest even.
+__global__ __launch_bounds__(256) void k_preprocess(const uint8_t *raw, int H, int W, const float *lut, uint8_t *out)
+{
+    const int o = blockIdx.x * 256 + threadIdx.x;
+    if (o >= net::FRAME) return;
+    const int i = o / 84, j = o % 84;
+    const uint8_t *im = raw + (long)blockIdx.y * H * W;
+    // the source coordinate (i + 1/2) H/84 - 1/2 = ((2i+1) H - 84) / 168 is kept as an exact
+    // fraction, so only the blend itself is rounded
+    const int ny = min(max((2 * i + 1) * H - 84, 0), 168 * (H - 1));
+    const int nx = min(max((2 * j + 1) * W - 84, 0), 168 * (W - 1));
+    const int y0 = ny / 168, x0 = nx / 168;
+    const int y1 = min(y0 + 1, H - 1), x1 = min(x0 + 1, W - 1);
+    const float fy = (float)(ny % 168) / 168.f, fx = (float)(nx % 168) / 168.f;
+    auto grey = [&](int y, int x) {
+        const uint8_t b = im[(long)y * W + x];
+        return lut ? lut[b] : (float)b;
+    };
+    const float top = grey(y0, x0) * (1.f - fx) + grey(y0, x1) * fx;
+    const float bot = grey(y1, x0) * (1.f - fx) + grey(y1, x1) * fx;
+    const float v = top * (1.f - fy) + bot * fy;
+    out[(long)blockIdx.y * net::FRAME + o] = (uint8_t)fminf(fmaxf(rintf(v), 0.f), 255.f);
+}
+
 // Copies up to nine short arrays of 4-byte words; grid (blocks, items).
 struct CopyOutArgs {
     struct Item {

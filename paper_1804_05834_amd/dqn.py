@@ -18,7 +18,7 @@ OK, ERR_INVALID_ARG, ERR_OOM, ERR_HIP, ERR_STATE, ERR_UNSUPPORTED = 0, -1, -2, -
 EXPORTS = ["dqn_query_sizes", "dqn_init", "dqn_act", "dqn_train_step", "per_sample", "per_update",
            "per_fill", "dqn_replay_write", "dqn_replay_gather", "dqn_sync_target", "dqn_get_params",
            "dqn_set_params", "dqn_profile_begin", "dqn_profile_end", "dqn_last_error", "dqn_destroy",
-           "dqn_replay_store", "dqn_replay_state", "dqn_schedule_default", "dqn_schedule_at"]
+           "dqn_replay_store", "dqn_replay_state", "dqn_schedule_default", "dqn_schedule_at", "dqn_preprocess"]
 
 
 class DqnConfig(C.Structure):
@@ -104,6 +104,7 @@ def lib():
             "dqn_replay_gather": [vp, vp, i32, vp, vp, vp, vp, vp, vp],
             "dqn_replay_store": [vp, i64, vp, vp, vp, vp, vp],
             "dqn_replay_state": [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)],
+            "dqn_preprocess": [vp, i64, i32, i32, vp, vp, vp],
             "dqn_schedule_default": [C.POINTER(DqnSchedule)],
             "dqn_schedule_at": [C.POINTER(DqnSchedule), i64, C.POINTER(DqnSchedulePoint)],
             "dqn_sync_target": [vp, vp],
@@ -319,3 +320,13 @@ def schedule_at(sc, step):
     if rc != 0:
         raise DqnError(rc, "dqn_schedule_at")
     return pt.epsilon, pt.beta, pt.train, pt.sync_target
+
+
+def preprocess(raw, grey_lut=None):
+    """raw uint8 device tensor [n][H][W] -> uint8 [n][84][84] (grey levels through grey_lut if given)."""
+    n, H, W = raw.shape
+    out = torch.empty(n, 84, 84, dtype=torch.uint8, device=raw.device)
+    rc = lib().dqn_preprocess(_ptr(raw), n, H, W, _ptr(grey_lut), _ptr(out), _stream())
+    if rc != 0:
+        raise DqnError(rc, (lib().dqn_last_error(None) or b"").decode())
+    return out

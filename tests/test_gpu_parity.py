@@ -530,6 +530,23 @@ def test_store_path_parity(dq, orc):
     m.close()
 
 
+@pytest.mark.parametrize("H,W,use_lut", [(210, 160, True), (84, 84, False), (100, 333, True)])
+def test_preprocess_parity(dq, orc, H, W, use_lut):
+    """Sec.3 preprocessing: bytes equal the oracle's, except where the oracle's unrounded value
+    lies within 1e-3 of a rounding boundary (the kernel blends in fp32), where one level is allowed."""
+    print("case preprocess", H, W, use_lut, flush=True)
+    n = 5
+    raw = (synth.u24(61, torch.arange(n * H * W)) * 256).floor().clamp(max=255).to(torch.uint8).reshape(n, H, W)
+    lut = (255.0 * synth.u24(62, torch.arange(256))).float() if use_lut else None
+    out = dq.preprocess(raw.cuda(), None if lut is None else lut.cuda()).cpu().numpy()
+    ref, val = orc.preprocess(raw.numpy(), None if lut is None else lut.numpy())
+    diff = out.astype(np.int32) - ref.astype(np.int32)
+    near = np.abs(val - np.floor(val) - 0.5) <= 1e-3
+    assert np.all(diff[~near] == 0) and np.all(np.abs(diff) <= 1), (np.abs(diff).max(), (diff != 0).sum())
+    with pytest.raises(dq.DqnError):
+        dq.preprocess(torch.zeros(0, H, W, dtype=torch.uint8, device="cuda"))
+
+
 def test_error_paths_on_device(dq):
     print("case errors", flush=True)
     m = dq.Dqn(dq.make_config(replay_capacity=100, max_batch=8, max_act_batch=8))
