@@ -110,9 +110,16 @@ def time_steps(m, torch, B, steps, warmup, seed0=0):
     for i in range(steps):
         m.train_step(B, None, beta=0.4, draw_seed=seed0 + warmup + i, outputs=False)
     e1.record()
-    t_enq = time.perf_counter() - t0
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    # host cost of enqueueing a step, over a burst short enough that the queues never fill
+    # (inside the long loop the host is held back by the device)
+    burst = 20
+    t1 = time.perf_counter()
+    for i in range(burst):
+        m.train_step(B, None, beta=0.4, draw_seed=seed0 + warmup + steps + i, outputs=False)
+    t_enq = (time.perf_counter() - t1) / burst * steps
+    torch.cuda.synchronize()
     return wall, e0.elapsed_time(e1) / 1e3, t_enq
 
 

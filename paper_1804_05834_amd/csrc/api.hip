@@ -379,7 +379,7 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         return tile;
     };
 
-    {  // conv1: one workgroup per sample, frames staged in LDS (read from the ring in ring mode)
+    {  // conv1: persistent workgroups, frames staged in LDS (read from the ring in ring mode)
         c1::FwdArgs A{};
         A.nseg = npass;
         int first = 0;

@@ -575,10 +575,21 @@ struct Src {                      // where the four frames of sample n come from
     int shift;                    // 0: frames i-3..i (s), 1: frames i-2..i+1 (s')
 };
 
-__device__ __forceinline__ const uint8_t *frame_ptr(const Src &S, int n, int k)
+// The sampled slot of sample n (ring mode; 0 otherwise).  Fetched one sample ahead of the frame
+// loads that depend on it, so that the two memory latencies do not add up.
+// The value stays in a vector register until it is used (frame_ptr makes it scalar): were it
+// made scalar where it is loaded, the wave would wait for every outstanding load right there.
+__device__ __forceinline__ int sample_slot(const Src &S, int n)
+{
+    int zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));  // opaque, so the load below is a vector load
+    return S.idx ? S.idx[n + zero] : 0;
+}
+
+__device__ __forceinline__ const uint8_t *frame_ptr(const Src &S, int n, int slot_n, int k)
 {
     if (!S.idx) return S.x + (long)n * S.xs + (long)k * FR;
-    long i = S.idx[n];
+    long i = __builtin_amdgcn_readfirstlane(slot_n);
     i = i < 0 ? 0 : (i >= S.cap ? S.cap - 1 : i);
     long slot = i - 3 + k + S.shift;  // within [-3, cap+1]: one wrap at most (cap >= 5)
     if (slot < 0) slot += S.cap;
@@ -595,14 +606,14 @@ template <int T, int NF> struct Staged {
     uint2 raw[NL];
 };
 template <int T, int NF>
-__device__ __forceinline__ void stage_load(Staged<T, NF> &R, const Src &S, int n, int k0, int tid)
+__device__ __forceinline__ void stage_load(Staged<T, NF> &R, const Src &S, int n, int slot_n, int k0, int tid)
 {
     using ST = Staged<T, NF>;
     // the (workgroup-uniform) frame addresses first, so that the slot lookup does not sit
     // between the frame loads and serialise them
     const uint8_t *f[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) f[k] = frame_ptr(S, n, k0 + (k < NF ? k : 0));
+    for (int k = 0; k < 4; ++k) f[k] = frame_ptr(S, n, slot_n, k0 + (k < NF ? k : 0));
 #pragma unroll
     for (int i = 0; i < ST::NL; ++i) {
         const int t = tid + i * T;
@@ -647,105 +658,130 @@ struct FwdArgs {
     int total;          // samples of all segments
 };
 
-// Persistent workgroups: workgroup b owns samples [b*total/G, (b+1)*total/G) of the launch-wide
-// list, keeps the weights in registers while the segment does not change, and loads the frames
-// of its next sample while it computes the current one.
-__global__ __launch_bounds__(512) void k_conv1_fwd(FwdArgs A)
+// One output block of 32 pixels x 32 channels: bias, 1/255, ReLU, bf16, 32 contiguous bytes per lane.
+// acc[4g + j] = Y[pixel li of the block][channel 16h + 4g + j]
+__device__ __forceinline__ void conv1_store(const v16f &acc, const v4f (&bias)[4], bf16_t *y, int m, int h)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t xin[XIN];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 31, h = lane >> 5;
-    const int g0 = (int)((long)blockIdx.x * A.total / gridDim.x);
-    const int g1 = (int)((long)(blockIdx.x + 1) * A.total / gridDim.x);
-    if (g0 >= g1) return;
-
-    auto seg_of = [&](int g) {
-        int s = 0;
-        if (A.nseg > 1 && g >= A.seg[1].first) s = 1;
-        if (A.nseg > 2 && g >= A.seg[2].first) s = 2;
-        return s;
-    };
-    auto pick = [&](int s) {
-        FwdSeg S = A.seg[0];
-        if (s == 1) S = A.seg[1];
-        if (s == 2) S = A.seg[2];
-        return S;
-    };
-
-    Staged<512, 4> R;
-    {
-        FwdSeg S = pick(seg_of(g0));
-        stage_load<512, 4>(R, S.src, g0 - S.first, 0, tid);
-    }
-    v8bf wb[16];
-    int loaded = -1;
-    for (int g = g0; g < g1; ++g) {
-        const int sg = seg_of(g);
-        const FwdSeg S = pick(sg);
-        if (sg != loaded) {
-            // Weight fragments for the 16 reduction steps.  MFMA row i carries output channel
-            // ch(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3), so that the 16 results of a lane
-            // (rows 8g + 4h + j) are the 16 consecutive channels 16h + 4g + j of its pixel.
-            const int ch = 16 * ((li >> 2) & 1) + 4 * (li >> 3) + (li & 3);
+    constexpr float sc = 1.0f / 255.0f;
+    uint2 o[4];
 #pragma unroll
-            for (int t = 0; t < 16; ++t)
-                wb[t] = __builtin_bit_cast(v8bf, ld8(S.w + ch * 256 + 16 * t + 8 * h));
-            loaded = sg;
+    for (int g4 = 0; g4 < 4; ++g4) {
+        const v4f bv = bias[g4];
+        o[g4] = pack4(fmaxf(acc[4 * g4] * sc + bv.x, 0.f), fmaxf(acc[4 * g4 + 1] * sc + bv.y, 0.f),
+                      fmaxf(acc[4 * g4 + 2] * sc + bv.z, 0.f), fmaxf(acc[4 * g4 + 3] * sc + bv.w, 0.f));
+    }
+    uint4 *d = reinterpret_cast<uint4 *>(y + m * 32 + 16 * h);
+    d[0] = uint4{o[0].x, o[0].y, o[1].x, o[1].y};
+    d[1] = uint4{o[2].x, o[2].y, o[3].x, o[3].y};
+}
+
+// Weight fragments for the 16 reduction steps.  MFMA row i carries output channel
+// ch(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3), so that the 16 results of a lane (rows 8g + 4h + j)
+// are the 16 consecutive channels 16h + 4g + j of its pixel.
+__device__ __forceinline__ void conv1_weights(v8bf (&wb)[16], const bf16_t *w, int li, int h)
+{
+    const int ch = 16 * ((li >> 2) & 1) + 4 * (li >> 3) + (li & 3);
+#pragma unroll
+    for (int t = 0; t < 16; ++t) wb[t] = __builtin_bit_cast(v8bf, ld8(w + ch * 256 + 16 * t + 8 * h));
+}
+
+// The MFMA loop of one sample for one wave: row blocks `wave` and (TWO) `wave + 8` of the 13
+// blocks of 32 output pixels, 16 reduction steps each.  Straight-line code, no lane-dependent
+// control flow, and the im2col fragments are fetched from LDS one group of four steps ahead
+// of the MFMAs that consume them, so the LDS latency is hidden behind the matrix unit.
+template <bool TWO>
+__device__ __forceinline__ void conv1_blocks(const bf16_t *xin, const v8bf (&wa)[16], const v4f (&bias)[4],
+                                             bf16_t *y, int wave, int li, int h)
+{
+    const int m0 = wave * 32 + li;
+    int m1 = (wave + 8) * 32 + li;
+    if (m1 > 399) m1 = 399;  // rows past the end read a valid pixel and are not stored
+    const bf16_t *px0 = xin + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20) + h * 84;
+    const bf16_t *px1 = xin + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20) + h * 84;
+    auto frag = [&](const bf16_t *px, int t) {
+        // k = 16t + 8h: channel t/4, kernel row (2t + h) % 8; 16 bytes at an 8-byte-aligned address
+        const uint2 *q = reinterpret_cast<const uint2 *>(px + (t >> 2) * FR + ((2 * t) & 7) * 84);
+        return __builtin_bit_cast(v8bf, uint4{q[0].x, q[0].y, q[1].x, q[1].y});
+    };
+    v16f acc0 = {0}, acc1 = {0};
+    v8bf f0[2][4], f1[2][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f0[0][j] = frag(px0, j);
+        if constexpr (TWO) f1[0][j] = frag(px1, j);
+    }
+#pragma unroll
+    for (int grp = 0; grp < 4; ++grp) {
+        const int cur = grp & 1, nxt = cur ^ 1;
+        if (grp < 3) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f0[nxt][j] = frag(px0, 4 * (grp + 1) + j);
+                if constexpr (TWO) f1[nxt][j] = frag(px1, 4 * (grp + 1) + j);
+            }
         }
+        // the scheduler would otherwise sink every read to just above its MFMA, which leaves
+        // one LDS access in flight per wave and the matrix unit waiting on LDS latency
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc0 = mfma(wa[4 * grp + j], f0[cur][j], acc0);  // transposed tile
+            if constexpr (TWO) acc1 = mfma(wa[4 * grp + j], f1[cur][j], acc1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    const int mm = (wave + 8) * 32 + li;
+    conv1_store(acc0, bias, y, m0, h);
+    if (TWO && mm < 400) conv1_store(acc1, bias, y, mm, h);
+}
+
+// The samples [g0, g1) of one segment.  Weights and bias stay in registers; the frames of the
+// next sample are loaded while the current one is computed, and the ring slot of the sample
+// after that is already on its way.
+__device__ __forceinline__ void conv1_fwd_range(const FwdSeg &S, int g0, int g1, bf16_t *xin, int tid)
+{
+    const int lane = tid & 63, li = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: the block choice below is a uniform branch
+    Staged<512, 4> R;
+    stage_load<512, 4>(R, S.src, g0, sample_slot(S.src, g0), 0, tid);
+    int slot_next = g0 + 1 < g1 ? sample_slot(S.src, g0 + 1) : 0;
+    v8bf wa[16];
+    conv1_weights(wa, S.w, li, h);
+    v4f bias[4];  // this lane's 16 channels: 16h + 4g + j
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) bias[g4] = *reinterpret_cast<const v4f *>(S.bias + 16 * h + 4 * g4);
+    // Everything requested so far has arrived before the loop starts.  Without this the first
+    // MFMA of every sample waits for "all outstanding vector loads" on account of the weight
+    // registers, and that includes the next sample's frames requested a moment earlier.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    for (int g = g0; g < g1; ++g) {
         sync_lds();  // the previous sample is no longer read
         stage_store<512, 4>(xin, R, tid);
         sync_lds();
         if (g + 1 < g1) {
-            FwdSeg Sn = pick(seg_of(g + 1));
-            stage_load<512, 4>(R, Sn.src, g + 1 - Sn.first, 0, tid);
+            stage_load<512, 4>(R, S.src, g + 1, slot_next, 0, tid);
+            if (g + 2 < g1) slot_next = sample_slot(S.src, g + 2);
         }
-        bf16_t *y = S.y + (long)(g - S.first) * (400 * 32);
-        // 13 blocks of 32 output pixels (the last one half empty).  Wave w takes blocks w and
-        // w+8 together: two independent accumulator chains hide the LDS latency of each other.
-        {
-            const bool two = wave + 8 < 13;
-            int m0 = wave * 32 + li, m1 = (wave + 8) * 32 + li;
-            if (m1 > 399) m1 = 399;  // rows past the end read a valid pixel and are not stored
-            const bf16_t *px0 = xin + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20);
-            const bf16_t *px1 = xin + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20);
-            v16f acc0 = {0}, acc1 = {0};
-#pragma unroll
-            for (int t = 0; t < 16; ++t) {
-                const int c = t >> 2, p = (2 * t) & 7;  // k = 16t + 8h: channel t/4, kernel row (2t+h)%8
-                const int off = c * FR + (p + h) * 84;
-                const uint2 *q0 = reinterpret_cast<const uint2 *>(px0 + off);
-                uint4 v0 = {q0[0].x, q0[0].y, q0[1].x, q0[1].y};
-                acc0 = mfma(wb[t], __builtin_bit_cast(v8bf, v0), acc0);  // transposed tile
-                if (two) {
-                    const uint2 *q1 = reinterpret_cast<const uint2 *>(px1 + off);
-                    uint4 v1 = {q1[0].x, q1[0].y, q1[1].x, q1[1].y};
-                    acc1 = mfma(wb[t], __builtin_bit_cast(v8bf, v1), acc1);
-                }
-            }
-            // acc[4g + j] = Y[pixel li of the block][channel 16h + 4g + j]: 32 contiguous bytes
-            {
-                constexpr float sc = 1.0f / 255.0f;
-                const float *bp = S.bias + 16 * h;
-                uint2 o0[4], o1[4];
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const v4f bv = *reinterpret_cast<const v4f *>(bp + 4 * g4);
-                    o0[g4] = pack4(fmaxf(acc0[4 * g4] * sc + bv.x, 0.f), fmaxf(acc0[4 * g4 + 1] * sc + bv.y, 0.f),
-                                   fmaxf(acc0[4 * g4 + 2] * sc + bv.z, 0.f), fmaxf(acc0[4 * g4 + 3] * sc + bv.w, 0.f));
-                    o1[g4] = pack4(fmaxf(acc1[4 * g4] * sc + bv.x, 0.f), fmaxf(acc1[4 * g4 + 1] * sc + bv.y, 0.f),
-                                   fmaxf(acc1[4 * g4 + 2] * sc + bv.z, 0.f), fmaxf(acc1[4 * g4 + 3] * sc + bv.w, 0.f));
-                }
-                uint4 *d0 = reinterpret_cast<uint4 *>(y + (wave * 32 + li) * 32 + 16 * h);
-                d0[0] = uint4{o0[0].x, o0[0].y, o0[1].x, o0[1].y};
-                d0[1] = uint4{o0[2].x, o0[2].y, o0[3].x, o0[3].y};
-                const int mm = (wave + 8) * 32 + li;
-                if (two && mm < 400) {
-                    uint4 *d1 = reinterpret_cast<uint4 *>(y + mm * 32 + 16 * h);
-                    d1[0] = uint4{o1[0].x, o1[0].y, o1[1].x, o1[1].y};
-                    d1[1] = uint4{o1[2].x, o1[2].y, o1[3].x, o1[3].y};
-                }
-            }
-        }
+        // 13 blocks of 32 output pixels (the last one half empty): waves 0-4 take two, 5-7 one
+        bf16_t *y = S.y + (long)g * (400 * 32);
+        if (wave + 8 < 13) conv1_blocks<true>(xin, wa, bias, y, wave, li, h);
+        else conv1_blocks<false>(xin, wa, bias, y, wave, li, h);
+    }
+}
+
+// Persistent workgroups: workgroup b owns samples [b*total/G, (b+1)*total/G) of the launch-wide
+// list (segment after segment).
+__global__ __launch_bounds__(512) void k_conv1_fwd(FwdArgs A)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t xin[XIN];
+    const int g0 = (int)((long)blockIdx.x * A.total / gridDim.x);
+    const int g1 = (int)((long)(blockIdx.x + 1) * A.total / gridDim.x);
+    for (int s = 0; s < A.nseg; ++s) {
+        FwdSeg S = A.seg[0];
+        if (s == 1) S = A.seg[1];
+        if (s == 2) S = A.seg[2];
+        const int lo = max(g0, S.first) - S.first, hi = min(g1, S.first + S.n) - S.first;
+        if (lo < hi) conv1_fwd_range(S, lo, hi, xin, threadIdx.x);
     }
 }
 
@@ -787,8 +823,8 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
 
     Staged<256, 2> R;
     uint4 ry[7];
-    auto load_sample = [&](int n) {
-        stage_load<256, 2>(R, A.src, n, 2 * cp, tid);
+    auto load_sample = [&](int n, int slot_n) {
+        stage_load<256, 2>(R, A.src, n, slot_n, 2 * cp, tid);
         const bf16_t *dyn = A.dy + (long)n * (400 * 32);
 #pragma unroll
         for (int i = 0; i < 7; ++i) {
@@ -796,7 +832,9 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
             if (t < 1600) ry[i] = ld8(dyn + (t >> 2) * 32 + (t & 3) * 8);
         }
     };
-    if (split < A.B) load_sample(split);
+    // the ring slot of a sample is fetched one sample ahead of the frame loads that need it
+    if (split < A.B) load_sample(split, sample_slot(A.src, split));
+    int slot_next = split + A.nsplit < A.B ? sample_slot(A.src, split + A.nsplit) : 0;
     for (int n = split; n < A.B; n += A.nsplit) {
         __syncthreads();  // the previous sample's tiles are no longer read
         stage_store<256, 2>(xin, R, tid);
@@ -806,7 +844,10 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
             if (t < 1600) *reinterpret_cast<uint4 *>(dys + (t >> 2) * LDY1 + (t & 3) * 8) = ry[i];
         }
         __syncthreads();
-        if (n + A.nsplit < A.B) load_sample(n + A.nsplit);  // in flight during the MFMA loop
+        if (n + A.nsplit < A.B) {
+            load_sample(n + A.nsplit, slot_next);  // in flight during the MFMA loop
+            if (n + 2 * A.nsplit < A.B) slot_next = sample_slot(A.src, n + 2 * A.nsplit);
+        }
 #pragma unroll 5
         for (int t = 0; t < 25; ++t) {  // 16 output pixels per step
             v8bf fa = frag_tr(yp + 16 * t * LDY1, LDY1);
