@@ -547,6 +547,99 @@ def test_preprocess_parity(dq, orc, H, W, use_lut):
         dq.preprocess(torch.zeros(0, H, W, dtype=torch.uint8, device="cuda"))
 
 
+# ------------------------------------------------------------------ degenerate and maximal cases
+@pytest.mark.parametrize("prec", [0, 1])
+def test_degenerate_batches(dq, orc, prec):
+    """Every transition terminal (y = r, Alg.1 terminal line), every importance weight zero (no
+    gradient: the parameters must not move at all), a single action (argmax trivial)."""
+    print("case degenerate", prec, flush=True)
+    tol = TOL_BF16 if prec else TOL
+    cfgd = CONFIGS["dueling_ddqn"]
+    K, B = 18, 40
+    m = dq.Dqn(dq.make_config(max_batch=64, precision=prec, **cfgd))
+    p = synth.he_uniform_params(1804, K, 1, bias_scale=0.02); pt = synth.he_uniform_params(5834, K, 1, bias_scale=0.02)
+    s, sn, a, r, d = synth.batch(11, B, K)
+    # all terminal
+    m.set_params(0, torch.from_numpy(p)); m.set_params(1, torch.from_numpy(pt))
+    ones = torch.ones_like(d)
+    out = m.train_step(B, tuple(dev(t) for t in (s, sn, a, r, ones)))
+    assert torch.equal(out["y"].cpu(), r)
+    ref = _oracle_step(orc, cfgd, p, pt, (s.numpy(), sn.numpy(), a.numpy(), r.numpy(), ones.numpy()), None, quant=prec)
+    assert relerr(out["td"].cpu().numpy(), ref["td"]) <= tol
+    # all weights zero: loss 0, gradient 0, parameters and optimizer state untouched bit for bit
+    m.set_params(0, torch.from_numpy(p)); m.set_params(3, torch.zeros(p.size))
+    before = m.get_params(0).clone()
+    out = m.train_step(B, tuple(dev(t) for t in (s, sn, a, r, d, torch.zeros(B))))
+    assert float(out["loss"][0]) == 0.0
+    assert float(m.get_params(2).abs().max()) == 0.0
+    assert torch.equal(m.get_params(0), before) and float(m.get_params(3).abs().max()) == 0.0
+    m.close()
+    # one action
+    m1 = dq.Dqn(dq.make_config(num_actions=1, dueling=1, double_q=1, loss_kind=1, max_batch=8, precision=prec))
+    p1 = synth.he_uniform_params(7, 1, 1, bias_scale=0.02)
+    m1.set_params(0, torch.from_numpy(p1)); m1.sync_target()
+    s, sn, a, r, d = synth.batch(12, 8, 1)
+    out = m1.train_step(8, tuple(dev(t) for t in (s, sn, a, r, d)))
+    assert int(out["a_star"].abs().max()) == 0
+    ref = _oracle_step(orc, dict(num_actions=1, dueling=1, double_q=1, loss_kind=1), p1, p1,
+                       (s.numpy(), sn.numpy(), a.numpy(), r.numpy(), d.numpy()), None, quant=prec)
+    assert relerr(out["q_s"].cpu().numpy(), ref["q_s"]) <= tol and relerr(out["td"].cpu().numpy(), ref["td"]) <= tol
+    m1.close()
+
+
+def test_smallest_ring_and_single_stored_transition(dq, orc):
+    """A ring of the minimum capacity (5 slots) and a tree with one non-zero leaf: every draw
+    returns that slot with weight 1."""
+    print("case tiny ring", flush=True)
+    m = dq.Dqn(dq.make_config(replay_capacity=5, max_batch=8, **CONFIGS["dueling_ddqn"]))
+    _fill_replay(m, 5, chunk=5)
+    m.per_fill(dev(np.array([0.7], np.float32)))
+    idx, w = m.per_sample(8, 0.4, 3)
+    assert int(idx.abs().max()) == 0 and torch.equal(w.cpu(), torch.ones(8))
+    m.per_fill(dev(np.array([1e-3, 0.5, 2.0, 1.0, 0.25], np.float32)))
+    tree_ref = orc.tree_build(np.array([1e-3, 0.5, 2.0, 1.0, 0.25], np.float32), m.L, float(np.float32(0.6)))
+    idx, w = m.per_sample(8, 0.4, 4)
+    _check_indices(orc, idx.cpu().numpy(), tree_ref, 5, 8, 0.4, 4)
+    out = m.train_step(8, None, beta=0.4, draw_seed=4)        # stacks wrap around the 5-slot ring
+    s, sn, _, _, _ = m.replay_gather(out["idx"])
+    fr = synth.frames(21, torch.arange(5)).numpy()
+    slots = (out["idx"].cpu().numpy()[:, None].astype(np.int64) - 3 + np.arange(5)[None, :]) % 5
+    assert np.array_equal(s.cpu().numpy(), fr[slots[:, :4]]) and np.array_equal(sn.cpu().numpy(), fr[slots[:, 1:]])
+    assert np.isfinite(float(out["loss"][0]))
+    m.close()
+
+
+def test_maximum_batch(dq, orc):
+    """max_batch = 1024 (the library's limit), fp32.  Per-row outputs: 64 sampled rows against
+    the oracle run on those rows alone (rows are independent in the forward passes).  Gradient:
+    a property that holds at any size: the loss is a mean over rows, so the gradient of the
+    1024-row step is the mean of the gradients of its two 512-row halves (a size the other
+    parity tests cover element by element)."""
+    print("case max batch", flush=True)
+    cfgd = CONFIGS["dueling_ddqn"]
+    K, B = 18, 1024
+    m = dq.Dqn(dq.make_config(max_batch=B, **cfgd))
+    p = synth.he_uniform_params(1804, K, 1, bias_scale=0.02); pt = synth.he_uniform_params(5834, K, 1, bias_scale=0.02)
+    s, sn, a, r, d = synth.batch(11, B, K)
+    full = tuple(dev(t) for t in (s, sn, a, r, d))
+
+    def step(rows):
+        m.set_params(0, torch.from_numpy(p)); m.set_params(1, torch.from_numpy(pt)); m.set_params(3, torch.zeros(p.size))
+        out = m.train_step(rows.stop - rows.start, tuple(t[rows] for t in full))
+        return out, m.get_params(2).cpu().numpy().astype(np.float64)
+
+    out, g_all = step(slice(0, B))
+    pick = np.arange(0, B, 16)
+    q_ref = orc.forward(p, K, 1, s.numpy()[pick])
+    assert relerr(out["q_s"].cpu().numpy()[pick], q_ref) <= TOL
+    qn_ref = orc.forward(pt, K, 1, sn.numpy()[pick])
+    assert relerr(out["q_next_target"].cpu().numpy()[pick], qn_ref) <= TOL
+    _, g_lo = step(slice(0, 512))
+    _, g_hi = step(slice(512, B))
+    assert relerr(g_all, 0.5 * (g_lo + g_hi)) <= TOL
+    m.close()
+
+
 def test_error_paths_on_device(dq):
     print("case errors", flush=True)
     m = dq.Dqn(dq.make_config(replay_capacity=100, max_batch=8, max_act_batch=8))
