@@ -95,26 +95,44 @@ __device__ __forceinline__ void head_rows(const float *hid /*LDS*/, const float 
 }
 
 // The same for the three passes of a training row at once: 3R dot products of length 512 spread
-// over groups of 16 lanes (32 independent loads per lane), so the whole head takes two rounds
-// of a 512-thread workgroup instead of one wave per row in turn.
-__device__ __forceinline__ void head_rows3(const float (*hid)[net::HID] /*LDS [3][512]*/, const float *head_on,
-                                           const float *head_tg, int K, int dueling,
-                                           float (*raw)[65] /*LDS [3][65]*/, int tid)
+// over groups of 16 lanes, so the whole head takes two rounds of a 512-thread workgroup instead
+// of one wave per row in turn.  The weights of a round do not depend on the hidden layer, so
+// head_rows3_load requests them while the fc1 partial sums are still being added up, and
+// head_rows3_dot only reads LDS.
+struct HeadRound {
+    float w[net::HID / 16];
+    float b;
+    int d;  // dot product number: pass = d / R, row = d % R; -1: none
+};
+__device__ __forceinline__ void head_rows3_load(HeadRound &H, int round, const float *head_on, const float *head_tg,
+                                                int K, int dueling, int tid)
 {
     const int R = K + (dueling ? 1 : 0);
     const int grp = tid >> 4, l = tid & 15;
-    for (int d = grp; d < 3 * R; d += 32) {
-        const int p = d / R, r = d - p * R;
-        const float *head = p == 2 ? head_tg : head_on;
-        const float *w = head + head_w_off(r, K, dueling);
-        const float *x = hid[p];
-        float acc = 0.f;
-#pragma unroll 8
-        for (int k = 0; k < net::HID / 16; ++k) acc += w[l + 16 * k] * x[l + 16 * k];
+    const int d = grp + 32 * round;
+    H.d = d < 3 * R ? d : -1;
+    if (H.d < 0) return;
+    const int p = d / R, r = d - p * R;
+    const float *head = p == 2 ? head_tg : head_on;
+    const float *w = head + head_w_off(r, K, dueling);
 #pragma unroll
-        for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-        if (l == 0) raw[p][r] = acc + head[head_b_off(r, K, dueling)];
-    }
+    for (int k = 0; k < net::HID / 16; ++k) H.w[k] = w[l + 16 * k];
+    H.b = head[head_b_off(r, K, dueling)];
+}
+__device__ __forceinline__ void head_rows3_dot(const HeadRound &H, const float (*hid)[net::HID] /*LDS [3][512]*/,
+                                               int K, int dueling, float (*raw)[65] /*LDS [3][65]*/, int tid)
+{
+    if (H.d < 0) return;  // uniform within the 16-lane group
+    const int R = K + (dueling ? 1 : 0);
+    const int l = tid & 15;
+    const int p = H.d / R, r = H.d - p * R;
+    const float *x = hid[p];
+    float acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < net::HID / 16; ++k) acc += H.w[k] * x[l + 16 * k];
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (l == 0) raw[p][r] = acc + H.b;
 }
 
 // Q_a = V + (A_a - mean A) (Eq.13) or the raw outputs; serial, K <= 64
@@ -181,6 +199,15 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         wnorm = 1.f / block_max_1024(m, shm);
     }
 
+    // column tid of the online head (for the back-propagation into the hidden layer at the end)
+    // and the head weights of the first two rounds (all of them when 3R <= 64) are requested now
+    constexpr int HW_PRE = 24;
+    float hw[HW_PRE];
+#pragma unroll
+    for (int r = 0; r < HW_PRE; ++r) hw[r] = r < R ? A.head_on[head_w_off(r, K, A.dueling) + tid] : 0.f;
+    HeadRound H0, H1;
+    head_rows3_load(H0, 0, A.head_on, A.head_tg, K, A.dueling, tid);
+    head_rows3_load(H1, 1, A.head_on, A.head_tg, K, A.dueling, tid);
     {
         const int i = tid;  // one hidden unit per thread
         float hs = hidden_unit(A.part, A.nsplit, A.split_stride, j, i, A.f1b_on);
@@ -190,7 +217,12 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         A.h_s[(long)j * net::HID + i] = hs;
     }
     __syncthreads();
-    head_rows3(hid, A.head_on, A.head_tg, K, A.dueling, raw, tid);
+    head_rows3_dot(H0, hid, K, A.dueling, raw, tid);
+    head_rows3_dot(H1, hid, K, A.dueling, raw, tid);
+    for (int round = 2; 32 * round < 3 * R; ++round) {  // more than 64 dot products: K > 20
+        head_rows3_load(H0, round, A.head_on, A.head_tg, K, A.dueling, tid);
+        head_rows3_dot(H0, hid, K, A.dueling, raw, tid);
+    }
     __syncthreads();
     if (tid < 3) combine_q(raw[tid], K, A.dueling, q[tid]);
     __syncthreads();
@@ -231,8 +263,10 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
     {
         const int i = tid;
         float acc = 0.f;
-#pragma unroll 4
-        for (int r = 0; r < R; ++r) acc += dA[r] * A.head_on[head_w_off(r, K, A.dueling) + i];
+#pragma unroll
+        for (int r = 0; r < HW_PRE; ++r)
+            if (r < R) acc += dA[r] * hw[r];
+        for (int r = HW_PRE; r < R; ++r) acc += dA[r] * A.head_on[head_w_off(r, K, A.dueling) + i];
         const float gmask = hid[0][i] > 0.f ? acc : 0.f;
         if (A.dh_bf16) static_cast<__hip_bfloat16 *>(A.dh)[(long)j * net::HID + i] = __float2bfloat16(gmask);
         else static_cast<float *>(A.dh)[(long)j * net::HID + i] = gmask;
