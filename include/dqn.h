@@ -161,7 +161,8 @@ int32_t per_sample(dqn_ctx *ctx, int32_t B, float beta, uint64_t draw_seed, int3
  * per_eps)^alpha) for j = 0..n-1 with the last occurrence of a repeated index
  * winning, every ancestor recomputed as fp32(left + right), and the running
  * maximum priority raised to max_j(|td_j| + per_eps).  idx values must lie in
- * [0, stored size); out-of-range entries are skipped.  1 <= n <= 1024. */
+ * [0, stored size); out-of-range entries and entries whose td is not finite are
+ * skipped (their leaves keep their values).  1 <= n <= 1024. */
 int32_t per_update(dqn_ctx *ctx, const int32_t *idx, const float *td_abs, int32_t n, void *stream);
 
 /* ---- auxiliary calls needed to drive and to check the five above ---- */

@@ -667,13 +667,16 @@ void orc_per_sample_cumsum(const float *tree, int64_t L, int64_t size, const flo
 
 /* Priority update: for j = 0..n-1 in order, leaf[idx_j] <- fp32((|td_j|+eps)^alpha)
  * and every ancestor is recomputed as left+right (so the last occurrence of a
- * repeated index wins).  max_p <- max(max_p, |td_j| + eps).            */
+ * repeated index wins).  max_p <- max(max_p, |td_j| + eps).  An entry whose
+ * error is not finite is skipped (the paper does not consider it; a NaN
+ * priority would poison every sum above it).                           */
 int32_t orc_per_update(float *tree, int64_t L, int64_t size, const int32_t *idx, const float *td_abs,
                        int32_t n, double alpha, double eps, float *max_p)
 {
     for (int j = 0; j < n; ++j) {
         if (idx[j] < 0 || idx[j] >= size) return -1;
         float p = (float)((double)fabsf(td_abs[j]) + eps);
+        if (!(p <= 3.0e38f)) continue;
         int64_t node = L + idx[j];
         tree[node] = leaf_value((double)p, alpha);
         for (node >>= 1; node >= 1; node >>= 1) tree[node] = tree[2 * node] + tree[2 * node + 1];

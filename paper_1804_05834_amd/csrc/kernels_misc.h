@@ -635,8 +635,10 @@ __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int le
     float p = 0.f;
     if (j < n) {
         const int v = idx[j];
-        if (v >= 0 && v < size) my = v;
         p = (float)((double)fabsf(td_abs[j]) + (double)eps);
+        // an entry with a slot outside the ring or a non-finite error is skipped: its leaf keeps
+        // its value, and the tree stays a tree of finite sums
+        if (v >= 0 && v < size && p <= 3.0e38f) my = v;   // the comparison is false for NaN
     }
     const bool valid = my >= 0;
     for (int t = j; t < PU_SLOTS; t += nt) { keys[t] = -1; ivals[t] = -1; }

@@ -315,6 +315,25 @@ def test_tree_fill_sample_update(dq, orc, cap, n, B, strat):
     m.close()
 
 
+def test_per_update_skips_non_finite_errors(dq, orc):
+    """A NaN or infinite TD error must not reach the tree: the entry is skipped on both sides."""
+    print("case per_update non-finite", flush=True)
+    cap, n = 1000, 64
+    m = dq.Dqn(dq.make_config(replay_capacity=cap, max_batch=n))
+    pri = synth.exp_priorities(9, cap)
+    m.per_fill(dev(pri))
+    tree_ref = orc.tree_build(pri.numpy(), m.L, float(np.float32(0.6)))
+    idx = torch.arange(0, 2 * n, 2, dtype=torch.int32)
+    td = (0.1 + synth.u24(5, torch.arange(n))).float()
+    td[7] = float("nan"); td[20] = float("inf"); td[21] = -float("inf")
+    m.per_update(dev(idx), dev(td))
+    mp = orc.per_update(tree_ref, cap, idx.numpy(), td.numpy(), float(np.float32(0.6)), float(np.float32(1e-6)), 1.0)
+    tree = m.tree.cpu().numpy()
+    assert np.all(np.isfinite(tree)) and np.array_equal(tree[1:], tree_ref[1:])
+    assert float(m.max_priority) == np.float32(mp) and np.isfinite(mp)
+    m.close()
+
+
 def test_replay_gather(dq, orc):
     print("case gather", flush=True)
     cap, K = 300, 18
