@@ -37,6 +37,7 @@ def flops_per_launch(B, R):
         "fc1_dgrad": B * F_FC1, "fc1_wgrad": B * F_FC1, "conv3_dgrad": B * F_CONV3,
         "conv3_wgrad": B * F_CONV3, "conv2_dgrad": B * F_CONV2, "conv2_wgrad": B * F_CONV2,
         "conv1_wgrad": B * F_CONV1,
+        "small_tail": B * (F_CONV1 + F_CONV2 + F_CONV3 + F_FC1),  # all weight gradients in one launch (small fp32 batches)
     }
 
 
@@ -44,6 +45,7 @@ def bytes_per_launch(B, n_params, bf16, levels=20):
     """Algorithmic HBM bytes of the kernels that move data rather than multiply."""
     return {
         "gather": B * 5 * 7056 * 2,                       # read 5 ring frames, write the 5-stack
+        "sample_gather": B * 5 * 7056 * 2,                # the same, with the draw in front (fp32 path)
         "rmsprop": n_params * (22 if bf16 else 20),       # r/w theta, v; read g (+ bf16 copy)
         "per_sample": B * levels * 4,                     # one useful node per level and draw
         "per_update": B * levels * 12,                    # read sibling, write node (+ leaf) per level

@@ -481,20 +481,79 @@ void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipS
     launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
 }
 
+// ----- small-batch tail: everything that is left once the input gradients are done -----
+// For a small batch on one stream the four trunk weight gradients, the head weight gradient and
+// the priority update are each a few short tiles; one launch of 256-thread workgroups runs them
+// side by side.  Workgroups [begin[p], begin[p+1]): p = 0..3 the trunk layers (conv1, conv2,
+// conv3, fc1), 4 the head (row r, 32 hidden units per workgroup), 5 the priority update (one
+// workgroup, at most 256 entries).
+struct SmallTail {
+    misc::HeadWgradArgs head;
+    misc::PerUpdateArgs update;
+    bool with_update;
+};
+struct SmallTailArgs {
+    g32::WgradArgs a[4];
+    int begin[7];
+    int gx[4], gy[4], gz[4];
+    misc::HeadWgradArgs head;
+    misc::PerUpdateArgs update;
+};
+__global__ __launch_bounds__(256) void k_small_tail(SmallTailArgs A)
+{
+    using namespace g32;
+    constexpr int LW = wgrad_lds<32, 128>() > wgrad_lds<64, 64>() ? wgrad_lds<32, 128>() : wgrad_lds<64, 64>();
+    constexpr int L = LW > misc::PU_LDS_WORDS ? LW : misc::PU_LDS_WORDS;
+    __shared__ __attribute__((aligned(16))) float lds[L];
+    // plain dispatch order: the problems' tiles differ in length, and round-robin over the dies
+    // spreads each of them over all dies
+    const int t = blockIdx.x;
+    int p = 0;
+#pragma unroll
+    for (int q = 1; q < 6; ++q)
+        if (t >= A.begin[q]) p = q;
+    const int u = t - A.begin[p];
+    int bx, by, bz;
+    if (p == 0) {
+        wgrad_tile_of(u, A.gx[0], A.gy[0], A.gz[0], bx, by, bz);
+        wgrad_tile<GConv1, 32, 128>(A.a[0], bx, by, bz, lds);
+    } else if (p == 1) {
+        wgrad_tile_of(u, A.gx[1], A.gy[1], A.gz[1], bx, by, bz);
+        wgrad_tile<GConv2, 64, 64>(A.a[1], bx, by, bz, lds);
+    } else if (p == 2) {
+        wgrad_tile_of(u, A.gx[2], A.gy[2], A.gz[2], bx, by, bz);
+        wgrad_tile<GConv3, 64, 64>(A.a[2], bx, by, bz, lds);
+    } else if (p == 3) {
+        wgrad_tile_of(u, A.gx[3], A.gy[3], A.gz[3], bx, by, bz);
+        wgrad_tile<GFc1, 64, 64>(A.a[3], bx, by, bz, lds);
+    } else if (p == 4) {
+        misc::head_wgrad_body<8>(A.head, u / 16, u % 16, lds);
+    } else {
+        misc::per_update_body(A.update, reinterpret_cast<int *>(lds));
+    }
+}
+
 // ----- backward through fc1, conv3, conv2, conv1 (no input gradient for conv1) -----
 // The input-gradient chain and conv1's weight gradient run on st; the weight gradients of fc1,
 // conv3 and conv2 run on sd behind the events the chain records.  All of st's kernels are
 // enqueued before any of sd's: handing the host from one stream to another costs more than a
 // launch, and the device does not care in which order the host filled the two queues.
 void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *ns2, int *ns3, hipStream_t st,
-                  hipStream_t sd)
+                  hipStream_t sd, const SmallTail *tail)
 {
     using namespace g32;
     const Workspace &w = c->ws;
     float *act1 = (float *)w.act1, *act2 = (float *)w.act2, *act3 = (float *)w.act3;
     float *dh = (float *)w.dh, *d3 = (float *)w.d3, *d2 = (float *)w.d2, *d1 = (float *)w.d1;
     const bool small = B <= 128;
-    int rps;
+    int rps1, rps2, rps3;
+    split_rows((long)B * 400, 1, MAX_WSPLIT1, 32, &rps1, ns1);
+    split_rows((long)B * 81, 8, MAX_WSPLIT, 32, &rps2, ns2);
+    split_rows((long)B * 49, 9, MAX_WSPLIT, 32, &rps3, ns3);
+    const WgradArgs G1{d1, s, w.gp1, B, rps1, xs, net::L1N, 1.0f / 255.0f};
+    const WgradArgs G2{d2, act1, w.gp2, B, rps2, net::A1, net::L2N, 1.0f};
+    const WgradArgs G3{d3, act2, w.gp3, B, rps3, net::A2, net::L3N, 1.0f};
+    const WgradArgs G4{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
     {
         DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
         if (small) launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 32, 4><<<dim3((B + 31) / 32, 98, 1), 256, 0, st>>>(D); });
@@ -513,27 +572,36 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
         long M = (long)B * 100;
         launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 64, 32, 4><<<dim3((M + 63) / 64, 1, 4), 512, 0, st>>>(D); });
     }
-    {
-        split_rows((long)B * 400, 1, MAX_WSPLIT1, 32, &rps, ns1);
-        WgradArgs G{d1, s, w.gp1, B, rps, xs, net::L1N, 1.0f / 255.0f};
-        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256><<<dim3(1, 1, *ns1), 512, 0, st>>>(G); });
+    if (sd == st) {
+        // one stream: the weight gradients are independent of each other once the input gradients
+        // are done, so they share one launch (with the head's and the priority update if given)
+        SmallTailArgs A{};
+        A.a[0] = G1; A.a[1] = G2; A.a[2] = G3; A.a[3] = G4;
+        const int gx[4] = {2, 8, 9, 49}, gy[4] = {1, 1, 1, 8}, gz[4] = {*ns1, *ns2, *ns3, 1};
+        int total = 0;
+        for (int p = 0; p < 4; ++p) {
+            A.begin[p] = total;
+            A.gx[p] = gx[p]; A.gy[p] = gy[p]; A.gz[p] = gz[p];
+            total += gx[p] * gy[p] * gz[p];
+        }
+        A.begin[4] = total;
+        if (tail) {
+            A.head = tail->head;
+            A.update = tail->update;
+            total += c->R * 16;
+        }
+        A.begin[5] = total;
+        if (tail && tail->with_update) total += 1;
+        A.begin[6] = total;
+        launch(c, "small_tail", st, [&] { k_small_tail<<<dim3(total), 256, 0, st>>>(A); });
+        return;
     }
-    {
-        WgradArgs G{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
-        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
-    }
-    {
-        split_rows((long)B * 49, 9, MAX_WSPLIT, 32, &rps, ns3);
-        WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
-        ev_wait(sd, c->ev_a, st);
-        launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G); });
-    }
-    {
-        split_rows((long)B * 81, 8, MAX_WSPLIT, 32, &rps, ns2);
-        WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
-        ev_wait(sd, c->ev_b, st);
-        launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
-    }
+    launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256><<<dim3(1, 1, *ns1), 512, 0, st>>>(G1); });
+    launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, sd>>>(G4); });
+    ev_wait(sd, c->ev_a, st);
+    launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G3); });
+    ev_wait(sd, c->ev_b, st);
+    launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G2); });
 }
 
 void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *ns3, hipStream_t st,
@@ -842,8 +910,8 @@ int32_t per_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, int32_
     if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "per_sample: beta must be >= 0");
     hipStream_t st = (hipStream_t)stream;
     launch(c, "per_sample", st, [&] {
-        misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(c->tree, c->L, c->levels, c->stored, B, beta, draw_seed,
-                                                        c->cfg.per_stratified, idx, is_w, misc::MetaGather{});
+        misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(misc::SampleArgs{
+            c->tree, c->L, c->levels, c->stored, B, beta, draw_seed, c->cfg.per_stratified, idx, is_w, misc::MetaGather{}});
     });
     launch(c, "per_normalise", st, [&] { misc::k_per_normalise<<<1, 1024, 0, st>>>(is_w, B); });
     return hip_status(c, "per_sample");
@@ -857,8 +925,8 @@ int32_t per_update(dqn_ctx *c, const int32_t *idx, const float *td_abs, int32_t 
     if (!idx || !td_abs) return fail(c, DQN_ERR_INVALID_ARG, "per_update: NULL argument");
     hipStream_t st = (hipStream_t)stream;
     launch(c, "per_update", st, [&] {
-        misc::k_per_update<<<1, (n + 63) / 64 * 64, 0, st>>>(c->tree, c->L, c->levels, c->stored, idx, td_abs, n,
-                                                c->cfg.per_alpha, c->cfg.per_eps);
+        misc::k_per_update<<<1, (n + 63) / 64 * 64, 0, st>>>(
+            misc::PerUpdateArgs{c->tree, c->L, c->levels, c->stored, idx, td_abs, n, c->cfg.per_alpha, c->cfg.per_eps});
     });
     return hip_status(c, "per_update");
 }
@@ -985,15 +1053,27 @@ int32_t dqn_act(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64
 }
 
 // ------------------------------------------------------------ training
-static void enqueue_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, hipStream_t st)
+static misc::SampleArgs sample_args(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed)
 {
     const Workspace &w = c->ws;
     // raw importance weights; the head kernel divides by their maximum
-    launch(c, "per_sample", st, [&] {
-        misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(c->tree, c->L, c->levels, c->stored, B, beta, draw_seed,
-                                                        c->cfg.per_stratified, w.b_idx, w.b_w,
-                                                        misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done});
-    });
+    return misc::SampleArgs{c->tree, c->L, c->levels, c->stored, B, beta, draw_seed, c->cfg.per_stratified,
+                            w.b_idx, w.b_w,
+                            misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done}};
+}
+
+// The sampling kernel of a replay-mode step.  The fp32 path copies the drawn frame stacks next
+// (its conv1 reads a materialised stack): there the two are one launch.
+static void enqueue_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, hipStream_t st)
+{
+    const misc::SampleArgs S = sample_args(c, B, beta, draw_seed);
+    if (c->cfg.precision == 0) {
+        misc::GatherArgs G{(const uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r, c->meta_done,
+                           (long)c->cfg.replay_capacity, c->ws.b_idx, c->ws.stack5, nullptr, nullptr, nullptr, nullptr, nullptr};
+        launch(c, "sample_gather", st, [&] { misc::k_sample_gather<<<dim3(B, 5), 256, 0, st>>>(S, G); });
+        return;
+    }
+    launch(c, "per_sample", st, [&] { misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(S); });
 }
 
 // Enqueues every kernel of one training step on st (and on the side streams, which fork from
@@ -1026,9 +1106,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
             ring_idx = w.b_idx;
             s = sn = (const uint8_t *)c->buf.replay_frames; xs = 0;
         } else {
-            misc::GatherArgs G{(const uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r, c->meta_done,
-                               (long)cfg.replay_capacity, w.b_idx, w.stack5, nullptr, nullptr, nullptr, nullptr, nullptr};
-            launch(c, "gather", st, [&] { misc::k_gather<<<dim3(B, 5), 256, 0, st>>>(G); });
+            // the frame stacks were copied by the sampling launch
             s = w.stack5; sn = w.stack5 + net::FRAME; xs = 5 * net::FRAME;
         }
         if (O.idx && hipMemcpyAsync(O.idx, w.b_idx, (size_t)B * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
@@ -1063,19 +1141,22 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     ev_wait(sd, c->ev_fork, st);
     if (sp != sd) ev_wait(sp, c->ev_fork, st);
     misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
-    launch(c, "head_wgrad", sp, [&] { misc::k_head_wgrad<<<dim3(c->R, 16), 512, 0, sp>>>(HW); });
-    if (!batch) {
-        // the indices come from the sampling kernel, so the ring capacity bounds them
-        launch(c, "per_update", sp, [&] {
-            misc::k_per_update<<<1, (B + 63) / 64 * 64, 0, sp>>>(c->tree, c->L, c->levels, (long)cfg.replay_capacity,
-                                                                 w.b_idx, w.td_abs, B, cfg.per_alpha, cfg.per_eps);
-        });
+    // the indices come from the sampling kernel, so the ring capacity bounds them
+    misc::PerUpdateArgs PU{c->tree, c->L, c->levels, (long)cfg.replay_capacity, w.b_idx, w.td_abs, B,
+                           cfg.per_alpha, cfg.per_eps};
+    // small fp32 batch on one stream: the head weight gradient and the priority update join the
+    // four trunk weight gradients in one launch at the end of the backward pass
+    SmallTail tail{HW, PU, !batch};
+    const bool fuse_tail = cfg.precision == 0 && sd == st && B <= 64;
+    if (!fuse_tail) {
+        launch(c, "head_wgrad", sp, [&] { misc::k_head_wgrad<<<dim3(c->R, 16), 512, 0, sp>>>(HW); });
+        if (!batch) launch(c, "per_update", sp, [&] { misc::k_per_update<<<1, (B + 63) / 64 * 64, 0, sp>>>(PU); });
     }
     if (sp != sd) (void)hipEventRecord(c->ev_join2, sp);
 
     int ns1, ns2, ns3;
     if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, sd);
-    else backward_f32(c, B, s, xs, &ns1, &ns2, &ns3, st, sd);
+    else backward_f32(c, B, s, xs, &ns1, &ns2, &ns3, st, sd, fuse_tail ? &tail : nullptr);
     ev_record(c->ev_join, sd, st);
     ev_wait(st, c->ev_join, sd);
     if (sp != sd) (void)hipStreamWaitEvent(st, c->ev_join2, 0);

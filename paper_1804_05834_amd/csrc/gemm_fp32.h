@@ -378,27 +378,22 @@ struct WgradArgs {
     float scale;       // multiplies dW (1/255 for conv1)
 };
 
+// LDS of one weight-gradient tile pair, in floats
+template <int BMO, int BNK> constexpr int wgrad_lds() { return BK * (BMO + 4) + BK * (BNK + 4); }
+
+// One weight-gradient tile: output channels [by*BMO, +BMO) x im2col columns [bx*BNK, +BNK) over the
+// rows of split bz.  T threads; Ys/Xs are the workgroup's LDS.
 template <class G, int BMO, int BNK>
-__global__ __launch_bounds__((BMO / 32) * (BNK / 32) * 64) void k_wgrad(WgradArgs A)
+__device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int bx, int by, int bz, float *lds)
 {
     constexpr int T = (BMO / 32) * (BNK / 32) * 64;
     constexpr int LDY = BMO + 4, LDX = BNK + 4;
     constexpr int YR = T / (BMO / 4), XR = T / (BNK / 4);  // tile rows filled per pass
     constexpr int NY = (BK + YR - 1) / YR, NX = (BK + XR - 1) / XR;
     using in_t = typename G::in_t;
-    __shared__ __attribute__((aligned(16))) float Ys[BK * LDY];
-    __shared__ __attribute__((aligned(16))) float Xs[BK * LDX];
+    float *Ys = lds, *Xs = lds + BK * LDY;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // tile order: with row splits (conv layers) all tiles of one split together; without
-    // (fc1) all output tiles of one input-column tile together
-    const int t = net::tile_of_workgroup();
-    int bx, by, bz;
-    if (gridDim.z > 1) {
-        bx = t % (int)gridDim.x; by = (t / (int)gridDim.x) % (int)gridDim.y; bz = t / (int)(gridDim.x * gridDim.y);
-    } else {
-        by = t % (int)gridDim.y; bx = t / (int)gridDim.y; bz = 0;
-    }
     const int kc0 = bx * BNK, o0 = by * BMO;
     const int mbeg = bz * A.rps;
     const int mend = min(mbeg + A.rps, A.B * G::P);
@@ -472,6 +467,26 @@ __global__ __launch_bounds__((BMO / 32) * (BNK / 32) * 64) void k_wgrad(WgradArg
         part[(long)o * G::K + col] = acc[r] * A.scale;
         if (do_bias && li == 0) part[(long)G::N * G::K + o] = accb[r];
     }
+}
+
+// tile number -> (bx, by, bz) of a grid (gx, gy, gz): with row splits (conv layers) all tiles of one
+// split together; without (fc1) all output tiles of one input-column tile together
+__device__ __forceinline__ void wgrad_tile_of(int t, int gx, int gy, int gz, int &bx, int &by, int &bz)
+{
+    if (gz > 1) {
+        bx = t % gx; by = (t / gx) % gy; bz = t / (gx * gy);
+    } else {
+        by = t % gy; bx = t / gy; bz = 0;
+    }
+}
+
+template <class G, int BMO, int BNK>
+__global__ __launch_bounds__((BMO / 32) * (BNK / 32) * 64) void k_wgrad(WgradArgs A)
+{
+    __shared__ __attribute__((aligned(16))) float lds[wgrad_lds<BMO, BNK>()];
+    int bx, by, bz;
+    wgrad_tile_of(net::tile_of_workgroup(), gridDim.x, gridDim.y, gridDim.z, bx, by, bz);
+    wgrad_tile<G, BMO, BNK>(A, bx, by, bz, lds);
 }
 
 }  // namespace g32

@@ -287,16 +287,18 @@ struct HeadWgradArgs {
 // grid (R, 16): block (r, c) owns hidden units [32c, 32c+32); its 512 threads split the
 // minibatch sixteen ways and combine through LDS in a fixed order.  Block (0,0) also folds the
 // per-row loss terms into L = (1/B) sum_j w_j l_j.
-__global__ __launch_bounds__(512) void k_head_wgrad(HeadWgradArgs A)
+// NG = threads / 32 groups over the minibatch; lds: NG * 34 floats.  Row r, hidden units [32c, 32c+32).
+template <int NG>
+__device__ __forceinline__ void head_wgrad_body(const HeadWgradArgs &A, int r, int c, float *lds)
 {
-    __shared__ float red[16][33];
-    __shared__ float redb[16];
-    const int r = blockIdx.x, il = threadIdx.x & 31, jg = threadIdx.x >> 5;
-    const int i = blockIdx.y * 32 + il;
+    float(*red)[33] = reinterpret_cast<float(*)[33]>(lds);
+    float *redb = lds + NG * 33;
+    const int il = threadIdx.x & 31, jg = threadIdx.x >> 5;
+    const int i = c * 32 + il;
     const int R = A.K + (A.dueling ? 1 : 0);
     float acc = 0.f, accb = 0.f;
 #pragma unroll 8
-    for (int j = jg; j < A.B; j += 16) {
+    for (int j = jg; j < A.B; j += NG) {
         float d = A.dA[(long)j * R + r];
         acc += d * A.h_s[(long)j * net::HID + i];
         accb += d;
@@ -307,16 +309,16 @@ __global__ __launch_bounds__(512) void k_head_wgrad(HeadWgradArgs A)
     if (jg == 0) {
         float s = red[0][il];
 #pragma unroll
-        for (int g = 1; g < 16; ++g) s += red[g][il];
+        for (int g = 1; g < NG; ++g) s += red[g][il];
         A.ghead[head_w_off(r, A.K, A.dueling) + i] = s;
-        if (il == 0 && blockIdx.y == 0) {
+        if (il == 0 && c == 0) {
             float sb = redb[0];
 #pragma unroll
-            for (int g = 1; g < 16; ++g) sb += redb[g];
+            for (int g = 1; g < NG; ++g) sb += redb[g];
             A.ghead[head_b_off(r, A.K, A.dueling)] = sb;
         }
     }
-    if (r == 0 && blockIdx.y == 0 && threadIdx.x >= 448) {  // the last wave sums the loss terms
+    if (r == 0 && c == 0 && (int)threadIdx.x >= NG * 32 - 64) {  // the last wave sums the loss terms
         const int lane = threadIdx.x & 63;
         float s = 0.f;
         for (int j = lane; j < A.B; j += 64) s += A.loss_j[j];
@@ -326,6 +328,12 @@ __global__ __launch_bounds__(512) void k_head_wgrad(HeadWgradArgs A)
             if (A.loss_out) *A.loss_out = s;
         }
     }
+}
+
+__global__ __launch_bounds__(512) void k_head_wgrad(HeadWgradArgs A)
+{
+    __shared__ float lds[16 * 34];
+    head_wgrad_body<16>(A, blockIdx.x, blockIdx.y, lds);
 }
 
 struct HeadActArgs {
@@ -515,20 +523,30 @@ struct MetaGather {
 // fetch is a contiguous run of the heap array.
 // is_w receives the RAW weight (N P(j))^-beta; k_per_normalise (or the consumer)
 // divides by the minibatch maximum.
-__global__ __launch_bounds__(256) void k_per_sample(const float *tree, long L, int levels, long size, int B,
-                                                    float beta, uint64_t seed, int stratified,
-                                                    int32_t *idx, float *is_w, MetaGather G)
+struct SampleArgs {
+    const float *tree;
+    long L;
+    int levels;
+    long size;
+    int B;
+    float beta;
+    uint64_t seed;
+    int stratified;
+    int32_t *idx;
+    float *is_w;
+    MetaGather G;
+};
+
+// Draw j by one wave; every lane returns the slot.
+__device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, int lane, float total)
 {
-    const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= B) return;
-    const float total = tree[1];
-    const float u = draw_u24(seed, (uint64_t)j);
-    float z = stratified ? __fmul_rn((float)j + u, total / (float)B) : __fmul_rn(u, total);
+    const float *tree = A.tree;
+    const float u = draw_u24(A.seed, (uint64_t)j);
+    float z = A.stratified ? __fmul_rn((float)j + u, total / (float)A.B) : __fmul_rn(u, total);
     long node = 1;
     const int lj = lane >= 2 ? 31 - __clz(lane) : 0;  // level of local heap node `lane`
-    for (int done = 0; done < levels;) {
-        const int r = min(6, levels - done);  // levels walked in this round
+    for (int done = 0; done < A.levels;) {
+        const int r = min(6, A.levels - done);  // levels walked in this round
         float va = 0.f, vb = 0.f;
         if (lane >= 2 && lane < (2 << min(r, 5))) va = tree[(node << lj) + (lane - (1 << lj))];
         if (r == 6) vb = tree[(node << 6) + lane];
@@ -546,18 +564,32 @@ __global__ __launch_bounds__(256) void k_per_sample(const float *tree, long L, i
         node = (node << r) + (cur - (1 << r));
         done += r;
     }
-    if (lane == 0) {
-        long slot = node - L;
-        if (slot > size - 1) slot = size - 1;
-        const double P = (double)tree[L + slot] / (double)total;
-        idx[j] = (int32_t)slot;
-        is_w[j] = (float)pow((double)size * P, -(double)beta);
-        if (G.a) {
-            G.a[j] = G.meta_a[slot];
-            G.r[j] = G.meta_r[slot];
-            G.done[j] = G.meta_done[slot];
-        }
+    long slot = node - A.L;
+    if (slot > A.size - 1) slot = A.size - 1;
+    return slot;
+}
+
+// What one lane writes for draw j once the slot is known: index, raw weight, transition data.
+__device__ __forceinline__ void per_sample_emit(const SampleArgs &A, int j, long slot, float total)
+{
+    const double P = (double)A.tree[A.L + slot] / (double)total;
+    A.idx[j] = (int32_t)slot;
+    A.is_w[j] = (float)pow((double)A.size * P, -(double)A.beta);
+    if (A.G.a) {
+        A.G.a[j] = A.G.meta_a[slot];
+        A.G.r[j] = A.G.meta_r[slot];
+        A.G.done[j] = A.G.meta_done[slot];
     }
+}
+
+__global__ __launch_bounds__(256) void k_per_sample(SampleArgs A)
+{
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= A.B) return;
+    const float total = A.tree[1];
+    const long slot = per_sample_descend(A, j, lane, total);
+    if (lane == 0) per_sample_emit(A, j, slot, total);
 }
 
 // w_j <- w_j / max_j w_j over the minibatch (single workgroup)
@@ -623,13 +655,29 @@ __device__ __forceinline__ int pu_find(const int *keys, int key)
     }
 }
 
-__global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int levels, long size,
-                                                     const int32_t *idx, const float *td_abs, int n,
-                                                     float alpha, float eps)
+struct PerUpdateArgs {
+    float *tree;
+    long L;
+    int levels;
+    long size;
+    const int32_t *idx;
+    const float *td_abs;
+    int n;
+    float alpha, eps;
+};
+constexpr int PU_LDS_WORDS = 2 * PU_SLOTS + 16;  // LDS of per_update_body, in 4-byte words
+
+// The whole workgroup (blockDim.x >= n threads) must call this.  lds: PU_LDS_WORDS words.
+__device__ __forceinline__ void per_update_body(const PerUpdateArgs &A, int *lds)
 {
-    __shared__ int keys[PU_SLOTS];
-    __shared__ int ivals[PU_SLOTS];  // largest entry number naming the slot's leaf
-    __shared__ float sh[16];
+    int *keys = lds, *ivals = lds + PU_SLOTS;  // ivals: largest entry number naming the slot's leaf
+    float *sh = reinterpret_cast<float *>(lds + 2 * PU_SLOTS);
+    float *tree = A.tree;
+    const long L = A.L, size = A.size;
+    const int levels = A.levels, n = A.n;
+    const int32_t *idx = A.idx;
+    const float *td_abs = A.td_abs;
+    const float alpha = A.alpha, eps = A.eps;
     const int j = threadIdx.x, nt = blockDim.x;
     int my = -1;
     float p = 0.f;
@@ -659,6 +707,12 @@ __global__ __launch_bounds__(1024) void k_per_update(float *tree, long L, int le
     const bool walk = valid && ivals[slot] == j;
     float v = (float)pow((double)p, (double)alpha);
     tree_walk(tree, node, v, walk, levels);
+}
+
+__global__ __launch_bounds__(1024) void k_per_update(PerUpdateArgs A)
+{
+    __shared__ int lds[PU_LDS_WORDS];
+    per_update_body(A, lds);
 }
 
 // Store path (Alg.2 "store transition with maximal priority"): n time steps have just been
@@ -773,6 +827,31 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A)
         if (A.r) A.r[j] = A.meta_r[i];
         if (A.done) A.done[j] = A.meta_done[i];
     }
+}
+
+// Sampling and the frame-stack gather in one launch (grid (B, 5), 256 threads): the first wave of
+// every workgroup repeats the draw of its transition (five workgroups per transition do the same
+// descent; it costs less than a launch), workgroup (j, 0) also emits the draw's outputs, then all
+// threads copy frame k of the stack.
+__global__ __launch_bounds__(256) void k_sample_gather(SampleArgs S, GatherArgs A)
+{
+    __shared__ long slot_sh;
+    const int j = blockIdx.x, k = blockIdx.y;
+    if (threadIdx.x < 64) {
+        const float total = S.tree[1];
+        const long slot = per_sample_descend(S, j, threadIdx.x, total);
+        if (threadIdx.x == 0) {
+            slot_sh = slot;
+            if (k == 0) per_sample_emit(S, j, slot, total);
+        }
+    }
+    __syncthreads();
+    const long i = slot_sh;
+    long slot = (i - 3 + k) % A.cap;
+    if (slot < 0) slot += A.cap;
+    const uint4 *src = reinterpret_cast<const uint4 *>(A.frames + slot * net::FRAME);
+    uint4 *d0 = reinterpret_cast<uint4 *>(A.stack5 + ((long)j * 5 + k) * net::FRAME);
+    for (int t = threadIdx.x; t < net::FRAME / 16; t += 256) d0[t] = src[t];
 }
 
 // Ring store: n frames into slots slot0.. (mod cap); grid (n).
