@@ -7,23 +7,9 @@
 #include <stdint.h>
 
 #include "net.h"
+#include "sumtree.h"
 
 namespace misc {
-
-// ----------------------------------------------------------------- draws
-// 64-bit counter mixer (SplitMix64 output function on seed + (ctr+1)*gamma);
-// a uniform in [0,1) is its top 24 bits times 2^-24.
-__host__ __device__ __forceinline__ uint64_t mix64(uint64_t seed, uint64_t ctr)
-{
-    uint64_t z = seed + (ctr + 1ull) * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-__host__ __device__ __forceinline__ float draw_u24(uint64_t seed, uint64_t ctr)
-{
-    return (float)(mix64(seed, ctr) >> 40) * (1.0f / 16777216.0f);
-}
 
 // Barrier that orders LDS traffic only: global loads and stores issued earlier stay in flight
 // across it (__syncthreads() would first wait for every one of them to complete).
@@ -503,84 +489,6 @@ __global__ void k_tree_level(float *tree, long first, long count)
     tree[node] = tree[2 * node] + tree[2 * node + 1];
 }
 
-
-// Optional per-slot transition data to carry along with the draw.
-struct MetaGather {
-    const int32_t *meta_a;
-    const float *meta_r;
-    const uint8_t *meta_done;
-    int32_t *a;
-    float *r;
-    uint8_t *done;
-};
-
-// Proportional sampling (Eq.10, Eq.12), one WAVE per draw.  The descent is the
-// sequential rule "z < left ? go left : (z -= left, go right)" in fp32, but the
-// memory side is batched: at a node x the wave fetches the whole 6-level subtree
-// below x in one round trip (lane l reads local heap node l of levels 1..5 and
-// node l of level 6), then walks those 6 levels out of registers with lane
-// shuffles.  20 levels cost 4 dependent round trips instead of 20, and every
-// fetch is a contiguous run of the heap array.
-// is_w receives the RAW weight (N P(j))^-beta; k_per_normalise (or the consumer)
-// divides by the minibatch maximum.
-struct SampleArgs {
-    const float *tree;
-    long L;
-    int levels;
-    long size;
-    int B;
-    float beta;
-    uint64_t seed;
-    int stratified;
-    int32_t *idx;
-    float *is_w;
-    MetaGather G;
-};
-
-// Draw j by one wave; every lane returns the slot.
-__device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, int lane, float total)
-{
-    const float *tree = A.tree;
-    const float u = draw_u24(A.seed, (uint64_t)j);
-    float z = A.stratified ? __fmul_rn((float)j + u, total / (float)A.B) : __fmul_rn(u, total);
-    long node = 1;
-    const int lj = lane >= 2 ? 31 - __clz(lane) : 0;  // level of local heap node `lane`
-    for (int done = 0; done < A.levels;) {
-        const int r = min(6, A.levels - done);  // levels walked in this round
-        float va = 0.f, vb = 0.f;
-        if (lane >= 2 && lane < (2 << min(r, 5))) va = tree[(node << lj) + (lane - (1 << lj))];
-        if (r == 6) vb = tree[(node << 6) + lane];
-        int cur = 1;  // local heap index
-        for (int t = 0; t < r; ++t) {
-            const int c = 2 * cur;  // left child
-            const float left = c < 64 ? __shfl(va, c, 64) : __shfl(vb, c - 64, 64);
-            if (z < left) {
-                cur = c;
-            } else {
-                z = z - left;
-                cur = c + 1;
-            }
-        }
-        node = (node << r) + (cur - (1 << r));
-        done += r;
-    }
-    long slot = node - A.L;
-    if (slot > A.size - 1) slot = A.size - 1;
-    return slot;
-}
-
-// What one lane writes for draw j once the slot is known: index, raw weight, transition data.
-__device__ __forceinline__ void per_sample_emit(const SampleArgs &A, int j, long slot, float total)
-{
-    const double P = (double)A.tree[A.L + slot] / (double)total;
-    A.idx[j] = (int32_t)slot;
-    A.is_w[j] = (float)pow((double)A.size * P, -(double)A.beta);
-    if (A.G.a) {
-        A.G.a[j] = A.G.meta_a[slot];
-        A.G.r[j] = A.G.meta_r[slot];
-        A.G.done[j] = A.G.meta_done[slot];
-    }
-}
 
 __global__ __launch_bounds__(256) void k_per_sample(SampleArgs A)
 {
