@@ -324,7 +324,7 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
         int tiles = build(A, BM, 81, [&](int i) { return (const void *)(act1 + row0[i] * net::A1); },
                           [&](int) { return (long)net::A1; }, net::C2W, net::C2B, act2, net::A2, true);
         A.klen = GConv2::K; A.split_stride = 0; A.scale = 1.0f;
-        if (small) launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 32, 64, 4><<<dim3(tiles, 1, 1), 512, 0, st>>>(A); });
+        if (small) launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 32, 32, 4><<<dim3(tiles, 2, 1), 256, 0, st>>>(A); });
         else launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 64, 64><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
     }
     {  // conv3
@@ -333,7 +333,7 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
         int tiles = build(A, BM, 49, [&](int i) { return (const void *)(act2 + row0[i] * net::A2); },
                           [&](int) { return (long)net::A2; }, net::C3W, net::C3B, act3, net::A3, true);
         A.klen = GConv3::K; A.split_stride = 0; A.scale = 1.0f;
-        if (small) launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 32, 64, 3><<<dim3(tiles, 1, 1), 384, 0, st>>>(A); });
+        if (small) launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 32, 32, 3><<<dim3(tiles, 2, 1), 192, 0, st>>>(A); });
         else launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 64, 64><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
     }
     {  // fc1: raw partial sums per reduction split; the head kernels finish it
@@ -563,7 +563,7 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     {
         DgradArgs D{d3, c->theta + net::C3W, act2, d2, B};
         long M = (long)B * 81;
-        if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 64, 3><<<dim3((M + 31) / 32, 1, 1), 384, 0, st>>>(D); });
+        if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 32, 6><<<dim3((M + 31) / 32, 2, 1), 384, 0, st>>>(D); });
         else launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_b, st, sd);
     }
