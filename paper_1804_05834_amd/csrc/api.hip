@@ -379,7 +379,7 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         return tile;
     };
 
-    {  // conv1: persistent workgroups, frames staged in LDS (read from the ring in ring mode)
+    {  // conv1: persistent waves, strips of the frames staged in LDS (read from the ring in ring mode)
         c1::FwdArgs A{};
         A.nseg = npass;
         int first = 0;
@@ -395,8 +395,9 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         }
         for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
         A.total = first;
-        const int grid = std::min(first, c->num_cu);  // one persistent workgroup per CU measured fastest
-        launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd<<<dim3(grid), 512, 0, st>>>(A); });
+        // one wave per strip of a sample, four waves per workgroup, two workgroups resident per CU
+        const int grid = std::min((first * c1::UNITS + 3) / 4, 2 * c->num_cu);
+        launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd<<<dim3(grid), 256, 0, st>>>(A); });
     }
     {  // 8 waves per workgroup, one 32x32 block each: the short reduction loops of these layers
        // are latency-bound, and more resident waves hide more of it than bigger per-wave tiles

@@ -61,6 +61,17 @@ __device__ __forceinline__ uint32_t pack2_u8(uint32_t lo, uint32_t hi)
 {
     return (__float_as_uint((float)lo) >> 16) | (__float_as_uint((float)hi) & 0xFFFF0000u);
 }
+// 8 pixels in two words -> 8 bf16 (exact): the upper halves of the floats, merged pairwise by a byte permute
+__device__ __forceinline__ uint4 cvt8_u8(uint32_t a, uint32_t b)
+{
+    auto pk = [](float lo, float hi) { return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u); };
+    uint4 o;
+    o.x = pk((float)(a & 0xFFu), (float)((a >> 8) & 0xFFu));
+    o.y = pk((float)((a >> 16) & 0xFFu), (float)(a >> 24));
+    o.z = pk((float)(b & 0xFFu), (float)((b >> 8) & 0xFFu));
+    o.w = pk((float)((b >> 16) & 0xFFu), (float)(b >> 24));
+    return o;
+}
 __device__ __forceinline__ uint4 ld8(const uint8_t *p)  // 8 pixels -> 8 bf16 (exact)
 {
     uint32_t a = *reinterpret_cast<const uint32_t *>(p), b = *reinterpret_cast<const uint32_t *>(p + 4);
@@ -658,130 +669,194 @@ struct FwdArgs {
     int total;          // samples of all segments
 };
 
-// One output block of 32 pixels x 32 channels: bias, 1/255, ReLU, bf16, 32 contiguous bytes per lane.
-// acc[4g + j] = Y[pixel li of the block][channel 16h + 4g + j]
-__device__ __forceinline__ void conv1_store(const v16f &acc, const v4f (&bias)[4], bf16_t *y, int m, int h)
+// Forward pass, one WAVE per unit of work and no workgroup barrier anywhere.
+//
+// A unit is a strip of 4 output rows of one sample: 80 output pixels = 16 lanes x 5 consecutive
+// pixels of one output row.  Its receptive field, input rows 16s .. 16s+19 of the four frames
+// (13,440 bytes as bf16), sits in a part of LDS that belongs to this wave alone, so staging,
+// matrix instructions and stores of different waves never wait for each other.
+//
+// v_mfma_f32_16x16x32_bf16, weights as the a-operand (row r = channel 8*(r/4) + 4*hh + r%4 for
+// channel half hh), pixels as the b-operand (column n = lane % 16: output row n/4 of the strip,
+// pixels 5*(n%4) .. +4 of that row).  Reduction step (c, xh) covers frame c, all 8 kernel rows,
+// kernel columns 4xh .. 4xh+3: lane group kg = lane/16 holds kernel rows 2kg and 2kg+1, four
+// columns each.  With that split the operand of pixel j at step (c, xh) is the "quad"
+//   q[c][j + xh] = { input row 2kg, columns 4(j+xh)..+3 ; input row 2kg+1, same columns },
+// i.e. six quads per frame serve all five pixels and both column halves, each fetched by ONE
+// two-address LDS read, and every input element is read from LDS 2.4 times instead of 4.
+// The result of lane (n, g = lane/16) is channels 8g .. 8g+7 of its pixels: 16 bytes per store.
+constexpr int SROWS = 20;               // input rows per strip
+constexpr int STRIP = 4 * SROWS * 84;   // elements per strip (four frames)
+constexpr int UNITS = 5;                // strips per sample
+constexpr int CHUNKS = STRIP / 16;      // 16-byte pieces of a strip's pixels: 420
+
+__device__ __forceinline__ v4f mfma16(v8bf a, v8bf b, v4f c)
 {
-    constexpr float sc = 1.0f / 255.0f;
-    uint2 o[4];
-#pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-        const v4f bv = bias[g4];
-        o[g4] = pack4(fmaxf(acc[4 * g4] * sc + bv.x, 0.f), fmaxf(acc[4 * g4 + 1] * sc + bv.y, 0.f),
-                      fmaxf(acc[4 * g4 + 2] * sc + bv.z, 0.f), fmaxf(acc[4 * g4 + 3] * sc + bv.w, 0.f));
-    }
-    uint4 *d = reinterpret_cast<uint4 *>(y + m * 32 + 16 * h);
-    d[0] = uint4{o[0].x, o[0].y, o[1].x, o[1].y};
-    d[1] = uint4{o[2].x, o[2].y, o[3].x, o[3].y};
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// Weight fragments for the 16 reduction steps.  MFMA row i carries output channel
-// ch(i) = 16*((i>>2)&1) + 4*(i>>3) + (i&3), so that the 16 results of a lane (rows 8g + 4h + j)
-// are the 16 consecutive channels 16h + 4g + j of its pixel.
-__device__ __forceinline__ void conv1_weights(v8bf (&wb)[16], const bf16_t *w, int li, int h)
-{
-    const int ch = 16 * ((li >> 2) & 1) + 4 * (li >> 3) + (li & 3);
-#pragma unroll
-    for (int t = 0; t < 16; ++t) wb[t] = __builtin_bit_cast(v8bf, ld8(w + ch * 256 + 16 * t + 8 * h));
-}
+struct StripRaw { uint4 raw[7]; };      // this lane's pieces lane, lane + 64, ... of a strip
+struct StripOff { uint32_t off[7]; };   // their byte offsets within four frames that are contiguous in memory
 
-// The MFMA loop of one sample for one wave: row blocks `wave` and (TWO) `wave + 8` of the 13
-// blocks of 32 output pixels, 16 reduction steps each.  Straight-line code, no lane-dependent
-// control flow, and the im2col fragments are fetched from LDS one group of four steps ahead
-// of the MFMAs that consume them, so the LDS latency is hidden behind the matrix unit.
-template <bool TWO>
-__device__ __forceinline__ void conv1_blocks(const bf16_t *xin, const v8bf (&wa)[16], const v4f (&bias)[4],
-                                             bf16_t *y, int wave, int li, int h)
+// The pixels of strip `strip` of sample g.  Four frames of a ring sample are contiguous unless
+// they straddle the end of the ring (or its start, for the first slots); explicit states always are.
+__device__ __forceinline__ void strip_load(StripRaw &R, const Src &S, int g, int slot_g, int strip, int lane,
+                                           const StripOff &O)
 {
-    const int m0 = wave * 32 + li;
-    int m1 = (wave + 8) * 32 + li;
-    if (m1 > 399) m1 = 399;  // rows past the end read a valid pixel and are not stored
-    const bf16_t *px0 = xin + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20) + h * 84;
-    const bf16_t *px1 = xin + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20) + h * 84;
-    auto frag = [&](const bf16_t *px, int t) {
-        // k = 16t + 8h: channel t/4, kernel row (2t + h) % 8; 16 bytes at an 8-byte-aligned address
-        const uint2 *q = reinterpret_cast<const uint2 *>(px + (t >> 2) * FR + ((2 * t) & 7) * 84);
-        return __builtin_bit_cast(v8bf, uint4{q[0].x, q[0].y, q[1].x, q[1].y});
-    };
-    v16f acc0 = {0}, acc1 = {0};
-    v8bf f0[2][4], f1[2][4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        f0[0][j] = frag(px0, j);
-        if constexpr (TWO) f1[0][j] = frag(px1, j);
+    const uint8_t *base;
+    bool contig = true;
+    long b = 0;
+    if (!S.idx) {
+        base = S.x + (long)g * S.xs;
+    } else {
+        long i = __builtin_amdgcn_readfirstlane(slot_g);
+        i = i < 0 ? 0 : (i >= S.cap ? S.cap - 1 : i);
+        b = i - 3 + S.shift;                      // slot of the first frame, within [-3, cap - 2]
+        contig = b >= 0 && b + 3 < S.cap;
+        base = S.x + b * FR;
     }
+    if (contig) {   // one scalar base, per-lane offsets that never change
+        base += strip * (16 * 84);
 #pragma unroll
-    for (int grp = 0; grp < 4; ++grp) {
-        const int cur = grp & 1, nxt = cur ^ 1;
-        if (grp < 3) {
+        for (int i = 0; i < 7; ++i)
+            if (i < 6 || lane < CHUNKS - 384) R.raw[i] = *reinterpret_cast<const uint4 *>(base + O.off[i]);
+    } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                f0[nxt][j] = frag(px0, 4 * (grp + 1) + j);
-                if constexpr (TWO) f1[nxt][j] = frag(px1, 4 * (grp + 1) + j);
+        for (int i = 0; i < 7; ++i) {
+            const int t = lane + 64 * i;
+            if (t < CHUNKS) {
+                long slot = b + t / (CHUNKS / 4);
+                if (slot < 0) slot += S.cap;
+                if (slot >= S.cap) slot -= S.cap;
+                R.raw[i] = *reinterpret_cast<const uint4 *>(S.x + slot * FR + strip * (16 * 84) + (t % (CHUNKS / 4)) * 16);
             }
         }
-        // the scheduler would otherwise sink every read to just above its MFMA, which leaves
-        // one LDS access in flight per wave and the matrix unit waiting on LDS latency
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            acc0 = mfma(wa[4 * grp + j], f0[cur][j], acc0);  // transposed tile
-            if constexpr (TWO) acc1 = mfma(wa[4 * grp + j], f1[cur][j], acc1);
-        }
-        __builtin_amdgcn_sched_barrier(0);
     }
-    const int mm = (wave + 8) * 32 + li;
-    conv1_store(acc0, bias, y, m0, h);
-    if (TWO && mm < 400) conv1_store(acc1, bias, y, mm, h);
 }
-
-// The samples [g0, g1) of one segment.  Weights and bias stay in registers; the frames of the
-// next sample are loaded while the current one is computed, and the ring slot of the sample
-// after that is already on its way.
-__device__ __forceinline__ void conv1_fwd_range(const FwdSeg &S, int g0, int g1, bf16_t *xin, int tid)
+// 16 pixels -> 16 bf16 -> two 16-byte LDS stores; consecutive lanes write consecutive 32 bytes
+__device__ __forceinline__ void strip_store(bf16_t *xs, const StripRaw &R, int lane)
 {
-    const int lane = tid & 63, li = lane & 31, h = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: the block choice below is a uniform branch
-    Staged<512, 4> R;
-    stage_load<512, 4>(R, S.src, g0, sample_slot(S.src, g0), 0, tid);
-    int slot_next = g0 + 1 < g1 ? sample_slot(S.src, g0 + 1) : 0;
-    v8bf wa[16];
-    conv1_weights(wa, S.w, li, h);
-    v4f bias[4];  // this lane's 16 channels: 16h + 4g + j
 #pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) bias[g4] = *reinterpret_cast<const v4f *>(S.bias + 16 * h + 4 * g4);
-    // Everything requested so far has arrived before the loop starts.  Without this the first
-    // MFMA of every sample waits for "all outstanding vector loads" on account of the weight
-    // registers, and that includes the next sample's frames requested a moment earlier.
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    for (int g = g0; g < g1; ++g) {
-        sync_lds();  // the previous sample is no longer read
-        stage_store<512, 4>(xin, R, tid);
-        sync_lds();
-        if (g + 1 < g1) {
-            stage_load<512, 4>(R, S.src, g + 1, slot_next, 0, tid);
-            if (g + 2 < g1) slot_next = sample_slot(S.src, g + 2);
+    for (int i = 0; i < 7; ++i) {
+        const int t = lane + 64 * i;
+        if (t < CHUNKS) {
+            const uint4 r = R.raw[i];
+            uint4 *d = reinterpret_cast<uint4 *>(xs + t * 16);
+            d[0] = cvt8_u8(r.x, r.y);
+            d[1] = cvt8_u8(r.z, r.w);
         }
-        // 13 blocks of 32 output pixels (the last one half empty): waves 0-4 take two, 5-7 one
-        bf16_t *y = S.y + (long)g * (400 * 32);
-        if (wave + 8 < 13) conv1_blocks<true>(xin, wa, bias, y, wave, li, h);
-        else conv1_blocks<false>(xin, wa, bias, y, wave, li, h);
     }
 }
 
-// Persistent workgroups: workgroup b owns samples [b*total/G, (b+1)*total/G) of the launch-wide
-// list (segment after segment).
-__global__ __launch_bounds__(512) void k_conv1_fwd(FwdArgs A)
+// Units [u0, u1) of one segment (unit = UNITS * sample + strip), processed by one wave.  Weights and
+// bias stay in registers; the pixels of the next unit are loaded while the current one is computed,
+// and the ring slot of the unit after that is already on its way.
+__device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1, bf16_t *xs, int lane)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t xin[XIN];
-    const int g0 = (int)((long)blockIdx.x * A.total / gridDim.x);
-    const int g1 = (int)((long)(blockIdx.x + 1) * A.total / gridDim.x);
+    const int n = lane & 15, kg = lane >> 4, oyl = n >> 2, q = n & 3;
+    StripOff O;
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+        const int t = lane + 64 * i;
+        O.off[i] = t < CHUNKS ? (t / (CHUNKS / 4)) * FR + (t % (CHUNKS / 4)) * 16 : 0;
+    }
+    StripRaw R;
+    int g = u0 / UNITS, strip = u0 % UNITS;   // current unit
+    int gn = g, sn = strip + 1;               // next unit
+    if (sn == UNITS) { sn = 0; ++gn; }
+    strip_load(R, S.src, g, sample_slot(S.src, g), strip, lane, O);
+    int slot_next = u0 + 1 < u1 ? sample_slot(S.src, gn) : 0;
+    v8bf wa[8][2];   // [2c + xh][channel half]
+#pragma unroll
+    for (int st = 0; st < 8; ++st)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int ch = 8 * (n >> 2) + 4 * hh + (n & 3);
+            const bf16_t *p = S.w + ch * 256 + (st >> 1) * 64 + (2 * kg) * 8 + 4 * (st & 1);
+            const uint2 lo = *reinterpret_cast<const uint2 *>(p), hi = *reinterpret_cast<const uint2 *>(p + 8);
+            wa[st][hh] = __builtin_bit_cast(v8bf, uint4{lo.x, lo.y, hi.x, hi.y});
+        }
+    const v4f b0 = *reinterpret_cast<const v4f *>(S.bias + 8 * kg), b1 = *reinterpret_cast<const v4f *>(S.bias + 8 * kg + 4);
+    // LDS byte address of this lane's first quad of frame 0; a frame is SROWS * 84 elements further
+    const uint32_t px = (uint32_t)(uintptr_t)(xs + (4 * oyl + 2 * kg) * 84 + 20 * q);
+    const uint32_t yoff = ((20 * oyl + 5 * q) * 32 + 8 * kg) * 2;   // bytes, within the unit's 80 output pixels
+    for (int u = u0; u < u1; ++u) {
+        strip_store(xs, R, lane);   // LDS operations of one wave complete in order: no wait needed around this
+        if (u + 1 < u1) {
+            strip_load(R, S.src, gn, slot_next, sn, lane, O);
+            int g2 = gn;
+            if (sn + 1 == UNITS) ++g2;
+            if (u + 2 < u1) slot_next = sample_slot(S.src, g2);
+        }
+        struct Quads { uint4 q[6]; };
+        // The compiler would pair neighbouring columns of ONE row into a two-address read and then
+        // shuffle registers; the pairing wanted here is the same columns of TWO rows (21 eight-byte
+        // steps apart), which lands each quad in the four consecutive registers the MFMA reads.
+        // These reads are invisible to the compiler's wait counting: the waits are written out.
+        auto quads = [&](int c) {
+            typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+            const uint32_t addr = px + c * (SROWS * 84 * 2);
+            Quads Q;
+#define C1_RD2(JJ) { v4u t; asm volatile("ds_read2_b64 %0, %1 offset0:%2 offset1:%3" : "=v"(t) : "v"(addr), "n"(JJ), "n"(JJ + 21)); Q.q[JJ] = uint4{t.x, t.y, t.z, t.w}; }
+            C1_RD2(0) C1_RD2(1) C1_RD2(2) C1_RD2(3) C1_RD2(4) C1_RD2(5)
+#undef C1_RD2
+            return Q;
+        };
+        v4f acc[5][2];
+#pragma unroll
+        for (int j = 0; j < 5; ++j) acc[j][0] = acc[j][1] = v4f{0, 0, 0, 0};
+        Quads cur = quads(0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            Quads nxt = cur;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // `cur` has arrived
+            if (c < 3) nxt = quads(c + 1);                        // in flight during the 20 MFMAs below
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int xh = 0; xh < 2; ++xh)
+#pragma unroll
+                for (int j = 0; j < 5; ++j) {
+                    const v8bf b = __builtin_bit_cast(v8bf, cur.q[j + xh]);
+                    acc[j][0] = mfma16(wa[2 * c + xh][0], b, acc[j][0]);
+                    acc[j][1] = mfma16(wa[2 * c + xh][1], b, acc[j][1]);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            cur = nxt;
+        }
+        // bias, 1/255, ReLU, bf16; the 80 pixels of a unit are contiguous in y
+        uint8_t *yb = reinterpret_cast<uint8_t *>(S.y) + ((long)g * 400 + 80 * strip) * 64;
+        constexpr float sc = 1.0f / 255.0f;
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const v4f a0 = acc[j][0], a1 = acc[j][1];
+            const uint2 lo = pack4(fmaxf(a0.x * sc + b0.x, 0.f), fmaxf(a0.y * sc + b0.y, 0.f),
+                                   fmaxf(a0.z * sc + b0.z, 0.f), fmaxf(a0.w * sc + b0.w, 0.f));
+            const uint2 hi = pack4(fmaxf(a1.x * sc + b1.x, 0.f), fmaxf(a1.y * sc + b1.y, 0.f),
+                                   fmaxf(a1.z * sc + b1.z, 0.f), fmaxf(a1.w * sc + b1.w, 0.f));
+            *reinterpret_cast<uint4 *>(yb + yoff + j * 64) = uint4{lo.x, lo.y, hi.x, hi.y};
+        }
+        g = gn; strip = sn;
+        if (++sn == UNITS) { sn = 0; ++gn; }
+    }
+}
+
+// Wave w of the launch owns units [w*U/W, (w+1)*U/W) of the launch-wide list (segment after segment,
+// U = UNITS * samples, W = 4 * gridDim.x).  Two workgroups of four waves fit one CU.
+__global__ __launch_bounds__(256, 2) void k_conv1_fwd(FwdArgs A)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t lds[4 * STRIP];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    bf16_t *xs = lds + wave * STRIP;
+    const long nw = (long)gridDim.x * 4, wid = (long)blockIdx.x * 4 + wave, units = (long)A.total * UNITS;
+    const int u0 = (int)(wid * units / nw), u1 = (int)((wid + 1) * units / nw);
     for (int s = 0; s < A.nseg; ++s) {
         FwdSeg S = A.seg[0];
         if (s == 1) S = A.seg[1];
         if (s == 2) S = A.seg[2];
-        const int lo = max(g0, S.first) - S.first, hi = min(g1, S.first + S.n) - S.first;
-        if (lo < hi) conv1_fwd_range(S, lo, hi, xin, threadIdx.x);
+        const int lo = max(u0, UNITS * S.first) - UNITS * S.first;
+        const int hi = min(u1, UNITS * (S.first + S.n)) - UNITS * S.first;
+        if (lo < hi) conv1_fwd_units(S, lo, hi, xs, lane);
     }
 }
 
