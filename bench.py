@@ -52,6 +52,28 @@ def bytes_per_launch(B, n_params, bf16, levels=20):
     }
 
 
+def gemm_bytes_per_launch(B, R, bf16):
+    """Algorithmic HBM bytes (read + write) of each GEMM kernel: every operand once, no split
+    partial sums, the five distinct ring frames of a transition once for the three forward passes."""
+    e = 2 if bf16 else 4                       # activation / shadow-weight element
+    a1, a2, a3, hid = 400 * 32 * e, 81 * 64 * e, 49 * 64 * e, 512 * 4
+    w1, w2, w3, wf = 32 * 256 * e, 64 * 512 * e, 64 * 576 * e, 512 * 3136 * e
+    frames = B * 5 * 7056 if bf16 else 3 * B * 4 * 7056   # fp32 path reads the gathered stacks
+    return {
+        "conv1_fwd": frames + w1 + 3 * B * a1,
+        "conv2_fwd": 3 * B * (a1 + a2) + w2,
+        "conv3_fwd": 3 * B * (a2 + a3) + w3,
+        "fc1_fwd": 3 * B * (a3 + hid) + wf,
+        "fc1_dgrad": B * (512 * e + 2 * a3) + wf,           # dH, ReLU mask, dX
+        "conv3_dgrad": B * (a3 + 2 * a2) + w3,
+        "conv2_dgrad": B * (a2 + 2 * a1) + w2,
+        "conv1_wgrad": B * (4 * 7056 + a1) + 32 * 256 * 4,
+        "conv2_wgrad": B * (a1 + a2) + 64 * 512 * 4,
+        "conv3_wgrad": B * (a2 + a3) + 64 * 576 * 4,
+        "fc1_wgrad": B * (a3 + 512 * e) + 512 * 3136 * 4,
+    }
+
+
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each
 # scaled by what the same counter shows for the ring-fill copy kernel of known size in the same
 # run (fetch x1.949, write x0.9875).  Keyed by (kernel, batch, precision); the figures and the
@@ -236,10 +258,15 @@ def kernel_table(prof, B, R, n_params, precision):
     """Per kernel: live HIP-event average duration, the roofline that bounds it, what it achieves."""
     fl = flops_per_launch(B, R)
     by = bytes_per_launch(B, n_params, precision == "bf16")
+    gb = gemm_bytes_per_launch(B, R, precision == "bf16")
     out = {}
     for k, (cnt, tot_ms) in prof.items():
         avg_s = tot_ms / cnt / 1e3
-        if k in fl:
+        if k in fl and k in gb and gb[k] / HBM_PEAK > fl[k] / PEAK[precision]:
+            # a GEMM kernel whose operands take longer to stream at the HBM peak than its flops
+            # take at the MFMA peak: HBM is the roof that binds
+            e = {"bound": "hbm", "achieved": gb[k] / avg_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
+        elif k in fl:
             e = {"bound": "mfma", "achieved": fl[k] / avg_s / 1e12, "peak": PEAK[precision] / 1e12, "unit": "TFLOP/s"}
         else:
             e = {"bound": "hbm", "achieved": by.get(k, 0) / avg_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}

@@ -492,6 +492,30 @@ def test_replay_train_step_full_size_bf16(dq, orc):
     m.close()
 
 
+def test_replay_train_step_wrapping_ring_bf16(dq, orc):
+    """bf16 step over a 40-slot ring with batch 96: most slots are drawn, so the four-frame windows
+    of s and s' that straddle the end (and the start) of the ring are read by the conv1 kernels'
+    non-contiguous path, next to windows that are contiguous."""
+    print("case replay step wrapping ring bf16", flush=True)
+    cap = 40
+    m = dq.Dqn(dq.make_config(replay_capacity=cap, max_batch=96, precision=1, **CONFIGS["dueling_ddqn"]))
+    _fill_replay(m, cap, K=18, chunk=cap)
+    for seed in (21, 22, 23):
+        try:
+            e = _replay_step_case(dq, orc, cap, 96, m=m, draw_seed=seed, tol=TOL_BF16)
+            break
+        except AssertionError as err:   # a draw on a bucket boundary: another seed
+            if "bucket boundary" not in str(err):
+                raise
+    else:
+        raise AssertionError("three draw seeds in a row hit a bucket boundary")
+    m.per_fill(synth.exp_priorities(9, cap, "cuda"))         # the tree the step drew from
+    idx = m.per_sample(96, 0.4, seed)[0].cpu().numpy()       # same tree, same seed: the step's draw
+    assert (idx < 3).any() and (idx == cap - 1).any(), "the draw must include wrapping windows"
+    print("  worst:", sorted(e.items(), key=lambda kv: -kv[1])[:4], flush=True)
+    m.close()
+
+
 # ------------------------------------------------------------------ error paths
 def test_store_path_parity(dq, orc):
     """Alg.2 store line: chunks of time steps appended at the cursor, every tree node compared
