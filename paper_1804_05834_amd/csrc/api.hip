@@ -399,22 +399,28 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         const int grid = std::min((first * c1::UNITS + 3) / 4, 2 * c->num_cu);
         launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd<<<dim3(grid), 256, 0, st>>>(A); });
     }
-    {  // 8 waves per workgroup, one 32x32 block each: the short reduction loops of these layers
-       // are latency-bound, and more resident waves hide more of it than bigger per-wave tiles
-        FwdArgs A{};
-        int tiles = build(A, 128, 81, [&](int i) { return (const void *)(act1 + row0[i] * net::A1); },
-                          [&](int) { return (long)net::A1; }, net::C2W, net::C2B,
-                          [&](int i) { return (void *)(act2 + row0[i] * net::A2); }, true);
-        A.klen = GConv2::K; A.split_stride = 0; A.scale = 1.0f;
-        launch(c, "conv2_fwd", st, [&] { k_fwd<GConv2, 128, 64, 1, 1, false><<<dim3(tiles, 1, 1), 512, 0, st>>>(A); });
+    // conv2, conv3: persistent workgroups that keep the weights in registers and take one sample at a time
+    auto per_sample = [&](ps::Args &A, const bf16_t *x, long xs, int64_t woff, int64_t boff, bf16_t *y, long ys) {
+        A.nseg = npass;
+        int first = 0;
+        for (int i = 0; i < npass; ++i) {
+            A.seg[i] = ps::Seg{x + row0[i] * xs, shadow_of(c, pass[i].net) + woff, theta_of(c, pass[i].net) + boff,
+                               y + row0[i] * ys, pass[i].n, first};
+            first += pass[i].n;
+        }
+        for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
+        A.total = first;
+        return std::min(first, 2 * c->num_cu);
+    };
+    {
+        ps::Args A{};
+        const int grid = per_sample(A, act1, net::A1, net::C2W, net::C2B, act2, net::A2);
+        launch(c, "conv2_fwd", st, [&] { ps::k_conv_fwd_ps<ps::G2><<<dim3(grid), 256, 0, st>>>(A); });
     }
     {
-        FwdArgs A{};
-        int tiles = build(A, 128, 49, [&](int i) { return (const void *)(act2 + row0[i] * net::A2); },
-                          [&](int) { return (long)net::A2; }, net::C3W, net::C3B,
-                          [&](int i) { return (void *)(act3 + row0[i] * net::A3); }, true);
-        A.klen = GConv3::K; A.split_stride = 0; A.scale = 1.0f;
-        launch(c, "conv3_fwd", st, [&] { k_fwd<GConv3, 128, 64, 1, 1, false><<<dim3(tiles, 1, 1), 512, 0, st>>>(A); });
+        ps::Args A{};
+        const int grid = per_sample(A, act2, net::A2, net::C3W, net::C3B, act3, net::A3);
+        launch(c, "conv3_fwd", st, [&] { ps::k_conv_fwd_ps<ps::G3><<<dim3(grid), 256, 0, st>>>(A); });
     }
     {
         FwdArgs A{};

@@ -42,6 +42,13 @@ __device__ __forceinline__ v16f mfma(v8bf a, v8bf b, v16f c)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// v_mfma_f32_16x16x32_bf16 (lane = 16*g + i): a-operand A[i][8g..8g+7], b-operand B[8g..8g+7][i],
+// result acc[j] = D[4g + j][i]
+__device__ __forceinline__ v4f mfma16(v8bf a, v8bf b, v4f c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
 __device__ __forceinline__ bf16_t f2bf(float f)  // round to nearest even
 {
     return __builtin_bit_cast(bf16_t, (__bf16)f);
@@ -690,11 +697,6 @@ constexpr int STRIP = 4 * SROWS * 84;   // elements per strip (four frames)
 constexpr int UNITS = 5;                // strips per sample
 constexpr int CHUNKS = STRIP / 16;      // 16-byte pieces of a strip's pixels: 420
 
-__device__ __forceinline__ v4f mfma16(v8bf a, v8bf b, v4f c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
 struct StripRaw { uint4 raw[7]; };      // this lane's pieces lane, lane + 64, ... of a strip
 struct StripOff { uint32_t off[7]; };   // their byte offsets within four frames that are contiguous in memory
 
@@ -947,4 +949,184 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
     }
 }
 }  // namespace c1
+
+// ===========================================================================
+// conv2 and conv3 forward, one sample per workgroup at a time ("ps" = per sample).
+//
+// The generic kernels above cut the batch into row tiles and walk the reduction in stages with
+// two barriers each; for these two layers a stage holds a handful of MFMAs, so the walk is a
+// chain of latencies.  Here a persistent workgroup of four waves keeps its share of the WEIGHTS in
+// registers (32 output channels x the whole reduction per wave), copies one sample's input
+// (25.6 KB / 10.4 KB) into LDS with one barrier per sample, double-buffered, and every b-operand
+// is a single 16-byte LDS read at base + immediate offset: no index arithmetic in the loop.
+//
+// v_mfma_f32_16x16x32_bf16, weights as the a-operand (row r = channel 32hh + 8(r/4) + 4cb + r%4 for
+// the wave's channel half hh and channel block cb), output positions as the b-operand columns; one
+// reduction step is one kernel tap x 32 input channels, lane group kg = lane/16 takes 8 of them.
+// Wave (ph, hh) owns half of the position blocks and half of the channels; the result of lane
+// (n, g = lane/16) is channels 32hh + 8g .. +7 of its positions: 16 bytes per store.
+//
+// LDS layout of a sample: pixels in raster order, padded so that the pixels which the 16 lanes of
+// one lane group read (two apart for the stride-2 layer, neighbours for the stride-1 layer) start
+// 144 bytes apart, i.e. one 16-byte bank group further each: conflict-free.
+// ===========================================================================
+namespace ps {
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a native vector: stays in registers across barriers
+
+struct Seg {
+    const bf16_t *x;    // [n][positions in][channels in]
+    const bf16_t *w;    // [64][K] bf16, K = (tap, channel)
+    const float *bias;  // [64]
+    bf16_t *y;          // [n][positions out][64]
+    int n;              // samples
+    int first;          // index of the segment's first sample in the launch-wide sample list
+};
+struct Args {
+    Seg seg[3];
+    int nseg;
+    int total;
+};
+
+// G: layer geometry.  IN_PIX pixels of IN_CH channels in, OUT x OUT positions out, TAPS x TAPS
+// kernel with stride STRIDE, IN_W pixels per input row.
+struct G2 { static constexpr int IN_PIX = 400, IN_CH = 32, IN_W = 20, OUT = 9, TAPS = 4, STRIDE = 2; };
+struct G3 { static constexpr int IN_PIX = 81, IN_CH = 64, IN_W = 9, OUT = 7, TAPS = 3, STRIDE = 1; };
+
+template <class G> struct Shape {
+    static constexpr int PB = G::IN_CH * 2;                        // bytes per pixel
+    static constexpr int GROUP = 128 / PB;                         // pixels per 128-byte group: 2 / 1
+    static constexpr int GB = 144;                                 // LDS bytes per group (128 + 16)
+    static constexpr int SAMPLE = (G::IN_PIX / GROUP + (G::IN_PIX % GROUP ? 1 : 0)) * GB;
+    static constexpr int K = G::TAPS * G::TAPS * G::IN_CH;
+    static constexpr int STEPS = K / 32;                           // reduction steps: 16 / 18
+    static constexpr int SPT = G::IN_CH / 32;                      // steps per tap: 1 / 2
+    static constexpr int WROW = K * 2 + 16;                        // LDS bytes per weight row in transit
+    static constexpr int NPOS = G::OUT * G::OUT;                   // 81 / 49
+    static constexpr int NBLK = (NPOS + 31) / 32;                  // position blocks per wave: 3 / 2
+    static constexpr int CHUNKS = G::IN_PIX * PB / 16;             // 16-byte pieces of a sample: 1600 / 648
+    static constexpr int NLD = (CHUNKS + 255) / 256;               // pieces per thread: 7 / 3
+    static constexpr int WCH = 32 * K * 2 / 16 / 256;              // weight pieces per thread and half: 8 / 9
+    static constexpr int LDS = 32 * WROW > 2 * SAMPLE ? 32 * WROW : 2 * SAMPLE;
+    // LDS byte offset of 16-byte piece c of pixel q
+    static __device__ __forceinline__ uint32_t at(int q, int c) { return (q / GROUP) * GB + (q % GROUP) * PB + c * 16; }
+};
+
+template <class G> struct Raw { u32x4 r[Shape<G>::NLD]; };
+template <class G>
+__device__ __forceinline__ void load_sample(Raw<G> &R, const bf16_t *x, int tid)
+{
+    using S = Shape<G>;
+    const u32x4 *p = reinterpret_cast<const u32x4 *>(x);
+#pragma unroll
+    for (int i = 0; i < S::NLD; ++i) { const int t = tid + 256 * i; R.r[i] = p[t < S::CHUNKS ? t : S::CHUNKS - 1]; }
+}
+template <class G>
+__device__ __forceinline__ void store_sample(uint8_t *buf, const Raw<G> &R, int tid)
+{
+    using S = Shape<G>;
+    constexpr int CPP = S::PB / 16;   // pieces per pixel
+#pragma unroll
+    for (int i = 0; i < S::NLD; ++i) {
+        const int t = tid + 256 * i;
+        if (t < S::CHUNKS) *reinterpret_cast<u32x4 *>(buf + S::at(t / CPP, t % CPP)) = R.r[i];
+    }
+}
+
+// Samples [g0, g1) of one segment.
+template <class G>
+__device__ __forceinline__ void run(const Seg &S, int g0, int g1, uint8_t *lds, int tid)
+{
+    using H = Shape<G>;
+    const int lane = tid & 63, n = lane & 15, kg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), ph = wave & 1, hh = wave >> 1;
+    Raw<G> R;
+    load_sample<G>(R, S.x + (long)g0 * (G::IN_PIX * G::IN_CH), tid);   // on its way while the weights are fetched
+    // The workgroup fetches each half of the weight matrix once, coalesced, into LDS; the two waves
+    // that own the half pick their fragments from there.
+    v8bf wa[H::STEPS][2];
+    for (int half = 0; half < 2; ++half) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(S.w + half * 32 * H::K);
+        sync_lds();   // LDS is free (the previous segment's last sample has been read)
+#pragma unroll
+        for (int i = 0; i < H::WCH; ++i) {
+            const int c = tid + 256 * i;   // row c / (K/8), piece c % (K/8)
+            *reinterpret_cast<u32x4 *>(lds + (c / (H::K / 8)) * H::WROW + (c % (H::K / 8)) * 16) = src[c];
+        }
+        sync_lds();
+        if (hh == half) {
+#pragma unroll
+            for (int st = 0; st < H::STEPS; ++st)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) {
+                    const int chl = 8 * (n >> 2) + 4 * cb + (n & 3);
+                    wa[st][cb] = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(lds + chl * H::WROW + st * 64 + kg * 16));
+                }
+        }
+    }
+    const v4f b0 = *reinterpret_cast<const v4f *>(S.bias + 32 * hh + 8 * kg);
+    const v4f b1 = *reinterpret_cast<const v4f *>(S.bias + 32 * hh + 8 * kg + 4);
+    // this lane's positions and the LDS offset of their first tap; positions past the end read a
+    // valid pixel and are not stored
+    uint32_t base[H::NBLK];
+    int pos[H::NBLK];
+#pragma unroll
+    for (int b = 0; b < H::NBLK; ++b) {
+        int p = 16 * (H::NBLK * ph + b) + n;
+        pos[b] = p;
+        if (p > H::NPOS - 1) p = H::NPOS - 1;
+        base[b] = H::at(G::STRIDE * (G::IN_W * (p / G::OUT) + (p % G::OUT)), kg);
+    }
+    sync_lds();   // the weight rows have been read
+    store_sample<G>(lds + (g0 & 1) * H::SAMPLE, R, tid);
+    load_sample<G>(R, S.x + (long)min(g0 + 1, g1 - 1) * (G::IN_PIX * G::IN_CH), tid);
+    for (int g = g0; g < g1; ++g) {
+        sync_lds();   // buffer g&1 is complete; buffer (g+1)&1 is no longer read
+        if (g + 1 < g1) store_sample<G>(lds + ((g + 1) & 1) * H::SAMPLE, R, tid);
+        // the last loads repeat the last sample: redundant, never out of range
+        load_sample<G>(R, S.x + (long)min(g + 2, g1 - 1) * (G::IN_PIX * G::IN_CH), tid);
+        const uint8_t *buf = lds + (g & 1) * H::SAMPLE;
+        v4f acc[H::NBLK][2];
+#pragma unroll
+        for (int b = 0; b < H::NBLK; ++b) acc[b][0] = acc[b][1] = v4f{0, 0, 0, 0};
+#pragma unroll
+        for (int st = 0; st < H::STEPS; ++st) {
+            const int tap = st / H::SPT, ky = tap / G::TAPS, kx = tap % G::TAPS;
+            // pixel (ky, kx) further, second half of its channels for odd steps of the 64-channel layer
+            const int off = (int)H::at(G::IN_W * ky + kx, 0) + (st % H::SPT) * 64;
+#pragma unroll
+            for (int b = 0; b < H::NBLK; ++b) {
+                const v8bf bb = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(buf + base[b] + off));
+                acc[b][0] = mfma16(wa[st][0], bb, acc[b][0]);
+                acc[b][1] = mfma16(wa[st][1], bb, acc[b][1]);
+            }
+        }
+        bf16_t *y = S.y + (long)g * (H::NPOS * 64) + 32 * hh + 8 * kg;
+#pragma unroll
+        for (int b = 0; b < H::NBLK; ++b) {
+            if (pos[b] < H::NPOS) {
+                const v4f a0 = acc[b][0], a1 = acc[b][1];
+                const uint2 lo = pack4(fmaxf(a0.x + b0.x, 0.f), fmaxf(a0.y + b0.y, 0.f), fmaxf(a0.z + b0.z, 0.f), fmaxf(a0.w + b0.w, 0.f));
+                const uint2 hi = pack4(fmaxf(a1.x + b1.x, 0.f), fmaxf(a1.y + b1.y, 0.f), fmaxf(a1.z + b1.z, 0.f), fmaxf(a1.w + b1.w, 0.f));
+                *reinterpret_cast<uint4 *>(y + pos[b] * 64) = uint4{lo.x, lo.y, hi.x, hi.y};
+            }
+        }
+    }
+}
+
+// Workgroup b owns samples [b*total/G, (b+1)*total/G) of the launch-wide list; two workgroups fit one CU.
+template <class G>
+__global__ __launch_bounds__(256, 2) void k_conv_fwd_ps(Args A)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[Shape<G>::LDS];
+    const int g0 = (int)((long)blockIdx.x * A.total / gridDim.x);
+    const int g1 = (int)((long)(blockIdx.x + 1) * A.total / gridDim.x);
+    for (int s = 0; s < A.nseg; ++s) {
+        Seg S = A.seg[0];
+        if (s == 1) S = A.seg[1];
+        if (s == 2) S = A.seg[2];
+        const int lo = max(g0, S.first) - S.first, hi = min(g1, S.first + S.n) - S.first;
+        if (lo < hi) run<G>(S, lo, hi, lds, threadIdx.x);
+    }
+}
+}  // namespace ps
 }  // namespace gbf
