@@ -350,8 +350,9 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
     return hip_status(c, "forward");
 }
 
+// draw != nullptr: the conv1 kernel draws the transitions itself (replay mode; no sampling kernel ran)
 int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
-                           hipStream_t st)
+                           hipStream_t st, const misc::SampleArgs *draw)
 {
     using namespace gbf;
     const Workspace &w = c->ws;
@@ -395,8 +396,14 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         }
         for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
         A.total = first;
+        A.draw = draw != nullptr;
+        if (draw) A.samp = *draw;
         // one wave per strip of a sample, four waves per workgroup, two workgroups resident per CU
         const int grid = std::min((first * c1::UNITS + 3) / 4, 2 * c->num_cu);
+        // a wave that draws for itself holds at most MAX_DRAWS slots: its units span that many samples at most
+        const int upw = (first * c1::UNITS + 4 * grid - 1) / (4 * grid) + 1;
+        if (draw && (upw + c1::UNITS - 1) / c1::UNITS + 1 > c1::MAX_DRAWS)
+            return fail(c, DQN_ERR_INVALID_ARG, "forward: batch too large for in-kernel sampling");
         launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd<<<dim3(grid), 256, 0, st>>>(A); });
     }
     // conv2, conv3: persistent workgroups that keep the weights in registers and take one sample at a time
@@ -436,9 +443,10 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
     return hip_status(c, "forward");
 }
 
-int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *ns, long *ss, hipStream_t st)
+int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *ns, long *ss, hipStream_t st,
+                      const misc::SampleArgs *draw = nullptr)
 {
-    return c->cfg.precision == 1 ? forward_trunk_bf16(c, pass, npass, ns, ss, st)
+    return c->cfg.precision == 1 ? forward_trunk_bf16(c, pass, npass, ns, ss, st, draw)
                                  : forward_trunk_f32(c, pass, npass, ns, ss, st);
 }
 
@@ -1086,7 +1094,9 @@ static void enqueue_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed
 // Enqueues every kernel of one training step on st (and on the side streams, which fork from
 // st and join it again before the function returns).  In replay mode the sampling kernel has
 // been enqueued by the caller.
-static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const dqn_step_out *out, hipStream_t st)
+// draw != nullptr (bf16 replay mode): no sampling kernel has run, the first forward kernel draws.
+static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const dqn_step_out *out, hipStream_t st,
+                            const misc::SampleArgs *draw = nullptr)
 {
     const dqn_config &cfg = c->cfg;
     const Workspace &w = c->ws;
@@ -1116,16 +1126,17 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
             // the frame stacks were copied by the sampling launch
             s = w.stack5; sn = w.stack5 + net::FRAME; xs = 5 * net::FRAME;
         }
-        if (O.idx && hipMemcpyAsync(O.idx, w.b_idx, (size_t)B * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
-            return fail(c, DQN_ERR_HIP, "dqn_train_step: copy failed");
     }
 
     // forward: online(s), online(s'), target(s') in one launch per layer
     Pass passes[3] = {{s, xs, 0, B, ring_idx, 0}, {sn, xs, 0, B, ring_idx, 1}, {sn, xs, 1, B, ring_idx, 1}};
     int ns;
     long ss;
-    int32_t rc = forward_trunk(c, passes, 3, &ns, &ss, st);
+    int32_t rc = forward_trunk(c, passes, 3, &ns, &ss, st, draw);
     if (rc) return rc;
+    // the drawn indices exist once the sampling kernel, or the first forward kernel, has run
+    if (!batch && O.idx && hipMemcpyAsync(O.idx, w.b_idx, (size_t)B * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return fail(c, DQN_ERR_HIP, "dqn_train_step: copy failed");
 
     misc::HeadArgs H{};
     H.part = w.f1part; H.nsplit = ns; H.split_stride = ss;
@@ -1207,10 +1218,16 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     if (batch) return enqueue_step(c, B, batch, out, st);
     if (c->cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "dqn_train_step: replay is empty");
     if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: beta must be >= 0");
+    const bool graphs = !c->prof && !c->graph_off && c->cap && c->side;
+    if (c->cfg.precision == 1 && !graphs) {
+        // bf16 path: the first forward kernel draws the transitions, one launch less on the critical path
+        const misc::SampleArgs S = sample_args(c, B, beta, draw_seed);
+        return enqueue_step(c, B, nullptr, out, st, &S);
+    }
     enqueue_sample(c, B, beta, draw_seed, st);
 
     dqn_ctx::StepGraph *g = nullptr;
-    if (!c->prof && !c->graph_off && c->cap && c->side) {
+    if (graphs) {
         for (dqn_ctx::StepGraph &x : c->graphs)
             if (x.B == B) g = &x;
         if (!g && c->graphs.size() < MAX_STEP_GRAPHS) {

@@ -27,6 +27,7 @@
 #include <stdint.h>
 
 #include "gemm_fp32.h"
+#include "sumtree.h"
 
 namespace gbf {
 
@@ -674,6 +675,9 @@ struct FwdArgs {
     FwdSeg seg[3];
     int nseg;
     int total;          // samples of all segments
+    int draw;           // replay mode: the kernel draws sample g of every segment itself (draw g of `samp`);
+                        // segment 0 publishes the draws
+    misc::SampleArgs samp;
 };
 
 // Forward pass, one WAVE per unit of work and no workgroup barrier anywhere.
@@ -696,6 +700,7 @@ constexpr int SROWS = 20;               // input rows per strip
 constexpr int STRIP = 4 * SROWS * 84;   // elements per strip (four frames)
 constexpr int UNITS = 5;                // strips per sample
 constexpr int CHUNKS = STRIP / 16;      // 16-byte pieces of a strip's pixels: 420
+constexpr int MAX_DRAWS = 8;            // samples one wave may draw for itself
 
 struct StripRaw { uint4 raw[7]; };      // this lane's pieces lane, lane + 64, ... of a strip
 struct StripOff { uint32_t off[7]; };   // their byte offsets within four frames that are contiguous in memory
@@ -753,7 +758,10 @@ __device__ __forceinline__ void strip_store(bf16_t *xs, const StripRaw &R, int l
 // Units [u0, u1) of one segment (unit = UNITS * sample + strip), processed by one wave.  Weights and
 // bias stay in registers; the pixels of the next unit are loaded while the current one is computed,
 // and the ring slot of the unit after that is already on its way.
-__device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1, bf16_t *xs, int lane)
+//
+// In draw mode the kernel has drawn the samples itself (see k_conv1_fwd) and `slots` holds them;
+// otherwise the slots are read from S.src.idx, where a sampling kernel left them.
+__device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1, bf16_t *xs, const int *slots, int lane)
 {
     const int n = lane & 15, kg = lane >> 4, oyl = n >> 2, q = n & 3;
     StripOff O;
@@ -766,8 +774,11 @@ __device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1,
     int g = u0 / UNITS, strip = u0 % UNITS;   // current unit
     int gn = g, sn = strip + 1;               // next unit
     if (sn == UNITS) { sn = 0; ++gn; }
-    strip_load(R, S.src, g, sample_slot(S.src, g), strip, lane, O);
-    int slot_next = u0 + 1 < u1 ? sample_slot(S.src, gn) : 0;
+    // draw mode: slots[] holds the slots of this wave's samples of this segment, first one at index 0
+    const int gfirst = g;
+    auto slot_of = [&](int gq) { return slots ? slots[gq - gfirst] : sample_slot(S.src, gq); };
+    strip_load(R, S.src, g, slot_of(g), strip, lane, O);
+    int slot_next = u0 + 1 < u1 ? slot_of(gn) : 0;
     v8bf wa[8][2];   // [2c + xh][channel half]
 #pragma unroll
     for (int st = 0; st < 8; ++st)
@@ -788,7 +799,7 @@ __device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1,
             strip_load(R, S.src, gn, slot_next, sn, lane, O);
             int g2 = gn;
             if (sn + 1 == UNITS) ++g2;
-            if (u + 2 < u1) slot_next = sample_slot(S.src, g2);
+            if (u + 2 < u1) slot_next = slot_of(g2);
         }
         struct Quads { uint4 q[6]; };
         // The compiler would pair neighbouring columns of ONE row into a two-address read and then
@@ -847,18 +858,43 @@ __device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1,
 __global__ __launch_bounds__(256, 2) void k_conv1_fwd(FwdArgs A)
 {
     __shared__ __attribute__((aligned(16))) bf16_t lds[4 * STRIP];
+    __shared__ int slot_tab[4][MAX_DRAWS];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     bf16_t *xs = lds + wave * STRIP;
     const long nw = (long)gridDim.x * 4, wid = (long)blockIdx.x * 4 + wave, units = (long)A.total * UNITS;
     const int u0 = (int)(wid * units / nw), u1 = (int)((wid + 1) * units / nw);
+    // Draw mode (replay: every segment has the same n samples, sample g of a segment is draw g).
+    // The wave walks the sum-tree (Eq.10) for the samples of its unit range before it requests a
+    // pixel: two draws per walk, its range touches two samples as a rule and never more than
+    // MAX_DRAWS (the host sizes the grid accordingly).  slot_tab[wave][k] = slot of the k-th sample
+    // of the range; the wave that owns strip 0 of a sample of the emitting segment publishes the
+    // index, the raw importance weight and the transition data for the kernels that follow.
+    if (A.draw && u0 < u1) {
+        const misc::SampleArgs P = A.samp;
+        const float total = P.tree[1];
+        const int n = A.seg[0].n, gs0 = u0 / UNITS, gs1 = (u1 - 1) / UNITS;   // launch-wide sample numbers
+#pragma unroll 1
+        for (int ga = gs0; ga <= gs1; ga += 2) {
+            const int gb = ga + 1 <= gs1 ? ga + 1 : ga;
+            long s0, s1;
+            misc::per_sample_descend2(P, ga % n, gb % n, lane, total, s0, s1);
+            if (lane == 0) {
+                slot_tab[wave][ga - gs0] = (int)s0;
+                slot_tab[wave][gb - gs0] = (int)s1;
+                if (ga < n && UNITS * ga >= u0) misc::per_sample_emit(P, ga, s0, total);   // segment 0 emits
+                if (gb < n && gb != ga) misc::per_sample_emit(P, gb, s1, total);
+            }
+        }
+    }
     for (int s = 0; s < A.nseg; ++s) {
         FwdSeg S = A.seg[0];
         if (s == 1) S = A.seg[1];
         if (s == 2) S = A.seg[2];
         const int lo = max(u0, UNITS * S.first) - UNITS * S.first;
         const int hi = min(u1, UNITS * (S.first + S.n)) - UNITS * S.first;
-        if (lo < hi) conv1_fwd_units(S, lo, hi, xs, lane);
+        // the first sample of [lo, hi) is launch-wide sample S.first + lo / UNITS
+        if (lo < hi) conv1_fwd_units(S, lo, hi, xs, A.draw ? slot_tab[wave] + (S.first + lo / UNITS - u0 / UNITS) : nullptr, lane);
     }
 }
 

@@ -87,6 +87,52 @@ __device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, i
     return slot;
 }
 
+// Draws j0 and j1 by one wave at once: the same walk as above for each, with the two fetches of a
+// round issued together, so the pair costs the four round trips of one.
+__device__ __forceinline__ void per_sample_descend2(const SampleArgs &A, int j0, int j1, int lane, float total,
+                                                    long &slot0, long &slot1)
+{
+    const float *tree = A.tree;
+    const int jj[2] = {j0, j1};
+    float z[2];
+    long node[2] = {1, 1};
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {
+        const float u = draw_u24(A.seed, (uint64_t)jj[d]);
+        z[d] = A.stratified ? __fmul_rn((float)jj[d] + u, total / (float)A.B) : __fmul_rn(u, total);
+    }
+    const int lj = lane >= 2 ? 31 - __clz(lane) : 0;
+    for (int done = 0; done < A.levels;) {
+        const int r = min(6, A.levels - done);
+        float va[2] = {0.f, 0.f}, vb[2] = {0.f, 0.f};
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            if (lane >= 2 && lane < (2 << min(r, 5))) va[d] = tree[(node[d] << lj) + (lane - (1 << lj))];
+            if (r == 6) vb[d] = tree[(node[d] << 6) + lane];
+        }
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            int cur = 1;
+            for (int t = 0; t < r; ++t) {
+                const int c = 2 * cur;
+                const float left = c < 64 ? __shfl(va[d], c, 64) : __shfl(vb[d], c - 64, 64);
+                if (z[d] < left) {
+                    cur = c;
+                } else {
+                    z[d] = z[d] - left;
+                    cur = c + 1;
+                }
+            }
+            node[d] = (node[d] << r) + (cur - (1 << r));
+        }
+        done += r;
+    }
+    slot0 = node[0] - A.L;
+    slot1 = node[1] - A.L;
+    if (slot0 > A.size - 1) slot0 = A.size - 1;
+    if (slot1 > A.size - 1) slot1 = A.size - 1;
+}
+
 // What one lane writes for draw j once the slot is known: index, raw weight, transition data.
 __device__ __forceinline__ void per_sample_emit(const SampleArgs &A, int j, long slot, float total)
 {
