@@ -620,9 +620,10 @@ __device__ __forceinline__ const uint8_t *frame_ptr(const Src &S, int n, int slo
 // that the global loads of the next sample can be in flight while the current one is computed:
 // stage_load issues every 16-byte load of a thread, stage_store converts (16 pixels -> 16 bf16)
 // and writes two 16-byte LDS stores per load.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a native vector: stays in registers
 template <int T, int NF> struct Staged {
-    static constexpr int CH = FR / 8, TOT = NF * CH, NL = (TOT + T - 1) / T;
-    uint2 raw[NL];
+    static constexpr int CH = FR / 16, TOT = NF * CH, NL = (TOT + T - 1) / T;
+    u32x4 raw[NL];
 };
 template <int T, int NF>
 __device__ __forceinline__ void stage_load(Staged<T, NF> &R, const Src &S, int n, int slot_n, int k0, int tid)
@@ -635,15 +636,14 @@ __device__ __forceinline__ void stage_load(Staged<T, NF> &R, const Src &S, int n
     for (int k = 0; k < 4; ++k) f[k] = frame_ptr(S, n, slot_n, k0 + (k < NF ? k : 0));
 #pragma unroll
     for (int i = 0; i < ST::NL; ++i) {
-        const int t = tid + i * T;
-        if (t < ST::TOT) {
-            const int k = t / ST::CH;
-            const uint8_t *fp = k == 0 ? f[0] : k == 1 ? f[1] : k == 2 ? f[2] : f[3];
-            R.raw[i] = *reinterpret_cast<const uint2 *>(fp + (t % ST::CH) * 8);
-        }
+        int t = tid + i * T;
+        if (t > ST::TOT - 1) t = ST::TOT - 1;   // the last pass repeats a piece rather than branching
+        const int k = t / ST::CH;
+        const uint8_t *fp = k == 0 ? f[0] : k == 1 ? f[1] : k == 2 ? f[2] : f[3];
+        R.raw[i] = *reinterpret_cast<const u32x4 *>(fp + (t % ST::CH) * 16);
     }
 }
-// 8 pixels -> 8 bf16 -> one 16-byte LDS store; consecutive lanes write consecutive 16 bytes
+// 16 pixels -> 16 bf16 -> two 16-byte LDS stores; consecutive lanes write consecutive 32 bytes
 template <int T, int NF>
 __device__ __forceinline__ void stage_store(bf16_t *xin, const Staged<T, NF> &R, int tid)
 {
@@ -652,13 +652,10 @@ __device__ __forceinline__ void stage_store(bf16_t *xin, const Staged<T, NF> &R,
     for (int i = 0; i < ST::NL; ++i) {
         const int t = tid + i * T;
         if (t < ST::TOT) {
-            const uint2 r = R.raw[i];
-            uint4 o;
-            o.x = pack2_u8(r.x & 0xFFu, (r.x >> 8) & 0xFFu);
-            o.y = pack2_u8((r.x >> 16) & 0xFFu, r.x >> 24);
-            o.z = pack2_u8(r.y & 0xFFu, (r.y >> 8) & 0xFFu);
-            o.w = pack2_u8((r.y >> 16) & 0xFFu, r.y >> 24);
-            *reinterpret_cast<uint4 *>(xin + t * 8) = o;  // frames are contiguous in xin: (t/CH)*FR + (t%CH)*8 == t*8
+            const u32x4 r = R.raw[i];
+            uint4 *d = reinterpret_cast<uint4 *>(xin + t * 16);  // frames are contiguous in xin: (t/CH)*FR + (t%CH)*16 == t*16
+            d[0] = cvt8_u8(r.x, r.y);
+            d[1] = cvt8_u8(r.z, r.w);
         }
     }
 }
@@ -928,7 +925,7 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
     const int xoff = (kc >> 6) * FR + ((kc >> 3) & 7) * 84 + (kc & 7);
     const bf16_t *yp = dys + rsub * LDY1 + 16 * half + 4 * (s16 & 3);
 
-    v16f acc = {0}, accb = {0};
+    v16f acc = {0}, acc2 = {0}, accb = {0};
     v8bf ones;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
@@ -961,7 +958,7 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
             load_sample(n + A.nsplit, slot_next);  // in flight during the MFMA loop
             if (n + 2 * A.nsplit < A.B) slot_next = sample_slot(A.src, n + 2 * A.nsplit);
         }
-#pragma unroll 5
+#pragma unroll 6
         for (int t = 0; t < 25; ++t) {  // 16 output pixels per step
             v8bf fa = frag_tr(yp + 16 * t * LDY1, LDY1);
             const int m0 = 16 * t + rsub, m1 = m0 + 4;
@@ -971,7 +968,9 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
             v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x1);
             typedef short v8s __attribute__((ext_vector_type(8)));
             v8s xb = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            acc = mfma(fa, __builtin_bit_cast(v8bf, xb), acc);
+            // two accumulators, alternating: consecutive MFMAs do not wait for each other's result
+            if (t & 1) acc2 = mfma(fa, __builtin_bit_cast(v8bf, xb), acc2);
+            else acc = mfma(fa, __builtin_bit_cast(v8bf, xb), acc);
             if (do_bias) accb = mfma(fa, ones, accb);
         }
     }
@@ -980,7 +979,7 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int o = 8 * (r / 4) + 4 * h + (r % 4);
-        part[o * 256 + 128 * cp + 32 * wave + li] = acc[r] * (1.0f / 255.0f);
+        part[o * 256 + 128 * cp + 32 * wave + li] = (acc[r] + acc2[r]) * (1.0f / 255.0f);
         if (do_bias && li == 0) part[32 * 256 + o] = accb[r];
     }
 }
