@@ -630,13 +630,13 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     int rps;
     {
         DgradArgs D{dh, sh + net::F1W, act3, d3, B};
-        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 64, 64, 1, 1><<<dim3((B + 63) / 64, 49, 1), 256, 0, st>>>(D); });
+        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 64, 64, 1, 1, true><<<dim3((B + 63) / 64, 49, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_a, st, sd);
     }
     {
         DgradArgs D{d3, sh + net::C3W, act2, d2, B};
         long M = (long)B * 81;
-        launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64, 1, 1><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
+        launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64, 1, 1, true><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_b, st, sd);
     }
     {

@@ -294,7 +294,11 @@ struct DgradArgs {
     int B;
 };
 
-template <class D, int BM, int BN, int WM, int WN>
+// DB: the LDS tiles are double-buffered, which leaves one barrier per reduction stage instead of two
+// (for the layers whose stages are so short that the barriers dominate them), and a wave with a
+// single output block alternates between two accumulators so that consecutive MFMAs do not wait
+// for each other's result.
+template <class D, int BM, int BN, int WM, int WN, bool DB = false>
 __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dgrad(DgradArgs A)
 {
     constexpr int WAVES_M = BM / (32 * WM), WAVES_N = BN / (32 * WN), T = WAVES_M * WAVES_N * 64;
@@ -304,8 +308,10 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
     constexpr int BROWS = T / BCH;       // rows filled per pass
     constexpr int NBL = (BK + BROWS - 1) / BROWS;
     static_assert(NA * T == BM * 8 && D::CO % BK == 0, "tile/threads mismatch");
-    __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDK];
-    __shared__ __attribute__((aligned(16))) bf16_t Bs[BK * LDB];
+    constexpr int NBUF = DB ? 2 : 1;
+    constexpr bool ACC2 = DB && WM * WN == 1;
+    __shared__ __attribute__((aligned(16))) bf16_t As2[NBUF][BM * LDK];
+    __shared__ __attribute__((aligned(16))) bf16_t Bs2[NBUF][BK * LDB];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // tile order: the parity classes of one row tile together, then the row tiles of one column tile
@@ -348,7 +354,8 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
             if (r < BK) rb[i] = ld8(A.w + ((long)((o0 + r) * D::KH + p) * D::KW + q) * D::CI + n0 + bc);
         }
     };
-    auto sstore = [&]() {
+    auto sstore = [&](int buf) {
+        bf16_t *As = As2[buf], *Bs = Bs2[buf];
 #pragma unroll
         for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4 *>(&As[(lr + i * (T / 8)) * LDK + kq]) = ra[i];
 #pragma unroll
@@ -360,9 +367,9 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
 
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
     const int li = lane & 31, h = lane >> 5, s16 = lane & 15, half = (lane >> 4) & 1;
-    const bf16_t *ap = &As[(wm * 32 * WM + li) * LDK + 8 * h];
+    const int apo = (wm * 32 * WM + li) * LDK + 8 * h;
     // transpose-read base: row 8h + s/4, column (wave block) + 16*half + 4*(s%4)
-    const bf16_t *bp = &Bs[(8 * h + (s16 >> 2)) * LDB + wn * 32 * WN + 16 * half + 4 * (s16 & 3)];
+    const int bpo = (8 * h + (s16 >> 2)) * LDB + wn * 32 * WN + 16 * half + 4 * (s16 & 3);
     v16f acc[WM][WN];
 #pragma unroll
     for (int a = 0; a < WM; ++a)
@@ -390,12 +397,9 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
                                             : uint2{0, 0};
     }
 
-    gload(0);
-    sstore();
-    __syncthreads();
-    for (int k0 = 0; k0 < D::K; k0 += BK) {
-        const bool more = k0 + BK < D::K;
-        if (more) gload(k0 + BK);
+    v16f acc2 = {0};   // second accumulator (ACC2 only)
+    auto compute = [&](int buf) {
+        const bf16_t *ap = As2[buf] + apo, *bp = Bs2[buf] + bpo;
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 16) {
             v8bf fa[WM], fb[WN];
@@ -406,12 +410,34 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
 #pragma unroll
             for (int a = 0; a < WM; ++a)
 #pragma unroll
-                for (int b = 0; b < WN; ++b) acc[a][b] = mfma(fb[b], fa[a], acc[a][b]);  // transposed tile
+                for (int b = 0; b < WN; ++b) {  // transposed tile
+                    if (ACC2 && (kk & 16)) acc2 = mfma(fb[b], fa[a], acc2);
+                    else acc[a][b] = mfma(fb[b], fa[a], acc[a][b]);
+                }
         }
+    };
+    gload(0);
+    if constexpr (DB) {
+        int s = 0;
+        for (int k0 = 0; k0 < D::K; k0 += BK, s ^= 1) {
+            sstore(s);
+            if (k0 + BK < D::K) gload(k0 + BK);
+            sync_lds();   // buffer s is complete; every wave is past the previous stage, which read buffer s^1
+            compute(s);
+        }
+        if (ACC2) acc[0][0] += acc2;
+    } else {
+        sstore(0);
         __syncthreads();
-        if (more) {
-            sstore();
+        for (int k0 = 0; k0 < D::K; k0 += BK) {
+            const bool more = k0 + BK < D::K;
+            if (more) gload(k0 + BK);
+            compute(0);
             __syncthreads();
+            if (more) {
+                sstore(0);
+                __syncthreads();
+            }
         }
     }
 
