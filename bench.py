@@ -79,15 +79,15 @@ def gemm_bytes_per_launch(B, R, bf16):
 # run (fetch x1.949, write x0.9875).  Keyed by (kernel, batch, precision); the figures and the
 # commands are in profiles/train_step_b512_bf16_hbm_traffic.md.
 MEASURED_TRAFFIC = {
-    ("conv1_fwd", 512, "bf16"): 42.9e6 + 38.8e6,
-    ("conv2_fwd", 512, "bf16"): 40.9e6 + 15.7e6,
-    ("conv3_fwd", 512, "bf16"): 16.2e6 + 9.5e6,
+    ("conv1_fwd", 512, "bf16"): 47.8e6 + 38.9e6,
+    ("conv2_fwd", 512, "bf16"): 39.5e6 + 15.7e6,
+    ("conv3_fwd", 512, "bf16"): 16.8e6 + 9.5e6,
     ("fc1_fwd", 512, "bf16"): 19.9e6 + 21.7e6,
-    ("head_train", 512, "bf16"): 22.3e6 + 1.6e6,
+    ("head_train", 512, "bf16"): 22.4e6 + 1.6e6,
     ("fc1_dgrad", 512, "bf16"): 11.4e6 + 3.2e6,
     ("conv3_dgrad", 512, "bf16"): 8.9e6 + 5.2e6,
     ("conv2_dgrad", 512, "bf16"): 18.5e6 + 12.9e6,
-    ("conv1_wgrad", 512, "bf16"): 27.0e6 + 8.3e6,
+    ("conv1_wgrad", 512, "bf16"): 27.1e6 + 8.3e6,
     ("conv2_wgrad", 512, "bf16"): 19.5e6 + 7.7e6,
     ("conv3_wgrad", 512, "bf16"): 8.4e6 + 8.2e6,
     ("fc1_wgrad", 512, "bf16"): 7.7e6 + 6.3e6,
