@@ -597,20 +597,20 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
 // conv1 (8x8 stride 4 over the uint8 frame stack), specialised.
 //
 // The generic kernels gather conv1's im2col rows from global memory in 4/8-byte
-// pieces at 84-byte strides, which is address-bound.  Here one workgroup owns
-// one sample: its four 84x84 frames are read once with 16-byte loads -- from a
-// materialised state, or straight from the replay ring through the sampled
-// slot (the frame-stack gather fused into the loader) -- converted to bf16 and
-// kept in LDS as [4][84][84].  Every operand of the 8x8/4 convolution is then
-// an LDS read at a computed address:
-//   forward : pixel row of A = 8 consecutive q for one (c,p): 16 bytes;
-//             all of W (32x256 bf16) sits in registers as 16 b-operands;
-//   wgrad   : 8 consecutive pixels of one im2col column, fetched with the LDS
-//             transpose load, whose lanes each supply their own address.
+// pieces at 84-byte strides, which is address-bound.  Here the 84x84 frames are
+// read with 16-byte loads -- from a materialised state, or straight from the
+// replay ring through the sampled slot (the frame-stack gather fused into the
+// loader) -- converted to bf16 and kept in LDS, and every operand of the 8x8/4
+// convolution is an LDS read at a computed address:
+//   forward : one WAVE stages the 20 input rows under 4 output rows of the four
+//             frames in LDS of its own and reads them as two-row "quads";
+//             all of W (32x256 bf16) sits in registers (see k_conv1_fwd);
+//   wgrad   : one WORKGROUP stages two whole frames of a sample; 8 consecutive
+//             pixels of one im2col column are fetched with the LDS transpose
+//             load, whose lanes each supply their own address.
 // ===========================================================================
 namespace c1 {
 constexpr int FR = 84 * 84;       // elements per frame
-constexpr int XIN = 4 * FR;       // staged state, elements
 
 struct Src {                      // where the four frames of sample n come from
     const uint8_t *x;             // explicit states [n][4][84][84] (idx == nullptr) or the ring
