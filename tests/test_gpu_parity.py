@@ -409,13 +409,17 @@ def test_replay_train_step_small_ring(dq, orc):
     _replay_step_case(dq, orc, cap=4096, B=32)
 
 
-@pytest.mark.parametrize("prec,B", [(0, 32), (1, 64)])
+@pytest.mark.parametrize("prec,B", [(0, 32), (1, 64), (1, 6), (1, 1024)])
 def test_recorded_step_replays_match_plain_launches(dq, prec, B):
     """With DQN_GRAPH=1 the replay-mode step is recorded into a HIP graph and replayed.  Two
     contexts over identical state, one on the graph and one on plain launches, must agree
     bit for bit on every replay: enqueued back to back, with other work and synchronisations
     between the replays, with the outputs requested and not requested, after a change of batch
-    size and after the number of stored transitions has changed."""
+    size and after the number of stored transitions has changed.
+
+    In bf16 the two also differ in who draws the transitions: the graph path runs the sampling
+    kernel in front of the graph, the plain path lets the first forward kernel walk the tree
+    (one sample per working wave at B = 6 and 3, three samples per wave at B = 1024)."""
     import os
     print("case graph replays", prec, B, flush=True)
     cap = 6000
@@ -513,6 +517,21 @@ def test_replay_train_step_wrapping_ring_bf16(dq, orc):
     idx = m.per_sample(96, 0.4, seed)[0].cpu().numpy()       # same tree, same seed: the step's draw
     assert (idx < 3).any() and (idx == cap - 1).any(), "the draw must include wrapping windows"
     print("  worst:", sorted(e.items(), key=lambda kv: -kv[1])[:4], flush=True)
+    m.close()
+
+
+def test_replay_train_step_bf16_maximum_batch(dq, orc):
+    """bf16 replay step at B = 1024, the library's limit: a wave's units of conv1 work span three
+    samples, the most its draw table is sized for.  (Very small bf16 batches are held against the
+    oracle with explicit batches, and their in-kernel draws against the sampling kernel bit for
+    bit in the recorded-step test: at B = 3 a single ReLU mask that flips on a bf16 rounding
+    boundary moves a third of a gradient entry, which no tolerance on the gradients survives.)"""
+    print("case replay step bf16 maximum batch", flush=True)
+    cap = 20000
+    m = dq.Dqn(dq.make_config(replay_capacity=cap, max_batch=1024, precision=1, **CONFIGS["dueling_ddqn"]))
+    _fill_replay(m, cap, K=18, chunk=cap)
+    e = _replay_step_case(dq, orc, cap, 1024, m=m, draw_seed=32, tol=TOL_BF16)
+    print("  B=1024 worst:", sorted(e.items(), key=lambda kv: -kv[1])[:3], flush=True)
     m.close()
 
 
