@@ -266,8 +266,10 @@ struct Pass {
     long xs;             // bytes between samples (states)
     int net;             // 0 online / 1 target parameters
     int n;               // samples
-    const int32_t *idx;  // ring mode (bf16 path): sampled slots; frames are read from the ring
+    const int32_t *idx;  // ring mode: sampled slots (or where the forward kernel leaves them); frames are read from the ring
     int shift;           // ring mode: 0 = s (frames i-3..i), 1 = s' (frames i-2..i+1)
+    uint8_t *stack;      // fp32 ring mode: where conv1 leaves a gathered copy of the frames for the weight gradient
+    int stack_mode;      // 1: frames 0-3 of the sample to stack frames 0-3; 2: frame 3 to stack frame 4
 };
 
 const float *theta_of(dqn_ctx *c, int net) { return net ? c->theta_t : c->theta; }
@@ -278,7 +280,7 @@ const gbf::bf16_t *shadow_of(dqn_ctx *c, int net)
 }
 
 int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
-                          hipStream_t st)
+                          hipStream_t st, const misc::SampleArgs *draw)
 {
     using namespace g32;
     const Workspace &w = c->ws;
@@ -310,13 +312,31 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
     // Few rows (small batches): the reduction slab of every stage is sliced over extra waves
     // (KS > 1), which shortens the dependent chain of stages per tile.
     const bool small = rows * 81 < 64 * 512;
-    {  // conv1
-        FwdArgs A{};
-        int tiles = build(A, small ? 64 : 128, 400, [&](int i) { return (const void *)pass[i].x; },
-                          [&](int i) { return pass[i].xs; }, net::C1W, net::C1B, act1, net::A1, true);
-        A.klen = GConv1::K; A.split_stride = 0; A.scale = 1.0f / 255.0f;
-        if (small) launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 64, 32, 4><<<dim3(tiles, 1, 1), 512, 0, st>>>(A); });
-        else launch(c, "conv1_fwd", st, [&] { k_fwd<GConv1, 128, 32><<<dim3(tiles, 1, 1), 256, 0, st>>>(A); });
+    {  // conv1: one wave per strip of a sample and channel half; a small batch also halves the reduction
+        using namespace gbf;
+        c1::FwdArgsF A{};
+        A.nseg = npass;
+        int first = 0;
+        for (int i = 0; i < npass; ++i) {
+            const float *theta = theta_of(c, pass[i].net);
+            A.seg[i] = c1::FwdSegF{c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift},
+                                   theta + net::C1W, theta + net::C1B, act1 + row0[i] * net::A1, pass[i].n, first,
+                                   pass[i].stack, pass[i].stack_mode};
+            first += pass[i].n;
+        }
+        for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
+        A.total = first;
+        A.draw = draw != nullptr;
+        if (draw) A.samp = *draw;
+        const int units = first * c1::UNITS;
+        const bool ks2 = 2 * units <= 4 * c->num_cu;   // fewer wave pairs than SIMDs: four waves per unit
+        const int grid = ks2 ? std::min(units, 2 * c->num_cu) : std::min((units + 1) / 2, 2 * c->num_cu);
+        const int groups = ks2 ? grid : 2 * grid;
+        const int upg = (units + groups - 1) / groups + 1;   // units per group of waves, at most
+        if (draw && (upg + c1::UNITS - 1) / c1::UNITS + 1 > c1::MAX_DRAWS)
+            return fail(c, DQN_ERR_INVALID_ARG, "forward: batch too large for in-kernel sampling");
+        if (ks2) launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd_f32<2><<<dim3(grid), 256, 0, st>>>(A); });
+        else launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd_f32<1><<<dim3(grid), 256, 0, st>>>(A); });
     }
     {  // conv2
         FwdArgs A{};
@@ -447,7 +467,7 @@ int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *ns, long *ss
                       const misc::SampleArgs *draw = nullptr)
 {
     return c->cfg.precision == 1 ? forward_trunk_bf16(c, pass, npass, ns, ss, st, draw)
-                                 : forward_trunk_f32(c, pass, npass, ns, ss, st);
+                                 : forward_trunk_f32(c, pass, npass, ns, ss, st, draw);
 }
 
 // reduction rows per split (a multiple of `unit`) and the resulting number of splits
@@ -1118,8 +1138,9 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
         a = batch->a; r = batch->r; done = batch->done; isw = batch->w;
     } else {
         a = w.b_a; r = w.b_r; done = w.b_done; isw = w.b_w;
-        if (cfg.precision == 1) {
-            // bf16 path: the conv1 kernels read the five frames of a transition straight from the ring
+        if (cfg.precision == 1 || draw) {
+            // the conv1 forward kernel reads the five frames of a transition straight from the ring (bf16: so
+            // does the conv1 weight gradient; fp32: the forward kernel leaves it a gathered copy)
             ring_idx = w.b_idx;
             s = sn = (const uint8_t *)c->buf.replay_frames; xs = 0;
         } else {
@@ -1127,9 +1148,12 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
             s = w.stack5; sn = w.stack5 + net::FRAME; xs = 5 * net::FRAME;
         }
     }
+    const bool stacking = !batch && cfg.precision == 0 && draw;
 
     // forward: online(s), online(s'), target(s') in one launch per layer
-    Pass passes[3] = {{s, xs, 0, B, ring_idx, 0}, {sn, xs, 0, B, ring_idx, 1}, {sn, xs, 1, B, ring_idx, 1}};
+    Pass passes[3] = {{s, xs, 0, B, ring_idx, 0, stacking ? w.stack5 : nullptr, 1},
+                      {sn, xs, 0, B, ring_idx, 1, stacking ? w.stack5 : nullptr, 2},
+                      {sn, xs, 1, B, ring_idx, 1, nullptr, 0}};
     int ns;
     long ss;
     int32_t rc = forward_trunk(c, passes, 3, &ns, &ss, st, draw);
@@ -1174,7 +1198,8 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
 
     int ns1, ns2, ns3;
     if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, sd);
-    else backward_f32(c, B, s, xs, &ns1, &ns2, &ns3, st, sd, fuse_tail ? &tail : nullptr);
+    else backward_f32(c, B, stacking ? w.stack5 : s, stacking ? 5L * net::FRAME : xs, &ns1, &ns2, &ns3, st, sd,
+                      fuse_tail ? &tail : nullptr);
     ev_record(c->ev_join, sd, st);
     ev_wait(st, c->ev_join, sd);
     if (sp != sd) (void)hipStreamWaitEvent(st, c->ev_join2, 0);
@@ -1219,8 +1244,9 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     if (c->cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "dqn_train_step: replay is empty");
     if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: beta must be >= 0");
     const bool graphs = !c->prof && !c->graph_off && c->cap && c->side;
-    if (c->cfg.precision == 1 && !graphs) {
-        // bf16 path: the first forward kernel draws the transitions, one launch less on the critical path
+    if (!graphs) {
+        // the first forward kernel draws the transitions (and, in fp32, gathers their frames for the
+        // weight gradient): one launch less on the critical path
         const misc::SampleArgs S = sample_args(c, B, beta, draw_seed);
         return enqueue_step(c, B, nullptr, out, st, &S);
     }

@@ -725,7 +725,7 @@ constexpr int UNITS = 5;                // strips per sample
 constexpr int CHUNKS = STRIP / 16;      // 16-byte pieces of a strip's pixels: 420
 constexpr int MAX_DRAWS = 8;            // samples one wave may draw for itself
 
-struct StripRaw { uint4 raw[7]; };      // this lane's pieces lane, lane + 64, ... of a strip
+struct StripRaw { u32x4 raw[7]; };      // this lane's pieces lane, lane + 64, ... of a strip
 struct StripOff { uint32_t off[7]; };   // their byte offsets within four frames that are contiguous in memory
 
 // The pixels of strip `strip` of sample g.  Four frames of a ring sample are contiguous unless
@@ -749,7 +749,7 @@ __device__ __forceinline__ void strip_load(StripRaw &R, const Src &S, int g, int
         base += strip * (16 * 84);
 #pragma unroll
         for (int i = 0; i < 7; ++i)
-            if (i < 6 || lane < CHUNKS - 384) R.raw[i] = *reinterpret_cast<const uint4 *>(base + O.off[i]);
+            if (i < 6 || lane < CHUNKS - 384) R.raw[i] = *reinterpret_cast<const u32x4 *>(base + O.off[i]);
     } else {
 #pragma unroll
         for (int i = 0; i < 7; ++i) {
@@ -758,7 +758,7 @@ __device__ __forceinline__ void strip_load(StripRaw &R, const Src &S, int g, int
                 long slot = b + t / (CHUNKS / 4);
                 if (slot < 0) slot += S.cap;
                 if (slot >= S.cap) slot -= S.cap;
-                R.raw[i] = *reinterpret_cast<const uint4 *>(S.x + slot * FR + strip * (16 * 84) + (t % (CHUNKS / 4)) * 16);
+                R.raw[i] = *reinterpret_cast<const u32x4 *>(S.x + slot * FR + strip * (16 * 84) + (t % (CHUNKS / 4)) * 16);
             }
         }
     }
@@ -770,7 +770,7 @@ __device__ __forceinline__ void strip_store(bf16_t *xs, const StripRaw &R, int l
     for (int i = 0; i < 7; ++i) {
         const int t = lane + 64 * i;
         if (t < CHUNKS) {
-            const uint4 r = R.raw[i];
+            const u32x4 r = R.raw[i];
             uint4 *d = reinterpret_cast<uint4 *>(xs + t * 16);
             d[0] = cvt8_u8(r.x, r.y);
             d[1] = cvt8_u8(r.z, r.w);
@@ -876,6 +876,31 @@ __device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1,
     }
 }
 
+// Draw mode (replay: every segment has the same n samples, sample g of a segment is draw g).
+// The wave walks the sum-tree (Eq.10) for the samples of its unit range [u0, u1) before it requests
+// a pixel: two draws per walk, its range touches two samples as a rule and never more than
+// MAX_DRAWS (the host sizes the grid accordingly).  slots[k] = slot of the k-th sample of the
+// range; with `publish`, the wave that owns strip 0 of a sample of segment 0 writes the index, the
+// raw importance weight and the transition data for the kernels that follow.
+__device__ __forceinline__ void draw_slots(const misc::SampleArgs &P, int n, int u0, int u1, int *slots, int lane,
+                                           bool publish)
+{
+    const float total = P.tree[1];
+    const int gs0 = u0 / UNITS, gs1 = (u1 - 1) / UNITS;   // launch-wide sample numbers
+#pragma unroll 1
+    for (int ga = gs0; ga <= gs1; ga += 2) {
+        const int gb = ga + 1 <= gs1 ? ga + 1 : ga;
+        long s0, s1;
+        misc::per_sample_descend2(P, ga % n, gb % n, lane, total, s0, s1);
+        if (lane == 0) {
+            slots[ga - gs0] = (int)s0;
+            slots[gb - gs0] = (int)s1;
+            if (publish && ga < n && UNITS * ga >= u0) misc::per_sample_emit(P, ga, s0, total);
+            if (publish && gb < n && gb != ga) misc::per_sample_emit(P, gb, s1, total);
+        }
+    }
+}
+
 // Wave w of the launch owns units [w*U/W, (w+1)*U/W) of the launch-wide list (segment after segment,
 // U = UNITS * samples, W = 4 * gridDim.x).  Two workgroups of four waves fit one CU.
 __global__ __launch_bounds__(256, 2) void k_conv1_fwd(FwdArgs A)
@@ -887,29 +912,7 @@ __global__ __launch_bounds__(256, 2) void k_conv1_fwd(FwdArgs A)
     bf16_t *xs = lds + wave * STRIP;
     const long nw = (long)gridDim.x * 4, wid = (long)blockIdx.x * 4 + wave, units = (long)A.total * UNITS;
     const int u0 = (int)(wid * units / nw), u1 = (int)((wid + 1) * units / nw);
-    // Draw mode (replay: every segment has the same n samples, sample g of a segment is draw g).
-    // The wave walks the sum-tree (Eq.10) for the samples of its unit range before it requests a
-    // pixel: two draws per walk, its range touches two samples as a rule and never more than
-    // MAX_DRAWS (the host sizes the grid accordingly).  slot_tab[wave][k] = slot of the k-th sample
-    // of the range; the wave that owns strip 0 of a sample of the emitting segment publishes the
-    // index, the raw importance weight and the transition data for the kernels that follow.
-    if (A.draw && u0 < u1) {
-        const misc::SampleArgs P = A.samp;
-        const float total = P.tree[1];
-        const int n = A.seg[0].n, gs0 = u0 / UNITS, gs1 = (u1 - 1) / UNITS;   // launch-wide sample numbers
-#pragma unroll 1
-        for (int ga = gs0; ga <= gs1; ga += 2) {
-            const int gb = ga + 1 <= gs1 ? ga + 1 : ga;
-            long s0, s1;
-            misc::per_sample_descend2(P, ga % n, gb % n, lane, total, s0, s1);
-            if (lane == 0) {
-                slot_tab[wave][ga - gs0] = (int)s0;
-                slot_tab[wave][gb - gs0] = (int)s1;
-                if (ga < n && UNITS * ga >= u0) misc::per_sample_emit(P, ga, s0, total);   // segment 0 emits
-                if (gb < n && gb != ga) misc::per_sample_emit(P, gb, s1, total);
-            }
-        }
-    }
+    if (A.draw && u0 < u1) draw_slots(A.samp, A.seg[0].n, u0, u1, slot_tab[wave], lane, true);
     for (int s = 0; s < A.nseg; ++s) {
         FwdSeg S = A.seg[0];
         if (s == 1) S = A.seg[1];
@@ -918,6 +921,173 @@ __global__ __launch_bounds__(256, 2) void k_conv1_fwd(FwdArgs A)
         const int hi = min(u1, UNITS * (S.first + S.n)) - UNITS * S.first;
         // the first sample of [lo, hi) is launch-wide sample S.first + lo / UNITS
         if (lo < hi) conv1_fwd_units(S, lo, hi, xs, A.draw ? slot_tab[wave] + (S.first + lo / UNITS - u0 / UNITS) : nullptr, lane);
+    }
+}
+
+
+// ---------------------------------------------------------------------------
+// The same forward pass in fp32 (v_mfma_f32_16x16x4_f32), for the full-precision path.
+//
+// Units and lanes as above (strip of 4 output rows, 16 lanes x 5 pixels), but the strip stays in
+// LDS as the uint8 it is (6,720 bytes per wave, no conversion while staging): the MFMA takes one
+// reduction element per lane and instruction, lane group kg supplies kernel row 4yq + kg, and a
+// lane's six 4-byte words of that row (pixels 4jj .. 4jj+3 of its run) serve, byte by byte, the
+// kernel columns of all five pixels: word jj is columns 0-3 of pixel jj and columns 4-7 of pixel
+// jj-1.  One v_cvt_f32_ubyte per byte, 24 per 40 MFMAs.
+// A wave holds the weights of 16 output channels (64 registers): waves work in pairs, one channel
+// half each.  KS = 2 (small batches: fewer units than SIMDs) also cuts the reduction in two, frames
+// 0-1 and 2-3, over two such pairs, which then add their sums through LDS in a fixed order.
+// The first wave of a group can copy its strip to a gathered stack (the weight-gradient kernel of
+// this path reads a materialised state): segment 0 supplies frames 0-3, segment 1 its last frame.
+// ---------------------------------------------------------------------------
+constexpr int RAWSTRIP = 4 * SROWS * 84;   // bytes of one strip as uint8
+struct FwdSegF {
+    Src src;
+    const float *w;     // [32][256] fp32, k = (c, ky, kx)
+    const float *bias;  // [32]
+    float *y;           // [n][400][32]
+    int n;
+    int first;
+    uint8_t *stack;     // [n][5][84][84] or nullptr
+    int stack_mode;     // 1: frames 0-3 of the sample to stack frames 0-3; 2: frame 3 to stack frame 4
+};
+struct FwdArgsF {
+    FwdSegF seg[3];
+    int nseg;
+    int total;
+    int draw;
+    misc::SampleArgs samp;
+};
+
+__device__ __forceinline__ v4f mfma4(float a, float b, v4f c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+template <int KS>
+__device__ __forceinline__ void conv1_fwd_units_f32(const FwdSegF &S, int u0, int u1, int hh, int ks, uint8_t *xs,
+                                                    v4f *red, const int *slots, int lane)
+{
+    constexpr int NCY = 8 / KS;   // (frame, kernel-row half) pairs of this wave
+    const int n = lane & 15, kg = lane >> 4, oyl = n >> 2, q = n & 3;
+    const bool first_wave = hh == 0 && ks == 0;
+    StripOff O;
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+        const int t = lane + 64 * i;
+        O.off[i] = t < CHUNKS ? (t / (CHUNKS / 4)) * FR + (t % (CHUNKS / 4)) * 16 : 0;
+    }
+    const int gfirst = u0 / UNITS;
+    auto slot_of = [&](int gq) { return slots ? slots[gq - gfirst] : sample_slot(S.src, gq); };
+    StripRaw R;
+    strip_load(R, S.src, gfirst, slot_of(gfirst), u0 % UNITS, lane, O);
+    int slot_next = u0 + 1 < u1 ? slot_of((u0 + 1) / UNITS) : 0;
+    // weights: wa[8 cyl + 4 xh + b] = W[16hh + n][frame, kernel row 4yq + kg of pair NCY ks + cyl][4 xh + b]
+    float wa[8 * NCY];
+#pragma unroll
+    for (int cyl = 0; cyl < NCY; ++cyl) {
+        const int cy = NCY * ks + cyl;
+        const float *p = S.w + (16 * hh + n) * 256 + (cy >> 1) * 64 + (4 * (cy & 1) + kg) * 8;
+        const v4f lo = *reinterpret_cast<const v4f *>(p), hi = *reinterpret_cast<const v4f *>(p + 4);
+        wa[8 * cyl + 0] = lo.x; wa[8 * cyl + 1] = lo.y; wa[8 * cyl + 2] = lo.z; wa[8 * cyl + 3] = lo.w;
+        wa[8 * cyl + 4] = hi.x; wa[8 * cyl + 5] = hi.y; wa[8 * cyl + 6] = hi.z; wa[8 * cyl + 7] = hi.w;
+    }
+    const v4f bias = *reinterpret_cast<const v4f *>(S.bias + 16 * hh + 4 * kg);
+    const uint8_t *px = xs + (4 * oyl + kg) * 84 + 20 * q;
+    for (int u = u0; u < u1; ++u) {
+        const int g = u / UNITS, strip = u % UNITS;
+#pragma unroll
+        for (int i = 0; i < 7; ++i) {
+            const int t = lane + 64 * i;
+            if (t < CHUNKS) {
+                *reinterpret_cast<u32x4 *>(xs + t * 16) = R.raw[i];
+                // rows 16s .. 16s+15 of the frames are this strip's own (the last strip owns all 20)
+                const int fr = t / (CHUNKS / 4), off = (t % (CHUNKS / 4)) * 16;
+                if (first_wave && S.stack && (off < 16 * 84 || strip == UNITS - 1) && (S.stack_mode == 1 || fr == 3))
+                    *reinterpret_cast<u32x4 *>(S.stack + ((long)g * 5 + (S.stack_mode == 1 ? fr : 4)) * FR + strip * (16 * 84) + off) = R.raw[i];
+            }
+        }
+        if (u + 1 < u1) {
+            strip_load(R, S.src, (u + 1) / UNITS, slot_next, (u + 1) % UNITS, lane, O);
+            if (u + 2 < u1) slot_next = slot_of((u + 2) / UNITS);
+        }
+        v4f acc[5];
+#pragma unroll
+        for (int j = 0; j < 5; ++j) acc[j] = v4f{0, 0, 0, 0};
+#pragma unroll
+        for (int cyl = 0; cyl < NCY; ++cyl) {
+            const int cy = NCY * ks + cyl;   // frame cy / 2, kernel rows 4 (cy % 2) + kg
+            const uint8_t *p = px + (cy >> 1) * (SROWS * 84) + (cy & 1) * (4 * 84);
+            uint32_t d[6];
+#pragma unroll
+            for (int jj = 0; jj < 6; ++jj) d[jj] = *reinterpret_cast<const uint32_t *>(p + 4 * jj);
+            float f[6][4];
+#pragma unroll
+            for (int jj = 0; jj < 6; ++jj) {
+                f[jj][0] = (float)(d[jj] & 0xFFu);
+                f[jj][1] = (float)((d[jj] >> 8) & 0xFFu);
+                f[jj][2] = (float)((d[jj] >> 16) & 0xFFu);
+                f[jj][3] = (float)(d[jj] >> 24);
+            }
+#pragma unroll
+            for (int xh = 0; xh < 2; ++xh)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int j = 0; j < 5; ++j) acc[j] = mfma4(wa[8 * cyl + 4 * xh + b], f[j + xh][b], acc[j]);
+        }
+        if constexpr (KS == 2) {   // frames 2-3 join frames 0-1; the buffer alternates, so one barrier per unit
+            v4f *r = red + (((u - u0) & 1) * 2 + hh) * (5 * 64);
+            if (ks == 1) {
+#pragma unroll
+                for (int j = 0; j < 5; ++j) r[j * 64 + lane] = acc[j];
+            }
+            sync_lds();
+            if (ks == 0) {
+#pragma unroll
+                for (int j = 0; j < 5; ++j) acc[j] += r[j * 64 + lane];
+            }
+        }
+        if (ks == 0) {
+            float *y = S.y + ((long)g * 400 + 20 * (4 * strip + oyl) + 5 * q) * 32 + 16 * hh + 4 * kg;
+            constexpr float sc = 1.0f / 255.0f;
+#pragma unroll
+            for (int j = 0; j < 5; ++j) {
+                v4f o;
+                o.x = fmaxf(acc[j].x * sc + bias.x, 0.f);
+                o.y = fmaxf(acc[j].y * sc + bias.y, 0.f);
+                o.z = fmaxf(acc[j].z * sc + bias.z, 0.f);
+                o.w = fmaxf(acc[j].w * sc + bias.w, 0.f);
+                *reinterpret_cast<v4f *>(y + j * 32) = o;
+            }
+        }
+    }
+}
+
+// KS = 1: the four waves of a workgroup are two pairs, each with a unit range of its own.
+// KS = 2: they are one group of four on one unit range.
+template <int KS>
+__global__ __launch_bounds__(256, 2) void k_conv1_fwd_f32(FwdArgsF A)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[4 * RAWSTRIP];
+    __shared__ __attribute__((aligned(16))) v4f red[KS == 2 ? 2 * 2 * 5 * 64 : 1];
+    __shared__ int slot_tab[4][MAX_DRAWS];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hh = wave & 1, ks = KS == 2 ? wave >> 1 : 0;
+    const long ng = (long)gridDim.x * (KS == 2 ? 1 : 2), gid = KS == 2 ? (long)blockIdx.x : (long)blockIdx.x * 2 + (wave >> 1);
+    const long units = (long)A.total * UNITS;
+    const int u0 = (int)(gid * units / ng), u1 = (int)((gid + 1) * units / ng);
+    if (A.draw && u0 < u1) draw_slots(A.samp, A.seg[0].n, u0, u1, slot_tab[wave], lane, hh == 0 && ks == 0);
+    for (int s = 0; s < A.nseg; ++s) {
+        FwdSegF S = A.seg[0];
+        if (s == 1) S = A.seg[1];
+        if (s == 2) S = A.seg[2];
+        const int lo = max(u0, UNITS * S.first) - UNITS * S.first;
+        const int hi = min(u1, UNITS * (S.first + S.n)) - UNITS * S.first;
+        if (lo < hi)
+            conv1_fwd_units_f32<KS>(S, lo, hi, hh, ks, lds + wave * RAWSTRIP, red,
+                                    A.draw ? slot_tab[wave] + (S.first + lo / UNITS - u0 / UNITS) : nullptr, lane);
     }
 }
 
