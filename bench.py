@@ -58,7 +58,7 @@ def gemm_bytes_per_launch(B, R, bf16):
     e = 2 if bf16 else 4                       # activation / shadow-weight element
     a1, a2, a3, hid = 400 * 32 * e, 81 * 64 * e, 49 * 64 * e, 512 * 4
     w1, w2, w3, wf = 32 * 256 * e, 64 * 512 * e, 64 * 576 * e, 512 * 3136 * e
-    frames = B * 5 * 7056 if bf16 else 3 * B * 4 * 7056   # fp32 path reads the gathered stacks
+    frames = B * 5 * 7056 * (1 if bf16 else 2)   # fp32 path: conv1 also writes the gathered 5-frame stacks
     return {
         "conv1_fwd": frames + w1 + 3 * B * a1,
         "conv2_fwd": 3 * B * (a1 + a2) + w2,
