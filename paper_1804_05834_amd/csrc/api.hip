@@ -671,19 +671,19 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     }
     {
         WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
-        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64, 1, 1><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
+        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64, 1, 1, true><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
     }
     {
         split_rows((long)B * 49, 9, MAX_WSPLIT, 64, &rps, ns3);
         WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
         ev_wait(sd, c->ev_a, st);
-        launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64, 1, 1><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G); });
+        launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64, 1, 1, true><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G); });
     }
     {
         split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
         ev_wait(sd, c->ev_b, st);
-        launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64, 1, 1><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
+        launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64, 1, 1, true><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
     }
 }
 

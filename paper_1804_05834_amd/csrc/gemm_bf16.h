@@ -473,7 +473,9 @@ struct WgradArgs {
     float scale;
 };
 
-template <class G, int BMO, int BNK, int WM, int WN>
+// DB: double-buffered LDS tiles (one barrier per reduction stage) and, for a wave with a single
+// output block, two alternating accumulators, as in k_dgrad.
+template <class G, int BMO, int BNK, int WM, int WN, bool DB = false>
 __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_wgrad(WgradArgs A)
 {
     constexpr int WAVES_M = BMO / (32 * WM), WAVES_N = BNK / (32 * WN), T = WAVES_M * WAVES_N * 64;
@@ -482,8 +484,10 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
     constexpr int YR = T / YCH, XR = T / XCH;            // rows filled per pass
     constexpr int NY = (BK + YR - 1) / YR, NX = (BK + XR - 1) / XR;
     using in_t = typename in_type<G>::t;
-    __shared__ __attribute__((aligned(16))) bf16_t Ys[BK * LDY];
-    __shared__ __attribute__((aligned(16))) bf16_t Xs[BK * LDX];
+    constexpr int NBUF = DB ? 2 : 1;
+    constexpr bool ACC2 = DB && WM * WN == 1;
+    __shared__ __attribute__((aligned(16))) bf16_t Ys2[NBUF][BK * LDY];
+    __shared__ __attribute__((aligned(16))) bf16_t Xs2[NBUF][BK * LDX];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // tile order: with row splits (conv layers) all tiles of one split together; without
@@ -516,7 +520,8 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
             rx[i] = (r < BK && m < mend) ? ld8(x + G::row_off(m, A.xs) + xko) : uint4{0, 0, 0, 0};
         }
     };
-    auto sstore = [&]() {
+    auto sstore = [&](int buf) {
+        bf16_t *Ys = Ys2[buf], *Xs = Xs2[buf];
 #pragma unroll
         for (int i = 0; i < NY; ++i) {
             int r = yr + i * YR;
@@ -532,8 +537,7 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
     const int wo = wave % WAVES_M, wk = wave / WAVES_M;
     const int li = lane & 31, h = lane >> 5, s16 = lane & 15, half = (lane >> 4) & 1;
     const int trow = 8 * h + (s16 >> 2), tcol = 16 * half + 4 * (s16 & 3);
-    const bf16_t *yp = &Ys[trow * LDY + wo * 32 * WM + tcol];
-    const bf16_t *xp = &Xs[trow * LDX + wk * 32 * WN + tcol];
+    const int ypo = trow * LDY + wo * 32 * WM + tcol, xpo = trow * LDX + wk * 32 * WN + tcol;
     const bool do_bias = bx == 0 && wk == 0;
     v16f acc[WM][WN], accb[WM];
 #pragma unroll
@@ -546,14 +550,9 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 
-    if (mbeg < mend) {
-        gload(mbeg);
-        sstore();
-    }
-    __syncthreads();
-    for (int mb = mbeg; mb < mend; mb += BK) {
-        const bool more = mb + BK < mend;
-        if (more) gload(mb + BK);
+    v16f acc2 = {0};   // second accumulator (ACC2 only)
+    auto compute = [&](int buf) {
+        const bf16_t *yp = Ys2[buf] + ypo, *xp = Xs2[buf] + xpo;
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 16) {
             v8bf fa[WM], fb[WN];
@@ -564,14 +563,39 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
 #pragma unroll
             for (int a = 0; a < WM; ++a) {
 #pragma unroll
-                for (int b = 0; b < WN; ++b) acc[a][b] = mfma(fa[a], fb[b], acc[a][b]);
+                for (int b = 0; b < WN; ++b) {
+                    if (ACC2 && (kk & 16)) acc2 = mfma(fa[a], fb[b], acc2);
+                    else acc[a][b] = mfma(fa[a], fb[b], acc[a][b]);
+                }
                 if (do_bias) accb[a] = mfma(fa[a], ones, accb[a]);
             }
         }
+    };
+    if constexpr (DB) {
+        if (mbeg < mend) gload(mbeg);
+        int sb = 0;
+        for (int mb = mbeg; mb < mend; mb += BK, sb ^= 1) {
+            sstore(sb);
+            if (mb + BK < mend) gload(mb + BK);
+            sync_lds();   // buffer sb is complete; every wave is past the previous stage, which read buffer sb^1
+            compute(sb);
+        }
+        if (ACC2) acc[0][0] += acc2;
+    } else {
+        if (mbeg < mend) {
+            gload(mbeg);
+            sstore(0);
+        }
         __syncthreads();
-        if (more) {
-            sstore();
+        for (int mb = mbeg; mb < mend; mb += BK) {
+            const bool more = mb + BK < mend;
+            if (more) gload(mb + BK);
+            compute(0);
             __syncthreads();
+            if (more) {
+                sstore(0);
+                __syncthreads();
+            }
         }
     }
 
