@@ -639,6 +639,11 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G2); });
 }
 
+// From this batch on the per-sample conv2 input gradient (weights fetched once per workgroup) beats the
+// tiled kernel, which spreads a small batch over more workgroups.  It is launched with one workgroup
+// per compute unit: the weight-gradient kernels of the side stream run beside it and need the room.
+constexpr int DPS_MIN_BATCH = 384;
+
 void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *ns3, hipStream_t st,
                    hipStream_t sd)
 {
@@ -662,7 +667,9 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     {
         DgradArgs D{d2, sh + net::C2W, act1, d1, B};
         long M = (long)B * 100;
-        launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32, 1, 1><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
+        dps::Args P{d2, sh + net::C2W, act1, d1, B};
+        if (B >= DPS_MIN_BATCH) launch(c, "conv2_dgrad", st, [&] { dps::k_conv2_dgrad_ps<<<std::min(B, c->num_cu), 256, 0, st>>>(P); });
+        else launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32, 1, 1><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
     }
     {  // conv1: one workgroup per split of samples, frames staged in LDS
         *ns1 = std::min(B, MAX_WSPLIT1);

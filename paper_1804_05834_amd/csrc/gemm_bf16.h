@@ -1384,4 +1384,150 @@ __global__ __launch_bounds__(256, 2) void k_conv_fwd_ps(Args A)
     }
 }
 }  // namespace ps
+
+// ===========================================================================
+// Input gradient of conv2, one sample per workgroup (Section 2.1 network, backward pass of the
+// Section 2.2 loss).  dX[pixel][ci] = sum over taps and co of dY[position][co] W[co][tap][ci]:
+// the reduction runs over (tap, co), so the weights are needed with co as the reduction index and
+// ci as the block row.  They are fetched once per workgroup in their natural [co][tap][ci] layout,
+// passed through LDS in two halves of 32 output channels, and read back with the transposing LDS
+// load (ds_read_tr16_b64) straight into a-operand registers, where they stay for all samples.
+//
+// A sample's dY image sits in LDS at a 144-byte pixel pitch inside a border of zeros (written
+// once), so taps that fall outside the image read zeros: no bounds test, and every b-operand is a
+// single 16-byte read at a per-lane base + immediate offset.  The next sample's dY is in flight
+// while the current one is multiplied.  The ReLU mask is the stored activation at the result's
+// own place (16 bytes per lane per block, prefetched); the lane's 8 results are 8 consecutive
+// channels, stored as 16 bytes.
+//
+// The kernel is 4x4 with stride 2, so the 20x20 input pixels fall into four stride-parity classes
+// (y%2, x%2); a pixel of class (py, px) is reached by the four taps (py + 2ty, px + 2tx) only.
+// Wave = class: 100 pixels = 7 position blocks, 4 taps x 64 co = 8 reduction steps, 64 weight
+// registers.  (The same scheme for the 3x3 stride-1 layer needs 144 weight registers per wave; it
+// is faster alone but leaves no room for the kernels that run beside it, and is not used.)
+// ===========================================================================
+namespace dps {
+using ps::u32x4;
+constexpr int PIX = 144;             // LDS bytes per dY pixel (128 + 16)
+constexpr int IMG = 11 * 11 * PIX;   // the 9x9 image inside a border of one zero pixel
+
+struct Args {
+    const bf16_t *dy;    // [B][positions out][64]
+    const bf16_t *w;     // [64][taps][channels in]
+    const bf16_t *xact;  // [B][pixels in][channels in], the layer input after ReLU
+    bf16_t *dx;          // [B][pixels in][channels in]
+    int B;
+};
+
+// a-operand of v_mfma_f32_16x16x32_bf16 out of a [reduction][column] tile in LDS: lane 16kg + s gets
+// reduction rows 8kg .. 8kg+7 of block row s.  The 16 block rows are four runs of four consecutive
+// tile columns; colbyte is the byte offset of the run that block row s belongs to.
+__device__ __forceinline__ v8bf frag_tr16(const uint8_t *tile, int pitch, int lane, int colbyte)
+{
+    typedef __attribute__((address_space(3))) v4s *lds_v4s;
+    typedef short v8s __attribute__((ext_vector_type(8)));
+    const int s = lane & 15, kg = lane >> 4;
+    const uint8_t *p = tile + (8 * kg + (s >> 2)) * pitch + colbyte;
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p));
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(p + 4 * pitch));
+    const v8s r = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    return __builtin_bit_cast(v8bf, r);
+}
+
+// 8 results of a lane through the ReLU mask (activation bits > 0 as a signed 16-bit test) to 16 bytes
+__device__ __forceinline__ uint4 masked8(const uint4 m, const v4f a0, const v4f a1)
+{
+    auto keep = [](uint32_t w2, int hi, float v) { return (int16_t)(hi ? (w2 >> 16) : (w2 & 0xFFFFu)) > 0 ? v : 0.f; };
+    const uint2 lo = pack4(keep(m.x, 0, a0.x), keep(m.x, 1, a0.y), keep(m.y, 0, a0.z), keep(m.y, 1, a0.w));
+    const uint2 hi = pack4(keep(m.z, 0, a1.x), keep(m.z, 1, a1.y), keep(m.w, 0, a1.z), keep(m.w, 1, a1.w));
+    return uint4{lo.x, lo.y, hi.x, hi.y};
+}
+
+constexpr int W2PITCH = 512 * 2 + 16;   // LDS bytes per conv2 weight row in transit (one co: 16 taps x 32 ci)
+
+// dy [B][81][64], w [64][4][4][32], xact and dx [B][400][32]
+__global__ __launch_bounds__(256, 2) void k_conv2_dgrad_ps(Args A)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[IMG + 32 * W2PITCH];
+    uint8_t *img = lds, *wt = lds + IMG;
+    const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), py = wave >> 1, px = wave & 1;
+    const int g0 = (int)((long)blockIdx.x * A.B / gridDim.x), g1 = (int)((long)(blockIdx.x + 1) * A.B / gridDim.x);
+    if (g0 >= g1) return;
+    // a sample's dY is 648 pieces of 16 bytes; the first sample's is on its way while the weights pass through
+    u32x4 r0, r1, r2;
+    auto load_dy = [&](int g) {
+        const u32x4 *p = reinterpret_cast<const u32x4 *>(A.dy + (long)g * (81 * 64));
+        r0 = p[tid]; r1 = p[tid + 256]; r2 = p[tid < 136 ? tid + 512 : 647];
+    };
+    load_dy(g0);
+    for (int i = tid; i < IMG / 16; i += 256) *reinterpret_cast<u32x4 *>(img + i * 16) = u32x4{0, 0, 0, 0};
+    // wa[2 tap + co half][ci block], tap = 2ty + tx = kernel element (py + 2ty, px + 2tx); block row s of ci
+    // block cb is input channel 8(s/4) + 4cb + s%4, so a lane's 8 results are 8 consecutive channels
+    v8bf wa[8][2];
+    for (int half = 0; half < 2; ++half) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(A.w + half * 32 * 512);
+        sync_lds();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = tid + 256 * i;   // row (co) c / 64, 16-byte piece c % 64
+            *reinterpret_cast<u32x4 *>(wt + (c >> 6) * W2PITCH + (c & 63) * 16) = src[c];
+        }
+        sync_lds();
+#pragma unroll
+        for (int tap = 0; tap < 4; ++tap)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                const int ky = py + 2 * (tap >> 1), kx = px + 2 * (tap & 1);
+                const int col = (ky * 4 + kx) * 32 + 8 * (n & 3) + 4 * cb;
+                wa[2 * tap + half][cb] = frag_tr16(wt, W2PITCH, lane, col * 2);
+            }
+    }
+    // pixel (2a + py, 2b + px) takes dY positions (a - ty, b - tx); image pixel (a - ty + 1, b - tx + 1) holds them.
+    // base = the (ty, tx) = (1, 1) corner, i.e. image pixel (a, b)
+    uint32_t base[7];
+    int pos[7];
+#pragma unroll
+    for (int b = 0; b < 7; ++b) {
+        int p = 16 * b + n;
+        pos[b] = p;
+        if (p > 99) p = 99;
+        base[b] = ((p / 10) * 11 + (p % 10)) * PIX + kg * 16;
+    }
+    for (int g = g0; g < g1; ++g) {
+        sync_lds();   // the previous sample's image (and, the first time, the weights in transit) has been read
+#define DPS_ST(I, V) { const int t = tid + 256 * I; const int q = t >> 3; *reinterpret_cast<u32x4 *>(img + ((q / 9 + 1) * 11 + q % 9 + 1) * PIX + (t & 7) * 16) = V; }
+        DPS_ST(0, r0) DPS_ST(1, r1)
+        if (tid < 136) DPS_ST(2, r2)
+#undef DPS_ST
+        if (g + 1 < g1) load_dy(g + 1);
+        const long obase = (long)g * (400 * 32) + 8 * kg;
+        uint4 mk[7];
+#pragma unroll
+        for (int b = 0; b < 7; ++b) {
+            const int p = pos[b] > 99 ? 99 : pos[b];
+            const int y = 2 * (p / 10) + py, x = 2 * (p % 10) + px;
+            mk[b] = *reinterpret_cast<const uint4 *>(A.xact + obase + (y * 20 + x) * 32);
+        }
+        sync_lds();
+#pragma unroll
+        for (int b = 0; b < 7; ++b) {
+            v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+            for (int st = 0; st < 8; ++st) {
+                const int tap = st >> 1, ty = tap >> 1, tx = tap & 1;
+                const int off = ((1 - ty) * 11 + (1 - tx)) * PIX + (st & 1) * 64;
+                const v8bf bb = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(img + base[b] + off));
+                acc0 = mfma16(wa[st][0], bb, acc0);
+                acc1 = mfma16(wa[st][1], bb, acc1);
+            }
+            if (pos[b] < 100) {
+                const int p = pos[b];
+                const int y = 2 * (p / 10) + py, x = 2 * (p % 10) + px;
+                *reinterpret_cast<uint4 *>(A.dx + obase + (y * 20 + x) * 32) = masked8(mk[b], acc0, acc1);
+            }
+        }
+    }
+}
+}  // namespace dps
 }  // namespace gbf
