@@ -178,12 +178,17 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
     __shared__ float shm[16];
     const int j = blockIdx.x, tid = threadIdx.x;
     const int K = A.K, R = K + (A.dueling ? 1 : 0);
-    float wnorm = 1.f;
-    if (A.w && A.w_raw) {  // maximum of the minibatch's raw importance weights (Alg.2 weighting line)
-        float m = 0.f;
-        for (int t = tid; t < A.B; t += 512) m = fmaxf(m, A.w[t]);
-        wnorm = 1.f / block_max_1024(m, shm);
-    }
+    // Everything the row needs from global memory is requested before the first barrier: the raw
+    // importance weights (for their maximum, Alg.2 weighting line), the row's transition, the
+    // head weights and the fc1 partial sums.
+    const bool norm = A.w && A.w_raw;
+    float wmax = 0.f;
+    if (norm)
+        for (int t = tid; t < A.B; t += 512) wmax = fmaxf(wmax, A.w[t]);
+    const int aj = A.a[j];
+    const bool dn = A.done[j] != 0;
+    const float rj = A.r[j];
+    const float wj = A.w ? A.w[j] : 1.f;
 
     // column tid of the online head (for the back-propagation into the hidden layer at the end)
     // and the head weights of the first two rounds (all of them when 3R <= 64) are requested now
@@ -202,6 +207,11 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         hid[2][i] = hidden_unit(A.part, A.nsplit, A.split_stride, 2L * A.B + j, i, A.f1b_tg);
         A.h_s[(long)j * net::HID + i] = hs;
     }
+    if (norm) {  // per-wave maxima; thread 0 combines them after the barriers below
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, o, 64));
+        if ((tid & 63) == 0) shm[tid >> 6] = wmax;
+    }
     __syncthreads();
     head_rows3_dot(H0, hid, K, A.dueling, raw, tid);
     head_rows3_dot(H1, hid, K, A.dueling, raw, tid);
@@ -213,12 +223,17 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
     if (tid < 3) combine_q(raw[tid], K, A.dueling, q[tid]);
     __syncthreads();
     if (tid == 0) {
-        const int aj = A.a[j];
+        float wnorm = 1.f;
+        if (norm) {
+            float m = shm[0];
+            for (int v = 1; v < 8; ++v) m = fmaxf(m, shm[v]);
+            wnorm = 1.f / m;
+        }
         const int as = argmax_low(A.double_q ? q[1] : q[2], K);
-        const float boot = A.done[j] ? 0.f : A.gamma * q[2][as];
-        const float y = A.r[j] + boot;
+        const float boot = dn ? 0.f : A.gamma * q[2][as];
+        const float y = rj + boot;
         const float d = y - q[0][aj];
-        const float w = A.w ? A.w[j] * wnorm : 1.f;
+        const float w = A.w ? wj * wnorm : 1.f;
         float l, dl;
         if (A.loss_kind == 1 && fabsf(d) > A.kappa) {
             l = A.kappa * (fabsf(d) - 0.5f * A.kappa);
