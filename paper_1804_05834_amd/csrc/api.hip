@@ -519,9 +519,10 @@ void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipS
 // ----- small-batch tail: everything that is left once the input gradients are done -----
 // For a small batch on one stream the four trunk weight gradients, the head weight gradient and
 // the priority update are each a few short tiles; one launch of 256-thread workgroups runs them
-// side by side.  Workgroups [begin[p], begin[p+1]): p = 0..3 the trunk layers (conv1, conv2,
-// conv3, fc1), 4 the head (row r, 32 hidden units per workgroup), 5 the priority update (one
-// workgroup, at most 256 entries).
+// side by side.  The priority update, a single workgroup and the longest of them (twenty tree
+// levels, one after the other), comes first in dispatch order so that it starts with the launch;
+// then workgroups [begin[p], begin[p+1]): p = 0..3 the trunk layers (conv1, conv2, conv3, fc1),
+// 4 the head (row r, 32 hidden units per workgroup).
 struct SmallTail {
     misc::HeadWgradArgs head;
     misc::PerUpdateArgs update;
@@ -529,7 +530,8 @@ struct SmallTail {
 };
 struct SmallTailArgs {
     g32::WgradArgs a[4];
-    int begin[7];
+    int begin[6];
+    int update_first;   // 1: workgroup 0 is the priority update (at most 256 entries), the others follow
     int gx[4], gy[4], gz[4];
     misc::HeadWgradArgs head;
     misc::PerUpdateArgs update;
@@ -542,10 +544,14 @@ __global__ __launch_bounds__(256) void k_small_tail(SmallTailArgs A)
     __shared__ __attribute__((aligned(16))) float lds[L];
     // plain dispatch order: the problems' tiles differ in length, and round-robin over the dies
     // spreads each of them over all dies
-    const int t = blockIdx.x;
+    if (A.update_first && blockIdx.x == 0) {
+        misc::per_update_body(A.update, reinterpret_cast<int *>(lds));
+        return;
+    }
+    const int t = blockIdx.x - A.update_first;
     int p = 0;
 #pragma unroll
-    for (int q = 1; q < 6; ++q)
+    for (int q = 1; q < 5; ++q)
         if (t >= A.begin[q]) p = q;
     const int u = t - A.begin[p];
     int bx, by, bz;
@@ -561,10 +567,8 @@ __global__ __launch_bounds__(256) void k_small_tail(SmallTailArgs A)
     } else if (p == 3) {
         wgrad_tile_of(u, A.gx[3], A.gy[3], A.gz[3], bx, by, bz);
         wgrad_tile<GFc1, 64, 64>(A.a[3], bx, by, bz, lds);
-    } else if (p == 4) {
-        misc::head_wgrad_body<8>(A.head, u / 16, u % 16, lds);
     } else {
-        misc::per_update_body(A.update, reinterpret_cast<int *>(lds));
+        misc::head_wgrad_body<8>(A.head, u / 16, u % 16, lds);
     }
 }
 
@@ -626,8 +630,8 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
             total += c->R * 16;
         }
         A.begin[5] = total;
-        if (tail && tail->with_update) total += 1;
-        A.begin[6] = total;
+        A.update_first = tail && tail->with_update ? 1 : 0;
+        total += A.update_first;
         launch(c, "small_tail", st, [&] { k_small_tail<<<dim3(total), 256, 0, st>>>(A); });
         return;
     }
