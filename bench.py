@@ -37,6 +37,8 @@ def flops_per_launch(B, R):
         "fc1_dgrad": B * F_FC1, "fc1_wgrad": B * F_FC1, "conv3_dgrad": B * F_CONV3,
         "conv3_wgrad": B * F_CONV3, "conv2_dgrad": B * F_CONV2, "conv2_wgrad": B * F_CONV2,
         "conv1_wgrad": B * F_CONV1,
+        # bf16: a layer's input gradient and weight gradient share one launch
+        "fc1_bwd": 2 * B * F_FC1, "conv3_bwd": 2 * B * F_CONV3, "conv2_bwd": 2 * B * F_CONV2,
         "small_tail": B * (F_CONV1 + F_CONV2 + F_CONV3 + F_FC1),  # all weight gradients in one launch (small fp32 batches)
     }
 
@@ -71,6 +73,10 @@ def gemm_bytes_per_launch(B, R, bf16):
         "conv2_wgrad": B * (a1 + a2) + 64 * 512 * 4,
         "conv3_wgrad": B * (a2 + a3) + 64 * 576 * 4,
         "fc1_wgrad": B * (a3 + 512 * e) + 512 * 3136 * 4,
+        # the merged launches read dY and the layer input once for both gradients
+        "fc1_bwd": B * (512 * e + 2 * a3) + wf + 512 * 3136 * 4,
+        "conv3_bwd": B * (a3 + 2 * a2) + w3 + 64 * 576 * 4,
+        "conv2_bwd": B * (a2 + 2 * a1) + w2 + 64 * 512 * 4,
     }
 
 
@@ -84,13 +90,7 @@ MEASURED_TRAFFIC = {
     ("conv3_fwd", 512, "bf16"): 16.8e6 + 9.5e6,
     ("fc1_fwd", 512, "bf16"): 19.9e6 + 21.7e6,
     ("head_train", 512, "bf16"): 22.4e6 + 1.6e6,
-    ("fc1_dgrad", 512, "bf16"): 11.4e6 + 3.2e6,
-    ("conv3_dgrad", 512, "bf16"): 8.9e6 + 5.2e6,
-    ("conv2_dgrad", 512, "bf16"): 18.5e6 + 12.9e6,
     ("conv1_wgrad", 512, "bf16"): 27.1e6 + 8.3e6,
-    ("conv2_wgrad", 512, "bf16"): 19.5e6 + 7.7e6,
-    ("conv3_wgrad", 512, "bf16"): 8.4e6 + 8.2e6,
-    ("fc1_wgrad", 512, "bf16"): 7.7e6 + 6.3e6,
     ("rmsprop", 512, "bf16"): 43.4e6 + 23.4e6,
 }
 

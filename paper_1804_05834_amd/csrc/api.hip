@@ -643,13 +643,12 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G2); });
 }
 
-// From this batch on the per-sample conv2 input gradient (weights fetched once per workgroup) beats the
-// tiled kernel, which spreads a small batch over more workgroups.  It is launched with one workgroup
-// per compute unit: the weight-gradient kernels of the side stream run beside it and need the room.
-constexpr int DPS_MIN_BATCH = 384;
-
-void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *ns3, hipStream_t st,
-                   hipStream_t sd)
+// bf16: one stream and one launch per layer, the layer's input gradient and weight gradient side by
+// side in it (both read the layer's dY and nothing else that the backward pass computes).  Events
+// between streams cost more than they gain here: a record or a wait on the critical stream adds
+// about 4 us to the gap between two kernels, and a kernel on another stream starts 11-14 us after
+// the kernel it waits for has ended.
+void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *ns3, hipStream_t st)
 {
     using namespace gbf;
     const Workspace &w = c->ws;
@@ -659,42 +658,30 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     int rps;
     {
         DgradArgs D{dh, sh + net::F1W, act3, d3, B};
-        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 64, 64, 1, 1, true><<<dim3((B + 63) / 64, 49, 1), 256, 0, st>>>(D); });
-        ev_record(c->ev_a, st, sd);
+        WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
+        const int gx = (B + 63) / 64;
+        PairGrid P{gx * 49, gx, 1, 49 * 8, 49, 8, 1};
+        launch(c, "fc1_bwd", st, [&] { k_bwd_pair<DFc1, GFc1><<<P.nd + P.nw, 256, 0, st>>>(D, G, P); });
     }
     {
         DgradArgs D{d3, sh + net::C3W, act2, d2, B};
-        long M = (long)B * 81;
-        launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64, 1, 1, true><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
-        ev_record(c->ev_b, st, sd);
+        split_rows((long)B * 49, 9, MAX_WSPLIT, 64, &rps, ns3);
+        WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
+        const int nd = (int)(((long)B * 81 + 63) / 64);
+        PairGrid P{nd, nd, 1, 9 * *ns3, 9, 1, *ns3};
+        launch(c, "conv3_bwd", st, [&] { k_bwd_pair<DConv3, GConv3><<<P.nd + P.nw, 256, 0, st>>>(D, G, P); });
     }
-    {
-        DgradArgs D{d2, sh + net::C2W, act1, d1, B};
-        long M = (long)B * 100;
+    {   // conv2: the per-sample input gradient, at most one workgroup per CU, beside the tiled weight gradient
         dps::Args P{d2, sh + net::C2W, act1, d1, B};
-        if (B >= DPS_MIN_BATCH) launch(c, "conv2_dgrad", st, [&] { dps::k_conv2_dgrad_ps<<<std::min(B, c->num_cu), 256, 0, st>>>(P); });
-        else launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 128, 32, 1, 1><<<dim3((M + 127) / 128, 1, 4), 256, 0, st>>>(D); });
+        split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
+        WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
+        const int nps = std::min(B, c->num_cu), nw = 8 * *ns2, gz = *ns2;
+        launch(c, "conv2_bwd", st, [&] { dps::k_conv2_bwd_pair<<<nps + nw, 256, 0, st>>>(P, G, nps, nw, 8, 1, gz); });
     }
-    {  // conv1: one workgroup per split of samples, frames staged in LDS
+    {   // conv1: one workgroup per split of samples, frames staged in LDS
         *ns1 = std::min(B, MAX_WSPLIT1);
         c1::WgradArgs G{c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift}, d1, w.gp1, B, *ns1};
         launch(c, "conv1_wgrad", st, [&] { c1::k_conv1_wgrad<<<dim3(*ns1, 2), 256, 0, st>>>(G); });
-    }
-    {
-        WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
-        launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64, 1, 1, true><<<dim3(49, 8, 1), 256, 0, sd>>>(G); });
-    }
-    {
-        split_rows((long)B * 49, 9, MAX_WSPLIT, 64, &rps, ns3);
-        WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
-        ev_wait(sd, c->ev_a, st);
-        launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64, 1, 1, true><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G); });
-    }
-    {
-        split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
-        WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
-        ev_wait(sd, c->ev_b, st);
-        launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64, 1, 1, true><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G); });
     }
 }
 
@@ -1185,12 +1172,14 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     H.a_star = O.a_star; H.is_w = O.is_w;
     launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 512, 0, st>>>(H); });
 
-    // fork: the weight gradients of the trunk go to one side stream, the head weight gradient
-    // and the priority update to another; both join again before the optimizer
+    // fork: the weight gradients of the trunk go to one side stream (fp32 only: the bf16 backward
+    // pass keeps them on st), the head weight gradient and the priority update to another; they
+    // join again before the optimizer
     // (a small batch stays on one stream: its kernels are too short to repay the hand-overs)
-    hipStream_t sd = (c->side && B > 64) ? c->side : st;
-    hipStream_t sp = (c->side2 && sd != st) ? c->side2 : sd;
-    ev_record(c->ev_fork, st, sd);
+    const bool multi = c->side && B > 64;
+    hipStream_t sd = (multi && cfg.precision == 0) ? c->side : st;
+    hipStream_t sp = multi ? (c->side2 ? c->side2 : c->side) : st;
+    if (sd != st || sp != st) (void)hipEventRecord(c->ev_fork, st);
     ev_wait(sd, c->ev_fork, st);
     if (sp != sd) ev_wait(sp, c->ev_fork, st);
     misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
@@ -1208,7 +1197,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     if (sp != sd) (void)hipEventRecord(c->ev_join2, sp);
 
     int ns1, ns2, ns3;
-    if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, sd);
+    if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st);
     else backward_f32(c, B, stacking ? w.stack5 : s, stacking ? 5L * net::FRAME : xs, &ns1, &ns2, &ns3, st, sd,
                       fuse_tail ? &tail : nullptr);
     ev_record(c->ev_join, sd, st);

@@ -298,8 +298,13 @@ struct DgradArgs {
 // (for the layers whose stages are so short that the barriers dominate them), and a wave with a
 // single output block alternates between two accumulators so that consecutive MFMAs do not wait
 // for each other's result.
-template <class D, int BM, int BN, int WM, int WN, bool DB = false>
-__global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dgrad(DgradArgs A)
+// LDS elements of an input-gradient tile
+template <int BM, int BN, bool DB> constexpr int dgrad_lds() { return (DB ? 2 : 1) * (BM * LDK + BK * (BN + 8)); }
+
+// Tile number t of a (gx, gy, gz) grid of tiles; tile order: the parity classes of one row tile
+// together, then the row tiles of one column tile.
+template <class D, int BM, int BN, int WM, int WN, bool DB>
+__device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, int gz, bf16_t *lds)
 {
     constexpr int WAVES_M = BM / (32 * WM), WAVES_N = BN / (32 * WN), T = WAVES_M * WAVES_N * 64;
     constexpr int NA = BM * 8 / T;
@@ -310,13 +315,11 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
     static_assert(NA * T == BM * 8 && D::CO % BK == 0, "tile/threads mismatch");
     constexpr int NBUF = DB ? 2 : 1;
     constexpr bool ACC2 = DB && WM * WN == 1;
-    __shared__ __attribute__((aligned(16))) bf16_t As2[NBUF][BM * LDK];
-    __shared__ __attribute__((aligned(16))) bf16_t Bs2[NBUF][BK * LDB];
+    bf16_t(*As2)[BM * LDK] = reinterpret_cast<bf16_t(*)[BM * LDK]>(lds);
+    bf16_t(*Bs2)[BK * LDB] = reinterpret_cast<bf16_t(*)[BK * LDB]>(lds + NBUF * BM * LDK);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // tile order: the parity classes of one row tile together, then the row tiles of one column tile
-    const int t = net::tile_of_workgroup();
-    const int bz = t % (int)gridDim.z, bx = (t / (int)gridDim.z) % (int)gridDim.x, by = t / (int)(gridDim.z * gridDim.x);
+    const int bz = t % gz, bx = (t / gz) % gx, by = t / (gz * gx);
     const int m0 = bx * BM, n0 = by * BN;
     const int ca = bz / D::S, cb = bz % D::S;
     const int Mc = A.B * D::PP;
@@ -461,6 +464,7 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_dg
     }
 }
 
+
 // ---------------------------------------------------------------------------
 struct WgradArgs {
     const bf16_t *dy;  // [B*P][N]
@@ -473,10 +477,15 @@ struct WgradArgs {
     float scale;
 };
 
+// LDS elements of a weight-gradient tile
+template <int BMO, int BNK, bool DB> constexpr int wgrad_lds() { return (DB ? 2 : 1) * BK * (BMO + 8 + BNK + 8); }
+
+// Tile number t of a (gx, gy, gz) grid of tiles; tile order: with row splits (conv layers) all
+// tiles of one split together; without (fc1) all output tiles of one input-column tile together.
 // DB: double-buffered LDS tiles (one barrier per reduction stage) and, for a wave with a single
-// output block, two alternating accumulators, as in k_dgrad.
-template <class G, int BMO, int BNK, int WM, int WN, bool DB = false>
-__global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_wgrad(WgradArgs A)
+// output block, two alternating accumulators, as in the input gradient.
+template <class G, int BMO, int BNK, int WM, int WN, bool DB>
+__device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int t, int gx, int gy, int gz, bf16_t *lds)
 {
     constexpr int WAVES_M = BMO / (32 * WM), WAVES_N = BNK / (32 * WN), T = WAVES_M * WAVES_N * 64;
     constexpr int LDY = BMO + 8, LDX = BNK + 8;
@@ -486,18 +495,15 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
     using in_t = typename in_type<G>::t;
     constexpr int NBUF = DB ? 2 : 1;
     constexpr bool ACC2 = DB && WM * WN == 1;
-    __shared__ __attribute__((aligned(16))) bf16_t Ys2[NBUF][BK * LDY];
-    __shared__ __attribute__((aligned(16))) bf16_t Xs2[NBUF][BK * LDX];
+    bf16_t(*Ys2)[BK * LDY] = reinterpret_cast<bf16_t(*)[BK * LDY]>(lds);
+    bf16_t(*Xs2)[BK * LDX] = reinterpret_cast<bf16_t(*)[BK * LDX]>(lds + NBUF * BK * LDY);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // tile order: with row splits (conv layers) all tiles of one split together; without
-    // (fc1) all output tiles of one input-column tile together
-    const int t = net::tile_of_workgroup();
     int bx, by, bz;
-    if (gridDim.z > 1) {
-        bx = t % (int)gridDim.x; by = (t / (int)gridDim.x) % (int)gridDim.y; bz = t / (int)(gridDim.x * gridDim.y);
+    if (gz > 1) {
+        bx = t % gx; by = (t / gx) % gy; bz = t / (gx * gy);
     } else {
-        by = t % (int)gridDim.y; bx = t / (int)gridDim.y; bz = 0;
+        by = t % gy; bx = t / gy; bz = 0;
     }
     const int kc0 = bx * BNK, o0 = by * BMO;
     const int mbeg = bz * A.rps;
@@ -613,6 +619,31 @@ __global__ __launch_bounds__((BMO / (32 * WM)) * (BNK / (32 * WN)) * 64) void k_
             if (do_bias && li == 0) part[(long)G::N * G::K + o] = accb[a][r];
         }
     }
+}
+
+// Dispatch-order number u of `total` workgroups -> tile number, die-aware as net::tile_of_workgroup
+// (a launch that holds two problems numbers each of them by itself).
+__device__ __forceinline__ int tile_of(int u, int total)
+{
+    const int die = u & 7, slot = u >> 3, q = total >> 3, r = total & 7;
+    return die * q + (die < r ? die : r) + slot;
+}
+
+// The input gradient and the weight gradient of one layer in ONE launch of 64x64 tiles (both read
+// the layer's dY and depend on nothing else that is computed in the backward pass): workgroups
+// [0, nd) are the input-gradient tiles, [nd, nd + nw) the weight-gradient tiles.
+struct PairGrid {
+    int nd, dgx, dgz;        // input gradient: tiles, grid x and z
+    int nw, wgx, wgy, wgz;   // weight gradient: tiles, grid
+};
+template <class D, class G>
+__global__ __launch_bounds__(256) void k_bwd_pair(DgradArgs DA, WgradArgs WA, PairGrid P)
+{
+    constexpr int LD = dgrad_lds<64, 64, true>(), LW = wgrad_lds<64, 64, true>();
+    __shared__ __attribute__((aligned(16))) bf16_t lds[LD > LW ? LD : LW];
+    const int id = blockIdx.x;
+    if (id < P.nd) dgrad_tile<D, 64, 64, 1, 1, true>(DA, tile_of(id, P.nd), P.dgx, P.dgz, lds);
+    else wgrad_tile<G, 64, 64, 1, 1, true>(WA, tile_of(id - P.nd, P.nw), P.wgx, P.wgy, P.wgz, lds);
 }
 
 
@@ -1127,14 +1158,14 @@ constexpr int LDY1 = 40;  // row stride (elements) of the staged dY tile
 
 // grid (nsplit, 2): a workgroup takes one channel pair y (frames 2y, 2y+1 = im2col columns
 // 128y .. 128y+127), so a workgroup stages half a state and two workgroups fit one CU.
-__global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
+constexpr int WG1_LDS = 2 * FR + 400 * LDY1;   // LDS elements of a workgroup
+// tile = 2 * split + channel pair
+__device__ __forceinline__ void conv1_wgrad_block(const WgradArgs &A, int tile, bf16_t *lds)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t xin[2 * FR];
-    __shared__ __attribute__((aligned(16))) bf16_t dys[400 * LDY1];
+    bf16_t *xin = lds, *dys = lds + 2 * FR;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;  // wave = block of 32 im2col columns
     const int li = lane & 31, h = lane >> 5, s16 = lane & 15, half = (lane >> 4) & 1;
     // the two channel pairs of one sample split run next to each other: same dY, same ring slots
-    const int tile = net::tile_of_workgroup();
     const int cp = tile & 1, split = tile >> 1;
     typedef __attribute__((address_space(3))) v4s *lds_v4s;
 
@@ -1202,6 +1233,11 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
         part[o * 256 + 128 * cp + 32 * wave + li] = (acc[r] + acc2[r]) * (1.0f / 255.0f);
         if (do_bias && li == 0) part[32 * 256 + o] = accb[r];
     }
+}
+__global__ __launch_bounds__(256) void k_conv1_wgrad(WgradArgs A)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t lds[WG1_LDS];
+    conv1_wgrad_block(A, net::tile_of_workgroup(), lds);
 }
 }  // namespace c1
 
@@ -1445,14 +1481,13 @@ __device__ __forceinline__ uint4 masked8(const uint4 m, const v4f a0, const v4f 
 
 constexpr int W2PITCH = 512 * 2 + 16;   // LDS bytes per conv2 weight row in transit (one co: 16 taps x 32 ci)
 
-// dy [B][81][64], w [64][4][4][32], xact and dx [B][400][32]
-__global__ __launch_bounds__(256, 2) void k_conv2_dgrad_ps(Args A)
+// dy [B][81][64], w [64][4][4][32], xact and dx [B][400][32]; workgroup `bid` of `nblocks`
+__device__ __forceinline__ void conv2_dgrad_ps_body(const Args &A, int bid, int nblocks, uint8_t *lds)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[IMG + 32 * W2PITCH];
     uint8_t *img = lds, *wt = lds + IMG;
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kg = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), py = wave >> 1, px = wave & 1;
-    const int g0 = (int)((long)blockIdx.x * A.B / gridDim.x), g1 = (int)((long)(blockIdx.x + 1) * A.B / gridDim.x);
+    const int g0 = (int)((long)bid * A.B / nblocks), g1 = (int)((long)(bid + 1) * A.B / nblocks);
     if (g0 >= g1) return;
     // a sample's dY is 648 pieces of 16 bytes; the first sample's is on its way while the weights pass through
     u32x4 r0, r1, r2;
@@ -1528,6 +1563,17 @@ __global__ __launch_bounds__(256, 2) void k_conv2_dgrad_ps(Args A)
             }
         }
     }
+}
+constexpr int PS_LDS = IMG + 32 * W2PITCH;   // bytes
+// conv2's per-sample input gradient (workgroups [0, nps)) and its tiled weight gradient (the nw
+// workgroups after them) in one launch: both read conv2's dY.
+__global__ __launch_bounds__(256, 2) void k_conv2_bwd_pair(Args PA, WgradArgs WA, int nps, int nw, int wgx, int wgy, int wgz)
+{
+    constexpr int LW = wgrad_lds<64, 64, true>() * 2;   // bytes
+    __shared__ __attribute__((aligned(16))) uint8_t lds[PS_LDS > LW ? PS_LDS : LW];
+    const int id = blockIdx.x;
+    if (id < nps) conv2_dgrad_ps_body(PA, id, nps, lds);
+    else wgrad_tile<GConv2, 64, 64, 1, 1, true>(WA, tile_of(id - nps, nw), wgx, wgy, wgz, reinterpret_cast<bf16_t *>(lds));
 }
 }  // namespace dps
 }  // namespace gbf

@@ -533,18 +533,34 @@ __global__ __launch_bounds__(1024) void k_per_normalise(float *is_w, int B)
 // the paths one after another).  All walkers sit on one compute unit, so workgroup scope is
 // enough: a store is complete before the barrier and the load after it sees it.  Every thread
 // of the workgroup must call this (it contains barriers).
-__device__ __forceinline__ void tree_walk(float *tree, int node, float v, bool walk, int levels)
+// W walkers per thread (a thread's walkers take the levels together).
+template <int W>
+__device__ __forceinline__ void tree_walk(float *tree, int (&node)[W], float (&v)[W], const bool (&walk)[W], int levels)
 {
-    if (walk) __hip_atomic_store(&tree[node], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+    for (int w = 0; w < W; ++w)
+        if (walk[w]) __hip_atomic_store(&tree[node[w]], v[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     for (int l = 0; l < levels; ++l) {
         __syncthreads();
-        if (walk) {
-            const float vs = __hip_atomic_load(&tree[node ^ 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            v = v + vs;
-            node >>= 1;
-            __hip_atomic_store(&tree[node], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
+        float vs[W];
+#pragma unroll
+        for (int w = 0; w < W; ++w)
+            vs[w] = walk[w] ? __hip_atomic_load(&tree[node[w] ^ 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : 0.f;
+#pragma unroll
+        for (int w = 0; w < W; ++w)
+            if (walk[w]) {
+                v[w] = v[w] + vs[w];
+                node[w] >>= 1;
+                __hip_atomic_store(&tree[node[w]], v[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
     }
+}
+__device__ __forceinline__ void tree_walk(float *tree, int node, float v, bool walk, int levels)
+{
+    int n1[1] = {node};
+    float v1[1] = {v};
+    const bool w1[1] = {walk};
+    tree_walk<1>(tree, n1, v1, w1, levels);
 }
 
 // Priority update (Eq.11): a single workgroup, one thread per entry.  Repeated
@@ -590,7 +606,9 @@ struct PerUpdateArgs {
 };
 constexpr int PU_LDS_WORDS = 2 * PU_SLOTS + 16;  // LDS of per_update_body, in 4-byte words
 
-// The whole workgroup (blockDim.x >= n threads) must call this.  lds: PU_LDS_WORDS words.
+// The whole workgroup must call this; it handles W entries per thread (W * blockDim.x >= n).
+// lds: PU_LDS_WORDS words.
+template <int W = 1>
 __device__ __forceinline__ void per_update_body(const PerUpdateArgs &A, int *lds)
 {
     int *keys = lds, *ivals = lds + PU_SLOTS;  // ivals: largest entry number naming the slot's leaf
@@ -601,41 +619,58 @@ __device__ __forceinline__ void per_update_body(const PerUpdateArgs &A, int *lds
     const int32_t *idx = A.idx;
     const float *td_abs = A.td_abs;
     const float alpha = A.alpha, eps = A.eps;
-    const int j = threadIdx.x, nt = blockDim.x;
-    int my = -1;
-    float p = 0.f;
-    if (j < n) {
-        const int v = idx[j];
-        p = (float)((double)fabsf(td_abs[j]) + (double)eps);
-        // an entry with a slot outside the ring or a non-finite error is skipped: its leaf keeps
-        // its value, and the tree stays a tree of finite sums
-        if (v >= 0 && v < size && p <= 3.0e38f) my = v;   // the comparison is false for NaN
+    const int tid = threadIdx.x, nt = blockDim.x;
+    int my[W];
+    float p[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const int j = tid + w * nt;
+        my[w] = -1;
+        p[w] = 0.f;
+        if (j < n) {
+            const int v = idx[j];
+            p[w] = (float)((double)fabsf(td_abs[j]) + (double)eps);
+            // an entry with a slot outside the ring or a non-finite error is skipped: its leaf keeps
+            // its value, and the tree stays a tree of finite sums
+            if (v >= 0 && v < size && p[w] <= 3.0e38f) my[w] = v;   // the comparison is false for NaN
+        }
     }
-    const bool valid = my >= 0;
-    for (int t = j; t < PU_SLOTS; t += nt) { keys[t] = -1; ivals[t] = -1; }
+    for (int t = tid; t < PU_SLOTS; t += nt) { keys[t] = -1; ivals[t] = -1; }
     __syncthreads();
-    int node = (int)L + (valid ? my : 0);
-    bool first;
-    int slot = 0;
-    if (valid) {
-        slot = pu_insert(keys, node, &first);
-        atomicMax(&ivals[slot], j);
+    int node[W], slot[W];
+    float pm = 0.f;
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const bool valid = my[w] >= 0;
+        node[w] = (int)L + (valid ? my[w] : 0);
+        slot[w] = 0;
+        if (valid) {
+            bool first;
+            slot[w] = pu_insert(keys, node[w], &first);
+            atomicMax(&ivals[slot[w]], tid + w * nt);
+            pm = fmaxf(pm, p[w]);
+        }
     }
-    const float pmax = block_max_1024(valid ? p : 0.f, sh);  // contains barriers
-    if (j == 0) tree[2 * L] = fmaxf(tree[2 * L], pmax);
-    // One thread per distinct leaf (the last entry naming it) walks to the root.  A level is one
+    const float pmax = block_max_1024(pm, sh);  // contains barriers
+    if (tid == 0) tree[2 * L] = fmaxf(tree[2 * L], pmax);
+    // One walker per distinct leaf (the last entry naming it) walks to the root.  A level is one
     // exchange through memory: every walker publishes its node, the workgroup meets, every
     // walker reads its sibling as it now stands.  Walkers whose paths have merged hold the same
     // value and store it to the same word.
-    const bool walk = valid && ivals[slot] == j;
-    float v = (float)pow((double)p, (double)alpha);
-    tree_walk(tree, node, v, walk, levels);
+    bool walk[W];
+    float v[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        walk[w] = my[w] >= 0 && ivals[slot[w]] == tid + w * nt;
+        v[w] = (float)pow((double)p[w], (double)alpha);
+    }
+    tree_walk<W>(tree, node, v, walk, levels);
 }
 
 __global__ __launch_bounds__(1024) void k_per_update(PerUpdateArgs A)
 {
     __shared__ int lds[PU_LDS_WORDS];
-    per_update_body(A, lds);
+    per_update_body<1>(A, lds);
 }
 
 // Store path (Alg.2 "store transition with maximal priority"): n time steps have just been
