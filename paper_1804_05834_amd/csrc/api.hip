@@ -29,6 +29,7 @@ struct Workspace {
     uint8_t *stack5;
     int32_t *b_idx, *b_a;
     float *b_w, *b_r, *td_abs, *loss_j, *loss_slot;
+    int *pu_state;   // walkers of a priority update that is split over two launches
     uint8_t *b_done;
     // activations, channel-last, rows = samples of all passes (fp32 or bf16 by precision)
     void *act1, *act2, *act3;
@@ -75,6 +76,7 @@ Workspace carve(const dqn_config &c, uint8_t *base)
     w.td_abs = (float *)take(MB * 4);
     w.loss_j = (float *)take(MB * 4);
     w.loss_slot = (float *)take(256);
+    w.pu_state = (int *)take(3 * misc::STATE_STRIDE * 4);
     w.b_done = take(MB);
     const size_t es = c.precision == 1 ? 2 : 4;  // bytes per activation element
     w.act1 = take(rows * net::A1 * es);
@@ -643,12 +645,87 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G2); });
 }
 
+// The priority update (one workgroup, twenty tree levels one after the other, needs only the TD
+// errors) rides in the four launches of the backward pass as their workgroup 0, four entries per
+// thread and a quarter of the levels per launch: each part is shorter than the launch it sits in,
+// so the update costs no launch, no stream and no event.
+struct SplitUpdate {
+    misc::PerUpdateArgs update;
+    int *state;
+    int part_levels;    // levels per launch (the last launch takes what is left)
+    int on;             // 0: no update in this step
+};
+// part k of the update (k = 0: settle duplicates, write the leaves, first levels)
+__device__ __forceinline__ void update_part(const SplitUpdate &U, int k, int *lds)
+{
+    if (k == 0) misc::per_update_body<4>(U.update, lds, U.part_levels, U.state);
+    else misc::per_update_resume<4>(U.update, k * U.part_levels, U.part_levels, U.state);
+}
+
+// fc1's backward pair (see gbf::k_bwd_pair) with the head's weight gradient as a third group of
+// workgroups (row r, 32 hidden units each): all three need only what the head kernel left.
+__global__ __launch_bounds__(256) void k_fc1_head_bwd(gbf::DgradArgs DA, gbf::WgradArgs WA, gbf::PairGrid P,
+                                                      misc::HeadWgradArgs H, SplitUpdate U)
+{
+    using namespace gbf;
+    constexpr int LD = dgrad_lds<64, 64, true>(), LW = wgrad_lds<64, 64, true>();
+    static_assert((LD > LW ? LD : LW) * 2 >= 8 * 34 * 4 && (LD > LW ? LD : LW) * 2 >= misc::PU_LDS_WORDS * 4, "LDS");
+    __shared__ __attribute__((aligned(16))) bf16_t lds[LD > LW ? LD : LW];
+    if (U.on && blockIdx.x == 0) return update_part(U, 0, reinterpret_cast<int *>(lds));
+    const int id = (int)blockIdx.x - U.on;
+    if (id < P.nd) {
+        dgrad_tile<DFc1, 64, 64, 1, 1, true>(DA, tile_of(id, P.nd), P.dgx, P.dgz, lds);
+    } else if (id < P.nd + P.nw) {
+        wgrad_tile<GFc1, 64, 64, 1, 1, true>(WA, tile_of(id - P.nd, P.nw), P.wgx, P.wgy, P.wgz, lds);
+    } else {
+        const int u = id - P.nd - P.nw;
+        misc::head_wgrad_body<8>(H, u / 16, u % 16, reinterpret_cast<float *>(lds));
+    }
+}
+
+// conv3's backward pair after workgroup 0
+__global__ __launch_bounds__(256) void k_conv3_bwd_pu(gbf::DgradArgs DA, gbf::WgradArgs WA, gbf::PairGrid P, SplitUpdate U)
+{
+    using namespace gbf;
+    constexpr int LD = dgrad_lds<64, 64, true>(), LW = wgrad_lds<64, 64, true>();
+    __shared__ __attribute__((aligned(16))) bf16_t lds[LD > LW ? LD : LW];
+    if (U.on && blockIdx.x == 0) return update_part(U, 1, reinterpret_cast<int *>(lds));
+    const int id = (int)blockIdx.x - U.on;
+    if (id < P.nd) dgrad_tile<DConv3, 64, 64, 1, 1, true>(DA, tile_of(id, P.nd), P.dgx, P.dgz, lds);
+    else wgrad_tile<GConv3, 64, 64, 1, 1, true>(WA, tile_of(id - P.nd, P.nw), P.wgx, P.wgy, P.wgz, lds);
+}
+
+// conv2's backward pair after workgroup 0: the per-sample input gradient (nps workgroups) and the
+// tiled weight gradient (nw workgroups); both read conv2's dY
+__global__ __launch_bounds__(256, 2) void k_conv2_bwd_pu(gbf::dps::Args PA, gbf::WgradArgs WA, int nps, int nw, int wgx,
+                                                         int wgy, int wgz, SplitUpdate U)
+{
+    using namespace gbf;
+    constexpr int LW = wgrad_lds<64, 64, true>() * 2;   // bytes
+    constexpr int LB = dps::PS_LDS > LW ? dps::PS_LDS : LW;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LB];
+    if (U.on && blockIdx.x == 0) return update_part(U, 2, reinterpret_cast<int *>(lds));
+    const int id = (int)blockIdx.x - U.on;
+    if (id < nps) dps::conv2_dgrad_ps_body(PA, id, nps, lds);
+    else wgrad_tile<GConv2, 64, 64, 1, 1, true>(WA, tile_of(id - nps, nw), wgx, wgy, wgz, reinterpret_cast<bf16_t *>(lds));
+}
+
+// conv1's weight gradient after workgroup 0
+__global__ __launch_bounds__(256) void k_conv1_wgrad_pu(gbf::c1::WgradArgs A, SplitUpdate U)
+{
+    __shared__ __attribute__((aligned(16))) gbf::bf16_t lds[gbf::c1::WG1_LDS];
+    if (U.on && blockIdx.x == 0) return update_part(U, 3, reinterpret_cast<int *>(lds));
+    const int u = (int)blockIdx.x - U.on, total = (int)gridDim.x - U.on;
+    gbf::c1::conv1_wgrad_block(A, gbf::tile_of(u, total), lds);
+}
+
 // bf16: one stream and one launch per layer, the layer's input gradient and weight gradient side by
 // side in it (both read the layer's dY and nothing else that the backward pass computes).  Events
 // between streams cost more than they gain here: a record or a wait on the critical stream adds
 // about 4 us to the gap between two kernels, and a kernel on another stream starts 11-14 us after
 // the kernel it waits for has ended.
-void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *ns3, hipStream_t st)
+void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *ns3, hipStream_t st,
+                   const SmallTail &tail)
 {
     using namespace gbf;
     const Workspace &w = c->ws;
@@ -656,12 +733,14 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     bf16_t *dh = (bf16_t *)w.dh, *d3 = (bf16_t *)w.d3, *d2 = (bf16_t *)w.d2, *d1 = (bf16_t *)w.d1;
     const bf16_t *sh = shadow_of(c, 0);
     int rps;
+    const SplitUpdate U{tail.update, w.pu_state, (c->levels + 3) / 4, tail.with_update ? 1 : 0};
     {
         DgradArgs D{dh, sh + net::F1W, act3, d3, B};
         WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
         const int gx = (B + 63) / 64;
         PairGrid P{gx * 49, gx, 1, 49 * 8, 49, 8, 1};
-        launch(c, "fc1_bwd", st, [&] { k_bwd_pair<DFc1, GFc1><<<P.nd + P.nw, 256, 0, st>>>(D, G, P); });
+        const int nh = c->R * 16;
+        launch(c, "fc1_bwd", st, [&] { k_fc1_head_bwd<<<P.nd + P.nw + nh + U.on, 256, 0, st>>>(D, G, P, tail.head, U); });
     }
     {
         DgradArgs D{d3, sh + net::C3W, act2, d2, B};
@@ -669,19 +748,19 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
         WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
         const int nd = (int)(((long)B * 81 + 63) / 64);
         PairGrid P{nd, nd, 1, 9 * *ns3, 9, 1, *ns3};
-        launch(c, "conv3_bwd", st, [&] { k_bwd_pair<DConv3, GConv3><<<P.nd + P.nw, 256, 0, st>>>(D, G, P); });
+        launch(c, "conv3_bwd", st, [&] { k_conv3_bwd_pu<<<P.nd + P.nw + U.on, 256, 0, st>>>(D, G, P, U); });
     }
     {   // conv2: the per-sample input gradient, at most one workgroup per CU, beside the tiled weight gradient
         dps::Args P{d2, sh + net::C2W, act1, d1, B};
         split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
         const int nps = std::min(B, c->num_cu), nw = 8 * *ns2, gz = *ns2;
-        launch(c, "conv2_bwd", st, [&] { dps::k_conv2_bwd_pair<<<nps + nw, 256, 0, st>>>(P, G, nps, nw, 8, 1, gz); });
+        launch(c, "conv2_bwd", st, [&] { k_conv2_bwd_pu<<<nps + nw + U.on, 256, 0, st>>>(P, G, nps, nw, 8, 1, gz, U); });
     }
     {   // conv1: one workgroup per split of samples, frames staged in LDS
         *ns1 = std::min(B, MAX_WSPLIT1);
         c1::WgradArgs G{c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift}, d1, w.gp1, B, *ns1};
-        launch(c, "conv1_wgrad", st, [&] { c1::k_conv1_wgrad<<<dim3(*ns1, 2), 256, 0, st>>>(G); });
+        launch(c, "conv1_wgrad", st, [&] { k_conv1_wgrad_pu<<<2 * *ns1 + U.on, 256, 0, st>>>(G, U); });
     }
 }
 
@@ -1172,12 +1251,12 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     H.a_star = O.a_star; H.is_w = O.is_w;
     launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 512, 0, st>>>(H); });
 
-    // fork: the weight gradients of the trunk go to one side stream (fp32 only: the bf16 backward
-    // pass keeps them on st), the head weight gradient and the priority update to another; they
-    // join again before the optimizer
-    // (a small batch stays on one stream: its kernels are too short to repay the hand-overs)
-    const bool multi = c->side && B > 64;
-    hipStream_t sd = (multi && cfg.precision == 0) ? c->side : st;
+    // fp32 fork: the weight gradients of the trunk go to one side stream, the head weight gradient
+    // and the priority update to another; they join again before the optimizer
+    // (a small batch stays on one stream: its kernels are too short to repay the hand-overs;
+    // the bf16 step never leaves st)
+    const bool multi = c->side && B > 64 && cfg.precision == 0;
+    hipStream_t sd = multi ? c->side : st;
     hipStream_t sp = multi ? (c->side2 ? c->side2 : c->side) : st;
     if (sd != st || sp != st) (void)hipEventRecord(c->ev_fork, st);
     ev_wait(sd, c->ev_fork, st);
@@ -1189,7 +1268,8 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     // small fp32 batch on one stream: the head weight gradient and the priority update join the
     // four trunk weight gradients in one launch at the end of the backward pass
     SmallTail tail{HW, PU, !batch};
-    const bool fuse_tail = cfg.precision == 0 && sd == st && B <= 64;
+    // bf16: they ride in the launches of the backward pass (see backward_bf16)
+    const bool fuse_tail = cfg.precision == 1 || (sd == st && B <= 64);
     if (!fuse_tail) {
         launch(c, "head_wgrad", sp, [&] { misc::k_head_wgrad<<<dim3(c->R, 16), 512, 0, sp>>>(HW); });
         if (!batch) launch(c, "per_update", sp, [&] { misc::k_per_update<<<1, (B + 63) / 64 * 64, 0, sp>>>(PU); });
@@ -1197,7 +1277,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     if (sp != sd) (void)hipEventRecord(c->ev_join2, sp);
 
     int ns1, ns2, ns3;
-    if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st);
+    if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, tail);
     else backward_f32(c, B, stacking ? w.stack5 : s, stacking ? 5L * net::FRAME : xs, &ns1, &ns2, &ns3, st, sd,
                       fuse_tail ? &tail : nullptr);
     ev_record(c->ev_join, sd, st);

@@ -629,24 +629,13 @@ __device__ __forceinline__ int tile_of(int u, int total)
     return die * q + (die < r ? die : r) + slot;
 }
 
-// The input gradient and the weight gradient of one layer in ONE launch of 64x64 tiles (both read
-// the layer's dY and depend on nothing else that is computed in the backward pass): workgroups
-// [0, nd) are the input-gradient tiles, [nd, nd + nw) the weight-gradient tiles.
+// The input gradient and the weight gradient of one layer go into ONE launch of 64x64 tiles (both
+// read the layer's dY and depend on nothing else that is computed in the backward pass): nd
+// input-gradient tiles, then nw weight-gradient tiles.
 struct PairGrid {
     int nd, dgx, dgz;        // input gradient: tiles, grid x and z
     int nw, wgx, wgy, wgz;   // weight gradient: tiles, grid
 };
-template <class D, class G>
-__global__ __launch_bounds__(256) void k_bwd_pair(DgradArgs DA, WgradArgs WA, PairGrid P)
-{
-    constexpr int LD = dgrad_lds<64, 64, true>(), LW = wgrad_lds<64, 64, true>();
-    __shared__ __attribute__((aligned(16))) bf16_t lds[LD > LW ? LD : LW];
-    const int id = blockIdx.x;
-    if (id < P.nd) dgrad_tile<D, 64, 64, 1, 1, true>(DA, tile_of(id, P.nd), P.dgx, P.dgz, lds);
-    else wgrad_tile<G, 64, 64, 1, 1, true>(WA, tile_of(id - P.nd, P.nw), P.wgx, P.wgy, P.wgz, lds);
-}
-
-
 
 // ===========================================================================
 // conv1 (8x8 stride 4 over the uint8 frame stack), specialised.
@@ -1565,15 +1554,5 @@ __device__ __forceinline__ void conv2_dgrad_ps_body(const Args &A, int bid, int 
     }
 }
 constexpr int PS_LDS = IMG + 32 * W2PITCH;   // bytes
-// conv2's per-sample input gradient (workgroups [0, nps)) and its tiled weight gradient (the nw
-// workgroups after them) in one launch: both read conv2's dY.
-__global__ __launch_bounds__(256, 2) void k_conv2_bwd_pair(Args PA, WgradArgs WA, int nps, int nw, int wgx, int wgy, int wgz)
-{
-    constexpr int LW = wgrad_lds<64, 64, true>() * 2;   // bytes
-    __shared__ __attribute__((aligned(16))) uint8_t lds[PS_LDS > LW ? PS_LDS : LW];
-    const int id = blockIdx.x;
-    if (id < nps) conv2_dgrad_ps_body(PA, id, nps, lds);
-    else wgrad_tile<GConv2, 64, 64, 1, 1, true>(WA, tile_of(id - nps, nw), wgx, wgy, wgz, reinterpret_cast<bf16_t *>(lds));
-}
 }  // namespace dps
 }  // namespace gbf

@@ -607,9 +607,13 @@ struct PerUpdateArgs {
 constexpr int PU_LDS_WORDS = 2 * PU_SLOTS + 16;  // LDS of per_update_body, in 4-byte words
 
 // The whole workgroup must call this; it handles W entries per thread (W * blockDim.x >= n).
-// lds: PU_LDS_WORDS words.
+// lds: PU_LDS_WORDS words.  With `state` the walk stops after `first_levels` levels and leaves
+// every walker (node, value, active) there, for per_update_resume to take to the root later:
+// entry j at state[j], state[STATE_STRIDE + j], state[2 * STATE_STRIDE + j].
+constexpr int STATE_STRIDE = 1024;
 template <int W = 1>
-__device__ __forceinline__ void per_update_body(const PerUpdateArgs &A, int *lds)
+__device__ __forceinline__ void per_update_body(const PerUpdateArgs &A, int *lds, int first_levels = -1,
+                                                int *state = nullptr)
 {
     int *keys = lds, *ivals = lds + PU_SLOTS;  // ivals: largest entry number naming the slot's leaf
     float *sh = reinterpret_cast<float *>(lds + 2 * PU_SLOTS);
@@ -664,7 +668,50 @@ __device__ __forceinline__ void per_update_body(const PerUpdateArgs &A, int *lds
         walk[w] = my[w] >= 0 && ivals[slot[w]] == tid + w * nt;
         v[w] = (float)pow((double)p[w], (double)alpha);
     }
-    tree_walk<W>(tree, node, v, walk, levels);
+    tree_walk<W>(tree, node, v, walk, state ? first_levels : levels);
+    if (state) {
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const int j = tid + w * nt;
+            if (j < STATE_STRIDE) {
+                state[j] = node[w];
+                state[STATE_STRIDE + j] = __float_as_int(v[w]);
+                state[2 * STATE_STRIDE + j] = walk[w] ? 1 : 0;
+            }
+        }
+    }
+}
+
+// A later part of a split priority update: the walkers that the part before left `done_levels`
+// levels above their leaves climb `walk_levels` more (to the root if that is all that is left;
+// otherwise they are left in `state` again).  Same workgroup shape as the first part.
+template <int W>
+__device__ __forceinline__ void per_update_resume(const PerUpdateArgs &A, int done_levels, int walk_levels, int *state)
+{
+    const int tid = threadIdx.x, nt = blockDim.x;
+    int node[W];
+    float v[W];
+    bool walk[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) {
+        const int j = tid + w * nt;
+        const bool in = j < A.n && j < STATE_STRIDE;
+        node[w] = in ? state[j] : 1;
+        v[w] = in ? __int_as_float(state[STATE_STRIDE + j]) : 0.f;
+        walk[w] = in && state[2 * STATE_STRIDE + j] != 0;
+    }
+    const bool last = done_levels + walk_levels >= A.levels;
+    tree_walk<W>(A.tree, node, v, walk, last ? A.levels - done_levels : walk_levels);
+    if (!last) {
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const int j = tid + w * nt;
+            if (j < A.n && j < STATE_STRIDE) {
+                state[j] = node[w];
+                state[STATE_STRIDE + j] = __float_as_int(v[w]);
+            }
+        }
+    }
 }
 
 __global__ __launch_bounds__(1024) void k_per_update(PerUpdateArgs A)
