@@ -574,6 +574,48 @@ __global__ __launch_bounds__(256) void k_small_tail(SmallTailArgs A)
     }
 }
 
+// ----- small fp32 batch: one launch per layer, as in the bf16 step -----
+// The layer's input-gradient tiles and its weight-gradient tiles share a launch (both read the
+// layer's dY); the input gradients of so small a batch are 100-200 workgroups, so the weight
+// gradient rides in what the launch leaves free.  fc1's launch also takes the head's weight
+// gradient and, as workgroup 0, the priority update.  A launch has the width of its widest tile
+// (256 / 384 / 512 threads); in a narrower tile the waves beyond leave at once.
+struct PairF32 {
+    int nd, dgx, dgz;        // input gradient: tiles, grid x and z
+    int nw, wgx, wgy, wgz;   // weight gradient: tiles, grid
+};
+template <class D, int BM, int BN, int KS, class G, int TH, bool HEAD>
+__global__ __launch_bounds__(TH) void k_layer_bwd_f32(g32::DgradArgs DA, g32::WgradArgs WA, PairF32 P, SmallTail X)
+{
+    using namespace g32;
+    constexpr int LD = dgrad_lds<BM, BN, KS>(), LW = wgrad_lds<64, 64>();
+    constexpr int L0 = LD > LW ? LD : LW;
+    constexpr int L = HEAD && misc::PU_LDS_WORDS > L0 ? misc::PU_LDS_WORDS : L0;
+    __shared__ __attribute__((aligned(16))) float lds[L];
+    int id = blockIdx.x;
+    if (HEAD) {
+        const int up = X.with_update ? 1 : 0;
+        if (up && id == 0) {
+            misc::per_update_body(X.update, reinterpret_cast<int *>(lds));
+            return;
+        }
+        id -= up;
+    }
+    if (id < P.nd) {
+        // dispatch order -> tile number, die-aware within the group
+        const int die = id & 7, slot = id >> 3, q = P.nd >> 3, r = P.nd & 7;
+        dgrad_tile<D, BM, BN, KS>(DA, die * q + (die < r ? die : r) + slot, P.dgx, P.dgz, lds);
+    } else if (id < P.nd + P.nw) {
+        int bx, by, bz;
+        wgrad_tile_of(id - P.nd, P.wgx, P.wgy, P.wgz, bx, by, bz);
+        wgrad_tile<G, 64, 64>(WA, bx, by, bz, lds);
+    } else if (HEAD) {
+        if ((int)threadIdx.x >= 256) return;
+        const int u = id - P.nd - P.nw;
+        misc::head_wgrad_body<8>(X.head, u / 16, u % 16, lds);
+    }
+}
+
 // ----- backward through fc1, conv3, conv2, conv1 (no input gradient for conv1) -----
 // The input-gradient chain and conv1's weight gradient run on st; the weight gradients of fc1,
 // conv3 and conv2 run on sd behind the events the chain records.  All of st's kernels are
@@ -595,6 +637,35 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     const WgradArgs G2{d2, act1, w.gp2, B, rps2, net::A1, net::L2N, 1.0f};
     const WgradArgs G3{d3, act2, w.gp3, B, rps3, net::A2, net::L3N, 1.0f};
     const WgradArgs G4{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
+    if (sd == st && tail) {
+        {
+            DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
+            const int gx = (B + 31) / 32;
+            PairF32 P{gx * 98, gx, 1, 49 * 8, 49, 8, 1};
+            const int nh = c->R * 16 + (tail->with_update ? 1 : 0);
+            launch(c, "fc1_bwd", st, [&] {
+                k_layer_bwd_f32<DFc1, 32, 32, 4, GFc1, 256, true><<<P.nd + P.nw + nh, 256, 0, st>>>(D, G4, P, *tail);
+            });
+        }
+        {
+            DgradArgs D{d3, c->theta + net::C3W, act2, d2, B};
+            const int gx = (int)(((long)B * 81 + 31) / 32);
+            PairF32 P{gx * 2, gx, 1, 9 * *ns3, 9, 1, *ns3};
+            launch(c, "conv3_bwd", st, [&] {
+                k_layer_bwd_f32<DConv3, 32, 32, 6, GConv3, 384, false><<<P.nd + P.nw, 384, 0, st>>>(D, G3, P, *tail);
+            });
+        }
+        {
+            DgradArgs D{d2, c->theta + net::C2W, act1, d1, B};
+            const int gx = (int)(((long)B * 100 + 63) / 64);
+            PairF32 P{gx * 4, gx, 4, 8 * *ns2, 8, 1, *ns2};
+            launch(c, "conv2_bwd", st, [&] {
+                k_layer_bwd_f32<DConv2, 64, 32, 4, GConv2, 512, false><<<P.nd + P.nw, 512, 0, st>>>(D, G2, P, *tail);
+            });
+        }
+        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 128><<<dim3(2, 1, *ns1), 256, 0, st>>>(G1); });
+        return;
+    }
     {
         DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
         if (small) launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 32, 4><<<dim3((B + 31) / 32, 98, 1), 256, 0, st>>>(D); });

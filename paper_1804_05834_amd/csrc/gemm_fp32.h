@@ -253,8 +253,15 @@ struct DgradArgs {
     int B;
 };
 
-template <class D, int BM, int BN, int KS = 1>
-__global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_dgrad(DgradArgs A)
+// LDS floats of an input-gradient tile
+template <int BM, int BN, int KS> constexpr int dgrad_lds() { return BM * (BK * KS + 4) + BK * KS * (BN + 4); }
+
+// Tile number t of a grid of (gx, gy, gz) tiles, computed by the first (BM/32)(BN/32) KS waves of
+// the workgroup (a launch may hold wider workgroups: the waves beyond leave at once; a barrier
+// counts only the waves that are still there).  Tile order: the parity classes of one row tile
+// together, then the row tiles of one column tile.
+template <class D, int BM, int BN, int KS>
+__device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, int gz, float *smem)
 {
     constexpr int NWT = (BM / 32) * (BN / 32), T = NWT * KS * 64;
     constexpr int BKS = BK * KS, LD = BKS + 4, CPR = BKS / 4, RPP = T / CPR;
@@ -264,13 +271,11 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_dgrad(Dgrad
     constexpr int NBL = BKS / BROWS;
     static_assert(NA * T == BM * CPR && NBL * BROWS == BKS && D::K % BKS == 0 && D::CO % 4 == 0, "tile/threads mismatch");
     static_assert(BM * LD + BKS * LDB >= (KS - 1) * NWT * 1024, "reduction scratch does not fit the tiles");
-    __shared__ __attribute__((aligned(16))) float smem[BM * LD + BKS * LDB];
+    if ((int)threadIdx.x >= T) return;
     float *As = smem, *Bs = smem + BM * LD;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // tile order: the parity classes of one row tile together, then the row tiles of one column tile
-    const int t = net::tile_of_workgroup();
-    const int bz = t % (int)gridDim.z, bx = (t / (int)gridDim.z) % (int)gridDim.x, by = t / (int)(gridDim.z * gridDim.x);
+    const int bz = t % gz, bx = (t / gz) % gx, by = t / (gz * gx);
     const int m0 = bx * BM, n0 = by * BN;
     const int ca = bz / D::S, cb = bz % D::S;
     const int Mc = A.B * D::PP;
@@ -359,6 +364,12 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_dgrad(Dgrad
         }
     }
 }
+template <class D, int BM, int BN, int KS = 1>
+__global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_dgrad(DgradArgs A)
+{
+    __shared__ __attribute__((aligned(16))) float smem[dgrad_lds<BM, BN, KS>()];
+    dgrad_tile<D, BM, BN, KS>(A, net::tile_of_workgroup(), gridDim.x, gridDim.z, smem);
+}
 
 // ---------------------------------------------------------------------------
 // Weight gradient: dW[o][k] = sum_m dY[m][o] * A(m,k), db[o] = sum_m dY[m][o].
@@ -382,7 +393,7 @@ struct WgradArgs {
 template <int BMO, int BNK> constexpr int wgrad_lds() { return BK * (BMO + 4) + BK * (BNK + 4); }
 
 // One weight-gradient tile: output channels [by*BMO, +BMO) x im2col columns [bx*BNK, +BNK) over the
-// rows of split bz.  T threads; Ys/Xs are the workgroup's LDS.
+// rows of split bz, computed by the first T threads of the workgroup; Ys/Xs are the workgroup's LDS.
 template <class G, int BMO, int BNK>
 __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int bx, int by, int bz, float *lds)
 {
@@ -391,6 +402,7 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int bx, int by, i
     constexpr int YR = T / (BMO / 4), XR = T / (BNK / 4);  // tile rows filled per pass
     constexpr int NY = (BK + YR - 1) / YR, NX = (BK + XR - 1) / XR;
     using in_t = typename G::in_t;
+    if ((int)threadIdx.x >= T) return;   // a wider workgroup: the waves beyond the tile's leave at once
     float *Ys = lds, *Xs = lds + BK * LDY;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
