@@ -518,65 +518,17 @@ void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipS
     launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
 }
 
-// ----- small-batch tail: everything that is left once the input gradients are done -----
-// For a small batch on one stream the four trunk weight gradients, the head weight gradient and
-// the priority update are each a few short tiles; one launch of 256-thread workgroups runs them
-// side by side.  The priority update, a single workgroup and the longest of them (twenty tree
-// levels, one after the other), comes first in dispatch order so that it starts with the launch;
-// then workgroups [begin[p], begin[p+1]): p = 0..3 the trunk layers (conv1, conv2, conv3, fc1),
-// 4 the head (row r, 32 hidden units per workgroup).
+// What rides in the launches of the backward pass beside the trunk's gradients: the head's weight
+// gradient and the priority update (Eq.11) of the transitions just trained on.
 struct SmallTail {
     misc::HeadWgradArgs head;
     misc::PerUpdateArgs update;
     bool with_update;
 };
-struct SmallTailArgs {
-    g32::WgradArgs a[4];
-    int begin[6];
-    int update_first;   // 1: workgroup 0 is the priority update (at most 256 entries), the others follow
-    int gx[4], gy[4], gz[4];
-    misc::HeadWgradArgs head;
-    misc::PerUpdateArgs update;
-};
-__global__ __launch_bounds__(256) void k_small_tail(SmallTailArgs A)
-{
-    using namespace g32;
-    constexpr int LW = wgrad_lds<32, 128>() > wgrad_lds<64, 64>() ? wgrad_lds<32, 128>() : wgrad_lds<64, 64>();
-    constexpr int L = LW > misc::PU_LDS_WORDS ? LW : misc::PU_LDS_WORDS;
-    __shared__ __attribute__((aligned(16))) float lds[L];
-    // plain dispatch order: the problems' tiles differ in length, and round-robin over the dies
-    // spreads each of them over all dies
-    if (A.update_first && blockIdx.x == 0) {
-        misc::per_update_body(A.update, reinterpret_cast<int *>(lds));
-        return;
-    }
-    const int t = blockIdx.x - A.update_first;
-    int p = 0;
-#pragma unroll
-    for (int q = 1; q < 5; ++q)
-        if (t >= A.begin[q]) p = q;
-    const int u = t - A.begin[p];
-    int bx, by, bz;
-    if (p == 0) {
-        wgrad_tile_of(u, A.gx[0], A.gy[0], A.gz[0], bx, by, bz);
-        wgrad_tile<GConv1, 32, 128>(A.a[0], bx, by, bz, lds);
-    } else if (p == 1) {
-        wgrad_tile_of(u, A.gx[1], A.gy[1], A.gz[1], bx, by, bz);
-        wgrad_tile<GConv2, 64, 64>(A.a[1], bx, by, bz, lds);
-    } else if (p == 2) {
-        wgrad_tile_of(u, A.gx[2], A.gy[2], A.gz[2], bx, by, bz);
-        wgrad_tile<GConv3, 64, 64>(A.a[2], bx, by, bz, lds);
-    } else if (p == 3) {
-        wgrad_tile_of(u, A.gx[3], A.gy[3], A.gz[3], bx, by, bz);
-        wgrad_tile<GFc1, 64, 64>(A.a[3], bx, by, bz, lds);
-    } else {
-        misc::head_wgrad_body<8>(A.head, u / 16, u % 16, lds);
-    }
-}
 
-// ----- small fp32 batch: one launch per layer, as in the bf16 step -----
+// ----- fp32 on one stream: one backward launch per layer, as in the bf16 step -----
 // The layer's input-gradient tiles and its weight-gradient tiles share a launch (both read the
-// layer's dY); the input gradients of so small a batch are 100-200 workgroups, so the weight
+// layer's dY); the input gradients of a small batch are 100-200 workgroups, so the weight
 // gradient rides in what the launch leaves free.  fc1's launch also takes the head's weight
 // gradient and, as workgroup 0, the priority update.  A launch has the width of its widest tile
 // (256 / 384 / 512 threads); in a narrower tile the waves beyond leave at once.
@@ -596,7 +548,7 @@ __global__ __launch_bounds__(TH) void k_layer_bwd_f32(g32::DgradArgs DA, g32::Wg
     if (HEAD) {
         const int up = X.with_update ? 1 : 0;
         if (up && id == 0) {
-            misc::per_update_body(X.update, reinterpret_cast<int *>(lds));
+            misc::per_update_body<4>(X.update, reinterpret_cast<int *>(lds));   // 4 x 256 >= the largest batch
             return;
         }
         id -= up;
@@ -637,23 +589,38 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     const WgradArgs G2{d2, act1, w.gp2, B, rps2, net::A1, net::L2N, 1.0f};
     const WgradArgs G3{d3, act2, w.gp3, B, rps3, net::A2, net::L3N, 1.0f};
     const WgradArgs G4{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
-    if (sd == st && tail) {
+    if (sd == st) {
         {
             DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
             const int gx = (B + 31) / 32;
-            PairF32 P{gx * 98, gx, 1, 49 * 8, 49, 8, 1};
             const int nh = c->R * 16 + (tail->with_update ? 1 : 0);
-            launch(c, "fc1_bwd", st, [&] {
-                k_layer_bwd_f32<DFc1, 32, 32, 4, GFc1, 256, true><<<P.nd + P.nw + nh, 256, 0, st>>>(D, G4, P, *tail);
-            });
+            if (small) {
+                PairF32 P{gx * 98, gx, 1, 49 * 8, 49, 8, 1};
+                launch(c, "fc1_bwd", st, [&] {
+                    k_layer_bwd_f32<DFc1, 32, 32, 4, GFc1, 256, true><<<P.nd + P.nw + nh, 256, 0, st>>>(D, G4, P, *tail);
+                });
+            } else {
+                PairF32 P{gx * 49, gx, 1, 49 * 8, 49, 8, 1};
+                launch(c, "fc1_bwd", st, [&] {
+                    k_layer_bwd_f32<DFc1, 32, 64, 1, GFc1, 256, true><<<P.nd + P.nw + nh, 256, 0, st>>>(D, G4, P, *tail);
+                });
+            }
         }
         {
             DgradArgs D{d3, c->theta + net::C3W, act2, d2, B};
-            const int gx = (int)(((long)B * 81 + 31) / 32);
-            PairF32 P{gx * 2, gx, 1, 9 * *ns3, 9, 1, *ns3};
-            launch(c, "conv3_bwd", st, [&] {
-                k_layer_bwd_f32<DConv3, 32, 32, 6, GConv3, 384, false><<<P.nd + P.nw, 384, 0, st>>>(D, G3, P, *tail);
-            });
+            if (small) {
+                const int gx = (int)(((long)B * 81 + 31) / 32);
+                PairF32 P{gx * 2, gx, 1, 9 * *ns3, 9, 1, *ns3};
+                launch(c, "conv3_bwd", st, [&] {
+                    k_layer_bwd_f32<DConv3, 32, 32, 6, GConv3, 384, false><<<P.nd + P.nw, 384, 0, st>>>(D, G3, P, *tail);
+                });
+            } else {
+                const int gx = (int)(((long)B * 81 + 63) / 64);
+                PairF32 P{gx, gx, 1, 9 * *ns3, 9, 1, *ns3};
+                launch(c, "conv3_bwd", st, [&] {
+                    k_layer_bwd_f32<DConv3, 64, 64, 1, GConv3, 256, false><<<P.nd + P.nw, 256, 0, st>>>(D, G3, P, *tail);
+                });
+            }
         }
         {
             DgradArgs D{d2, c->theta + net::C2W, act1, d1, B};
@@ -663,20 +630,19 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
                 k_layer_bwd_f32<DConv2, 64, 32, 4, GConv2, 512, false><<<P.nd + P.nw, 512, 0, st>>>(D, G2, P, *tail);
             });
         }
-        launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 128><<<dim3(2, 1, *ns1), 256, 0, st>>>(G1); });
+        if (B <= 64) launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 128><<<dim3(2, 1, *ns1), 256, 0, st>>>(G1); });
+        else launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256><<<dim3(1, 1, *ns1), 512, 0, st>>>(G1); });
         return;
     }
     {
         DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
-        if (small) launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 32, 4><<<dim3((B + 31) / 32, 98, 1), 256, 0, st>>>(D); });
-        else launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
+        launch(c, "fc1_dgrad", st, [&] { k_dgrad<DFc1, 32, 64><<<dim3((B + 31) / 32, 49, 1), 128, 0, st>>>(D); });
         ev_record(c->ev_a, st, sd);
     }
     {
         DgradArgs D{d3, c->theta + net::C3W, act2, d2, B};
         long M = (long)B * 81;
-        if (small) launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 32, 32, 6><<<dim3((M + 31) / 32, 2, 1), 384, 0, st>>>(D); });
-        else launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
+        launch(c, "conv3_dgrad", st, [&] { k_dgrad<DConv3, 64, 64><<<dim3((M + 63) / 64, 1, 1), 256, 0, st>>>(D); });
         ev_record(c->ev_b, st, sd);
     }
     {
@@ -684,30 +650,8 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
         long M = (long)B * 100;
         launch(c, "conv2_dgrad", st, [&] { k_dgrad<DConv2, 64, 32, 4><<<dim3((M + 63) / 64, 1, 4), 512, 0, st>>>(D); });
     }
-    if (sd == st) {
-        // one stream: the weight gradients are independent of each other once the input gradients
-        // are done, so they share one launch (with the head's and the priority update if given)
-        SmallTailArgs A{};
-        A.a[0] = G1; A.a[1] = G2; A.a[2] = G3; A.a[3] = G4;
-        const int gx[4] = {2, 8, 9, 49}, gy[4] = {1, 1, 1, 8}, gz[4] = {*ns1, *ns2, *ns3, 1};
-        int total = 0;
-        for (int p = 0; p < 4; ++p) {
-            A.begin[p] = total;
-            A.gx[p] = gx[p]; A.gy[p] = gy[p]; A.gz[p] = gz[p];
-            total += gx[p] * gy[p] * gz[p];
-        }
-        A.begin[4] = total;
-        if (tail) {
-            A.head = tail->head;
-            A.update = tail->update;
-            total += c->R * 16;
-        }
-        A.begin[5] = total;
-        A.update_first = tail && tail->with_update ? 1 : 0;
-        total += A.update_first;
-        launch(c, "small_tail", st, [&] { k_small_tail<<<dim3(total), 256, 0, st>>>(A); });
-        return;
-    }
+    // large batch on three streams: the input-gradient chain and conv1's weight gradient on st, the other
+    // weight gradients on sd behind the events of their input gradients
     launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 256><<<dim3(1, 1, *ns1), 512, 0, st>>>(G1); });
     launch(c, "fc1_wgrad", sd, [&] { k_wgrad<GFc1, 64, 64><<<dim3(49, 8, 1), 256, 0, sd>>>(G4); });
     ev_wait(sd, c->ev_a, st);
@@ -1322,11 +1266,12 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     H.a_star = O.a_star; H.is_w = O.is_w;
     launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 512, 0, st>>>(H); });
 
-    // fp32 fork: the weight gradients of the trunk go to one side stream, the head weight gradient
-    // and the priority update to another; they join again before the optimizer
-    // (a small batch stays on one stream: its kernels are too short to repay the hand-overs;
-    // the bf16 step never leaves st)
-    const bool multi = c->side && B > 64 && cfg.precision == 0;
+    // large fp32 batches fork: the weight gradients of the trunk go to one side stream, the head
+    // weight gradient and the priority update to another; they join again before the optimizer.
+    // Their kernels are long enough (50-120 us) to repay the events; everything else stays on st
+    // with one backward launch per layer.
+    // measured: 645 against 665 us/step at B = 512 with the streams, 547 against 536 at 384, 277 against 245 at 128
+    const bool multi = c->side && cfg.precision == 0 && B > 448;
     hipStream_t sd = multi ? c->side : st;
     hipStream_t sp = multi ? (c->side2 ? c->side2 : c->side) : st;
     if (sd != st || sp != st) (void)hipEventRecord(c->ev_fork, st);
@@ -1336,11 +1281,9 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     // the indices come from the sampling kernel, so the ring capacity bounds them
     misc::PerUpdateArgs PU{c->tree, c->L, c->levels, (long)cfg.replay_capacity, w.b_idx, w.td_abs, B,
                            cfg.per_alpha, cfg.per_eps};
-    // small fp32 batch on one stream: the head weight gradient and the priority update join the
-    // four trunk weight gradients in one launch at the end of the backward pass
+    // one stream: they ride in the launches of the backward pass (see backward_bf16, backward_f32)
     SmallTail tail{HW, PU, !batch};
-    // bf16: they ride in the launches of the backward pass (see backward_bf16)
-    const bool fuse_tail = cfg.precision == 1 || (sd == st && B <= 64);
+    const bool fuse_tail = sd == st;
     if (!fuse_tail) {
         launch(c, "head_wgrad", sp, [&] { misc::k_head_wgrad<<<dim3(c->R, 16), 512, 0, sp>>>(HW); });
         if (!batch) launch(c, "per_update", sp, [&] { misc::k_per_update<<<1, (B + 63) / 64 * 64, 0, sp>>>(PU); });
