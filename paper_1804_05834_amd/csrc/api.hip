@@ -662,19 +662,20 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
 
 // The priority update (one workgroup, twenty tree levels one after the other, needs only the TD
 // errors) rides in the four launches of the backward pass as their workgroup 0, four entries per
-// thread and a quarter of the levels per launch: each part is shorter than the launch it sits in,
-// so the update costs no launch, no stream and no event.
+// thread and a share of the levels per launch (the first part, which also settles the duplicates and
+// raises the new priorities to the power alpha, takes the fewest): each part is shorter than the
+// launch it sits in, so the update costs no launch, no stream and no event.
 struct SplitUpdate {
     misc::PerUpdateArgs update;
     int *state;
-    int part_levels;    // levels per launch (the last launch takes what is left)
+    int upto[3];        // tree levels walked when part 0, 1, 2 ends (part 3 goes to the root)
     int on;             // 0: no update in this step
 };
 // part k of the update (k = 0: settle duplicates, write the leaves, first levels)
 __device__ __forceinline__ void update_part(const SplitUpdate &U, int k, int *lds)
 {
-    if (k == 0) misc::per_update_body<4>(U.update, lds, U.part_levels, U.state);
-    else misc::per_update_resume<4>(U.update, k * U.part_levels, U.part_levels, U.state);
+    if (k == 0) misc::per_update_body<4>(U.update, lds, U.upto[0], U.state);
+    else misc::per_update_resume<4>(U.update, U.upto[k - 1], k < 3 ? U.upto[k] - U.upto[k - 1] : U.update.levels, U.state);
 }
 
 // fc1's backward pair (see gbf::k_bwd_pair) with the head's weight gradient as a third group of
@@ -748,7 +749,8 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     bf16_t *dh = (bf16_t *)w.dh, *d3 = (bf16_t *)w.d3, *d2 = (bf16_t *)w.d2, *d1 = (bf16_t *)w.d1;
     const bf16_t *sh = shadow_of(c, 0);
     int rps;
-    const SplitUpdate U{tail.update, w.pu_state, (c->levels + 3) / 4, tail.with_update ? 1 : 0};
+    const int lv = c->levels;
+    const SplitUpdate U{tail.update, w.pu_state, {lv / 10, 3 * lv / 10, 6 * lv / 10}, tail.with_update ? 1 : 0};
     {
         DgradArgs D{dh, sh + net::F1W, act3, d3, B};
         WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
