@@ -39,7 +39,6 @@ def flops_per_launch(B, R):
         "conv1_wgrad": B * F_CONV1,
         # bf16: a layer's input gradient and weight gradient share one launch
         "fc1_bwd": 2 * B * F_FC1, "conv3_bwd": 2 * B * F_CONV3, "conv2_bwd": 2 * B * F_CONV2,
-        "small_tail": B * (F_CONV1 + F_CONV2 + F_CONV3 + F_FC1),  # all weight gradients in one launch (small fp32 batches)
     }
 
 
@@ -90,9 +89,9 @@ MEASURED_TRAFFIC = {
     ("conv3_fwd", 512, "bf16"): 16.8e6 + 9.5e6,
     ("fc1_fwd", 512, "bf16"): 19.9e6 + 21.7e6,
     ("head_train", 512, "bf16"): 22.4e6 + 1.6e6,
-    ("fc1_bwd", 512, "bf16"): 13.6e6 + 9.7e6,
-    ("conv3_bwd", 512, "bf16"): 9.2e6 + 13.5e6,
-    ("conv2_bwd", 512, "bf16"): 36.1e6 + 20.6e6,
+    ("fc1_bwd", 512, "bf16"): 13.5e6 + 9.6e6,
+    ("conv3_bwd", 512, "bf16"): 9.3e6 + 13.5e6,
+    ("conv2_bwd", 512, "bf16"): 36.2e6 + 20.6e6,
     ("conv1_wgrad", 512, "bf16"): 27.1e6 + 8.3e6,
     ("rmsprop", 512, "bf16"): 43.4e6 + 23.4e6,
 }
