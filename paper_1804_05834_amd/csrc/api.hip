@@ -526,33 +526,45 @@ struct SmallTail {
     bool with_update;
 };
 
+// The priority update (one workgroup, twenty tree levels one after the other, needs only the TD
+// errors) rides in the launches of the backward pass (four in bf16, the first three in fp32) as their workgroup 0, four entries per
+// thread and a share of the levels per launch (the first part, which also settles the duplicates and
+// raises the new priorities to the power alpha, takes the fewest): each part is shorter than the
+// launch it sits in, so the update costs no launch, no stream and no event.
+struct SplitUpdate {
+    misc::PerUpdateArgs update;
+    int *state;
+    int upto[3];        // tree levels walked when part 0, 1, 2 ends (part 3 goes to the root)
+    int on;             // 0: no update in this step
+};
+// part k of the update (k = 0: settle duplicates, write the leaves, first levels)
+__device__ __forceinline__ void update_part(const SplitUpdate &U, int k, int *lds)
+{
+    if (k == 0) misc::per_update_body<4>(U.update, lds, U.upto[0], U.state);
+    else misc::per_update_resume<4>(U.update, U.upto[k - 1], k < 3 ? U.upto[k] - U.upto[k - 1] : U.update.levels, U.state);
+}
+
 // ----- fp32 on one stream: one backward launch per layer, as in the bf16 step -----
 // The layer's input-gradient tiles and its weight-gradient tiles share a launch (both read the
 // layer's dY); the input gradients of a small batch are 100-200 workgroups, so the weight
 // gradient rides in what the launch leaves free.  fc1's launch also takes the head's weight
-// gradient and, as workgroup 0, the priority update.  A launch has the width of its widest tile
+// gradient; workgroup 0 of each launch is part PART of the priority update.  A launch has the width of its widest tile
 // (256 / 384 / 512 threads); in a narrower tile the waves beyond leave at once.
 struct PairF32 {
     int nd, dgx, dgz;        // input gradient: tiles, grid x and z
     int nw, wgx, wgy, wgz;   // weight gradient: tiles, grid
 };
-template <class D, int BM, int BN, int KS, class G, int TH, bool HEAD>
-__global__ __launch_bounds__(TH) void k_layer_bwd_f32(g32::DgradArgs DA, g32::WgradArgs WA, PairF32 P, SmallTail X)
+template <class D, int BM, int BN, int KS, class G, int TH, bool HEAD, int PART>
+__global__ __launch_bounds__(TH) void k_layer_bwd_f32(g32::DgradArgs DA, g32::WgradArgs WA, PairF32 P,
+                                                      misc::HeadWgradArgs H, SplitUpdate U)
 {
     using namespace g32;
     constexpr int LD = dgrad_lds<BM, BN, KS>(), LW = wgrad_lds<64, 64>();
     constexpr int L0 = LD > LW ? LD : LW;
-    constexpr int L = HEAD && misc::PU_LDS_WORDS > L0 ? misc::PU_LDS_WORDS : L0;
+    constexpr int L = PART == 0 && misc::PU_LDS_WORDS > L0 ? misc::PU_LDS_WORDS : L0;
     __shared__ __attribute__((aligned(16))) float lds[L];
-    int id = blockIdx.x;
-    if (HEAD) {
-        const int up = X.with_update ? 1 : 0;
-        if (up && id == 0) {
-            misc::per_update_body<4>(X.update, reinterpret_cast<int *>(lds));   // 4 x 256 >= the largest batch
-            return;
-        }
-        id -= up;
-    }
+    if (U.on && blockIdx.x == 0) return update_part(U, PART, reinterpret_cast<int *>(lds));
+    const int id = (int)blockIdx.x - U.on;
     if (id < P.nd) {
         // dispatch order -> tile number, die-aware within the group
         const int die = id & 7, slot = id >> 3, q = P.nd >> 3, r = P.nd & 7;
@@ -564,7 +576,7 @@ __global__ __launch_bounds__(TH) void k_layer_bwd_f32(g32::DgradArgs DA, g32::Wg
     } else if (HEAD) {
         if ((int)threadIdx.x >= 256) return;
         const int u = id - P.nd - P.nw;
-        misc::head_wgrad_body<8>(X.head, u / 16, u % 16, lds);
+        misc::head_wgrad_body<8>(H, u / 16, u % 16, lds);
     }
 }
 
@@ -590,19 +602,23 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     const WgradArgs G3{d3, act2, w.gp3, B, rps3, net::A2, net::L3N, 1.0f};
     const WgradArgs G4{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
     if (sd == st) {
+        // the priority update in three parts: few levels beside fc1's short launch, the rest in halves
+        const int lv = c->levels;
+        const SplitUpdate U{tail->update, w.pu_state, {lv / 10, 11 * lv / 20, 11 * lv / 20}, tail->with_update ? 1 : 0};
+        const misc::HeadWgradArgs &HW = tail->head;
         {
             DgradArgs D{dh, c->theta + net::F1W, act3, d3, B};
             const int gx = (B + 31) / 32;
-            const int nh = c->R * 16 + (tail->with_update ? 1 : 0);
+            const int nh = c->R * 16 + U.on;
             if (small) {
                 PairF32 P{gx * 98, gx, 1, 49 * 8, 49, 8, 1};
                 launch(c, "fc1_bwd", st, [&] {
-                    k_layer_bwd_f32<DFc1, 32, 32, 4, GFc1, 256, true><<<P.nd + P.nw + nh, 256, 0, st>>>(D, G4, P, *tail);
+                    k_layer_bwd_f32<DFc1, 32, 32, 4, GFc1, 256, true, 0><<<P.nd + P.nw + nh, 256, 0, st>>>(D, G4, P, HW, U);
                 });
             } else {
                 PairF32 P{gx * 49, gx, 1, 49 * 8, 49, 8, 1};
                 launch(c, "fc1_bwd", st, [&] {
-                    k_layer_bwd_f32<DFc1, 32, 64, 1, GFc1, 256, true><<<P.nd + P.nw + nh, 256, 0, st>>>(D, G4, P, *tail);
+                    k_layer_bwd_f32<DFc1, 32, 64, 1, GFc1, 256, true, 0><<<P.nd + P.nw + nh, 256, 0, st>>>(D, G4, P, HW, U);
                 });
             }
         }
@@ -612,13 +628,13 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
                 const int gx = (int)(((long)B * 81 + 31) / 32);
                 PairF32 P{gx * 2, gx, 1, 9 * *ns3, 9, 1, *ns3};
                 launch(c, "conv3_bwd", st, [&] {
-                    k_layer_bwd_f32<DConv3, 32, 32, 6, GConv3, 384, false><<<P.nd + P.nw, 384, 0, st>>>(D, G3, P, *tail);
+                    k_layer_bwd_f32<DConv3, 32, 32, 6, GConv3, 384, false, 1><<<P.nd + P.nw + U.on, 384, 0, st>>>(D, G3, P, HW, U);
                 });
             } else {
                 const int gx = (int)(((long)B * 81 + 63) / 64);
                 PairF32 P{gx, gx, 1, 9 * *ns3, 9, 1, *ns3};
                 launch(c, "conv3_bwd", st, [&] {
-                    k_layer_bwd_f32<DConv3, 64, 64, 1, GConv3, 256, false><<<P.nd + P.nw, 256, 0, st>>>(D, G3, P, *tail);
+                    k_layer_bwd_f32<DConv3, 64, 64, 1, GConv3, 256, false, 1><<<P.nd + P.nw + U.on, 256, 0, st>>>(D, G3, P, HW, U);
                 });
             }
         }
@@ -627,7 +643,7 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
             const int gx = (int)(((long)B * 100 + 63) / 64);
             PairF32 P{gx * 4, gx, 4, 8 * *ns2, 8, 1, *ns2};
             launch(c, "conv2_bwd", st, [&] {
-                k_layer_bwd_f32<DConv2, 64, 32, 4, GConv2, 512, false><<<P.nd + P.nw, 512, 0, st>>>(D, G2, P, *tail);
+                k_layer_bwd_f32<DConv2, 64, 32, 4, GConv2, 512, false, 3><<<P.nd + P.nw + U.on, 512, 0, st>>>(D, G2, P, HW, U);
             });
         }
         if (B <= 64) launch(c, "conv1_wgrad", st, [&] { k_wgrad<GConv1, 32, 128><<<dim3(2, 1, *ns1), 256, 0, st>>>(G1); });
@@ -658,24 +674,6 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     launch(c, "conv3_wgrad", sd, [&] { k_wgrad<GConv3, 64, 64><<<dim3(9, 1, *ns3), 256, 0, sd>>>(G3); });
     ev_wait(sd, c->ev_b, st);
     launch(c, "conv2_wgrad", sd, [&] { k_wgrad<GConv2, 64, 64><<<dim3(8, 1, *ns2), 256, 0, sd>>>(G2); });
-}
-
-// The priority update (one workgroup, twenty tree levels one after the other, needs only the TD
-// errors) rides in the four launches of the backward pass as their workgroup 0, four entries per
-// thread and a share of the levels per launch (the first part, which also settles the duplicates and
-// raises the new priorities to the power alpha, takes the fewest): each part is shorter than the
-// launch it sits in, so the update costs no launch, no stream and no event.
-struct SplitUpdate {
-    misc::PerUpdateArgs update;
-    int *state;
-    int upto[3];        // tree levels walked when part 0, 1, 2 ends (part 3 goes to the root)
-    int on;             // 0: no update in this step
-};
-// part k of the update (k = 0: settle duplicates, write the leaves, first levels)
-__device__ __forceinline__ void update_part(const SplitUpdate &U, int k, int *lds)
-{
-    if (k == 0) misc::per_update_body<4>(U.update, lds, U.upto[0], U.state);
-    else misc::per_update_resume<4>(U.update, U.upto[k - 1], k < 3 ? U.upto[k] - U.upto[k - 1] : U.update.levels, U.state);
 }
 
 // fc1's backward pair (see gbf::k_bwd_pair) with the head's weight gradient as a third group of
