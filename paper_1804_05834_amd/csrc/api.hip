@@ -53,7 +53,7 @@ constexpr size_t MAX_STEP_GRAPHS = 16;  // recorded steps kept per context (one 
 int fc1_splits(long M, int precision)
 {
     if (precision == 1) return M <= 2048 ? 7 : 1;
-    return M <= 192 ? 14 : M <= 512 ? 7 : M <= 1536 ? 2 : 1;
+    return M <= 512 ? 7 : M <= 1536 ? 2 : 1;
 }
 
 Workspace carve(const dqn_config &c, uint8_t *base)
@@ -364,7 +364,8 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
         int tiles = build(A, 32, 1, [&](int i) { return (const void *)(act3 + row0[i] * net::A3); },
                           [&](int) { return (long)net::A3; }, net::F1W, net::F1B, w.f1part, net::HID, false);
         A.klen = GFc1::K / ns; A.split_stride = rows * net::HID; A.scale = 1.0f;
-        if (ns == 14) launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 32, 32, 7><<<dim3(tiles, 16, ns), 448, 0, st>>>(A); });
+        // few rows: the reduction of a split is sliced over seven wave groups of the workgroup as well
+        if (rows <= 192) launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 32, 32, 7><<<dim3(tiles, 16, ns), 448, 0, st>>>(A); });
         else launch(c, "fc1_fwd", st, [&] { k_fwd<GFc1, 32, 64><<<dim3(tiles, 8, ns), 128, 0, st>>>(A); });
         *nsplit_out = ns;
         *split_stride_out = rows * net::HID;
