@@ -494,9 +494,39 @@ void ev_wait(hipStream_t waiter, hipEvent_t e, hipStream_t other)
     if (waiter != other) (void)hipStreamWaitEvent(waiter, e, 0);
 }
 
+// The priority update (one workgroup, twenty tree levels one after the other, needs only the TD
+// errors) rides in other launches as their workgroup 0 (bf16: the backward launches of fc1, conv3 and conv2 and the RMSProp launch; fp32: those three backward launches), four entries per
+// thread and a share of the levels per launch (the first part, which also settles the duplicates and
+// raises the new priorities to the power alpha, takes the fewest): each part is shorter than the
+// launch it sits in, so the update costs no launch, no stream and no event.
+struct SplitUpdate {
+    misc::PerUpdateArgs update;
+    int *state;
+    int upto[3];        // tree levels walked when part 0, 1, 2 ends (part 3 goes to the root)
+    int on;             // 0: no update in this step
+};
+// part k of the update (k = 0: settle duplicates, write the leaves, first levels)
+__device__ __forceinline__ void update_part(const SplitUpdate &U, int k, int *lds)
+{
+    if (k == 0) misc::per_update_body<4>(U.update, lds, U.upto[0], U.state);
+    else misc::per_update_resume<4>(U.update, U.upto[k - 1], k < 3 ? U.upto[k] - U.upto[k - 1] : U.update.levels, U.state);
+}
+
+// RMSProp after workgroup 0, which finishes the priority update (conv1's weight-gradient launch
+// fills every workgroup slot of the chip with its own 512 workgroups; RMSProp's are many and short)
+__global__ __launch_bounds__(256) void k_rmsprop_pu(misc::RmsArgs A, SplitUpdate U)
+{
+    __shared__ float red[4][64];
+    if (blockIdx.x == 0) return update_part(U, 3, nullptr);
+    const int bx = (int)blockIdx.x - 1;
+    RMS_SELECT_SEGMENT(A, bx, S)
+    misc::rmsprop_block(A, S, bx, red);
+}
+
 // ----- RMSProp over a subset of the layers (bit i of `layers`: conv1, conv2, conv3, fc1, head) -----
 enum : unsigned { RMS_CONV1 = 1, RMS_CONV2 = 2, RMS_CONV3 = 4, RMS_FC1 = 8, RMS_HEAD = 16, RMS_ALL = 31 };
-void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipStream_t st)
+void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipStream_t st,
+                    const SplitUpdate *last_part = nullptr)
 {
     const dqn_config &cfg = c->cfg;
     const Workspace &w = c->ws;
@@ -516,7 +546,8 @@ void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipS
     RA.theta = c->theta; RA.v = c->rms_v; RA.m = c->rms_m; RA.g = c->grads;
     RA.shadow = cfg.precision == 1 ? (__hip_bfloat16 *)c->buf.shadow_bf16 : nullptr;
     RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps;
-    launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
+    if (last_part && last_part->on) launch(c, "rmsprop", st, [&] { k_rmsprop_pu<<<blk + 1, 256, 0, st>>>(RA, *last_part); });
+    else launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
 }
 
 // What rides in the launches of the backward pass beside the trunk's gradients: the head's weight
@@ -526,24 +557,6 @@ struct SmallTail {
     misc::PerUpdateArgs update;
     bool with_update;
 };
-
-// The priority update (one workgroup, twenty tree levels one after the other, needs only the TD
-// errors) rides in the launches of the backward pass (four in bf16, the first three in fp32) as their workgroup 0, four entries per
-// thread and a share of the levels per launch (the first part, which also settles the duplicates and
-// raises the new priorities to the power alpha, takes the fewest): each part is shorter than the
-// launch it sits in, so the update costs no launch, no stream and no event.
-struct SplitUpdate {
-    misc::PerUpdateArgs update;
-    int *state;
-    int upto[3];        // tree levels walked when part 0, 1, 2 ends (part 3 goes to the root)
-    int on;             // 0: no update in this step
-};
-// part k of the update (k = 0: settle duplicates, write the leaves, first levels)
-__device__ __forceinline__ void update_part(const SplitUpdate &U, int k, int *lds)
-{
-    if (k == 0) misc::per_update_body<4>(U.update, lds, U.upto[0], U.state);
-    else misc::per_update_resume<4>(U.update, U.upto[k - 1], k < 3 ? U.upto[k] - U.upto[k - 1] : U.update.levels, U.state);
-}
 
 // ----- fp32 on one stream: one backward launch per layer, as in the bf16 step -----
 // The layer's input-gradient tiles and its weight-gradient tiles share a launch (both read the
@@ -725,22 +738,13 @@ __global__ __launch_bounds__(256, 2) void k_conv2_bwd_pu(gbf::dps::Args PA, gbf:
     else wgrad_tile<GConv2, 64, 64, 1, 1, true>(WA, tile_of(id - nps, nw), wgx, wgy, wgz, reinterpret_cast<bf16_t *>(lds));
 }
 
-// conv1's weight gradient after workgroup 0
-__global__ __launch_bounds__(256) void k_conv1_wgrad_pu(gbf::c1::WgradArgs A, SplitUpdate U)
-{
-    __shared__ __attribute__((aligned(16))) gbf::bf16_t lds[gbf::c1::WG1_LDS];
-    if (U.on && blockIdx.x == 0) return update_part(U, 3, reinterpret_cast<int *>(lds));
-    const int u = (int)blockIdx.x - U.on, total = (int)gridDim.x - U.on;
-    gbf::c1::conv1_wgrad_block(A, gbf::tile_of(u, total), lds);
-}
-
 // bf16: one stream and one launch per layer, the layer's input gradient and weight gradient side by
 // side in it (both read the layer's dY and nothing else that the backward pass computes).  Events
 // between streams cost more than they gain here: a record or a wait on the critical stream adds
 // about 4 us to the gap between two kernels, and a kernel on another stream starts 11-14 us after
 // the kernel it waits for has ended.
 void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *ns3, hipStream_t st,
-                   const SmallTail &tail)
+                   const misc::HeadWgradArgs &head, const SplitUpdate &U)
 {
     using namespace gbf;
     const Workspace &w = c->ws;
@@ -748,15 +752,13 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     bf16_t *dh = (bf16_t *)w.dh, *d3 = (bf16_t *)w.d3, *d2 = (bf16_t *)w.d2, *d1 = (bf16_t *)w.d1;
     const bf16_t *sh = shadow_of(c, 0);
     int rps;
-    const int lv = c->levels;
-    const SplitUpdate U{tail.update, w.pu_state, {lv / 10, 3 * lv / 10, 6 * lv / 10}, tail.with_update ? 1 : 0};
     {
         DgradArgs D{dh, sh + net::F1W, act3, d3, B};
         WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
         const int gx = (B + 63) / 64;
         PairGrid P{gx * 49, gx, 1, 49 * 8, 49, 8, 1};
         const int nh = c->R * 16;
-        launch(c, "fc1_bwd", st, [&] { k_fc1_head_bwd<<<P.nd + P.nw + nh + U.on, 256, 0, st>>>(D, G, P, tail.head, U); });
+        launch(c, "fc1_bwd", st, [&] { k_fc1_head_bwd<<<P.nd + P.nw + nh + U.on, 256, 0, st>>>(D, G, P, head, U); });
     }
     {
         DgradArgs D{d3, sh + net::C3W, act2, d2, B};
@@ -776,7 +778,7 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     {   // conv1: one workgroup per split of samples, frames staged in LDS
         *ns1 = std::min(B, MAX_WSPLIT1);
         c1::WgradArgs G{c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift}, d1, w.gp1, B, *ns1};
-        launch(c, "conv1_wgrad", st, [&] { k_conv1_wgrad_pu<<<2 * *ns1 + U.on, 256, 0, st>>>(G, U); });
+        launch(c, "conv1_wgrad", st, [&] { c1::k_conv1_wgrad<<<dim3(*ns1, 2), 256, 0, st>>>(G); });
     }
 }
 
@@ -1292,14 +1294,17 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     if (sp != sd) (void)hipEventRecord(c->ev_join2, sp);
 
     int ns1, ns2, ns3;
-    if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, tail);
+    // bf16: the update in four parts: beside fc1's, conv3's and conv2's gradients and inside the RMSProp launch
+    const int lv = c->levels;
+    const SplitUpdate U{PU, w.pu_state, {lv / 10, 3 * lv / 10, 6 * lv / 10}, batch ? 0 : 1};
+    if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, HW, U);
     else backward_f32(c, B, stacking ? w.stack5 : s, stacking ? 5L * net::FRAME : xs, &ns1, &ns2, &ns3, st, sd,
                       fuse_tail ? &tail : nullptr);
     ev_record(c->ev_join, sd, st);
     ev_wait(st, c->ev_join, sd);
     if (sp != sd) (void)hipStreamWaitEvent(st, c->ev_join2, 0);
 
-    launch_rmsprop(c, RMS_ALL, ns1, ns2, ns3, st);
+    launch_rmsprop(c, RMS_ALL, ns1, ns2, ns3, st, cfg.precision == 1 ? &U : nullptr);
     return hip_status(c, "dqn_train_step");
 }
 

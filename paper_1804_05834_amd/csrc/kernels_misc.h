@@ -416,19 +416,24 @@ __device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g)
     if (A.shadow) A.shadow[i] = __float2bfloat16(th);
 }
 
-__global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
+// The segment that workgroup bx belongs to.  A macro, to be used on the KERNEL PARAMETER itself: picked
+// through a reference or a copy of the argument structure, the segment array ends up in scratch memory.
+#define RMS_SELECT_SEGMENT(A, bx, S)                                  \
+    misc::RmsSeg S = (A).seg[0];                                     \
+    {                                                                \
+        int s_ = 0;                                                  \
+        _Pragma("unroll") for (int t_ = 1; t_ < 5; ++t_)             \
+            if ((bx) >= (A).seg[t_].block_begin) s_ = t_;            \
+        if (s_ == 1) S = (A).seg[1];                                 \
+        if (s_ == 2) S = (A).seg[2];                                 \
+        if (s_ == 3) S = (A).seg[3];                                 \
+        if (s_ == 4) S = (A).seg[4];                                 \
+    }
+
+// workgroup bx (256 threads) of the update, in segment S; red: 256 floats of LDS
+__device__ __forceinline__ void rmsprop_block(const RmsArgs &A, const RmsSeg &S, int bx, float (*red)[64])
 {
-    __shared__ float red[4][64];
-    const int bx = blockIdx.x, tid = threadIdx.x;
-    int s = 0;
-#pragma unroll
-    for (int t = 1; t < 5; ++t)
-        if (bx >= A.seg[t].block_begin) s = t;
-    RmsSeg S = A.seg[0];
-    if (s == 1) S = A.seg[1];
-    if (s == 2) S = A.seg[2];
-    if (s == 3) S = A.seg[3];
-    if (s == 4) S = A.seg[4];
+    const int tid = threadIdx.x;
     if (S.nsplit > 1) {
         const int pl = tid & 63, sg = tid >> 6;
         const long o = (long)(bx - S.block_begin) * 64 + pl;
@@ -445,6 +450,12 @@ __global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
         const long o = (long)(bx - S.block_begin) * 256 + tid;
         if (o < S.count) rms_update(A, S.begin + o, S.part[o]);
     }
+}
+__global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
+{
+    __shared__ float red[4][64];
+    RMS_SELECT_SEGMENT(A, (int)blockIdx.x, S)
+    rmsprop_block(A, S, blockIdx.x, red);
 }
 
 // fp32 -> bf16 copy (round to nearest even)
