@@ -33,6 +33,7 @@ def flops_per_launch(B, R):
     head = 2 * 512 * R
     return {
         "conv1_fwd": 3 * B * F_CONV1, "conv2_fwd": 3 * B * F_CONV2, "conv3_fwd": 3 * B * F_CONV3,
+        "conv12_fwd": 3 * B * (F_CONV1 + F_CONV2),   # bf16, larger batches: conv1 + conv2 in one launch
         "fc1_fwd": 3 * B * F_FC1, "head_train": 4 * B * head, "head_wgrad": B * head,
         "fc1_dgrad": B * F_FC1, "fc1_wgrad": B * F_FC1, "conv3_dgrad": B * F_CONV3,
         "conv3_wgrad": B * F_CONV3, "conv2_dgrad": B * F_CONV2, "conv2_wgrad": B * F_CONV2,
@@ -63,6 +64,8 @@ def gemm_bytes_per_launch(B, R, bf16):
     return {
         "conv1_fwd": frames + w1 + 3 * B * a1,
         "conv2_fwd": 3 * B * (a1 + a2) + w2,
+        # the fused launch keeps conv1's output on the CU; only the training rows' copy goes to memory
+        "conv12_fwd": frames + w1 + w2 + B * a1 + 3 * B * a2,
         "conv3_fwd": 3 * B * (a2 + a3) + w3,
         "fc1_fwd": 3 * B * (a3 + hid) + wf,
         "fc1_dgrad": B * (512 * e + 2 * a3) + wf,           # dH, ReLU mask, dX

@@ -132,6 +132,9 @@ struct dqn_ctx {
     // side stream: kernels off the critical chain (weight gradients, priority update) overlap
     // the input-gradient chain of the backward pass
     int num_cu = 256;  // compute units of the device
+    // bf16: conv1 + conv2 forward run as one launch (gbf::c12) from this many samples per launch on;
+    // INT_MAX: never (the launch needs 140 KB of LDS per workgroup, granted at initialisation)
+    int conv12_min = INT32_MAX;
     hipStream_t side = nullptr;
     hipStream_t side2 = nullptr;  // the single-workgroup priority update gets a lane of its own
     hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_c = nullptr, ev_join = nullptr, ev_join2 = nullptr;
@@ -403,6 +406,34 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         return tile;
     };
 
+    // conv1 + conv2 as one launch, one workgroup per CU, when every CU gets several samples
+    bool fused12 = rows >= c->conv12_min && npass <= c->num_cu;
+    const int grid12 = (int)std::min<long>(rows, c->num_cu);
+    for (int i = 0; fused12 && i < npass; ++i) {
+        const int wgs = (int)((long)grid12 * (i + 1) / npass - (long)grid12 * i / npass);
+        if (wgs < 1 || (pass[i].n + wgs - 1) / wgs > c12::MAX_PER_WG) fused12 = false;
+        if (draw && pass[i].n != pass[0].n) fused12 = false;
+    }
+    if (fused12) {
+        c12::Args A{};
+        A.nseg = npass;
+        for (int i = 0; i < npass; ++i) {
+            c12::Seg &S = A.seg[i];
+            S.src = c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift};
+            S.w1 = shadow_of(c, pass[i].net) + net::C1W;
+            S.b1 = theta_of(c, pass[i].net) + net::C1B;
+            // only the backward pass reads conv1's output, and only the rows of the first pass of a training step
+            S.y1 = npass == 3 && i == 0 ? act1 + row0[i] * net::A1 : nullptr;
+            S.w2 = shadow_of(c, pass[i].net) + net::C2W;
+            S.b2 = theta_of(c, pass[i].net) + net::C2B;
+            S.y2 = act2 + row0[i] * net::A2;
+            S.n = pass[i].n;
+        }
+        for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
+        A.draw = draw != nullptr;
+        if (draw) A.samp = *draw;
+        launch(c, "conv12_fwd", st, [&] { c12::k_conv12_fwd<<<dim3(grid12), 512, c12::LDS_BYTES, st>>>(A); });
+    } else
     {  // conv1: persistent waves, strips of the frames staged in LDS (read from the ring in ring mode)
         c1::FwdArgs A{};
         A.nseg = npass;
@@ -442,7 +473,7 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         A.total = first;
         return std::min(first, 2 * c->num_cu);
     };
-    {
+    if (!fused12) {
         ps::Args A{};
         const int grid = per_sample(A, act1, net::A1, net::C2W, net::C2B, act2, net::A2);
         launch(c, "conv2_fwd", st, [&] { ps::k_conv_fwd_ps<ps::G2><<<dim3(grid), 256, 0, st>>>(A); });
@@ -894,6 +925,16 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
             c->num_cu = cus;
+    }
+    // DQN_CONV12_MIN_SAMPLES in the environment moves the batch size from which the fused conv1 + conv2
+    // forward launch is used (samples of all passes of a launch; a huge value switches it off)
+    if (cfg->precision == 1 &&
+        hipFuncSetAttribute((const void *)gbf::c12::k_conv12_fwd, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            gbf::c12::LDS_BYTES) == hipSuccess) {
+        const char *m = std::getenv("DQN_CONV12_MIN_SAMPLES");
+        c->conv12_min = m && m[0] ? std::atoi(m) : 3 * c->num_cu;
+    } else {
+        (void)hipGetLastError();
     }
     // side stream at the default priority; if anything fails the step simply runs on one stream
     // (DQN_SINGLE_STREAM=1 in the environment keeps everything on the caller's stream)

@@ -1411,6 +1411,278 @@ __global__ __launch_bounds__(256, 2) void k_conv_fwd_ps(Args A)
 }  // namespace ps
 
 // ===========================================================================
+// conv1 + conv2 forward in ONE launch (Section 2.1 network): conv1's output of a sample never leaves
+// the CU unless a later kernel reads it (the backward pass reads it for the training rows only).
+//
+// A workgroup of eight waves owns a run of samples of one segment.  Waves 0-3 are PRODUCERS: each
+// computes one conv1 strip per interval exactly as c1::k_conv1_fwd does (strip staged in LDS of its
+// own, weights in registers, next strip's pixels in flight) and writes the 80 x 32 result into the
+// sample's place in a ring of three LDS images, in the layout ps::run reads.  Waves 4-7 are
+// CONSUMERS: they hold conv2's weights in registers as ps::k_conv_fwd_ps does and, in every interval
+// in which a sample has become complete, compute its conv2 output out of the ring.  One barrier per
+// interval.  Strips are dealt out in order, four per interval, five per sample: sample k is complete
+// after interval floor((5k+4)/4) and is consumed in the first interval i with 4i >= 5k+5, which is a
+// different interval for every k; the producers are then at most two samples ahead of the sample
+// being read, so three images suffice.
+//
+// Replay mode: the workgroup draws its samples first (Eq.10 walk, two draws per wave and walk, all
+// eight waves), while the consumers' weight loads are in flight; the workgroups of segment 0 publish
+// the draws.  Otherwise the slots (ring mode) are copied into LDS from where a sampling kernel left them.
+// Workgroups are dealt out per segment, so none pays the start-up twice.
+// ===========================================================================
+namespace c12 {
+using c1::Src;
+using c1::StripOff;
+using c1::StripRaw;
+using c1::STRIP;
+using c1::UNITS;
+using S2 = ps::Shape<ps::G2>;
+using ps::u32x4;
+
+struct Seg {
+    Src src;
+    const bf16_t *w1;   // [32][256]
+    const float *b1;    // [32]
+    bf16_t *y1;         // [n][400][32], or nullptr: conv1's output is not kept
+    const bf16_t *w2;   // [64][512]
+    const float *b2;    // [64]
+    bf16_t *y2;         // [n][81][64]
+    int n;              // samples
+};
+struct Args {
+    Seg seg[3];
+    int nseg;
+    int draw;           // replay mode: sample g of every segment is draw g of `samp`; segment 0 publishes
+    misc::SampleArgs samp;
+};
+
+constexpr int NRING = 3;                                    // conv1 images in LDS
+constexpr int MAX_PER_WG = 32;                              // samples one workgroup may own (slot table)
+constexpr int STRIPS_B = 4 * STRIP * 2;                     // 53,760 bytes: one strip per producer wave
+constexpr int RING_B = NRING * S2::SAMPLE;                  // 86,400 bytes
+constexpr int LDS_BYTES = STRIPS_B + RING_B + MAX_PER_WG * 4;
+constexpr int intervals(int ns) { return (UNITS * ns + 3) / 4 + 1; }
+
+// samples [lo, hi) of segment S, consumer wave (ph, hh) = (position half, channel half)
+__device__ __forceinline__ void run_consumer(const Seg &S, int lo, int hi, const uint8_t *ring, const v8bf (&wa)[16][2],
+                                             int lane, int ph, int hh)
+{
+    const int n = lane & 15, kg = lane >> 4;
+    const int ns = hi - lo, nint = intervals(ns);
+    const v4f b0 = *reinterpret_cast<const v4f *>(S.b2 + 32 * hh + 8 * kg);
+    const v4f b1 = *reinterpret_cast<const v4f *>(S.b2 + 32 * hh + 8 * kg + 4);
+    uint32_t base[3];
+    int pos[3];
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        int p = 16 * (3 * ph + b) + n;
+        pos[b] = p;
+        if (p > 80) p = 80;   // positions past the end read a valid pixel and are not stored
+        base[b] = S2::at(2 * (20 * (p / 9) + (p % 9)), kg);
+    }
+    int kc = 0;   // next sample to consume
+    for (int i = 0; i < nint; ++i) {
+        if (kc < ns && UNITS * kc + UNITS <= 4 * i) {
+            const uint8_t *buf = ring + (kc % NRING) * S2::SAMPLE;
+            v4f acc[3][2];
+#pragma unroll
+            for (int b = 0; b < 3; ++b) acc[b][0] = acc[b][1] = v4f{0, 0, 0, 0};
+            // the operands of step st+1 are requested before the matrix instructions of step st
+            uint4 cur[3], nxt[3];
+#pragma unroll
+            for (int b = 0; b < 3; ++b) cur[b] = *reinterpret_cast<const uint4 *>(buf + base[b]);
+#pragma unroll
+            for (int st = 0; st < 16; ++st) {
+                if (st < 15) {
+                    const int off = (int)S2::at(20 * ((st + 1) >> 2) + ((st + 1) & 3), 0);
+#pragma unroll
+                    for (int b = 0; b < 3; ++b) nxt[b] = *reinterpret_cast<const uint4 *>(buf + base[b] + off);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int b = 0; b < 3; ++b) {
+                    const v8bf bb = __builtin_bit_cast(v8bf, cur[b]);
+                    acc[b][0] = mfma16(wa[st][0], bb, acc[b][0]);
+                    acc[b][1] = mfma16(wa[st][1], bb, acc[b][1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int b = 0; b < 3; ++b) cur[b] = nxt[b];
+            }
+            bf16_t *y = S.y2 + (long)(lo + kc) * (81 * 64) + 32 * hh + 8 * kg;
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                if (pos[b] < 81) {
+                    const v4f a0 = acc[b][0], a1 = acc[b][1];
+                    const uint2 l2 = pack4(fmaxf(a0.x + b0.x, 0.f), fmaxf(a0.y + b0.y, 0.f), fmaxf(a0.z + b0.z, 0.f), fmaxf(a0.w + b0.w, 0.f));
+                    const uint2 h2 = pack4(fmaxf(a1.x + b1.x, 0.f), fmaxf(a1.y + b1.y, 0.f), fmaxf(a1.z + b1.z, 0.f), fmaxf(a1.w + b1.w, 0.f));
+                    *reinterpret_cast<uint4 *>(y + pos[b] * 64) = uint4{l2.x, l2.y, h2.x, h2.y};
+                }
+            }
+            ++kc;
+        }
+        sync_lds();
+    }
+}
+
+// samples [lo, hi) of segment S, producer wave w: strips w, w + 4, ... of the run's strip list.
+// R holds the pixels of strip w (requested by the caller); slots: the run's ring slots (ring mode).
+__device__ __forceinline__ void run_producer(const Seg &S, int lo, int hi, bf16_t *xs, uint8_t *ring, const int *slots,
+                                             StripRaw &R, const StripOff &O, int lane, int w)
+{
+    const int n = lane & 15, kg = lane >> 4, oyl = n >> 2, q = n & 3;
+    const int ns = hi - lo, nstrips = UNITS * ns, nint = intervals(ns);
+    v8bf wa[8][2];   // [2c + xh][channel half], as in c1::conv1_fwd_units
+#pragma unroll
+    for (int st = 0; st < 8; ++st)
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+            const int ch = 8 * (n >> 2) + 4 * h2 + (n & 3);
+            const bf16_t *p = S.w1 + ch * 256 + (st >> 1) * 64 + (2 * kg) * 8 + 4 * (st & 1);
+            const uint2 l2 = *reinterpret_cast<const uint2 *>(p), hi2 = *reinterpret_cast<const uint2 *>(p + 8);
+            wa[st][h2] = __builtin_bit_cast(v8bf, uint4{l2.x, l2.y, hi2.x, hi2.y});
+        }
+    const v4f b0 = *reinterpret_cast<const v4f *>(S.b1 + 8 * kg), b1 = *reinterpret_cast<const v4f *>(S.b1 + 8 * kg + 4);
+    const uint32_t px = (uint32_t)(uintptr_t)(xs + (4 * oyl + 2 * kg) * 84 + 20 * q);
+    int u = w;
+    for (int i = 0; i < nint; ++i) {
+        if (u < nstrips) {
+            const int k = u / UNITS, strip = u % UNITS;
+            c1::strip_store(xs, R, lane);   // LDS operations of one wave complete in order
+            const int un = u + 4;
+            if (un < nstrips) c1::strip_load(R, S.src, lo + un / UNITS, S.src.idx ? slots[un / UNITS] : 0, un % UNITS, lane, O);
+            struct Quads { uint4 q[6]; };
+            auto quads = [&](int c) {   // see c1::conv1_fwd_units
+                typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+                const uint32_t addr = px + c * (c1::SROWS * 84 * 2);
+                Quads Q;
+#define C12_RD2(JJ) { v4u t; asm volatile("ds_read2_b64 %0, %1 offset0:%2 offset1:%3" : "=v"(t) : "v"(addr), "n"(JJ), "n"(JJ + 21)); Q.q[JJ] = uint4{t.x, t.y, t.z, t.w}; }
+                C12_RD2(0) C12_RD2(1) C12_RD2(2) C12_RD2(3) C12_RD2(4) C12_RD2(5)
+#undef C12_RD2
+                return Q;
+            };
+            v4f acc[5][2];
+#pragma unroll
+            for (int j = 0; j < 5; ++j) acc[j][0] = acc[j][1] = v4f{0, 0, 0, 0};
+            Quads cur = quads(0);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                Quads nxt = cur;
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // `cur` has arrived
+                if (c < 3) nxt = quads(c + 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int xh = 0; xh < 2; ++xh)
+#pragma unroll
+                    for (int j = 0; j < 5; ++j) {
+                        const v8bf b = __builtin_bit_cast(v8bf, cur.q[j + xh]);
+                        acc[j][0] = mfma16(wa[2 * c + xh][0], b, acc[j][0]);
+                        acc[j][1] = mfma16(wa[2 * c + xh][1], b, acc[j][1]);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+                cur = nxt;
+            }
+            // bias, 1/255, ReLU, bf16: into the sample's image in the ring and, where kept, to memory
+            uint8_t *img = ring + (k % NRING) * S2::SAMPLE;
+            uint8_t *yb = S.y1 ? reinterpret_cast<uint8_t *>(S.y1) + ((long)(lo + k) * 400 + 80 * strip) * 64 +
+                                     ((20 * oyl + 5 * q) * 32 + 8 * kg) * 2
+                               : nullptr;
+            constexpr float sc = 1.0f / 255.0f;
+#pragma unroll
+            for (int j = 0; j < 5; ++j) {
+                const v4f a0 = acc[j][0], a1 = acc[j][1];
+                const uint2 l2 = pack4(fmaxf(a0.x * sc + b0.x, 0.f), fmaxf(a0.y * sc + b0.y, 0.f),
+                                       fmaxf(a0.z * sc + b0.z, 0.f), fmaxf(a0.w * sc + b0.w, 0.f));
+                const uint2 h2 = pack4(fmaxf(a1.x * sc + b1.x, 0.f), fmaxf(a1.y * sc + b1.y, 0.f),
+                                       fmaxf(a1.z * sc + b1.z, 0.f), fmaxf(a1.w * sc + b1.w, 0.f));
+                const uint4 v = uint4{l2.x, l2.y, h2.x, h2.y};
+                *reinterpret_cast<uint4 *>(img + S2::at(80 * strip + 20 * oyl + 5 * q + j, kg)) = v;
+                if (yb) *reinterpret_cast<uint4 *>(yb + j * 64) = v;
+            }
+            u = un;
+        }
+        sync_lds();
+    }
+}
+
+// Segment t owns workgroups [G t / nseg, G (t+1) / nseg); each of them an even share of its samples.
+// The host sizes the grid so that no share exceeds MAX_PER_WG.  Dynamic LDS: LDS_BYTES.
+__global__ __launch_bounds__(512) void k_conv12_fwd(Args A)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    int s = 0, w0 = 0, w1 = 1;
+    for (int t = 0; t < A.nseg; ++t) {
+        const int a = (int)((long)gridDim.x * t / A.nseg), b = (int)((long)gridDim.x * (t + 1) / A.nseg);
+        if ((int)blockIdx.x >= a && (int)blockIdx.x < b) { s = t; w0 = a; w1 = b; }
+    }
+    Seg S = A.seg[0];
+    if (s == 1) S = A.seg[1];
+    if (s == 2) S = A.seg[2];
+    const int lo = (int)((long)((int)blockIdx.x - w0) * S.n / (w1 - w0));
+    const int hi = (int)((long)((int)blockIdx.x - w0 + 1) * S.n / (w1 - w0));
+    if (lo >= hi) return;   // the whole workgroup
+    const int ns = hi - lo;
+    uint8_t *ring = lds + STRIPS_B;
+    int *slots = reinterpret_cast<int *>(lds + STRIPS_B + RING_B);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // The slots of the run: drawn here, two per wave and walk, or copied from the index list.
+    auto fill_slots = [&]() {
+        if (!S.src.idx) return;
+        if (A.draw) {
+            const float total = A.samp.tree[1];
+#pragma unroll 1
+            for (int k = 2 * wave; k < ns; k += 16) {
+                const int kb = k + 1 < ns ? k + 1 : k;
+                long s0, s1;
+                misc::per_sample_descend2(A.samp, lo + k, lo + kb, lane, total, s0, s1);
+                if (lane == 0) {
+                    slots[k] = (int)s0;
+                    slots[kb] = (int)s1;
+                    if (s == 0) {
+                        misc::per_sample_emit(A.samp, lo + k, s0, total);
+                        if (kb != k) misc::per_sample_emit(A.samp, lo + kb, s1, total);
+                    }
+                }
+            }
+        } else {
+            for (int k = tid; k < ns; k += 512) slots[k] = S.src.idx[lo + k];
+        }
+    };
+
+    if (wave >= 4) {
+        const int n = lane & 15, kg = lane >> 4, ph = wave & 1, hh = (wave >> 1) & 1;
+        // this wave's share of conv2's weights, straight into a-operand registers (row 8(n/4) + 4cb + n%4 of
+        // channel half hh, reduction elements 32st + 8kg .. +7); on its way while the slots are found
+        v8bf wa[16][2];
+#pragma unroll
+        for (int st = 0; st < 16; ++st)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                const int chl = 8 * (n >> 2) + 4 * cb + (n & 3);
+                wa[st][cb] = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(S.w2 + (32 * hh + chl) * 512 + st * 32 + kg * 8));
+            }
+        fill_slots();
+        sync_lds();   // the slot table is complete
+        run_consumer(S, lo, hi, ring, wa, lane, ph, hh);
+    } else {
+        StripOff O;
+#pragma unroll
+        for (int i = 0; i < 7; ++i) {
+            const int t = lane + 64 * i;
+            O.off[i] = t < c1::CHUNKS ? (t / (c1::CHUNKS / 4)) * c1::FR + (t % (c1::CHUNKS / 4)) * 16 : 0;
+        }
+        fill_slots();
+        sync_lds();   // the slot table is complete
+        StripRaw R;
+        if (wave < UNITS * ns) c1::strip_load(R, S.src, lo + wave / UNITS, S.src.idx ? slots[wave / UNITS] : 0, wave % UNITS, lane, O);
+        run_producer(S, lo, hi, reinterpret_cast<bf16_t *>(lds) + wave * STRIP, ring, slots, R, O, lane, wave);
+    }
+}
+}  // namespace c12
+
+// ===========================================================================
 // Input gradient of conv2, one sample per workgroup (Section 2.1 network, backward pass of the
 // Section 2.2 loss).  dX[pixel][ci] = sum over taps and co of dY[position][co] W[co][tap][ci]:
 // the reduction runs over (tap, co), so the weights are needed with co as the reduction index and
