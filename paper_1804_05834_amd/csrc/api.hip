@@ -406,7 +406,7 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         return tile;
     };
 
-    // conv1 + conv2 as one launch, one workgroup per CU, when every CU gets several samples
+    // conv1 + conv2 as one launch, one workgroup per CU (faster from a handful of samples on)
     bool fused12 = rows >= c->conv12_min && npass <= c->num_cu;
     const int grid12 = (int)std::min<long>(rows, c->num_cu);
     for (int i = 0; fused12 && i < npass; ++i) {
@@ -932,7 +932,7 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
         hipFuncSetAttribute((const void *)gbf::c12::k_conv12_fwd, hipFuncAttributeMaxDynamicSharedMemorySize,
                             gbf::c12::LDS_BYTES) == hipSuccess) {
         const char *m = std::getenv("DQN_CONV12_MIN_SAMPLES");
-        c->conv12_min = m && m[0] ? std::atoi(m) : 3 * c->num_cu;
+        c->conv12_min = m && m[0] ? std::atoi(m) : 8;
     } else {
         (void)hipGetLastError();
     }

@@ -442,6 +442,44 @@ def test_replay_train_step_small_ring(dq, orc):
     _replay_step_case(dq, orc, cap=4096, B=32)
 
 
+@pytest.mark.parametrize("B", [5, 33, 512])
+def test_fused_and_separate_conv_launches_agree(dq, B):
+    """bf16: conv1 and conv2 of the forward pass run as one launch (conv1's output handed over in
+    LDS) from a handful of samples on, and as two launches below that or when
+    DQN_CONV12_MIN_SAMPLES says so.  Both do the same arithmetic in the same order: two contexts over
+    identical state, one on each path, must agree bit for bit -- in replay mode (the first forward
+    kernel draws the transitions), on an explicit batch, and when acting.  B = 5: workgroups with a
+    single sample; 33: ragged shares; 512: six or seven samples per workgroup."""
+    import os
+    print("case fused conv1+conv2", B, flush=True)
+    cap = 3000
+    cfgd = dict(CONFIGS["dueling_ddqn"], max_batch=B, max_act_batch=max(B, 8), precision=1, replay_capacity=cap)
+    ms = []
+    for least in ("1", "1000000000"):
+        os.environ["DQN_CONV12_MIN_SAMPLES"] = least
+        try:
+            m = dq.Dqn(dq.make_config(**cfgd))
+        finally:
+            os.environ.pop("DQN_CONV12_MIN_SAMPLES", None)
+        _fill_replay(m, cap)
+        m.per_fill(synth.exp_priorities(9, cap, "cuda"))
+        ms.append(m)
+    batch = tuple(dev(t) for t in synth.batch(17, B, 18))
+    obs = batch[0]
+    for step in range(3):
+        outs = [m.train_step(B, None, beta=0.5, draw_seed=70 + step) for m in ms]
+        for k in ("idx", "td", "loss", "q_s"):
+            assert torch.equal(outs[0][k], outs[1][k]), (step, k)
+        assert torch.equal(ms[0].get_params(0), ms[1].get_params(0)), step
+    outs = [m.train_step(B, batch) for m in ms]
+    assert torch.equal(outs[0]["td"], outs[1]["td"])
+    assert torch.equal(ms[0].get_params(2), ms[1].get_params(2))
+    acts = [m.act(obs, 0.0, 3, want_q=True) for m in ms]
+    assert torch.equal(acts[0][1], acts[1][1]) and torch.equal(acts[0][0], acts[1][0])
+    for m in ms:
+        m.close()
+
+
 @pytest.mark.parametrize("prec,B", [(0, 32), (1, 64), (1, 6), (1, 1024)])
 def test_recorded_step_replays_match_plain_launches(dq, prec, B):
     """With DQN_GRAPH=1 the replay-mode step is recorded into a HIP graph and replayed.  Two
