@@ -87,8 +87,7 @@ def gemm_bytes_per_launch(B, R, bf16):
 # run (fetch x1.949, write x0.9875).  Keyed by (kernel, batch, precision); the figures and the
 # commands are in profiles/train_step_b512_bf16_hbm_traffic.md.
 MEASURED_TRAFFIC = {
-    ("conv1_fwd", 512, "bf16"): 47.9e6 + 38.9e6,
-    ("conv2_fwd", 512, "bf16"): 39.6e6 + 15.7e6,
+    ("conv12_fwd", 512, "bf16"): 46.0e6 + 28.7e6,
     ("conv3_fwd", 512, "bf16"): 16.8e6 + 9.5e6,
     ("fc1_fwd", 512, "bf16"): 19.9e6 + 21.7e6,
     ("head_train", 512, "bf16"): 22.4e6 + 1.6e6,
