@@ -311,7 +311,7 @@ def cpu_baseline(torch, synth, B, sample_rows):
         oracle.train_step(cfg, theta, pt, v, *args)
         reps += 1
         el = time.perf_counter() - t0
-        if el > 10.0 or reps >= 20:
+        if el > 12.0 or reps >= 200:   # about 12 s of CPU work
             break
     per_step = el / reps * (B / sample_rows)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count()))
