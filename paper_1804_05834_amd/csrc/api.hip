@@ -793,9 +793,13 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     }
     {
         DgradArgs D{d3, sh + net::C3W, act2, d2, B};
-        split_rows((long)B * 49, 9, MAX_WSPLIT, 64, &rps, ns3);
-        WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
         const int nd = (int)(((long)B * 81 + 63) / 64);
+        // four workgroups of this launch fit one CU: where fewer splits let the whole launch run in one
+        // round of workgroups, take fewer (B = 512: 41 instead of 56; 153.2 against 154.6 us/step)
+        int cap3 = (4 * c->num_cu - 1 - nd) / 9;
+        if (cap3 < 32 || cap3 > MAX_WSPLIT) cap3 = MAX_WSPLIT;
+        split_rows((long)B * 49, 9, cap3, 64, &rps, ns3);
+        WgradArgs G{d3, act2, w.gp3, B, rps, net::A2, net::L3N, 1.0f};
         PairGrid P{nd, nd, 1, 9 * *ns3, 9, 1, *ns3};
         launch(c, "conv3_bwd", st, [&] { k_conv3_bwd_pu<<<P.nd + P.nw + U.on, 256, 0, st>>>(D, G, P, U); });
     }
