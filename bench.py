@@ -92,10 +92,10 @@ MEASURED_TRAFFIC = {
     ("fc1_fwd", 512, "bf16"): 19.9e6 + 21.7e6,
     ("head_train", 512, "bf16"): 22.4e6 + 1.6e6,
     ("fc1_bwd", 512, "bf16"): 13.4e6 + 9.6e6,
-    ("conv3_bwd", 512, "bf16"): 9.3e6 + 13.5e6,
+    ("conv3_bwd", 512, "bf16"): 9.9e6 + 11.2e6,
     ("conv2_bwd", 512, "bf16"): 36.2e6 + 20.6e6,
     ("conv1_wgrad", 512, "bf16"): 27.1e6 + 8.3e6,
-    ("rmsprop", 512, "bf16"): 43.4e6 + 23.4e6,
+    ("rmsprop", 512, "bf16"): 41.1e6 + 23.4e6,
 }
 
 
