@@ -1368,17 +1368,32 @@ __device__ __forceinline__ void run(const Seg &S, int g0, int g1, uint8_t *lds, 
         v4f acc[H::NBLK][2];
 #pragma unroll
         for (int b = 0; b < H::NBLK; ++b) acc[b][0] = acc[b][1] = v4f{0, 0, 0, 0};
+        // byte offset of reduction step st: pixel (ky, kx) further, second half of its channels for odd
+        // steps of the 64-channel layer
+        auto step_off = [](int st) {
+            const int tap = st / H::SPT, ky = tap / G::TAPS, kx = tap % G::TAPS;
+            return (int)H::at(G::IN_W * ky + kx, 0) + (st % H::SPT) * 64;
+        };
+        // the operands of step st+1 are requested before the matrix instructions of step st
+        uint4 cur[H::NBLK], nxt[H::NBLK];
+#pragma unroll
+        for (int b = 0; b < H::NBLK; ++b) cur[b] = *reinterpret_cast<const uint4 *>(buf + base[b] + step_off(0));
 #pragma unroll
         for (int st = 0; st < H::STEPS; ++st) {
-            const int tap = st / H::SPT, ky = tap / G::TAPS, kx = tap % G::TAPS;
-            // pixel (ky, kx) further, second half of its channels for odd steps of the 64-channel layer
-            const int off = (int)H::at(G::IN_W * ky + kx, 0) + (st % H::SPT) * 64;
+            if (st + 1 < H::STEPS) {
+#pragma unroll
+                for (int b = 0; b < H::NBLK; ++b) nxt[b] = *reinterpret_cast<const uint4 *>(buf + base[b] + step_off(st + 1));
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int b = 0; b < H::NBLK; ++b) {
-                const v8bf bb = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(buf + base[b] + off));
+                const v8bf bb = __builtin_bit_cast(v8bf, cur[b]);
                 acc[b][0] = mfma16(wa[st][0], bb, acc[b][0]);
                 acc[b][1] = mfma16(wa[st][1], bb, acc[b][1]);
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < H::NBLK; ++b) cur[b] = nxt[b];
         }
         bf16_t *y = S.y + (long)g * (H::NPOS * 64) + 32 * hh + 8 * kg;
 #pragma unroll
