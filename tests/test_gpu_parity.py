@@ -62,7 +62,7 @@ def test_init_and_param_roundtrip(dq, K, dueling):
 
 # ------------------------------------------------------------------ acting / forward
 @pytest.mark.parametrize("K,dueling,E,prec", [(4, 0, 37, 0), (18, 1, 70, 0), (1, 1, 3, 0), (64, 0, 5, 0),
-                                              (18, 1, 70, 1), (4, 0, 300, 1)])
+                                              (18, 1, 70, 1), (4, 0, 300, 1), (18, 1, 3, 1)])
 def test_act_forward_parity(dq, orc, K, dueling, E, prec):
     print("case act", K, dueling, E, prec, flush=True)
     TOL = TOL_BF16 if prec else globals()["TOL"]
