@@ -395,6 +395,16 @@ def main():
         also.append(time_act_train(dqn, synth, torch, args.capacity, max(50, args.steps // 5), 10))
         also.append(time_agent_loop(dqn, synth, torch, args.capacity, max(200, 2 * args.steps)))
         also.append(time_variants(dqn, synth, torch, args.capacity, max(100, args.steps // 2), args.warmup))
+        if not (B == 32 and prec == 1):
+            m32 = build_model(dqn, synth, torch, 32, 1, args.capacity)
+            w32, d32, _ = time_steps(m32, torch, 32, args.steps, args.warmup)
+            also.append({"workload": "same step, batch 32, bf16", "value": args.steps / w32,
+                         "unit": "train steps/s", "ms_per_step": w32 / args.steps * 1e3,
+                         "device_ms_per_step": d32 / args.steps * 1e3,
+                         "mfma_frac_step": step_flops(32, R) * args.steps / w32 / PEAK["bf16"]})
+            m32.close()
+            del m32
+            torch.cuda.empty_cache()
         res["also"] = also
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(torch, synth, B, min(B, 64))
