@@ -114,6 +114,8 @@ typedef struct {
     int32_t *a_star;      /* [B]    the action the target bootstraps from            */
     int32_t *idx;         /* [B]    sampled replay slots (replay mode only)          */
     float *is_w;          /* [B]    importance weights used                          */
+    float *td_abs_mean;   /* [1]    (1/B) sum_j |td_j| (rows with a finite error)    */
+    float *q_max_mean;    /* [1]    (1/B) sum_j max_a Q(s_j, a; theta)               */
 } dqn_step_out;
 
 /* Sizes of every buffer dqn_init needs.  `cfg`, `out`: host pointers. */
@@ -144,7 +146,13 @@ int32_t dqn_act(dqn_ctx *ctx, const uint8_t *obs, int32_t E, float epsilon, uint
  * are drawn as by per_sample(beta, draw_seed), their frame stacks gathered
  * from the ring, and after the update their priorities are set from |td| as by
  * per_update.  `out` (host pointer, may be NULL) names optional outputs.
- * 1 <= B <= max_batch. */
+ * 1 <= B <= max_batch.
+ * A row whose action lies outside [0, num_actions) is not trained on: it enters
+ * the loss and the gradient with weight 0, its td is reported as NaN, and in
+ * replay mode its priority is left alone.  In replay mode, if the tree holds no
+ * mass at all (every stored transition has priority zero: nothing can be drawn),
+ * every importance weight is 0, the parameters do not move and no priority is
+ * written. */
 int32_t dqn_train_step(dqn_ctx *ctx, int32_t B, const dqn_batch *batch, float beta,
                        uint64_t draw_seed, const dqn_step_out *out, void *stream);
 
@@ -153,7 +161,12 @@ int32_t dqn_train_step(dqn_ctx *ctx, int32_t B, const dqn_batch *batch, float be
  * descends the sum-tree with mass fp32(u_j * total), stratified mode with
  * fp32((j + u_j) * fp32(total / B)).  idx[j] is the leaf reached (clamped to
  * the stored size); is_w[j] = (N * P(j))^-beta / max_j(...), N = stored
- * transitions.  Returns DQN_ERR_STATE if nothing is stored.  1 <= B <= 1024. */
+ * transitions.  A slot whose leaf is 0 has probability zero and is never
+ * returned, also where the fp32 sums of the tree would let the textbook
+ * descent overshoot into it: the walk turns left whenever the right child is 0.
+ * Returns DQN_ERR_STATE if nothing is stored (the call cannot see on the host
+ * whether every stored leaf is 0: then idx = 0 and is_w = 0 are written).
+ * 1 <= B <= 1024. */
 int32_t per_sample(dqn_ctx *ctx, int32_t B, float beta, uint64_t draw_seed, int32_t *idx,
                    float *is_w, void *stream);
 
@@ -235,6 +248,13 @@ int32_t dqn_schedule_at(const dqn_schedule *s, int64_t step, dqn_schedule_point 
  * (any output may be NULL).  1 <= n <= max_batch. */
 int32_t dqn_replay_gather(dqn_ctx *ctx, const int32_t *idx, int32_t n, uint8_t *s, uint8_t *s_next,
                           int32_t *a, float *r, uint8_t *done, void *stream);
+
+/* Diagnostics: the stored outputs (after ReLU) of layer 1-3 (the convolutions) or
+ * 4 (the 512-unit hidden layer) of Section 3's network for the first n rows of
+ * the online pass on s of the last dqn_train_step, as fp32 in canonical order:
+ * dst [n][32][20][20], [n][64][9][9], [n][64][7][7] or [n][512].  These are
+ * the numbers the backward pass takes its ReLU decisions on.  1 <= n <= max_batch. */
+int32_t dqn_get_activations(dqn_ctx *ctx, int32_t layer, int32_t n, float *dst, void *stream);
 
 /* theta^- <- theta (Alg.2 "copy weights into target network"). */
 int32_t dqn_sync_target(dqn_ctx *ctx, void *stream);

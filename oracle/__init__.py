@@ -59,6 +59,9 @@ def lib():
         L.orc_forward_q.restype = C.c_int32
         L.orc_forward_q.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
                                     C.c_void_p, C.c_void_p]
+        L.orc_forward_acts.restype = C.c_int32
+        L.orc_forward_acts.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.orc_round_bf16.restype = C.c_double
         L.orc_round_bf16.argtypes = [C.c_double]
         L.orc_target_loss.restype = C.c_int32
@@ -165,6 +168,20 @@ def forward(params, K, dueling, states, want_hidden=False, quant=0):
     rc = lib().orc_forward_q(_p(params), K, int(dueling), int(quant), _p(states), n, _p(q), _p(h))
     assert rc == 0, rc
     return (q, h) if want_hidden else q
+
+
+def forward_acts(params, K, dueling, states, quant=0):
+    """Layer outputs after ReLU: dict a1 [n,32,20,20], a2 [n,64,9,9], a3 [n,64,7,7], h [n,512]."""
+    params = _chk(params, np.float32)
+    states = _chk(states, np.uint8)
+    n = states.shape[0]
+    assert states.shape[1:] == (4, 84, 84) and params.size == param_count(K, dueling)
+    out = dict(a1=np.zeros((n, 32, 20, 20)), a2=np.zeros((n, 64, 9, 9)), a3=np.zeros((n, 64, 7, 7)),
+               h=np.zeros((n, 512)))
+    rc = lib().orc_forward_acts(_p(params), K, int(dueling), int(quant), _p(states), n, _p(out["a1"]),
+                                _p(out["a2"]), _p(out["a3"]), _p(out["h"]))
+    assert rc == 0, rc
+    return out
 
 
 def target_loss(q_s, q_no, q_nt, a, r, done, w=None, *, double_q, loss_kind, kappa=1.0, gamma=0.99):

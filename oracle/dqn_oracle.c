@@ -309,6 +309,35 @@ int32_t orc_forward_q(const float *params, int32_t K, int32_t dueling, int32_t q
     return fail ? -2 : 0;
 }
 
+/* The layer outputs of n states (after ReLU; conv outputs [C][H][W] per state):
+ * a1 [n][32][20][20], a2 [n][64][9][9], a3 [n][64][7][7], h [n][512]; any may be
+ * NULL.  Same arithmetic as orc_forward_q (it calls the same per-sample forward). */
+int32_t orc_forward_acts(const float *params, int32_t K, int32_t dueling, int32_t quant,
+                         const uint8_t *states, int64_t n, double *a1, double *a2, double *a3,
+                         double *h)
+{
+    if (K < 1 || K > 64) return -1;
+    orc_layout L = make_layout(K, dueling);
+    float *Pq = quant ? quantized_copy(params, &L) : NULL;
+    if (quant && !Pq) return -2;
+    if (quant) params = Pq;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t j = 0; j < n; ++j) {
+        orc_acts *A = (orc_acts *)malloc(sizeof(orc_acts));
+        double q[64];
+        if (!A) { fail = 1; continue; }
+        net_forward_one(params, &L, K, dueling, quant, states + j * (IN_C * IN_H * IN_W), A, q);
+        if (a1) memcpy(a1 + j * (C1_O * C1_H * C1_H), A->a1, sizeof(A->a1));
+        if (a2) memcpy(a2 + j * (C2_O * C2_H * C2_H), A->a2, sizeof(A->a2));
+        if (a3) memcpy(a3 + j * FC_IN, A->a3, sizeof(A->a3));
+        if (h) memcpy(h + j * FC_OUT, A->h, sizeof(A->h));
+        free(A);
+    }
+    free(Pq);
+    return fail ? -2 : 0;
+}
+
 int32_t orc_forward(const float *params, int32_t K, int32_t dueling, const uint8_t *states,
                     int64_t n, double *q, double *hidden)
 {
@@ -590,13 +619,23 @@ void orc_tree_build(const float *raw_p, int64_t n, int64_t L, double alpha, floa
     for (int64_t i = L - 1; i >= 1; --i) tree[i] = tree[2 * i] + tree[2 * i + 1];
 }
 
-/* Prefix descent for one mass z; returns the leaf slot (not clamped). */
+/* Prefix descent for one mass z; returns the leaf slot (not clamped).
+ * Eq.10 gives a transition of priority zero the probability zero, and Eq.11's
+ * small constant exists so that no stored transition has it; a leaf of value 0
+ * is a slot that holds no drawable transition.  In exact arithmetic the
+ * descent never enters a subtree whose sum is 0.  In fp32 it can: a parent is
+ * the ROUNDED sum of its children, so z < parent does not imply
+ * z - left < right, and fp32(u * total) can equal the total.  The rule
+ * therefore turns left whenever nothing lies to the right (right == 0): with
+ * a positive total every visited node then has a positive sum, and the leaf
+ * reached is a stored transition with P(j) > 0 -- the rightmost one of the
+ * subtree when z overshoots it.                                            */
 static int64_t tree_descend(const float *tree, int64_t L, float z)
 {
     int64_t node = 1;
     while (node < L) {
-        float left = tree[2 * node];
-        if (z < left) {
+        float left = tree[2 * node], right = tree[2 * node + 1];
+        if (z < left || right == 0.0f) {
             node = 2 * node;
         } else {
             z = z - left;
@@ -643,7 +682,7 @@ int32_t orc_per_sample(const float *tree, int64_t L, int64_t size, int32_t B, do
 }
 
 /* Definitional sampler: smallest slot whose inclusive cumulative sum of the
- * leaves (in double) exceeds z.  Also returns the distance from z to the
+ * leaves (in double) exceeds z (a slot with a zero leaf never is that slot).  Also returns the distance from z to the
  * nearest bucket boundary, so a caller can accept an off-by-a-bucket index
  * when z sits within rounding of that boundary.                         */
 void orc_per_sample_cumsum(const float *tree, int64_t L, int64_t size, const float *z, int32_t B,
@@ -651,12 +690,14 @@ void orc_per_sample_cumsum(const float *tree, int64_t L, int64_t size, const flo
 {
     for (int j = 0; j < B; ++j) {
         double c = 0.0, zz = (double)z[j], lo = 0.0;
-        int64_t slot = size - 1;
+        int64_t slot = -1, last = size - 1; /* last: the last slot with a non-zero leaf */
         for (int64_t i = 0; i < size; ++i) {
+            if (tree[L + i] > 0.0f) last = i;
             lo = c;
             c += (double)tree[L + i];
             if (c > zz) { slot = i; break; }
         }
+        if (slot < 0) { slot = last; } /* z at or beyond the exact total: the last drawable slot */
         idx[j] = (int32_t)slot;
         if (boundary_dist) {
             double d1 = fabs(zz - lo), d2 = fabs(c - zz);
@@ -676,7 +717,7 @@ int32_t orc_per_update(float *tree, int64_t L, int64_t size, const int32_t *idx,
     for (int j = 0; j < n; ++j) {
         if (idx[j] < 0 || idx[j] >= size) return -1;
         float p = (float)((double)fabsf(td_abs[j]) + eps);
-        if (!(p <= 3.0e38f)) continue;
+        if (!isfinite(p)) continue;
         int64_t node = L + idx[j];
         tree[node] = leaf_value((double)p, alpha);
         for (node >>= 1; node >= 1; node >>= 1) tree[node] = tree[2 * node] + tree[2 * node + 1];

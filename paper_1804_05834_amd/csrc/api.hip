@@ -28,7 +28,7 @@ struct Workspace {
     // minibatch staging (replay mode)
     uint8_t *stack5;
     int32_t *b_idx, *b_a;
-    float *b_w, *b_r, *td_abs, *loss_j, *loss_slot;
+    float *b_w, *b_r, *td_abs, *loss_j, *qmax_j, *loss_slot;
     int *pu_state;   // walkers of a priority update that is split over two launches
     uint8_t *b_done;
     // activations, channel-last, rows = samples of all passes (fp32 or bf16 by precision)
@@ -75,6 +75,7 @@ Workspace carve(const dqn_config &c, uint8_t *base)
     w.b_r = (float *)take(MB * 4);
     w.td_abs = (float *)take(MB * 4);
     w.loss_j = (float *)take(MB * 4);
+    w.qmax_j = (float *)take(MB * 4);
     w.loss_slot = (float *)take(256);
     w.pu_state = (int *)take(3 * misc::STATE_STRIDE * 4);
     w.b_done = take(MB);
@@ -284,6 +285,58 @@ const gbf::bf16_t *shadow_of(dqn_ctx *c, int net)
     return sh + (net ? align_up((size_t)c->n * 2, 256) / 2 : 0);
 }
 
+// Launch shapes of the conv1 forward kernels for `samples` samples (all passes), and whether a wave's
+// (wave group's) share of strips spans few enough samples for it to draw them itself.
+struct Conv1Plan {
+    bool ks2;        // fp32: four waves per strip (fewer wave pairs than SIMDs)
+    int grid;
+    bool draw_fits;
+};
+Conv1Plan conv1_plan_f32(int samples, int num_cu)
+{
+    const int units = samples * gbf::c1::UNITS;
+    Conv1Plan P;
+    P.ks2 = 2 * units <= 4 * num_cu;
+    P.grid = P.ks2 ? std::min(units, 2 * num_cu) : std::min((units + 1) / 2, 2 * num_cu);
+    const int groups = P.ks2 ? P.grid : 2 * P.grid;
+    const int upg = (units + groups - 1) / groups + 1;   // strips per group of waves, at most
+    P.draw_fits = (upg + gbf::c1::UNITS - 1) / gbf::c1::UNITS + 1 <= gbf::c1::MAX_DRAWS;
+    return P;
+}
+Conv1Plan conv1_plan_bf16(int samples, int num_cu)
+{
+    const int units = samples * gbf::c1::UNITS;
+    Conv1Plan P;
+    P.ks2 = false;
+    // one wave per strip of a sample, four waves per workgroup, two workgroups resident per CU
+    P.grid = std::min((units + 3) / 4, 2 * num_cu);
+    const int upw = (units + 4 * P.grid - 1) / (4 * P.grid) + 1;
+    P.draw_fits = (upw + gbf::c1::UNITS - 1) / gbf::c1::UNITS + 1 <= gbf::c1::MAX_DRAWS;
+    return P;
+}
+// bf16: conv1 + conv2 as one launch, one workgroup per CU, for passes of n[0..npass) samples?
+bool fused12_fits(const dqn_ctx *c, const int *n, int npass, bool draw)
+{
+    long rows = 0;
+    for (int i = 0; i < npass; ++i) rows += n[i];
+    if (rows < c->conv12_min || npass > c->num_cu) return false;
+    const int grid12 = (int)std::min<long>(rows, c->num_cu);
+    for (int i = 0; i < npass; ++i) {
+        const int wgs = (int)((long)grid12 * (i + 1) / npass - (long)grid12 * i / npass);
+        if (wgs < 1 || (n[i] + wgs - 1) / wgs > gbf::c12::MAX_PER_WG) return false;
+        if (draw && n[i] != n[0]) return false;
+    }
+    return true;
+}
+// Can the first forward kernel of a replay-mode step of batch B draw the transitions itself?  If not
+// (few compute units and a large batch), a sampling launch runs in front of the step.
+bool in_kernel_draw_fits(const dqn_ctx *c, int B)
+{
+    if (c->cfg.precision == 0) return conv1_plan_f32(3 * B, c->num_cu).draw_fits;
+    const int n[3] = {B, B, B};
+    return fused12_fits(c, n, 3, true) || conv1_plan_bf16(3 * B, c->num_cu).draw_fits;
+}
+
 int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
                           hipStream_t st, const misc::SampleArgs *draw)
 {
@@ -333,12 +386,10 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
         A.total = first;
         A.draw = draw != nullptr;
         if (draw) A.samp = *draw;
-        const int units = first * c1::UNITS;
-        const bool ks2 = 2 * units <= 4 * c->num_cu;   // fewer wave pairs than SIMDs: four waves per unit
-        const int grid = ks2 ? std::min(units, 2 * c->num_cu) : std::min((units + 1) / 2, 2 * c->num_cu);
-        const int groups = ks2 ? grid : 2 * grid;
-        const int upg = (units + groups - 1) / groups + 1;   // units per group of waves, at most
-        if (draw && (upg + c1::UNITS - 1) / c1::UNITS + 1 > c1::MAX_DRAWS)
+        const Conv1Plan plan = conv1_plan_f32(first, c->num_cu);
+        const bool ks2 = plan.ks2;
+        const int grid = plan.grid;
+        if (draw && !plan.draw_fits)   // the caller asks in_kernel_draw_fits first
             return fail(c, DQN_ERR_INVALID_ARG, "forward: batch too large for in-kernel sampling");
         if (ks2) launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd_f32<2><<<dim3(grid), 256, 0, st>>>(A); });
         else launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd_f32<1><<<dim3(grid), 256, 0, st>>>(A); });
@@ -407,13 +458,9 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
     };
 
     // conv1 + conv2 as one launch, one workgroup per CU (faster from a handful of samples on)
-    bool fused12 = rows >= c->conv12_min && npass <= c->num_cu;
+    const int pass_n[3] = {pass[0].n, npass > 1 ? pass[1].n : 0, npass > 2 ? pass[2].n : 0};
+    const bool fused12 = fused12_fits(c, pass_n, npass, draw != nullptr);
     const int grid12 = (int)std::min<long>(rows, c->num_cu);
-    for (int i = 0; fused12 && i < npass; ++i) {
-        const int wgs = (int)((long)grid12 * (i + 1) / npass - (long)grid12 * i / npass);
-        if (wgs < 1 || (pass[i].n + wgs - 1) / wgs > c12::MAX_PER_WG) fused12 = false;
-        if (draw && pass[i].n != pass[0].n) fused12 = false;
-    }
     if (fused12) {
         c12::Args A{};
         A.nseg = npass;
@@ -452,11 +499,10 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
         A.total = first;
         A.draw = draw != nullptr;
         if (draw) A.samp = *draw;
-        // one wave per strip of a sample, four waves per workgroup, two workgroups resident per CU
-        const int grid = std::min((first * c1::UNITS + 3) / 4, 2 * c->num_cu);
         // a wave that draws for itself holds at most MAX_DRAWS slots: its units span that many samples at most
-        const int upw = (first * c1::UNITS + 4 * grid - 1) / (4 * grid) + 1;
-        if (draw && (upw + c1::UNITS - 1) / c1::UNITS + 1 > c1::MAX_DRAWS)
+        const Conv1Plan plan = conv1_plan_bf16(first, c->num_cu);
+        const int grid = plan.grid;
+        if (draw && !plan.draw_fits)   // the caller asks in_kernel_draw_fits first
             return fail(c, DQN_ERR_INVALID_ARG, "forward: batch too large for in-kernel sampling");
         launch(c, "conv1_fwd", st, [&] { c1::k_conv1_fwd<<<dim3(grid), 256, 0, st>>>(A); });
     }
@@ -1041,6 +1087,21 @@ int32_t dqn_set_params(dqn_ctx *c, int32_t which, const float *src, void *stream
     return hip_status(c, "dqn_set_params");
 }
 
+int32_t dqn_get_activations(dqn_ctx *c, int32_t layer, int32_t n, float *dst, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (layer < 1 || layer > 4) return fail(c, DQN_ERR_INVALID_ARG, "dqn_get_activations: layer must be 1..4");
+    if (n < 1 || n > c->cfg.max_batch || !dst) return fail(c, DQN_ERR_INVALID_ARG, "dqn_get_activations: n out of range or dst NULL");
+    const Workspace &w = c->ws;
+    const void *src[4] = {w.act1, w.act2, w.act3, w.h_s};
+    const int P[4] = {400, 81, 49, 1}, Cn[4] = {32, 64, 64, net::HID};
+    const int k = layer - 1;
+    const long total = (long)n * P[k] * Cn[k];
+    hipStream_t st = (hipStream_t)stream;
+    misc::k_read_act<<<grid1(total, 256), 256, 0, st>>>(src[k], k < 3 && c->cfg.precision == 1, n, P[k], Cn[k], dst);
+    return hip_status(c, "dqn_get_activations");
+}
+
 int32_t dqn_sync_target(dqn_ctx *c, void *stream)
 {
     if (!c) return DQN_ERR_INVALID_ARG;
@@ -1310,6 +1371,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     H.head_on = c->theta + net::HEAD; H.head_tg = c->theta_t + net::HEAD;
     H.a = a; H.r = r; H.done = done; H.w = isw; H.w_raw = batch ? 0 : 1;
     H.h_s = w.h_s; H.dh = w.dh; H.dh_bf16 = cfg.precision == 1; H.dA = w.dA; H.td_abs = w.td_abs; H.loss_j = w.loss_j;
+    H.qmax_j = w.qmax_j;
     H.q_s = O.q_s; H.q_no = O.q_next_online; H.q_nt = O.q_next_target; H.y = O.y; H.td = O.td;
     H.a_star = O.a_star; H.is_w = O.is_w;
     launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 512, 0, st>>>(H); });
@@ -1325,7 +1387,8 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     if (sd != st || sp != st) (void)hipEventRecord(c->ev_fork, st);
     ev_wait(sd, c->ev_fork, st);
     if (sp != sd) ev_wait(sp, c->ev_fork, st);
-    misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling};
+    misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling,
+                           w.td_abs, w.qmax_j, O.td_abs_mean, O.q_max_mean};
     // the indices come from the sampling kernel, so the ring capacity bounds them
     misc::PerUpdateArgs PU{c->tree, c->L, c->levels, (long)cfg.replay_capacity, w.b_idx, w.td_abs, B,
                            cfg.per_alpha, cfg.per_eps};
@@ -1362,6 +1425,7 @@ static dqn_ctx::StepGraph *record_step_graph(dqn_ctx *c, int32_t B)
     dqn_step_out O{};
     O.loss = w.o_loss; O.q_s = w.o_q; O.q_next_online = w.o_q + BK; O.q_next_target = w.o_q + 2 * BK;
     O.y = w.o_y; O.td = w.o_td; O.a_star = w.o_astar; O.is_w = w.o_isw;  // idx: already in b_idx
+    O.td_abs_mean = w.o_loss + 1; O.q_max_mean = w.o_loss + 2;
     if (hipStreamBeginCapture(c->cap, hipStreamCaptureModeRelaxed) != hipSuccess) {
         (void)hipGetLastError();
         return nullptr;
@@ -1389,6 +1453,10 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
     if (c->cfg.replay_capacity <= 0 || c->stored <= 0) return fail(c, DQN_ERR_STATE, "dqn_train_step: replay is empty");
     if (!(beta >= 0.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_train_step: beta must be >= 0");
     const bool graphs = !c->prof && !c->graph_off && c->cap && c->side;
+    if (!graphs && !in_kernel_draw_fits(c, B)) {
+        enqueue_sample(c, B, beta, draw_seed, st);
+        return enqueue_step(c, B, nullptr, out, st);
+    }
     if (!graphs) {
         // the first forward kernel draws the transitions (and, in fp32, gathers their frames for the
         // weight gradient): one launch less on the critical path
@@ -1430,6 +1498,8 @@ int32_t dqn_train_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, float beta
         add(out->a_star, w.o_astar, B);
         add(out->idx, w.b_idx, B);
         add(out->is_w, w.o_isw, B);
+        add(out->td_abs_mean, w.o_loss + 1, 1);
+        add(out->q_max_mean, w.o_loss + 2, 1);
         if (n) misc::k_copy_out<<<dim3((nq + 255) / 256, n), 256, 0, st>>>(A);
     }
     return hip_status(c, "dqn_train_step");

@@ -158,8 +158,9 @@ struct HeadArgs {
     void *dh;        // [B][512] gradient w.r.t. the fc1 pre-activation (fp32, or bf16 if dh_bf16)
     int dh_bf16;
     float *dA;       // [B][R]   gradient w.r.t. the head rows
-    float *td_abs;   // [B]
+    float *td_abs;   // [B] |td_j|; NaN for a row the priority update must skip
     float *loss_j;   // [B] w_j * l(td_j)
+    float *qmax_j;   // [B] max_a Q(s_j, a; theta)
     float *q_s, *q_no, *q_nt, *y, *td;  // optional outputs
     int32_t *a_star;
     float *is_w;
@@ -185,7 +186,11 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
     float wmax = 0.f;
     if (norm)
         for (int t = tid; t < A.B; t += 512) wmax = fmaxf(wmax, A.w[t]);
-    const int aj = A.a[j];
+    // an action outside [0, K) cannot be trained on: the row contributes nothing (weight 0), its TD
+    // error is reported as NaN and the priority update skips it
+    const int aj_raw = A.a[j];
+    const bool a_ok = aj_raw >= 0 && aj_raw < K;
+    const int aj = a_ok ? aj_raw : 0;
     const bool dn = A.done[j] != 0;
     const float rj = A.r[j];
     const float wj = A.w ? A.w[j] : 1.f;
@@ -227,13 +232,13 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         if (norm) {
             float m = shm[0];
             for (int v = 1; v < 8; ++v) m = fmaxf(m, shm[v]);
-            wnorm = 1.f / m;
+            wnorm = m > 0.f ? 1.f / m : 0.f;   // no mass in the tree: every weight is 0
         }
         const int as = argmax_low(A.double_q ? q[1] : q[2], K);
         const float boot = dn ? 0.f : A.gamma * q[2][as];
         const float y = rj + boot;
         const float d = y - q[0][aj];
-        const float w = A.w ? wj * wnorm : 1.f;
+        const float w = !a_ok ? 0.f : A.w ? wj * wnorm : 1.f;
         float l, dl;
         if (A.loss_kind == 1 && fabsf(d) > A.kappa) {
             l = A.kappa * (fabsf(d) - 0.5f * A.kappa);
@@ -249,10 +254,15 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         } else {
             for (int a = 0; a < K; ++a) dA[a] = a == aj ? g : 0.f;
         }
-        A.td_abs[j] = fabsf(d);
+        // a drawn row whose raw weight is 0 came from a tree without mass: its slot holds nothing to update
+        const bool skip = !a_ok || (norm && !(wj > 0.f));
+        A.td_abs[j] = skip ? __int_as_float(0x7fc00000) : fabsf(d);
         A.loss_j[j] = w * l;
+        float qm = q[0][0];
+        for (int a = 1; a < K; ++a) qm = fmaxf(qm, q[0][a]);
+        A.qmax_j[j] = qm;
         if (A.y) A.y[j] = y;
-        if (A.td) A.td[j] = d;
+        if (A.td) A.td[j] = a_ok ? d : __int_as_float(0x7fc00000);
         if (A.a_star) A.a_star[j] = as;
         if (A.is_w) A.is_w[j] = w;
     }
@@ -282,6 +292,10 @@ struct HeadWgradArgs {
     float *loss_out;      // optional
     float *loss_slot;     // always written
     int B, K, dueling;
+    const float *td_abs;  // [B]
+    const float *qmax_j;  // [B]
+    float *td_abs_mean;   // optional [1]: (1/B) sum_j |td_j| over the rows with a finite error
+    float *q_max_mean;    // optional [1]: (1/B) sum_j max_a Q(s_j, a; theta)
 };
 
 // Head weight gradient: dW[r][i] = sum_j dA[j][r] h[j][i], db[r] = sum_j dA[j][r].
@@ -321,12 +335,21 @@ __device__ __forceinline__ void head_wgrad_body(const HeadWgradArgs &A, int r, i
     }
     if (r == 0 && c == 0 && (int)threadIdx.x >= NG * 32 - 64) {  // the last wave sums the loss terms
         const int lane = threadIdx.x & 63;
-        float s = 0.f;
-        for (int j = lane; j < A.B; j += 64) s += A.loss_j[j];
+        float s = 0.f, sd = 0.f, sq = 0.f;
+        for (int j = lane; j < A.B; j += 64) {
+            s += A.loss_j[j];
+            const float d = A.td_abs[j];
+            if (d <= 3.4028234e38f) sd += d;   // false for NaN
+            sq += A.qmax_j[j];
+        }
         s = wave_sum(s) / (float)A.B;
+        sd = wave_sum(sd) / (float)A.B;
+        sq = wave_sum(sq) / (float)A.B;
         if (lane == 0) {
             *A.loss_slot = s;
             if (A.loss_out) *A.loss_out = s;
+            if (A.td_abs_mean) *A.td_abs_mean = sd;
+            if (A.q_max_mean) *A.q_max_mean = sq;
         }
     }
 }
@@ -533,7 +556,7 @@ __global__ __launch_bounds__(1024) void k_per_normalise(float *is_w, int B)
     const int j = threadIdx.x;
     const float w = j < B ? is_w[j] : 0.f;
     const float wmax = block_max_1024(w, sh);
-    if (j < B) is_w[j] = w / wmax;
+    if (j < B) is_w[j] = wmax > 0.f ? w / wmax : 0.f;
 }
 
 // Leaf-to-root repair by the threads of ONE workgroup, each starting from its own distinct leaf
@@ -647,7 +670,7 @@ __device__ __forceinline__ void per_update_body(const PerUpdateArgs &A, int *lds
             p[w] = (float)((double)fabsf(td_abs[j]) + (double)eps);
             // an entry with a slot outside the ring or a non-finite error is skipped: its leaf keeps
             // its value, and the tree stays a tree of finite sums
-            if (v >= 0 && v < size && p[w] <= 3.0e38f) my[w] = v;   // the comparison is false for NaN
+            if (v >= 0 && v < size && p[w] <= 3.4028234663852886e38f) my[w] = v;   // finite: false for NaN and infinity
         }
     }
     for (int t = tid; t < PU_SLOTS; t += nt) { keys[t] = -1; ivals[t] = -1; }
@@ -789,13 +812,26 @@ __global__ __launch_bounds__(256) void k_preprocess(const uint8_t *raw, int H, i
     out[(long)blockIdx.y * net::FRAME + o] = (uint8_t)fminf(fmaxf(rintf(v), 0.f), 255.f);
 }
 
-// Copies up to nine short arrays of 4-byte words; grid (blocks, items).
+// Stored layer outputs back in the canonical order: src [n][P][C] (channel-last, fp32 or bf16) ->
+// dst fp32 [n][C][P].  One thread per element.
+__global__ __launch_bounds__(256) void k_read_act(const void *src, int is_bf16, long n, int P, int Cn, float *dst)
+{
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;   // canonical index
+    if (e >= n * P * Cn) return;
+    const long row = e / ((long)P * Cn);
+    const int c = (int)((e / P) % Cn), pos = (int)(e % P);
+    const long in = (row * P + pos) * Cn + c;
+    dst[e] = is_bf16 ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(src)[in] << 16)
+                     : static_cast<const float *>(src)[in];
+}
+
+// Copies up to eleven short arrays of 4-byte words; grid (blocks, items).
 struct CopyOutArgs {
     struct Item {
         uint32_t *dst;
         const uint32_t *src;
         int words;
-    } item[9];
+    } item[11];
 };
 __global__ __launch_bounds__(256) void k_copy_out(CopyOutArgs A)
 {

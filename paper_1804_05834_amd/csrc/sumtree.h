@@ -33,8 +33,12 @@ struct MetaGather {
 };
 
 // Proportional sampling (Eq.10, Eq.12), one WAVE per draw.  The descent is the
-// sequential rule "z < left ? go left : (z -= left, go right)" in fp32, but the
-// memory side is batched: at a node x the wave fetches the whole 6-level subtree
+// sequential rule "z < left ? go left : (z -= left, go right)" in fp32, except that it also
+// turns left when the right child is 0: a parent is the ROUNDED sum of its children, so a mass
+// below the parent can still overshoot the right child, and the walk would end on a leaf of
+// value 0, a slot that holds no drawable transition (Eq.10 gives it probability zero; its
+// importance weight would be infinite).  With a positive total every node visited is positive.
+// The memory side is batched: at a node x the wave fetches the whole 6-level subtree
 // below x in one round trip (lane l reads local heap node l of levels 1..5 and
 // node l of level 6), then walks those 6 levels out of registers with lane
 // shuffles.  20 levels cost 4 dependent round trips instead of 20, and every
@@ -72,7 +76,8 @@ __device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, i
         for (int t = 0; t < r; ++t) {
             const int c = 2 * cur;  // left child
             const float left = c < 64 ? __shfl(va, c, 64) : __shfl(vb, c - 64, 64);
-            if (z < left) {
+            const float right = c < 64 ? __shfl(va, c + 1, 64) : __shfl(vb, c - 63, 64);
+            if (z < left || right == 0.f) {   // nothing on the right: a zero leaf is never drawn
                 cur = c;
             } else {
                 z = z - left;
@@ -116,7 +121,8 @@ __device__ __forceinline__ void per_sample_descend2(const SampleArgs &A, int j0,
             for (int t = 0; t < r; ++t) {
                 const int c = 2 * cur;
                 const float left = c < 64 ? __shfl(va[d], c, 64) : __shfl(vb[d], c - 64, 64);
-                if (z[d] < left) {
+                const float right = c < 64 ? __shfl(va[d], c + 1, 64) : __shfl(vb[d], c - 63, 64);
+                if (z[d] < left || right == 0.f) {
                     cur = c;
                 } else {
                     z[d] = z[d] - left;
@@ -138,7 +144,8 @@ __device__ __forceinline__ void per_sample_emit(const SampleArgs &A, int j, long
 {
     const double P = (double)A.tree[A.L + slot] / (double)total;
     A.idx[j] = (int32_t)slot;
-    A.is_w[j] = (float)pow((double)A.size * P, -(double)A.beta);
+    // a tree without mass (every stored transition has priority zero) has nothing to draw: weight 0
+    A.is_w[j] = total > 0.f ? (float)pow((double)A.size * P, -(double)A.beta) : 0.f;
     if (A.G.a) {
         A.G.a[j] = A.G.meta_a[slot];
         A.G.r[j] = A.G.meta_r[slot];

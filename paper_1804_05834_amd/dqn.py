@@ -18,7 +18,8 @@ OK, ERR_INVALID_ARG, ERR_OOM, ERR_HIP, ERR_STATE, ERR_UNSUPPORTED = 0, -1, -2, -
 EXPORTS = ["dqn_query_sizes", "dqn_init", "dqn_act", "dqn_train_step", "per_sample", "per_update",
            "per_fill", "dqn_replay_write", "dqn_replay_gather", "dqn_sync_target", "dqn_get_params",
            "dqn_set_params", "dqn_profile_begin", "dqn_profile_end", "dqn_last_error", "dqn_destroy",
-           "dqn_replay_store", "dqn_replay_state", "dqn_schedule_default", "dqn_schedule_at", "dqn_preprocess"]
+           "dqn_replay_store", "dqn_replay_state", "dqn_schedule_default", "dqn_schedule_at", "dqn_preprocess",
+           "dqn_get_activations"]
 
 
 class DqnConfig(C.Structure):
@@ -52,7 +53,7 @@ class DqnBatch(C.Structure):
 
 class DqnStepOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("loss", "q_s", "q_next_online", "q_next_target", "y", "td",
-                                          "a_star", "idx", "is_w")]
+                                          "a_star", "idx", "is_w", "td_abs_mean", "q_max_mean")]
 
 
 class DqnSchedule(C.Structure):
@@ -110,6 +111,7 @@ def lib():
             "dqn_sync_target": [vp, vp],
             "dqn_get_params": [vp, i32, vp, vp],
             "dqn_set_params": [vp, i32, vp, vp],
+            "dqn_get_activations": [vp, i32, i32, vp, vp],
             "dqn_profile_begin": [vp],
             "dqn_profile_end": [vp, i32, C.POINTER(C.c_char_p), C.POINTER(i64), C.POINTER(C.c_double)],
             "dqn_destroy": [vp],
@@ -228,7 +230,8 @@ class Dqn:
                        q_next_target=torch.empty(B, self.K, device=dev), y=torch.empty(B, device=dev),
                        td=torch.empty(B, device=dev),
                        a_star=torch.empty(B, dtype=torch.int32, device=dev),
-                       is_w=torch.empty(B, device=dev))
+                       is_w=torch.empty(B, device=dev), td_abs_mean=torch.empty(1, device=dev),
+                       q_max_mean=torch.empty(1, device=dev))
             if batch is None:
                 out["idx"] = torch.empty(B, dtype=torch.int32, device=dev)
             so = DqnStepOut(**{k: v.data_ptr() for k, v in out.items()})
@@ -293,6 +296,13 @@ class Dqn:
         assert src.numel() == self.n
         self._check(lib().dqn_set_params(self._h, which, _ptr(src), _stream()))
         torch.cuda.current_stream().synchronize()   # src may be a temporary
+
+    def get_activations(self, layer, n):
+        """Stored outputs of layer 1..4 for the first n training rows of the last step (fp32, canonical order)."""
+        shape = {1: (n, 32, 20, 20), 2: (n, 64, 9, 9), 3: (n, 64, 7, 7), 4: (n, 512)}[layer]
+        dst = torch.empty(shape, dtype=torch.float32, device=self.device)
+        self._check(lib().dqn_get_activations(self._h, layer, n, _ptr(dst), _stream()))
+        return dst
 
     def profile_begin(self):
         self._check(lib().dqn_profile_begin(self._h))

@@ -57,6 +57,71 @@ def test_descent_equals_cumulative_sum_definition(orc):
         assert idx.min() >= 0 and idx.max() < n
 
 
+def _plain_descent(tree, L, z):
+    """The textbook rule alone (z < left ? left : right with z -= left), vectorised."""
+    node = np.ones(z.size, np.int64)
+    z = z.astype(np.float32).copy()
+    while node[0] < L:
+        left = tree[2 * node]
+        go_left = z < left
+        z = np.where(go_left, z, (z - left).astype(np.float32))
+        node = 2 * node + (~go_left)
+    return node - L
+
+
+def test_descent_never_returns_a_zero_leaf(orc):
+    """Eq.10: a transition of priority zero has probability zero.  Every one of the 2^24 possible
+    draws u is pushed through a tree whose odd slots (and a run of slots) hold zero leaves, as the
+    store path leaves them.  The textbook rule ends on a zero leaf for the few u whose mass
+    overshoots a subtree (a parent is the rounded sum of its children); the oracle's rule never
+    does, agrees with the textbook rule everywhere else, and where it differs it returns the
+    drawable slot next to the one the exact cumulative sums name, with z on their boundary."""
+    n, L, alpha = 3000, 4096, 0.6
+    p = synth.exp_priorities(13, n).numpy()   # a seed for which the textbook rule is known to fail once
+    p[1::2] = 0.0
+    tree = orc.tree_build(p, L, alpha)
+    total = tree[1]
+    assert total > 0 and np.all(tree[L + 1:L + n:2] == 0)
+    hits = 0
+    for part in range(16):
+        u = (np.arange(part << 20, (part + 1) << 20, dtype=np.float64) * 2.0 ** -24).astype(np.float32)
+        z = u * total                                   # fp32 product, as specified
+        got = orc.tree_descend(tree, z)
+        assert np.all(tree[L + got] > 0)
+        plain = _plain_descent(tree, L, z)
+        diff = np.flatnonzero(got != plain)
+        assert np.all(tree[L + plain[diff]] == 0)       # they differ only where the textbook rule fails
+        if diff.size:
+            hits += diff.size
+            ref, dist = orc.per_sample_cumsum(tree, n, z[diff])
+            assert np.all(tree[L + ref] > 0)
+            assert np.all(dist <= 4 * np.spacing(total))
+            # the slot returned is the last drawable one before the slot the exact sums name
+            for g, r in zip(got[diff], ref):
+                assert g <= r and not np.any(tree[L + g + 1:L + r] > 0), (g, r)
+    assert hits > 0, "the case the rule exists for never occurred: the test does not bite"
+    # the draw found by that sweep, on its own: u = 6410600 * 2^-24 overshoots an inner node
+    z1 = np.array([np.float32(6410600 * 2.0 ** -24) * total], np.float32)
+    assert tree[L + _plain_descent(tree, L, z1)[0]] == 0 and tree[L + orc.tree_descend(tree, z1)[0]] > 0
+    # stratified masses reach the total itself: still a drawable slot
+    idx, w, z = orc.per_sample(tree, n, 1024, 0.4, 5, stratified=True)
+    assert np.all(tree[L + idx] > 0) and np.all(np.isfinite(w)) and w.max() == 1.0
+    # z == total exactly
+    assert tree[L + orc.tree_descend(tree, np.array([total, np.float32(2) * total], np.float32))].min() > 0
+
+
+def test_descent_rule_is_the_textbook_rule_without_zero_leaves(orc):
+    for seed, n, L in ((3, 64, 64), (4, 1000, 1024)):
+        tree = orc.tree_build(synth.exp_priorities(seed, n).numpy(), L, 0.6)
+        u = (np.arange(0, 1 << 24, 37, dtype=np.float64) * 2.0 ** -24).astype(np.float32)
+        z = u * tree[1]
+        got = orc.tree_descend(tree, z)
+        plain = _plain_descent(tree, L, z)
+        bad = got != plain
+        # only where the textbook rule walks past the last stored slot into the padding
+        assert np.all(plain[bad] >= n) and np.all(got < n)
+
+
 def test_sampling_uses_the_specified_draws(orc):
     p = synth.exp_priorities(8, 100).numpy()
     tree = orc.tree_build(p, 128, 0.6)
@@ -139,6 +204,23 @@ def test_priority_update(orc):
     assert np.array_equal(t2[L + 20:L + 64], tree[L + 20:L + 64])
     with pytest.raises(ValueError):
         orc.per_update(t2, n, np.array([n], np.int32), np.array([1.0], np.float32), alpha, eps)
+
+
+def test_priority_update_skips_non_finite_errors_only(orc):
+    """NaN and +-inf errors are skipped (their leaves keep their values); any finite error, however
+    large, is applied."""
+    n, L, alpha, eps = 16, 16, 0.6, 1e-6
+    tree = orc.tree_build(synth.exp_priorities(2, n).numpy(), L, alpha)
+    before = tree.copy()
+    idx = np.array([1, 2, 3, 4, 5], np.int32)
+    td = np.array([np.nan, np.inf, -np.inf, 3.2e38, 0.5], np.float32)
+    mp = orc.per_update(tree, n, idx, td, alpha, eps, max_p=1.0)
+    assert np.array_equal(tree[L + 1:L + 4], before[L + 1:L + 4])
+    assert tree[L + 4] == np.float32(np.float64(np.float32(3.2e38)) ** alpha)
+    assert tree[L + 5] == np.float32((0.5 + eps) ** alpha)
+    assert np.all(np.isfinite(tree)) and mp == np.float32(3.2e38)
+    for i in range(L - 1, 0, -1):
+        assert tree[i] == np.float32(tree[2 * i] + tree[2 * i + 1])
 
 
 def test_gather_stacks(orc):
