@@ -178,6 +178,22 @@ int32_t per_sample(dqn_ctx *ctx, int32_t B, float beta, uint64_t draw_seed, int3
  * skipped (their leaves keep their values).  1 <= n <= 1024. */
 int32_t per_update(dqn_ctx *ctx, const int32_t *idx, const float *td_abs, int32_t n, void *stream);
 
+/* dqn_act for callers that cannot allocate device memory or pass a workspace of
+ * their own sizing: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and bit-identical results
+ * as dqn_act, but the activations and partial sums go to a static device array
+ * inside the library (4 MiB per GPU, held until the process ends) instead of
+ * the context's workspace, so E is limited to DQN_ACT_STATIC_MAX; a larger E
+ * is DQN_ERR_INVALID_ARG.  The call allocates nothing (no hipMalloc, no
+ * hipFree, no events); the array's device address is looked up once per device,
+ * at dqn_init or on the first call there.  Nothing in the array has to start
+ * at zero: every word read has been written earlier in the same call.  All
+ * calls on one GPU share the array: calls that overlap on one GPU (two
+ * streams, two contexts, two threads) race and give undefined results. */
+#define DQN_ACT_STATIC_MAX 32
+int32_t dqn_act_static(dqn_ctx *ctx, const uint8_t *obs, int32_t E, float epsilon, uint64_t draw_seed,
+                       int32_t *actions, float *q_opt, void *stream);
+
 /* ---- auxiliary calls needed to drive and to check the five above ---- */
 
 /* Bulk (re)build of the sum-tree from n raw priorities p_i > 0 for slots

@@ -17,9 +17,36 @@
 #include "kernels_misc.h"
 #include "net.h"
 
+// Scratch memory of dqn_act_static, the entry point for callers that cannot allocate: activations and
+// fc1 partial sums of up to DQN_ACT_STATIC_MAX observations.  Each GPU the library runs on holds its own
+// copy of this array, at its own address, until the process ends.  In host code the array's name is
+// only a stand-in for the symbol; the device address is looked up once per device (below).
+constexpr size_t SCRATCH_BYTES = 4u << 20;
+static __device__ __align__(256) uint8_t scratch[SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_err;  // errors without a context
+
+constexpr int MAX_DEVICES = 64;
+uint8_t *g_scratch_ptr[MAX_DEVICES];   // device address of `scratch` on each device, once looked up
+
+// The address of `scratch` on the current device (looked up on first use on that device, with that
+// device current; no allocation), or nullptr.
+uint8_t *scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = static_cast<uint8_t *>(p);
+    }
+    return g_scratch_ptr[dev];
+}
 
 constexpr int MAX_WSPLIT = 64;   // most reduction splits of a conv2/conv3 weight gradient
 constexpr int MAX_WSPLIT1 = 256; // ... of the conv1 weight gradient (one output tile only)
@@ -337,11 +364,10 @@ bool in_kernel_draw_fits(const dqn_ctx *c, int B)
     return fused12_fits(c, n, 3, true) || conv1_plan_bf16(3 * B, c->num_cu).draw_fits;
 }
 
-int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
-                          hipStream_t st, const misc::SampleArgs *draw)
+int32_t forward_trunk_f32(dqn_ctx *c, const Workspace &w, const Pass *pass, int npass, int *nsplit_out,
+                          long *split_stride_out, hipStream_t st, const misc::SampleArgs *draw)
 {
     using namespace g32;
-    const Workspace &w = c->ws;
     float *act1 = (float *)w.act1, *act2 = (float *)w.act2, *act3 = (float *)w.act3;
     long row0[3];
     long rows = 0;
@@ -428,11 +454,10 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_o
 }
 
 // draw != nullptr: the conv1 kernel draws the transitions itself (replay mode; no sampling kernel ran)
-int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_out, long *split_stride_out,
-                           hipStream_t st, const misc::SampleArgs *draw)
+int32_t forward_trunk_bf16(dqn_ctx *c, const Workspace &w, const Pass *pass, int npass, int *nsplit_out,
+                           long *split_stride_out, hipStream_t st, const misc::SampleArgs *draw)
 {
     using namespace gbf;
-    const Workspace &w = c->ws;
     bf16_t *act1 = (bf16_t *)w.act1, *act2 = (bf16_t *)w.act2, *act3 = (bf16_t *)w.act3;
     long row0[3];
     long rows = 0;
@@ -543,11 +568,13 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Pass *pass, int npass, int *nsplit_
     return hip_status(c, "forward");
 }
 
-int32_t forward_trunk(dqn_ctx *c, const Pass *pass, int npass, int *ns, long *ss, hipStream_t st,
+// w: where the activations and the fc1 partial sums go (the context's workspace, or a view of the
+// library's static scratch array)
+int32_t forward_trunk(dqn_ctx *c, const Workspace &w, const Pass *pass, int npass, int *ns, long *ss, hipStream_t st,
                       const misc::SampleArgs *draw = nullptr)
 {
-    return c->cfg.precision == 1 ? forward_trunk_bf16(c, pass, npass, ns, ss, st, draw)
-                                 : forward_trunk_f32(c, pass, npass, ns, ss, st, draw);
+    return c->cfg.precision == 1 ? forward_trunk_bf16(c, w, pass, npass, ns, ss, st, draw)
+                                 : forward_trunk_f32(c, w, pass, npass, ns, ss, st, draw);
 }
 
 // reduction rows per split (a multiple of `unit`) and the resulting number of splits
@@ -970,6 +997,7 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
         delete c;
         return fail(nullptr, DQN_ERR_HIP, "dqn_init: device initialisation failed");
     }
+    (void)scratch_of_current_device();   // set-up: the address of the static scratch array on this device
     {
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) == hipSuccess &&
@@ -1280,12 +1308,51 @@ int32_t dqn_act(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64
     Pass p{obs, net::STATE, 0, E, nullptr, 0};
     int ns;
     long ss;
-    int32_t rc = forward_trunk(c, &p, 1, &ns, &ss, st);
+    int32_t rc = forward_trunk(c, c->ws, &p, 1, &ns, &ss, st);
     if (rc) return rc;
     misc::HeadActArgs H{c->ws.f1part, ns, ss, E, c->cfg.num_actions, c->cfg.dueling, c->theta + net::F1B,
                         c->theta + net::HEAD, epsilon, draw_seed, actions, q_opt};
     launch(c, "head_act", st, [&] { misc::k_head_act<<<E, 256, 0, st>>>(H); });
     return hip_status(c, "dqn_act");
+}
+
+int32_t dqn_act_static(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64_t draw_seed,
+                       int32_t *actions, float *q_opt, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    if (E < 1 || E > DQN_ACT_STATIC_MAX)
+        return fail(c, DQN_ERR_INVALID_ARG, "dqn_act_static: E must be in 1..DQN_ACT_STATIC_MAX (32): the static scratch array holds no more");
+    if (!obs || !actions || !aligned(obs, 16)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act_static: NULL or misaligned argument");
+    if (!(epsilon >= 0.f && epsilon <= 1.f)) return fail(c, DQN_ERR_INVALID_ARG, "dqn_act_static: epsilon must be in [0,1]");
+    uint8_t *base = scratch_of_current_device();
+    if (!base) return fail(c, DQN_ERR_HIP, "dqn_act_static: the address of the static scratch array is not available on this device");
+    // a view of the scratch array laid out like the part of the workspace that acting uses; every word a
+    // kernel reads from it has been written by an earlier kernel of this call, so nothing is cleared
+    Workspace w{};
+    const size_t es = c->cfg.precision == 1 ? 2 : 4, n = DQN_ACT_STATIC_MAX;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { uint8_t *q = base + off; off += align_up(bytes, 256); return q; };
+    w.act1 = take(n * net::A1 * es);
+    w.act2 = take(n * net::A2 * es);
+    w.act3 = take(n * net::A3 * es);
+    w.f1part = (float *)take(n * 14 * net::HID * 4);
+    static_assert(DQN_ACT_STATIC_MAX * (size_t)(net::A1 + net::A2 + net::A3) * 4 + DQN_ACT_STATIC_MAX * 14 * (size_t)net::HID * 4 + 4 * 256
+                      <= SCRATCH_BYTES, "scratch array too small");
+    hipStream_t st = (hipStream_t)stream;
+    Pass p{obs, net::STATE, 0, E, nullptr, 0};
+    int ns;
+    long ss;
+    const bool prof = c->prof;   // per-kernel timing creates events: not on this path
+    c->prof = false;
+    int32_t rc = forward_trunk(c, w, &p, 1, &ns, &ss, st);
+    if (rc == DQN_OK) {
+        misc::HeadActArgs H{w.f1part, ns, ss, E, c->cfg.num_actions, c->cfg.dueling, c->theta + net::F1B,
+                            c->theta + net::HEAD, epsilon, draw_seed, actions, q_opt};
+        misc::k_head_act<<<E, 256, 0, st>>>(H);
+        rc = hip_status(c, "dqn_act_static");
+    }
+    c->prof = prof;
+    return rc;
 }
 
 // ------------------------------------------------------------ training
@@ -1357,7 +1424,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
                       {sn, xs, 1, B, ring_idx, 1, nullptr, 0}};
     int ns;
     long ss;
-    int32_t rc = forward_trunk(c, passes, 3, &ns, &ss, st, draw);
+    int32_t rc = forward_trunk(c, w, passes, 3, &ns, &ss, st, draw);
     if (rc) return rc;
     // the drawn indices exist once the sampling kernel, or the first forward kernel, has run
     if (!batch && O.idx && hipMemcpyAsync(O.idx, w.b_idx, (size_t)B * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)

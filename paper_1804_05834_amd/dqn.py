@@ -19,7 +19,7 @@ EXPORTS = ["dqn_query_sizes", "dqn_init", "dqn_act", "dqn_train_step", "per_samp
            "per_fill", "dqn_replay_write", "dqn_replay_gather", "dqn_sync_target", "dqn_get_params",
            "dqn_set_params", "dqn_profile_begin", "dqn_profile_end", "dqn_last_error", "dqn_destroy",
            "dqn_replay_store", "dqn_replay_state", "dqn_schedule_default", "dqn_schedule_at", "dqn_preprocess",
-           "dqn_get_activations"]
+           "dqn_get_activations", "dqn_act_static"]
 
 
 class DqnConfig(C.Structure):
@@ -97,6 +97,7 @@ def lib():
             "dqn_query_sizes": [C.POINTER(DqnConfig), C.POINTER(DqnSizes)],
             "dqn_init": [C.POINTER(vp), C.POINTER(DqnConfig), C.POINTER(DqnBuffers), vp],
             "dqn_act": [vp, vp, i32, f32, u64, vp, vp, vp],
+            "dqn_act_static": [vp, vp, i32, f32, u64, vp, vp, vp],
             "dqn_train_step": [vp, i32, C.POINTER(DqnBatch), f32, u64, C.POINTER(DqnStepOut), vp],
             "per_sample": [vp, i32, f32, u64, vp, vp, vp],
             "per_update": [vp, vp, vp, i32, vp],
@@ -210,13 +211,18 @@ class Dqn:
         return self._bufs["tree"].view(torch.float32)[2 * self.L]
 
     # -- the five calls ----------------------------------------------------------------
-    def act(self, obs, epsilon, draw_seed, want_q=False):
+    def act(self, obs, epsilon, draw_seed, want_q=False, static=False, out=None):
+        """static: through dqn_act_static (scratch in the library's static device array).
+        out: (actions, q) tensors to write into instead of new ones."""
         E = obs.shape[0]
-        actions = torch.empty(E, dtype=torch.int32, device=self.device)
-        q = torch.empty(E, self.K, dtype=torch.float32, device=self.device) if want_q else None
-        self._check(lib().dqn_act(self._h, _ptr(obs), E, epsilon, draw_seed, _ptr(actions), _ptr(q),
-                                  _stream()))
-        return (actions, q) if want_q else actions
+        if out is not None:
+            actions, q = out
+        else:
+            actions = torch.empty(E, dtype=torch.int32, device=self.device)
+            q = torch.empty(E, self.K, dtype=torch.float32, device=self.device) if want_q else None
+        fn = lib().dqn_act_static if static else lib().dqn_act
+        self._check(fn(self._h, _ptr(obs), E, epsilon, draw_seed, _ptr(actions), _ptr(q), _stream()))
+        return (actions, q) if (want_q or out is not None) else actions
 
     def train_step(self, B, batch=None, beta=0.4, draw_seed=0, outputs=True):
         """batch: None (replay mode) or a tuple (s, s_next, a, r, done[, w]) of device tensors.
