@@ -61,6 +61,7 @@ struct Workspace {
     // activations, channel-last, rows = samples of all passes (fp32 or bf16 by precision)
     void *act1, *act2, *act3;
     float *f1part, *h_s;
+    size_t f1rows;   // rows of 512 partial sums that f1part holds (rows of a launch x reduction splits)
     // backward (dh, d3, d2, d1: fp32 or bf16 by precision)
     float *dA;
     void *dh, *d3, *d2, *d1;
@@ -114,6 +115,7 @@ Workspace carve(const dqn_config &c, uint8_t *base)
                               std::min<size_t>(rows, 1536) * 2, rows});
     if (c.precision == 1) f1rows = std::max(f1rows, std::min<size_t>(rows, 2048) * 7);
     w.f1part = (float *)take(f1rows * net::HID * 4);
+    w.f1rows = f1rows;
     w.h_s = (float *)take(MB * net::HID * 4);
     w.dA = (float *)take(MB * R * 4);
     w.dh = take(MB * net::HID * es);
@@ -163,6 +165,9 @@ struct dqn_ctx {
     // bf16: conv1 + conv2 forward run as one launch (gbf::c12) from this many samples per launch on;
     // INT_MAX: never (the launch needs 140 KB of LDS per workgroup, granted at initialisation)
     int conv12_min = INT32_MAX;
+    // bf16: fc1 forward as 128 x 128 tiles (gbf::f1) from this many rows per launch on; needs 72 KB of LDS
+    bool fc1_big = false;
+    int fc1_big_rows = 512, fc1_big_splits = 0;
     hipStream_t side = nullptr;
     hipStream_t side2 = nullptr;  // the single-workgroup priority update gets a lane of its own
     hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_c = nullptr, ev_join = nullptr, ev_join2 = nullptr;
@@ -554,7 +559,29 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Workspace &w, const Pass *pass, int
         const int grid = per_sample(A, act2, net::A2, net::C3W, net::C3B, act3, net::A3);
         launch(c, "conv3_fwd", st, [&] { ps::k_conv_fwd_ps<ps::G3><<<dim3(grid), 256, 0, st>>>(A); });
     }
-    {
+    if (c->fc1_big && rows >= c->fc1_big_rows) {
+        // many rows: 128 x 128 tiles, double-buffered stages, few reduction splits
+        f1::Args A{};
+        A.nseg = npass;
+        int tile = 0;
+        for (int i = 0; i < npass; ++i) {
+            A.seg[i] = FwdSeg{act3 + row0[i] * net::A3, shadow_of(c, pass[i].net) + net::F1W, nullptr,
+                              w.f1part + row0[i] * net::HID, pass[i].n, tile, (long)net::A3};
+            tile += (pass[i].n + f1::BM - 1) / f1::BM;
+        }
+        for (int i = npass; i < 3; ++i) A.seg[i] = A.seg[0];
+        A.tiles_m = tile;
+        // as many splits as it takes to give about three quarters of the compute units a workgroup, seven at
+        // most: every further split is another 3 MB of partial sums per 1536 rows to write and to read back
+        // (measured at 1536 rows: 3 / 4 / 5 / 6 / 7 splits give 151.3 / 149.8 / 152 / 153.5 / 152.6 us per step)
+        int ns = c->fc1_big_splits > 0 ? c->fc1_big_splits : (3 * c->num_cu / 4 + 2 * tile) / (4 * tile);
+        ns = std::max<long>(1, std::min<long>({(long)ns, 7L, (long)(w.f1rows / (size_t)rows)}));
+        A.nsplit = ns;
+        A.split_stride = rows * net::HID;
+        launch(c, "fc1_fwd", st, [&] { f1::k_fc1_fwd<<<dim3(4 * tile * ns), 256, f1::LDS_BYTES, st>>>(A); });
+        *nsplit_out = ns;
+        *split_stride_out = rows * net::HID;
+    } else {
         FwdArgs A{};
         const int ns = fc1_splits(rows, 1);
         int tiles = build(A, 64, 1, [&](int i) { return (const void *)(act3 + row0[i] * net::A3); },
@@ -1014,6 +1041,15 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
     } else {
         (void)hipGetLastError();
     }
+    if (cfg->precision == 1 &&
+        hipFuncSetAttribute((const void *)gbf::f1::k_fc1_fwd, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            gbf::f1::LDS_BYTES) == hipSuccess) {
+        c->fc1_big = true;
+        if (const char *m = std::getenv("DQN_FC1_BIG_ROWS")) if (m[0]) c->fc1_big_rows = std::atoi(m);
+        if (const char *m = std::getenv("DQN_FC1_SPLITS")) if (m[0]) c->fc1_big_splits = std::atoi(m);
+    } else {
+        (void)hipGetLastError();
+    }
     // side stream at the default priority; if anything fails the step simply runs on one stream
     // (DQN_SINGLE_STREAM=1 in the environment keeps everything on the caller's stream)
     const char *single = std::getenv("DQN_SINGLE_STREAM");
@@ -1336,6 +1372,7 @@ int32_t dqn_act_static(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon,
     w.act2 = take(n * net::A2 * es);
     w.act3 = take(n * net::A3 * es);
     w.f1part = (float *)take(n * 14 * net::HID * 4);
+    w.f1rows = n * 14;
     static_assert(DQN_ACT_STATIC_MAX * (size_t)(net::A1 + net::A2 + net::A3) * 4 + DQN_ACT_STATIC_MAX * 14 * (size_t)net::HID * 4 + 4 * 256
                       <= SCRATCH_BYTES, "scratch array too small");
     hipStream_t st = (hipStream_t)stream;

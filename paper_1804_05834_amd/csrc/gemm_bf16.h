@@ -281,6 +281,171 @@ __global__ __launch_bounds__((BM / (32 * WM)) * (BN / (32 * WN)) * 64) void k_fw
     }
 }
 
+// Dispatch-order number u of `total` workgroups -> tile number, die-aware as net::tile_of_workgroup
+// (a launch that holds two problems numbers each of them by itself).
+__device__ __forceinline__ int tile_of(int u, int total)
+{
+    const int die = u & 7, slot = u >> 3, q = total >> 3, r = total & 7;
+    return die * q + (die < r ? die : r) + slot;
+}
+
+// ---------------------------------------------------------------------------
+// fc1 forward for many rows (Section 3 fourth layer: 3136 -> 512): raw fp32 partial sums of a few
+// reduction splits, which the head kernel adds up.
+//
+// 128 x 128 output tile per workgroup of four waves, 64 x 64 per wave (2 x 2 MFMA blocks, so every
+// LDS fragment feeds two matrix instructions), reduction stages of 64 elements in LDS tiles that are
+// double-buffered: ONE barrier per stage and sixteen 32x32x16 MFMAs per wave between two barriers.
+// While stage s is multiplied, stage s+1 goes from registers to the other LDS buffer and stage s+3
+// is requested from memory.  The 49 stages of the reduction are dealt out evenly to the splits.
+// Measured per stage and workgroup in the steady state: 16 MFMAs per wave take 250 ns, with the LDS
+// reads beside them 285 ns, with the 32 KB of LDS writes as well 430 ns: the loop is bound by LDS
+// bandwidth (96 KB per stage and compute unit), not by the matrix pipe.
+// Tile order: the four column tiles of one row tile and split next to each other (they share the
+// activations), row tiles of one split after each other (they share the weights).
+// ---------------------------------------------------------------------------
+namespace f1 {
+constexpr int BM = 128, BN = 128;
+constexpr int TILE = BM * LDK;                   // elements of one operand tile in LDS
+constexpr int LDS_BYTES = 2 * 2 * TILE * 2;      // two operands, two buffers: 73,728 bytes
+constexpr int STAGES = GFc1::K / BK;             // 49
+
+struct Args {
+    FwdSeg seg[3];      // tile_begin counts row tiles of BM rows; y = fp32 [M][512] of split 0
+    int nseg;
+    int nsplit;
+    int tiles_m;        // row tiles of all segments
+    long split_stride;  // elements between the partial sums of consecutive splits
+};
+
+// Barrier that orders LDS traffic only, written with the builtins so that the compiler's own wait
+// counting knows that every LDS operation of the wave has completed at this point.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+}
+
+__global__ __launch_bounds__(256, 2) void k_fc1_fwd(Args A)
+{
+    extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
+    bf16_t *As = lds, *Bs = lds + 2 * TILE;      // [buffer][row][LDK]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t = tile_of(blockIdx.x, gridDim.x);
+    const int by = t & 3, bx = (t >> 2) % A.tiles_m, bz = (t >> 2) / A.tiles_m;
+    FwdSeg S = A.seg[0];
+    if (A.nseg > 1 && bx >= A.seg[1].tile_begin) S = A.seg[1];
+    if (A.nseg > 2 && bx >= A.seg[2].tile_begin) S = A.seg[2];
+    const int m0 = (bx - S.tile_begin) * BM, n0 = by * BN;
+    const int s0 = STAGES * bz / A.nsplit, n = STAGES * (bz + 1) / A.nsplit - s0;
+    const bf16_t *x = static_cast<const bf16_t *>(S.x);
+
+    // staging: 16-byte piece c = tid + 256 i of a 128 x 64 tile is row c / 8, elements 8 (c % 8) .. +7
+    const int lr = tid >> 3, kq = (tid & 7) * 8;
+    const bf16_t *pa[4], *pb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int m = m0 + lr + 32 * i;
+        if (m > S.M - 1) m = S.M - 1;             // rows past the end repeat the last row; they are never stored
+        pa[i] = x + (long)m * S.xs + kq;
+        pb[i] = S.w + (long)(n0 + lr + 32 * i) * GFc1::K + kq;
+    }
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a native vector: stays in registers
+    struct Regs { u32x4 a[4], b[4]; };
+    Regs R0, R1;                                  // two stages on their way from memory
+    auto gload = [&](Regs &R, int st) {
+        const int k0 = (s0 + st) * BK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            R.a[i] = *reinterpret_cast<const u32x4 *>(pa[i] + k0);
+            R.b[i] = *reinterpret_cast<const u32x4 *>(pb[i] + k0);
+        }
+    };
+    auto sstore = [&](const Regs &R, int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<u32x4 *>(&As[buf * TILE + (lr + 32 * i) * LDK + kq]) = R.a[i];
+            *reinterpret_cast<u32x4 *>(&Bs[buf * TILE + (lr + 32 * i) * LDK + kq]) = R.b[i];
+        }
+    };
+    const int wm = wave & 1, wn = wave >> 1;
+    const int li = lane & 31, h = lane >> 5;
+    const int apo = (wm * 64 + li) * LDK + 8 * h, bpo = (wn * 64 + li) * LDK + 8 * h;
+    v16f acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = v16f{0};
+    struct Frag { v8bf a[2], b[2]; };             // the operands of one 16-deep step of the wave's 64 x 64
+    auto rd = [&](int buf, int kk) {
+        Frag F;
+        const bf16_t *ap = As + buf * TILE + apo + kk, *bp = Bs + buf * TILE + bpo + kk;
+        F.a[0] = frag_k(ap); F.a[1] = frag_k(ap + 32 * LDK);
+        F.b[0] = frag_k(bp); F.b[1] = frag_k(bp + 32 * LDK);
+        return F;
+    };
+    auto mm = [&](const Frag &F) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) acc[a][b] = mfma(F.b[b], F.a[a], acc[a][b]);  // transposed tile
+    };
+
+    gload(R0, 0);
+    if (n > 1) gload(R1, 1);
+    sstore(R0, 0);
+    if (n > 2) gload(R0, 2);
+    lds_barrier();
+    Frag cur = rd(0, 0);
+    // Stage i out of buffer buf.  NX holds stage i + 1 (requested two stages ago) and is refilled with
+    // stage i + 3.  The operands of a step are requested before the matrix instructions of the step
+    // before it; the barrier sits in front of the stage's last step, whose matrix instructions then
+    // cover the barrier and the first LDS reads of the next stage.  The other buffer was last read
+    // before the previous barrier, so it may be written at any point of this stage.
+    auto stage = [&](int i, int buf, Regs &NX) {
+        Frag f1 = rd(buf, 16);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(cur);
+        __builtin_amdgcn_sched_barrier(0);
+        Frag f2 = rd(buf, 32);
+        if (i + 1 < n) sstore(NX, buf ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(f1);
+        __builtin_amdgcn_sched_barrier(0);
+        Frag f3 = rd(buf, 48);
+        if (i + 3 < n) gload(NX, i + 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(f2);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_barrier();
+        if (i + 1 < n) cur = rd(buf ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(f3);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int i = 0; i < n; i += 2) {              // unrolled by two: the register sets alternate statically
+        stage(i, 0, R1);
+        if (i + 1 < n) stage(i + 1, 1, R0);
+    }
+
+    // acc[a][b][4g + j] = Y[row block a, lane li][column block b, 8g + 4h + j]
+    float *y = static_cast<float *>(S.y) + (long)bz * A.split_stride;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        const int m = m0 + (wm * 2 + a) * 32 + li;
+        if (m >= S.M) continue;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = n0 + (wn * 2 + b) * 32 + 8 * g + 4 * h;
+                *reinterpret_cast<v4f *>(y + (long)m * GFc1::N + col) =
+                    v4f{acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+            }
+    }
+}
+}  // namespace f1
+
 // ---------------------------------------------------------------------------
 using g32::DConv2;
 using g32::DConv3;
@@ -619,14 +784,6 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int t, int gx, in
             if (do_bias && li == 0) part[(long)G::N * G::K + o] = accb[a][r];
         }
     }
-}
-
-// Dispatch-order number u of `total` workgroups -> tile number, die-aware as net::tile_of_workgroup
-// (a launch that holds two problems numbers each of them by itself).
-__device__ __forceinline__ int tile_of(int u, int total)
-{
-    const int die = u & 7, slot = u >> 3, q = total >> 3, r = total & 7;
-    return die * q + (die < r ? die : r) + slot;
 }
 
 // The input gradient and the weight gradient of one layer go into ONE launch of 64x64 tiles (both

@@ -170,52 +170,67 @@ struct HeadArgs {
 // for the three passes, evaluates the head three times, forms the target
 // (Eq.8 / Eq.9), the TD error, the loss term and the gradient w.r.t. the
 // head rows, and back-propagates through the head into the hidden layer.
+//
+// The kernel is a chain of latencies, so it is written to have ONE round trip to memory: every
+// global operand (partial sums and biases first, then the head weights of the dot products, the
+// thread's column of the online head for the back-propagation, the raw importance weights, the
+// row's transition) is requested before anything is waited for, in the order of first use.  The
+// dueling combine (Eq.13) and the argmax run on one wave per pass with lane a holding action a.
+constexpr int HEAD_MAX_SPLITS = 7;   // reduction splits of fc1 that the kernel holds in registers
 __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
 {
     __shared__ float hid[3][net::HID];
     __shared__ float raw[3][MAXR];
     __shared__ float q[3][64];
-    __shared__ float dA[MAXR];
     __shared__ float shm[16];
+    __shared__ float res_q[3];     // Q(s, a_j; theta), max_a Q(s, a; theta), -
+    __shared__ int res_as[3];      // argmax_a of pass p
     const int j = blockIdx.x, tid = threadIdx.x;
     const int K = A.K, R = K + (A.dueling ? 1 : 0);
-    // Everything the row needs from global memory is requested before the first barrier: the raw
-    // importance weights (for their maximum, Alg.2 weighting line), the row's transition, the
-    // head weights and the fc1 partial sums.
     const bool norm = A.w && A.w_raw;
-    float wmax = 0.f;
-    if (norm)
-        for (int t = tid; t < A.B; t += 512) wmax = fmaxf(wmax, A.w[t]);
-    // an action outside [0, K) cannot be trained on: the row contributes nothing (weight 0), its TD
-    // error is reported as NaN and the priority update skips it
+
+    // ---- every global load, in the order of first use
+    float ps[3][HEAD_MAX_SPLITS];
+    const long row[3] = {(long)j, (long)A.B + j, 2L * A.B + j};
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+#pragma unroll
+        for (int sp = 0; sp < HEAD_MAX_SPLITS; ++sp)
+            ps[p][sp] = sp < A.nsplit ? A.part[sp * A.split_stride + row[p] * net::HID + tid] : 0.f;
+    const float b_on = A.f1b_on[tid], b_tg = A.f1b_tg[tid];
+    HeadRound H0, H1;
+    head_rows3_load(H0, 0, A.head_on, A.head_tg, K, A.dueling, tid);
+    head_rows3_load(H1, 1, A.head_on, A.head_tg, K, A.dueling, tid);
     const int aj_raw = A.a[j];
-    const bool a_ok = aj_raw >= 0 && aj_raw < K;
-    const int aj = a_ok ? aj_raw : 0;
     const bool dn = A.done[j] != 0;
     const float rj = A.r[j];
     const float wj = A.w ? A.w[j] : 1.f;
-
-    // column tid of the online head (for the back-propagation into the hidden layer at the end)
-    // and the head weights of the first two rounds (all of them when 3R <= 64) are requested now
+    float w0 = 0.f, w1 = 0.f;   // raw importance weights tid and tid + 512 (B <= 1024), for their maximum
+    if (norm) {
+        w0 = tid < A.B ? A.w[tid] : 0.f;
+        w1 = tid + 512 < A.B ? A.w[tid + 512] : 0.f;
+    }
+    // column tid of the online head, for the back-propagation into the hidden layer at the end
     constexpr int HW_PRE = 24;
     float hw[HW_PRE];
 #pragma unroll
     for (int r = 0; r < HW_PRE; ++r) hw[r] = r < R ? A.head_on[head_w_off(r, K, A.dueling) + tid] : 0.f;
-    HeadRound H0, H1;
-    head_rows3_load(H0, 0, A.head_on, A.head_tg, K, A.dueling, tid);
-    head_rows3_load(H1, 1, A.head_on, A.head_tg, K, A.dueling, tid);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- hidden layer: split sums in split order, bias, ReLU
     {
-        const int i = tid;  // one hidden unit per thread
-        float hs = hidden_unit(A.part, A.nsplit, A.split_stride, j, i, A.f1b_on);
-        hid[0][i] = hs;
-        hid[1][i] = hidden_unit(A.part, A.nsplit, A.split_stride, (long)A.B + j, i, A.f1b_on);
-        hid[2][i] = hidden_unit(A.part, A.nsplit, A.split_stride, 2L * A.B + j, i, A.f1b_tg);
-        A.h_s[(long)j * net::HID + i] = hs;
-    }
-    if (norm) {  // per-wave maxima; thread 0 combines them after the barriers below
+        float acc[3] = {0.f, 0.f, 0.f};
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, o, 64));
-        if ((tid & 63) == 0) shm[tid >> 6] = wmax;
+        for (int p = 0; p < 3; ++p) {
+#pragma unroll
+            for (int sp = 0; sp < HEAD_MAX_SPLITS; ++sp) acc[p] += ps[p][sp];
+            for (int sp = HEAD_MAX_SPLITS; sp < A.nsplit; ++sp) acc[p] += A.part[sp * A.split_stride + row[p] * net::HID + tid];
+        }
+        const float hs = fmaxf(acc[0] + b_on, 0.f);
+        hid[0][tid] = hs;
+        hid[1][tid] = fmaxf(acc[1] + b_on, 0.f);
+        hid[2][tid] = fmaxf(acc[2] + b_tg, 0.f);
+        A.h_s[(long)j * net::HID + tid] = hs;
     }
     __syncthreads();
     head_rows3_dot(H0, hid, K, A.dueling, raw, tid);
@@ -224,8 +239,37 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         head_rows3_load(H0, round, A.head_on, A.head_tg, K, A.dueling, tid);
         head_rows3_dot(H0, hid, K, A.dueling, raw, tid);
     }
+    if (norm) {  // per-wave maxima of the raw weights; thread 0 combines them below
+        float wmax = fmaxf(w0, w1);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, o, 64));
+        if ((tid & 63) == 0) shm[tid >> 6] = wmax;
+    }
     __syncthreads();
-    if (tid < 3) combine_q(raw[tid], K, A.dueling, q[tid]);
+    const bool a_ok = aj_raw >= 0 && aj_raw < K;
+    const int aj = a_ok ? aj_raw : 0;
+    if (tid < 192) {
+        // wave p: lane a holds Q_a of pass p (Eq.13: V + A_a - mean A, or the plain outputs)
+        const int p = tid >> 6, a = tid & 63;
+        const float v = a < K ? raw[p][A.dueling ? 1 + a : a] : 0.f;
+        float qa = v;
+        if (A.dueling) qa = raw[p][0] + (v - wave_sum(v) / (float)K);
+        if (a < K) q[p][a] = qa;
+        // argmax with the lowest index winning ties; lanes past K never win
+        float bv = a < K ? qa : -3.4028234663852886e38f;
+        int bi = a < K ? a : 64;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        const float q_aj = __shfl(qa, aj, 64);
+        if (a == 0) {
+            res_as[p] = bi;
+            if (p == 0) { res_q[0] = q_aj; res_q[1] = bv; }
+        }
+    }
     __syncthreads();
     if (tid == 0) {
         float wnorm = 1.f;
@@ -234,10 +278,12 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
             for (int v = 1; v < 8; ++v) m = fmaxf(m, shm[v]);
             wnorm = m > 0.f ? 1.f / m : 0.f;   // no mass in the tree: every weight is 0
         }
-        const int as = argmax_low(A.double_q ? q[1] : q[2], K);
+        const int as = res_as[A.double_q ? 1 : 2];
         const float boot = dn ? 0.f : A.gamma * q[2][as];
         const float y = rj + boot;
-        const float d = y - q[0][aj];
+        const float d = y - res_q[0];
+        // an action outside [0, K) cannot be trained on: the row contributes nothing (weight 0), its TD
+        // error is reported as NaN and the priority update skips it
         const float w = !a_ok ? 0.f : A.w ? wj * wnorm : 1.f;
         float l, dl;
         if (A.loss_kind == 1 && fabsf(d) > A.kappa) {
@@ -247,20 +293,12 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
             l = 0.5f * d * d;
             dl = d;
         }
-        const float g = -w * dl / (float)A.B;  // dL/dQ(s_j, a_j)
-        if (A.dueling) {
-            dA[0] = g;
-            for (int a = 0; a < K; ++a) dA[1 + a] = (a == aj ? g : 0.f) - g / (float)K;
-        } else {
-            for (int a = 0; a < K; ++a) dA[a] = a == aj ? g : 0.f;
-        }
+        shm[8] = -w * dl / (float)A.B;  // dL/dQ(s_j, a_j)
         // a drawn row whose raw weight is 0 came from a tree without mass: its slot holds nothing to update
         const bool skip = !a_ok || (norm && !(wj > 0.f));
         A.td_abs[j] = skip ? __int_as_float(0x7fc00000) : fabsf(d);
         A.loss_j[j] = w * l;
-        float qm = q[0][0];
-        for (int a = 1; a < K; ++a) qm = fmaxf(qm, q[0][a]);
-        A.qmax_j[j] = qm;
+        A.qmax_j[j] = res_q[1];
         if (A.y) A.y[j] = y;
         if (A.td) A.td[j] = a_ok ? d : __int_as_float(0x7fc00000);
         if (A.a_star) A.a_star[j] = as;
@@ -270,17 +308,21 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
     if (A.q_no && tid >= 128 && tid < 128 + K) A.q_no[(long)j * K + tid - 128] = q[1][tid - 128];
     if (A.q_nt && tid >= 192 && tid < 192 + K) A.q_nt[(long)j * K + tid - 192] = q[2][tid - 192];
     __syncthreads();
-    if (tid < R) A.dA[(long)j * R + tid] = dA[tid];
     {
-        const int i = tid;
+        // gradient w.r.t. the head rows (dueling: dV = g, dA_a = [a = a_j] g - g / K), every thread for itself
+        const float g = shm[8];
+        const float gk = A.dueling ? g / (float)K : 0.f;
+        const int hit = A.dueling ? 1 + aj : aj;
+        if (tid < R) A.dA[(long)j * R + tid] = (A.dueling && tid == 0) ? g : (tid == hit ? g : 0.f) - gk;
         float acc = 0.f;
 #pragma unroll
         for (int r = 0; r < HW_PRE; ++r)
-            if (r < R) acc += dA[r] * hw[r];
-        for (int r = HW_PRE; r < R; ++r) acc += dA[r] * A.head_on[head_w_off(r, K, A.dueling) + i];
-        const float gmask = hid[0][i] > 0.f ? acc : 0.f;
-        if (A.dh_bf16) static_cast<__hip_bfloat16 *>(A.dh)[(long)j * net::HID + i] = __float2bfloat16(gmask);
-        else static_cast<float *>(A.dh)[(long)j * net::HID + i] = gmask;
+            if (r < R) acc += ((A.dueling && r == 0) ? g : (r == hit ? g : 0.f) - gk) * hw[r];
+        for (int r = HW_PRE; r < R; ++r)
+            acc += ((A.dueling && r == 0) ? g : (r == hit ? g : 0.f) - gk) * A.head_on[head_w_off(r, K, A.dueling) + tid];
+        const float gmask = hid[0][tid] > 0.f ? acc : 0.f;
+        if (A.dh_bf16) static_cast<__hip_bfloat16 *>(A.dh)[(long)j * net::HID + tid] = __float2bfloat16(gmask);
+        else static_cast<float *>(A.dh)[(long)j * net::HID + tid] = gmask;
     }
 }
 
