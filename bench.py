@@ -127,8 +127,16 @@ def fill_ring(m, synth, torch, capacity, K):
     torch.cuda.synchronize()
 
 
+SPIN_UP_STEPS = 300   # untimed, before the counted warm-up: clocks and caches reach their steady state
+
+
 def time_steps(m, torch, B, steps, warmup, seed0=0):
-    """Returns (wall seconds, device seconds, host seconds spent enqueueing) for `steps` steps."""
+    """Returns (wall seconds, device seconds, host seconds spent enqueueing) for `steps` steps.
+    A fixed spin-up runs first, so that a short run (--steps 20 --warmup 5) measures the same steady
+    state as a long one."""
+    for i in range(SPIN_UP_STEPS):
+        m.train_step(B, None, beta=0.4, draw_seed=seed0 + 5_000_000 + i, outputs=False)
+    torch.cuda.synchronize()
     for i in range(warmup):
         m.train_step(B, None, beta=0.4, draw_seed=seed0 + i, outputs=False)
     torch.cuda.synchronize()
@@ -258,14 +266,24 @@ def time_agent_loop(dqn, synth, torch, capacity, env_steps, K=18, B=32):
             "train_steps": trains}
 
 
-def kernel_table(prof, B, R, n_params, precision):
-    """Per kernel: live HIP-event average duration, the roofline that bounds it, what it achieves."""
+def kernel_table(prof, B, R, n_params, precision, step_s=None):
+    """Per kernel: live HIP-event average duration, the roofline that bounds it, what it achieves.
+    An event pair around a kernel adds a fixed cost to what it measures (the events themselves are
+    commands on the stream).  step_s, the duration of a step timed WITHOUT per-kernel events, gives
+    that cost: the kernels of a step run back to back on one stream, so the event-timed durations
+    exceed the step by (launches per step) x (cost per pair).  It is subtracted (`avg_us`; the raw
+    event time stays in `avg_us_events`), so that the kernel times add up to the step."""
     fl = flops_per_launch(B, R)
     by = bytes_per_launch(B, n_params, precision == "bf16")
     gb = gemm_bytes_per_launch(B, R, precision == "bf16")
     out = {}
+    overhead_s = 0.0
+    if step_s is not None and prof:
+        per_step = sum(tot_ms / cnt for cnt, tot_ms in prof.values()) / 1e3
+        overhead_s = max(0.0, (per_step - step_s) / len(prof))
     for k, (cnt, tot_ms) in prof.items():
-        avg_s = tot_ms / cnt / 1e3
+        raw_s = tot_ms / cnt / 1e3
+        avg_s = max(raw_s - overhead_s, 0.25 * raw_s)
         if k in fl and k in gb and gb[k] / HBM_PEAK > fl[k] / PEAK[precision]:
             # a GEMM kernel whose operands take longer to stream at the HBM peak than its flops
             # take at the MFMA peak: HBM is the roof that binds
@@ -276,6 +294,7 @@ def kernel_table(prof, B, R, n_params, precision):
             e = {"bound": "hbm", "achieved": by.get(k, 0) / avg_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
         e["frac"] = e["achieved"] / e["peak"]
         e["avg_us"] = round(avg_s * 1e6, 2)
+        e["avg_us_events"] = round(raw_s * 1e6, 2)
         e["achieved"] = round(e["achieved"], 3)
         e["frac"] = round(e["frac"], 5)
         out[k] = e
@@ -292,6 +311,61 @@ def check_health(m, torch, B):
     assert loss == loss and abs(loss) < 1e6, loss
     assert abs(root - leaves) <= 1e-4 * leaves, (root, leaves)
     return loss
+
+
+def time_replay_calls(m, torch, synth, capacity, reps=200):
+    """The replay calls of the boundary on their own, over the same ring: microseconds per call and
+    the algorithmic bytes they move against the HBM peak.  (Inside the training step the draws ride in
+    the first forward kernel and the priority update in the backward launches; the tree walks are
+    chains of dependent loads, so the time per call is the figure that matters.)"""
+    out = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, n):
+        for _ in range(10):
+            fn(0)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / n
+
+    levels = max(1, (m.L - 1).bit_length())
+    for B in (32, 512):
+        t = timed(lambda i: m.per_sample(B, 0.4, 1000 + i), reps)
+        out.append({"call": "per_sample", "batch": B, "us_per_call": t * 1e6, "algorithmic_bytes": B * levels * 4,
+                    "achieved_GBps": B * levels * 4 / t / 1e9, "frac_of_hbm_peak": B * levels * 4 / t / HBM_PEAK})
+        idx, _ = m.per_sample(B, 0.4, 7)
+        td = synth.u24(5, torch.arange(B)).cuda()
+        t = timed(lambda i: m.per_update(idx, td), reps)
+        out.append({"call": "per_update", "batch": B, "us_per_call": t * 1e6, "algorithmic_bytes": B * levels * 12,
+                    "achieved_GBps": B * levels * 12 / t / 1e9, "frac_of_hbm_peak": B * levels * 12 / t / HBM_PEAK})
+        # rotate over distinct index sets so the frames are not cache-resident
+        sets = [m.per_sample(B, 0.4, 50 + k)[0] for k in range(16)]
+        from paper_1804_05834_amd import dqn as _d
+        s = torch.empty(B, 4, 84, 84, dtype=torch.uint8, device="cuda")
+        sn = torch.empty_like(s)
+        a = torch.empty(B, dtype=torch.int32, device="cuda")
+        r = torch.empty(B, device="cuda")
+        d = torch.empty(B, dtype=torch.uint8, device="cuda")
+
+        def gather(i):
+            ix = sets[i % 16]
+            m._check(_d.lib().dqn_replay_gather(m._h, _d._ptr(ix), B, _d._ptr(s), _d._ptr(sn), _d._ptr(a), _d._ptr(r),
+                                                _d._ptr(d), _d._stream()))
+        t = timed(gather, reps)
+        nb = B * (5 * 7056 + 2 * 4 * 7056)     # five ring frames read, two four-frame stacks written
+        out.append({"call": "dqn_replay_gather", "batch": B, "us_per_call": t * 1e6, "algorithmic_bytes": nb,
+                    "achieved_GBps": nb / t / 1e9, "frac_of_hbm_peak": nb / t / HBM_PEAK})
+    pri = synth.exp_priorities(9, capacity, "cuda")
+    t = timed(lambda i: m.per_fill(pri), 20)
+    nb = capacity * 4 + 2 * m.L * 4          # priorities read, every node of the tree written
+    out.append({"call": "per_fill", "slots": capacity, "us_per_call": t * 1e6, "algorithmic_bytes": nb,
+                "achieved_GBps": nb / t / 1e9, "frac_of_hbm_peak": nb / t / HBM_PEAK,
+                "launches": 1 + levels})
+    return {"workload": "the replay calls of the boundary on their own, %d-slot ring" % capacity, "calls": out}
 
 
 def cpu_baseline(torch, synth, B, sample_rows):
@@ -315,9 +389,10 @@ def cpu_baseline(torch, synth, B, sample_rows):
             break
     per_step = el / reps * (B / sample_rows)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count()))
-    return {"value": 1.0 / per_step, "unit": "train steps/s", "cores": cores, "kind": "oracle",
-            "sample": "%d full oracle steps (fp64, explicit batch) on %d of the %d rows, time scaled by %d/%d"
-                      % (reps, sample_rows, B, B, sample_rows)}
+    sample = ("%d full oracle steps (fp64, explicit batch) on all %d rows" % (reps, B) if sample_rows == B else
+              "%d full oracle steps (fp64, explicit batch) on %d of the %d rows, time scaled by %d/%d"
+              % (reps, sample_rows, B, B, sample_rows))
+    return {"value": 1.0 / per_step, "unit": "train steps/s", "cores": cores, "kind": "oracle", "sample": sample}
 
 
 def main():
@@ -350,7 +425,7 @@ def main():
 
     prof = profile_kernels(m, torch, B, min(args.steps, 100), seed0=10_000_000)
     loss = check_health(m, torch, B)
-    table = kernel_table(prof, B, R, m.n, args.precision)
+    table = kernel_table(prof, B, R, m.n, args.precision, step_s=dev_s / args.steps)
     # the dominant kernel: the largest total time among the kernels of the step (the tree
     # kernels are listed in the table too; they are bound by dependent-load latency, not by a
     # throughput roofline; in the bf16 step per_update rides inside the backward launches)
@@ -372,16 +447,18 @@ def main():
         "mfma_frac_step": step_flops(B, R) * value / PEAK[args.precision],
         "device_ms_per_step": dev_s / args.steps * 1e3,
         "host_enqueue_ms_per_step": enq_s / args.steps * 1e3,
+        "spin_up_steps": SPIN_UP_STEPS,
         "final_loss": loss,
         "roofline": roof,
         "kernels": table,
     }
+    replay_calls = None if args.no_also else time_replay_calls(m, torch, synth, args.capacity)
     m.close()
     del m
     torch.cuda.empty_cache()
 
     if not args.no_also:
-        also = []
+        also = [replay_calls]
         if not (B == 32 and prec == 0):
             m32 = build_model(dqn, synth, torch, 32, 0, args.capacity)
             w32, d32, _ = time_steps(m32, torch, 32, args.steps, args.warmup)
@@ -407,7 +484,7 @@ def main():
             torch.cuda.empty_cache()
         res["also"] = also
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(torch, synth, B, min(B, 64))
+        res["cpu_baseline"] = cpu_baseline(torch, synth, B, B)   # whole steps on all rows, about 12 s of CPU work
     print(json.dumps(res))
 
 

@@ -272,6 +272,15 @@ int32_t dqn_replay_gather(dqn_ctx *ctx, const int32_t *idx, int32_t n, uint8_t *
  * the numbers the backward pass takes its ReLU decisions on.  1 <= n <= max_batch. */
 int32_t dqn_get_activations(dqn_ctx *ctx, int32_t layer, int32_t n, float *dst, void *stream);
 
+/* Host-only self-check, no device work: replays, for a run of ns samples per
+ * workgroup (1..32), the schedule by which the fused conv1 + conv2 forward launch
+ * of the bf16 path hands conv1's output of a sample (Section 3, first and second
+ * layer) from its producer waves to its consumer waves through a ring of images
+ * in LDS, using the very functions the kernel's loops call.  Returns 0 if every
+ * sample is complete before it is read, read exactly once, and never overwritten
+ * while unread; a positive code otherwise. */
+int32_t dqn_selftest_fused_conv_schedule(int32_t ns);
+
 /* theta^- <- theta (Alg.2 "copy weights into target network"). */
 int32_t dqn_sync_target(dqn_ctx *ctx, void *stream);
 

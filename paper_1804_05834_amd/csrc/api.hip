@@ -171,6 +171,11 @@ struct dqn_ctx {
     hipStream_t side = nullptr;
     hipStream_t side2 = nullptr;  // the single-workgroup priority update gets a lane of its own
     hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr, ev_c = nullptr, ev_join = nullptr, ev_join2 = nullptr;
+    // Uniform replay (priority exponent 0, the "without prioritized replay" settings of Sec.4) over a tree
+    // that a bulk fill built: every stored leaf is 1 and stays 1, the descent returns floor(z) and every
+    // importance weight is 1, so sampling reads no tree node and the priority update writes none.  The store
+    // path gives leaf 0 to slots that hold no whole transition: after it the tree is walked again.
+    bool leaves_all_one = false;
     int64_t cursor = 0;  // next ring slot of the store path
     int64_t seq = 0;     // time steps stored so far (stream position of the next one)
     bool prof = false;
@@ -251,6 +256,12 @@ void launch(dqn_ctx *c, const char *name, hipStream_t st, F &&f)
         }
     }
     f();
+}
+
+int uniform_replay(const dqn_ctx *c)
+{
+    const char *off = std::getenv("DQN_NO_UNIFORM_FAST_PATH");   // for A/B measurements
+    return c->leaves_all_one && !(off && off[0] == '1') ? 1 : 0;
 }
 
 int32_t hip_status(dqn_ctx *c, const char *where)
@@ -1166,6 +1177,11 @@ int32_t dqn_get_activations(dqn_ctx *c, int32_t layer, int32_t n, float *dst, vo
     return hip_status(c, "dqn_get_activations");
 }
 
+int32_t dqn_selftest_fused_conv_schedule(int32_t ns)
+{
+    return gbf::c12::schedule_is_safe(ns);
+}
+
 int32_t dqn_sync_target(dqn_ctx *c, void *stream)
 {
     if (!c) return DQN_ERR_INVALID_ARG;
@@ -1198,6 +1214,7 @@ int32_t per_fill(dqn_ctx *c, const float *priorities, int64_t n, void *stream)
     c->stored = n;
     c->seq = n;
     c->cursor = n % c->cfg.replay_capacity;
+    c->leaves_all_one = c->cfg.per_alpha == 0.f && n <= (1 << 24);   // sums of ones are exact up to 2^24
     return hip_status(c, "per_fill");
 }
 
@@ -1211,7 +1228,8 @@ int32_t per_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, int32_
     hipStream_t st = (hipStream_t)stream;
     launch(c, "per_sample", st, [&] {
         misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(misc::SampleArgs{
-            c->tree, c->L, c->levels, c->stored, B, beta, draw_seed, c->cfg.per_stratified, idx, is_w, misc::MetaGather{}});
+            c->tree, c->L, c->levels, c->stored, B, beta, draw_seed, c->cfg.per_stratified, idx, is_w, misc::MetaGather{},
+            uniform_replay(c)});
     });
     launch(c, "per_normalise", st, [&] { misc::k_per_normalise<<<1, 1024, 0, st>>>(is_w, B); });
     return hip_status(c, "per_sample");
@@ -1226,7 +1244,7 @@ int32_t per_update(dqn_ctx *c, const int32_t *idx, const float *td_abs, int32_t 
     hipStream_t st = (hipStream_t)stream;
     launch(c, "per_update", st, [&] {
         misc::k_per_update<<<1, (n + 63) / 64 * 64, 0, st>>>(
-            misc::PerUpdateArgs{c->tree, c->L, c->levels, c->stored, idx, td_abs, n, c->cfg.per_alpha, c->cfg.per_eps});
+            misc::PerUpdateArgs{c->tree, c->L, c->levels, c->stored, idx, td_abs, n, c->cfg.per_alpha, c->cfg.per_eps, 0});
     });
     return hip_status(c, "per_update");
 }
@@ -1267,6 +1285,7 @@ int32_t dqn_replay_store(dqn_ctx *c, int64_t n, const uint8_t *frames, const int
         misc::k_store_priorities<<<1, (int)((n + 4 + 63) / 64 * 64), 0, st>>>(c->tree, c->L, c->levels, cap, h0, c->seq,
                                                                              (int)n, c->meta_done, c->cfg.per_alpha);
     });
+    c->leaves_all_one = false;
     c->cursor = (h0 + n) % cap;
     c->seq += n;
     c->stored = std::min<int64_t>(c->seq, cap);
@@ -1399,7 +1418,7 @@ static misc::SampleArgs sample_args(dqn_ctx *c, int32_t B, float beta, uint64_t 
     // raw importance weights; the head kernel divides by their maximum
     return misc::SampleArgs{c->tree, c->L, c->levels, c->stored, B, beta, draw_seed, c->cfg.per_stratified,
                             w.b_idx, w.b_w,
-                            misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done}};
+                            misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done}, uniform_replay(c)};
 }
 
 // The sampling kernel of a replay-mode step.  The fp32 path copies the drawn frame stacks next
@@ -1495,7 +1514,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
                            w.td_abs, w.qmax_j, O.td_abs_mean, O.q_max_mean};
     // the indices come from the sampling kernel, so the ring capacity bounds them
     misc::PerUpdateArgs PU{c->tree, c->L, c->levels, (long)cfg.replay_capacity, w.b_idx, w.td_abs, B,
-                           cfg.per_alpha, cfg.per_eps};
+                           cfg.per_alpha, cfg.per_eps, uniform_replay(c)};
     // one stream: they ride in the launches of the backward pass (see backward_bf16, backward_f32)
     SmallTail tail{HW, PU, !batch};
     const bool fuse_tail = sd == st;

@@ -1086,7 +1086,7 @@ __device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1,
 __device__ __forceinline__ void draw_slots(const misc::SampleArgs &P, int n, int u0, int u1, int *slots, int lane,
                                            bool publish)
 {
-    const float total = P.tree[1];
+    const float total = misc::sample_total(P);
     const int gs0 = u0 / UNITS, gs1 = (u1 - 1) / UNITS;   // launch-wide sample numbers
 #pragma unroll 1
     for (int ga = gs0; ga <= gs1; ga += 2) {
@@ -1633,7 +1633,47 @@ constexpr int MAX_PER_WG = 32;                              // samples one workg
 constexpr int STRIPS_B = 4 * STRIP * 2;                     // 53,760 bytes: one strip per producer wave
 constexpr int RING_B = NRING * S2::SAMPLE;                  // 86,400 bytes
 constexpr int LDS_BYTES = STRIPS_B + RING_B + MAX_PER_WG * 4;
-constexpr int intervals(int ns) { return (UNITS * ns + 3) / 4 + 1; }
+// The hand-over schedule, as functions the kernel's loops and the host-side check
+// (schedule_is_safe, behind dqn_selftest_fused_conv_schedule) both call.
+constexpr int PRODUCERS = 4;                                // producer waves: strips per interval
+__host__ __device__ constexpr int intervals(int ns) { return (UNITS * ns + PRODUCERS - 1) / PRODUCERS + 1; }
+// sample that strip u of a run belongs to, and the image of the ring that holds a sample
+__host__ __device__ constexpr int sample_of_strip(int u) { return u / UNITS; }
+__host__ __device__ constexpr int image_of_sample(int k) { return k % NRING; }
+// is sample kc consumed in interval i?  (its last strip was produced in an earlier interval)
+__host__ __device__ constexpr bool consumed_in(int kc, int i) { return UNITS * kc + UNITS <= PRODUCERS * i; }
+
+// Replays the schedule on the host for a run of ns samples: a sample is complete before it is read, it
+// is read exactly once, and no strip is written into an image that still holds a sample which has
+// not been read or is being read in the same interval.  Returns 0 if safe, else a code naming the failure.
+inline int schedule_is_safe(int ns)
+{
+    if (ns < 1 || ns > MAX_PER_WG) return 1;
+    int holds[NRING], written[MAX_PER_WG], consumed[MAX_PER_WG];
+    for (int r = 0; r < NRING; ++r) holds[r] = -1;
+    for (int k = 0; k < ns; ++k) written[k] = consumed[k] = 0;
+    int kc = 0;
+    for (int i = 0; i < intervals(ns); ++i) {
+        int reading = -1;
+        if (kc < ns && consumed_in(kc, i)) {
+            if (written[kc] != UNITS || holds[image_of_sample(kc)] != kc) return 2;   // read before complete
+            reading = kc;
+        }
+        for (int u = PRODUCERS * i; u < PRODUCERS * i + PRODUCERS && u < UNITS * ns; ++u) {
+            const int k = sample_of_strip(u), img = image_of_sample(k);
+            if (holds[img] != k) {
+                if (holds[img] >= 0 && !consumed[holds[img]]) return 3;               // overwrites an unread sample
+                if (reading >= 0 && image_of_sample(reading) == img) return 4;        // overwrites the sample being read
+                holds[img] = k;
+            }
+            ++written[k];
+        }
+        if (reading >= 0) { consumed[reading] = 1; ++kc; }
+    }
+    for (int k = 0; k < ns; ++k)
+        if (!consumed[k] || written[k] != UNITS) return 5;                             // something left over
+    return 0;
+}
 
 // samples [lo, hi) of segment S, consumer wave (ph, hh) = (position half, channel half)
 __device__ __forceinline__ void run_consumer(const Seg &S, int lo, int hi, const uint8_t *ring, const v8bf (&wa)[16][2],
@@ -1654,8 +1694,8 @@ __device__ __forceinline__ void run_consumer(const Seg &S, int lo, int hi, const
     }
     int kc = 0;   // next sample to consume
     for (int i = 0; i < nint; ++i) {
-        if (kc < ns && UNITS * kc + UNITS <= 4 * i) {
-            const uint8_t *buf = ring + (kc % NRING) * S2::SAMPLE;
+        if (kc < ns && consumed_in(kc, i)) {
+            const uint8_t *buf = ring + image_of_sample(kc) * S2::SAMPLE;
             v4f acc[3][2];
 #pragma unroll
             for (int b = 0; b < 3; ++b) acc[b][0] = acc[b][1] = v4f{0, 0, 0, 0};
@@ -1719,9 +1759,9 @@ __device__ __forceinline__ void run_producer(const Seg &S, int lo, int hi, bf16_
     int u = w;
     for (int i = 0; i < nint; ++i) {
         if (u < nstrips) {
-            const int k = u / UNITS, strip = u % UNITS;
+            const int k = sample_of_strip(u), strip = u % UNITS;
             c1::strip_store(xs, R, lane);   // LDS operations of one wave complete in order
-            const int un = u + 4;
+            const int un = u + PRODUCERS;
             if (un < nstrips) c1::strip_load(R, S.src, lo + un / UNITS, S.src.idx ? slots[un / UNITS] : 0, un % UNITS, lane, O);
             struct Quads { uint4 q[6]; };
             auto quads = [&](int c) {   // see c1::conv1_fwd_units
@@ -1755,7 +1795,7 @@ __device__ __forceinline__ void run_producer(const Seg &S, int lo, int hi, bf16_
                 cur = nxt;
             }
             // bias, 1/255, ReLU, bf16: into the sample's image in the ring and, where kept, to memory
-            uint8_t *img = ring + (k % NRING) * S2::SAMPLE;
+            uint8_t *img = ring + image_of_sample(k) * S2::SAMPLE;
             uint8_t *yb = S.y1 ? reinterpret_cast<uint8_t *>(S.y1) + ((long)(lo + k) * 400 + 80 * strip) * 64 +
                                      ((20 * oyl + 5 * q) * 32 + 8 * kg) * 2
                                : nullptr;
@@ -1803,7 +1843,7 @@ __global__ __launch_bounds__(512) void k_conv12_fwd(Args A)
     auto fill_slots = [&]() {
         if (!S.src.idx) return;
         if (A.draw) {
-            const float total = A.samp.tree[1];
+            const float total = misc::sample_total(A.samp);
 #pragma unroll 1
             for (int k = 2 * wave; k < ns; k += 16) {
                 const int kb = k + 1 < ns ? k + 1 : k;

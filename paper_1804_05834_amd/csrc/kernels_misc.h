@@ -586,7 +586,7 @@ __global__ __launch_bounds__(256) void k_per_sample(SampleArgs A)
     const int lane = threadIdx.x & 63;
     const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (j >= A.B) return;
-    const float total = A.tree[1];
+    const float total = sample_total(A);
     const long slot = per_sample_descend(A, j, lane, total);
     if (lane == 0) per_sample_emit(A, j, slot, total);
 }
@@ -679,6 +679,8 @@ struct PerUpdateArgs {
     const float *td_abs;
     int n;
     float alpha, eps;
+    int leaves_fixed;   // 1: priority exponent 0 over a tree of ones: a leaf's new value is its old one, so
+                        // only the running maximum priority is updated and no node is read or written
 };
 constexpr int PU_LDS_WORDS = 2 * PU_SLOTS + 16;  // LDS of per_update_body, in 4-byte words
 
@@ -733,6 +735,7 @@ __device__ __forceinline__ void per_update_body(const PerUpdateArgs &A, int *lds
     }
     const float pmax = block_max_1024(pm, sh);  // contains barriers
     if (tid == 0) tree[2 * L] = fmaxf(tree[2 * L], pmax);
+    if (A.leaves_fixed) return;   // uniform for the workgroup
     // One walker per distinct leaf (the last entry naming it) walks to the root.  A level is one
     // exchange through memory: every walker publishes its node, the workgroup meets, every
     // walker reads its sibling as it now stands.  Walkers whose paths have merged hold the same
@@ -765,6 +768,7 @@ template <int W>
 __device__ __forceinline__ void per_update_resume(const PerUpdateArgs &A, int done_levels, int walk_levels, int *state)
 {
     const int tid = threadIdx.x, nt = blockDim.x;
+    if (A.leaves_fixed) return;
     int node[W];
     float v[W];
     bool walk[W];
@@ -932,7 +936,7 @@ __global__ __launch_bounds__(256) void k_sample_gather(SampleArgs S, GatherArgs 
     __shared__ long slot_sh;
     const int j = blockIdx.x, k = blockIdx.y;
     if (threadIdx.x < 64) {
-        const float total = S.tree[1];
+        const float total = sample_total(S);
         const long slot = per_sample_descend(S, j, threadIdx.x, total);
         if (threadIdx.x == 0) {
             slot_sh = slot;

@@ -57,7 +57,12 @@ struct SampleArgs {
     int32_t *idx;
     float *is_w;
     MetaGather G;
+    int uniform;   // 1: every stored slot has leaf 1 (priority exponent 0, tree built by a bulk fill): no tree reads
 };
+
+// The mass the draws are scaled by: the root of the tree; in uniform mode the number of stored slots
+// (the root of a tree of ones), without a memory access.
+__device__ __forceinline__ float sample_total(const SampleArgs &A) { return A.uniform ? (float)A.size : A.tree[1]; }
 
 // Draw j by one wave; every lane returns the slot.
 __device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, int lane, float total)
@@ -65,6 +70,11 @@ __device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, i
     const float *tree = A.tree;
     const float u = draw_u24(A.seed, (uint64_t)j);
     float z = A.stratified ? __fmul_rn((float)j + u, total / (float)A.B) : __fmul_rn(u, total);
+    if (A.uniform) {
+        // a tree whose stored leaves are all 1 holds exact integers, and its descent returns floor(z)
+        long slot = (long)z;
+        return slot > A.size - 1 ? A.size - 1 : slot;
+    }
     long node = 1;
     const int lj = lane >= 2 ? 31 - __clz(lane) : 0;  // level of local heap node `lane`
     for (int done = 0; done < A.levels;) {
@@ -106,6 +116,13 @@ __device__ __forceinline__ void per_sample_descend2(const SampleArgs &A, int j0,
         const float u = draw_u24(A.seed, (uint64_t)jj[d]);
         z[d] = A.stratified ? __fmul_rn((float)jj[d] + u, total / (float)A.B) : __fmul_rn(u, total);
     }
+    if (A.uniform) {
+        slot0 = (long)z[0];
+        slot1 = (long)z[1];
+        if (slot0 > A.size - 1) slot0 = A.size - 1;
+        if (slot1 > A.size - 1) slot1 = A.size - 1;
+        return;
+    }
     const int lj = lane >= 2 ? 31 - __clz(lane) : 0;
     for (int done = 0; done < A.levels;) {
         const int r = min(6, A.levels - done);
@@ -142,10 +159,14 @@ __device__ __forceinline__ void per_sample_descend2(const SampleArgs &A, int j0,
 // What one lane writes for draw j once the slot is known: index, raw weight, transition data.
 __device__ __forceinline__ void per_sample_emit(const SampleArgs &A, int j, long slot, float total)
 {
-    const double P = (double)A.tree[A.L + slot] / (double)total;
     A.idx[j] = (int32_t)slot;
-    // a tree without mass (every stored transition has priority zero) has nothing to draw: weight 0
-    A.is_w[j] = total > 0.f ? (float)pow((double)A.size * P, -(double)A.beta) : 0.f;
+    if (A.uniform) {
+        A.is_w[j] = 1.f;   // (N * 1/N)^-beta
+    } else {
+        const double P = (double)A.tree[A.L + slot] / (double)total;
+        // a tree without mass (every stored transition has priority zero) has nothing to draw: weight 0
+        A.is_w[j] = total > 0.f ? (float)pow((double)A.size * P, -(double)A.beta) : 0.f;
+    }
     if (A.G.a) {
         A.G.a[j] = A.G.meta_a[slot];
         A.G.r[j] = A.G.meta_r[slot];

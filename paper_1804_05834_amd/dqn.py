@@ -19,7 +19,7 @@ EXPORTS = ["dqn_query_sizes", "dqn_init", "dqn_act", "dqn_train_step", "per_samp
            "per_fill", "dqn_replay_write", "dqn_replay_gather", "dqn_sync_target", "dqn_get_params",
            "dqn_set_params", "dqn_profile_begin", "dqn_profile_end", "dqn_last_error", "dqn_destroy",
            "dqn_replay_store", "dqn_replay_state", "dqn_schedule_default", "dqn_schedule_at", "dqn_preprocess",
-           "dqn_get_activations", "dqn_act_static"]
+           "dqn_get_activations", "dqn_act_static", "dqn_selftest_fused_conv_schedule"]
 
 
 class DqnConfig(C.Structure):
@@ -113,6 +113,7 @@ def lib():
             "dqn_get_params": [vp, i32, vp, vp],
             "dqn_set_params": [vp, i32, vp, vp],
             "dqn_get_activations": [vp, i32, i32, vp, vp],
+            "dqn_selftest_fused_conv_schedule": [i32],
             "dqn_profile_begin": [vp],
             "dqn_profile_end": [vp, i32, C.POINTER(C.c_char_p), C.POINTER(i64), C.POINTER(C.c_double)],
             "dqn_destroy": [vp],

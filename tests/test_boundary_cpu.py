@@ -84,34 +84,13 @@ def test_product_does_not_touch_the_oracle():
                 assert "oracle" not in text.lower(), (dirpath, f)
 
 
-def test_fused_conv_ring_schedule_never_overwrites_an_unread_image():
+def test_fused_conv_ring_schedule_never_overwrites_an_unread_image(lib):
     """The fused conv1 + conv2 forward launch (bf16) hands conv1's output to the conv2 waves through
-    a ring of three LDS images with one barrier per interval: four conv1 strips are produced per
-    interval, five make a sample, and sample k is consumed in the first interval i with 4i >= 5k+5.
-    Replayed here on the host for every run length a workgroup can get: a sample is complete before
-    it is read, it is read exactly once, and no strip is written into an image that still holds a
-    sample which has not been read (or is being read in the same interval)."""
-    units, ring = 5, 3
+    a ring of LDS images with one barrier per interval.  The library replays that schedule on the
+    host with the same functions its kernel loops call (which strip belongs to which sample, which
+    image holds a sample, in which interval a sample is consumed, how many intervals a run takes),
+    for every run length a workgroup can get: a sample is complete before it is read, it is read
+    exactly once, and no strip is written into an image that still holds an unread sample."""
     for ns in range(1, 33):
-        nint = (units * ns + 3) // 4 + 1
-        holds = [None] * ring            # sample whose strips the image holds
-        written = [0] * ns               # strips of each sample written so far
-        consumed = [False] * ns
-        kc = 0
-        for i in range(nint):
-            reading = None
-            if kc < ns and units * kc + units <= 4 * i:
-                assert written[kc] == units and holds[kc % ring] == kc
-                reading = kc
-            for u in range(4 * i, min(4 * i + 4, units * ns)):
-                k = u // units
-                img = k % ring
-                if holds[img] != k:
-                    assert holds[img] is None or consumed[holds[img]], (ns, i, k)
-                    assert reading is None or reading % ring != img, (ns, i, k)
-                    holds[img] = k
-                written[k] += 1
-            if reading is not None:
-                consumed[reading] = True
-                kc += 1
-        assert all(consumed) and written == [units] * ns, ns
+        assert lib.dqn_selftest_fused_conv_schedule(ns) == 0, ns
+    assert lib.dqn_selftest_fused_conv_schedule(0) != 0 and lib.dqn_selftest_fused_conv_schedule(33) != 0

@@ -547,6 +547,62 @@ def test_replay_step_settings(dq, orc, name, B, prec, alpha, strat):
         raise AssertionError("three draw seeds in a row hit a bucket boundary")
 
 
+@pytest.mark.parametrize("prec,B,n", [(0, 32, 20000), (1, 512, 20000), (0, 7, 777)])
+def test_uniform_replay_without_the_tree(dq, orc, prec, B, n):
+    """Priority exponent 0 (the settings without prioritized replay of the paper's performance
+    figure) over a bulk-filled tree: sampling reads no tree node and the priority update writes none.
+    The result must be what the walk over the tree of ones gives, bit for bit: the same slots and
+    weights from standalone sampling, the same parameters, the same tree and running maximum
+    priority after training steps (DQN_NO_UNIFORM_FAST_PATH=1 sends the same context through the
+    tree).  After the store path, which leaves zero leaves behind, the tree is walked again."""
+    import os
+    print("case uniform replay", prec, B, n, flush=True)
+    K = 18
+    ms = []
+    for _ in range(2):
+        m = dq.Dqn(dq.make_config(replay_capacity=n + 100, max_batch=B, per_alpha=0.0, precision=prec, **CONFIGS["dueling_ddqn"]))
+        _fill_replay(m, n + 100, K=K, chunk=n + 100)
+        m.per_fill(synth.exp_priorities(9, n, "cuda"))
+        ms.append(m)
+    tree_ref = orc.tree_build(synth.exp_priorities(9, n).numpy(), ms[0].L, 0.0)
+    for strat_seed in (3, 4):
+        idx_ref, w_ref, _ = orc.per_sample(tree_ref, n, B, 0.4, strat_seed)
+        idx, w = ms[0].per_sample(B, 0.4, strat_seed)
+        assert np.array_equal(idx.cpu().numpy(), idx_ref) and np.all(w.cpu().numpy() == 1.0) and np.all(w_ref == 1.0)
+    try:
+        for step in range(3):
+            os.environ.pop("DQN_NO_UNIFORM_FAST_PATH", None)
+            o0 = ms[0].train_step(B, None, beta=0.5, draw_seed=40 + step)
+            os.environ["DQN_NO_UNIFORM_FAST_PATH"] = "1"
+            o1 = ms[1].train_step(B, None, beta=0.5, draw_seed=40 + step)
+            for k in o0:
+                assert torch.equal(o0[k], o1[k]), (step, k)
+            assert torch.equal(ms[0].get_params(0), ms[1].get_params(0)) and torch.equal(ms[0].tree, ms[1].tree)
+            assert float(ms[0].max_priority) == float(ms[1].max_priority) >= 1.0
+    finally:
+        os.environ.pop("DQN_NO_UNIFORM_FAST_PATH", None)
+    # the store path: slots without a whole transition get leaf 0 and must not be drawn
+    m = ms[0]
+    ref = orc.ReplayState(n + 100, 0.0)
+    m2 = dq.Dqn(dq.make_config(replay_capacity=n + 100, max_batch=B, per_alpha=0.0, precision=prec, **CONFIGS["dueling_ddqn"]))
+    pos = 0
+    for cnt in (200, 300):
+        fr = synth.frames(21, torch.arange(pos, pos + cnt, device="cuda"), device="cuda")
+        d = synth.dones(42, cnt, 0.1, "cuda", first=pos)
+        m2.replay_store(fr, synth.actions(40, cnt, K, "cuda", first=pos), synth.rewards(41, cnt, "cuda", first=pos), d)
+        ref.store(d.cpu().numpy())
+        pos += cnt
+    assert np.array_equal(m2.tree.cpu().numpy()[1:], ref.tree[1:])
+    idx_ref, w_ref, _ = orc.per_sample(ref.tree, ref.stored, B, 0.4, 9)
+    idx, w = m2.per_sample(B, 0.4, 9)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref) and ref.tree[ref.L + idx_ref].min() == 1.0
+    assert relerr(w.cpu().numpy(), w_ref) <= TOL
+    out = m2.train_step(B, None, beta=0.4, draw_seed=9)
+    assert np.array_equal(out["idx"].cpu().numpy(), idx_ref)
+    for mm in ms + [m2]:
+        mm.close()
+
+
 def _seed_for_draw(u_index, ctr=0):
     """A draw seed whose draw number `ctr` is u = u_index * 2^-24: the mixer is a bijection of the
     64-bit word seed + (ctr + 1) * gamma, so it is inverted step by step."""
