@@ -160,36 +160,54 @@ def time_steps(m, torch, B, steps, warmup, seed0=0):
 
 
 def time_act_train(dqn, synth, torch, capacity, iters, warmup, E=2048, B=256, K=18):
-    """Acting on E environments (epsilon 0.05) interleaved with batch-B bf16 train steps.  The
-    observations rotate among four pre-generated sets so they are not cache-resident; the acted
-    frames are not written back into the ring."""
+    """The fifth configuration as a closed loop: act on E environments (epsilon 0.05), store the E
+    new time steps with the maximal priority (one sub-ring of capacity / E slots per environment
+    stream), train on a batch of B drawn from what the streams stored (bf16).  The observations and
+    the frames that are stored rotate among pre-generated sets so they are not cache-resident; the
+    ring is filled through the same store path before the clock starts."""
     cfg = dqn.make_config(num_actions=K, dueling=1, double_q=1, precision=1, loss_kind=1,
                           huber_delta=1.0, gamma=0.99, lr=2.5e-4, rms_decay=0.95, rms_eps=0.01,
                           max_batch=B, max_act_batch=E, replay_capacity=capacity, per_alpha=0.6,
                           per_eps=1e-6, seed=1804, target_seed=5834)
     m = dqn.Dqn(cfg)
-    fill_ring(m, synth, torch, capacity, K)
     obs = [synth.states(31 + i, E, device="cuda") for i in range(4)]
-    for i in range(warmup):
-        m.act(obs[i % 4], 0.05, i)
-        m.train_step(B, None, beta=0.4, draw_seed=i, outputs=False)
+    rew = [synth.rewards(41 + i, E, "cuda") for i in range(4)]
+    don = [synth.dones(45 + i, E, 0.01, "cuda") for i in range(4)]
+    sub = capacity // E
+    for t in range(sub + 8):                       # every sub-ring full, written through the store path
+        k = t % 4
+        m.replay_store_envs(obs[k][:, 3].contiguous() if t < 4 else obs[k][:, t % 4].contiguous(),
+                            synth.actions(40, E, K, "cuda", first=t * E), rew[k], don[k])
     torch.cuda.synchronize()
+    newest = [o[:, 3].contiguous() for o in obs]   # the newest frame of every observation: what gets stored
+
+    def loop(n, first, store, train):
+        for i in range(n):
+            k = i % 4
+            act = m.act(obs[k], 0.05, first + i)
+            if store:
+                m.replay_store_envs(newest[k], act, rew[k], don[k])
+            if train:
+                m.train_step(B, None, beta=0.4, draw_seed=first + i, outputs=False)
+        torch.cuda.synchronize()
+
+    loop(warmup, 0, True, True)
     t0 = time.perf_counter()
-    for i in range(iters):
-        m.act(obs[i % 4], 0.05, warmup + i)
-        m.train_step(B, None, beta=0.4, draw_seed=warmup + i, outputs=False)
-    torch.cuda.synchronize()
+    loop(iters, warmup, True, True)
     wall = time.perf_counter() - t0
-    t1 = time.perf_counter()
-    for i in range(iters):
-        m.act(obs[i % 4], 0.05, warmup + i)
-    torch.cuda.synchronize()
-    act_only = time.perf_counter() - t1
+    t0 = time.perf_counter()
+    loop(iters, warmup + iters, False, True)
+    no_store = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    loop(iters, warmup + 2 * iters, False, False)
+    act_only = time.perf_counter() - t0
     m.close()
     act_flops = E * (F_CONV1 + F_CONV2 + F_CONV3 + F_FC1 + 2 * 512 * 19)
-    return {"workload": "act on %d environments (epsilon 0.05) + train step batch %d, bf16, alternating" % (E, B),
-            "value": iters / wall, "unit": "act+train iterations/s", "ms_per_iteration": wall / iters * 1e3,
-            "env_steps_per_s": E * iters / wall, "act_only_ms": act_only / iters * 1e3,
+    return {"workload": "act on %d environments (epsilon 0.05) + store their %d time steps (one sub-ring per "
+                        "environment, maximal priority) + train step batch %d, bf16" % (E, E, B),
+            "value": iters / wall, "unit": "act+store+train iterations/s", "ms_per_iteration": wall / iters * 1e3,
+            "env_steps_per_s": E * iters / wall, "ms_per_iteration_without_store": no_store / iters * 1e3,
+            "act_only_ms": act_only / iters * 1e3,
             "act_only_mfma_frac": act_flops * iters / act_only / PEAK["bf16"]}
 
 

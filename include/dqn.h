@@ -227,6 +227,22 @@ int32_t dqn_replay_write(dqn_ctx *ctx, int64_t slot0, int64_t n, const uint8_t *
 int32_t dqn_replay_store(dqn_ctx *ctx, int64_t n, const uint8_t *frames, const int32_t *a,
                          const float *r, const uint8_t *done, void *stream);
 
+/* Store path for many environment streams (Alg.1 "store transition" with one
+ * emulator per stream, as batched acting needs it).  The ring becomes E sub-rings
+ * of C = capacity / E slots (integer division; stream e owns slots [eC, (e+1)C));
+ * the first call on an empty context fixes E.  Every call appends ONE time step to
+ * every stream, at local slot (calls so far) mod C: frame x_t of stream e with the
+ * action taken on it, reward and terminal flag.  Each stream follows the rules of
+ * dqn_replay_store within its own sub-ring: the transition before the new step
+ * enters with the maximal priority unless its stack would reach before the
+ * stream's start or across an episode end; the slot just written and the three
+ * after it get leaf 0.  A transition's frames are read back modulo its sub-ring, so
+ * no stack ever mixes two streams.  The stored count (N of Eq.12) is
+ * E * min(calls, C).  frames: [E][84][84] device, 16-byte aligned; a, r, done: [E].
+ * 1 <= E <= capacity / 16.  per_fill returns the context to one stream. */
+int32_t dqn_replay_store_envs(dqn_ctx *ctx, int32_t E, const uint8_t *frames, const int32_t *a,
+                              const float *r, const uint8_t *done, void *stream);
+
 /* Host-side view of the store path: next slot, stored count, time steps so far.
  * Any pointer may be NULL. */
 int32_t dqn_replay_state(const dqn_ctx *ctx, int64_t *cursor, int64_t *stored, int64_t *steps);

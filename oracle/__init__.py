@@ -82,6 +82,9 @@ def lib():
         L.orc_per_sample.restype = C.c_int32
         L.orc_per_sample.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_double,
                                      C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_per_sample_n.restype = C.c_int32
+        L.orc_per_sample_n.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_double,
+                                       C.c_uint64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.orc_tree_descend.restype = None
         L.orc_tree_descend.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
         L.orc_per_sample_cumsum.restype = None
@@ -275,11 +278,13 @@ def tree_build(raw_p, L, alpha):
     return tree
 
 
-def per_sample(tree, size, B, beta, draw_seed, stratified=False):
+def per_sample(tree, size, B, beta, draw_seed, stratified=False, limit=None):
+    """size: stored transitions (N of Eq.12).  limit: slots [0, limit) may hold a transition
+    (default: size, one stream written from slot 0)."""
     L = tree.size // 2
     idx = np.zeros(B, np.int32); w = np.zeros(B, np.float32); z = np.zeros(B, np.float32)
-    rc = lib().orc_per_sample(_p(tree), L, size, B, beta, C.c_uint64(draw_seed), int(stratified),
-                              _p(idx), _p(w), _p(z))
+    rc = lib().orc_per_sample_n(_p(tree), L, size if limit is None else limit, size, B, beta,
+                                C.c_uint64(draw_seed), int(stratified), _p(idx), _p(w), _p(z))
     if rc != 0:
         raise ValueError("orc_per_sample rc=%d" % rc)
     return idx, w, z

@@ -651,16 +651,19 @@ void orc_tree_descend(const float *tree, int64_t L, const float *z, int32_t n, i
     for (int j = 0; j < n; ++j) idx[j] = (int32_t)tree_descend(tree, L, z[j]);
 }
 
-/* B draws.  size = number of stored transitions (the N of Eq.12).
+/* B draws.  n_stored = number of stored transitions (the N of Eq.12); the slots that may hold a
+ * transition are [0, limit) (limit = n_stored for one stream written from slot 0; with many
+ * environment streams, each in a sub-ring of its own, the stored transitions are not the first
+ * n_stored slots).
  * independent: z = fp32(u_j * total); stratified: z = fp32((j+u_j)*fp32(total/B)).
- * w_j = (size * P(j))^-beta, then divided by the maximum over the minibatch.
+ * w_j = (n_stored * P(j))^-beta, then divided by the maximum over the minibatch.
  * Returns -4 if the tree is empty (total <= 0).                        */
-int32_t orc_per_sample(const float *tree, int64_t L, int64_t size, int32_t B, double beta,
-                       uint64_t draw_seed, int32_t stratified, int32_t *idx, float *is_w,
-                       float *z_out)
+int32_t orc_per_sample_n(const float *tree, int64_t L, int64_t limit, int64_t n_stored, int32_t B,
+                         double beta, uint64_t draw_seed, int32_t stratified, int32_t *idx, float *is_w,
+                         float *z_out)
 {
     float total = tree[1];
-    if (!(total > 0.0f) || size < 1) return -4;
+    if (!(total > 0.0f) || n_stored < 1 || limit < 1) return -4;
     float seg = total / (float)B;
     double wmax = 0.0;
     double *wr = (double *)malloc(sizeof(double) * (size_t)B);
@@ -669,16 +672,23 @@ int32_t orc_per_sample(const float *tree, int64_t L, int64_t size, int32_t B, do
         float u = orc_draw_u24(draw_seed, (uint64_t)j);
         float z = stratified ? ((float)j + u) * seg : u * total;
         int64_t slot = tree_descend(tree, L, z);
-        if (slot > size - 1) slot = size - 1;
+        if (slot > limit - 1) slot = limit - 1;
         idx[j] = (int32_t)slot;
         if (z_out) z_out[j] = z;
         double P = (double)tree[L + slot] / (double)total;
-        wr[j] = pow((double)size * P, -beta);
+        wr[j] = pow((double)n_stored * P, -beta);
         if (wr[j] > wmax) wmax = wr[j];
     }
     for (int j = 0; j < B; ++j) is_w[j] = (float)(wr[j] / wmax);
     free(wr);
     return 0;
+}
+
+int32_t orc_per_sample(const float *tree, int64_t L, int64_t size, int32_t B, double beta,
+                       uint64_t draw_seed, int32_t stratified, int32_t *idx, float *is_w,
+                       float *z_out)
+{
+    return orc_per_sample_n(tree, L, size, size, B, beta, draw_seed, stratified, idx, is_w, z_out);
 }
 
 /* Definitional sampler: smallest slot whose inclusive cumulative sum of the

@@ -176,6 +176,10 @@ struct dqn_ctx {
     // importance weight is 1, so sampling reads no tree node and the priority update writes none.  The store
     // path gives leaf 0 to slots that hold no whole transition: after it the tree is walked again.
     bool leaves_all_one = false;
+    // The ring as sub-rings: one environment stream (sub = capacity) or, after dqn_replay_store_envs, `envs`
+    // streams of `sub` slots each.  slot_limit: slots that may hold a transition are [0, slot_limit).
+    int envs = 0;
+    long sub = 0, slot_limit = 0;
     int64_t cursor = 0;  // next ring slot of the store path
     int64_t seq = 0;     // time steps stored so far (stream position of the next one)
     bool prof = false;
@@ -256,6 +260,16 @@ void launch(dqn_ctx *c, const char *name, hipStream_t st, F &&f)
         }
     }
     f();
+}
+
+// Every internal node of the sum-tree from its leaves, twelve levels per launch.
+void rebuild_tree(dqn_ctx *c, hipStream_t st)
+{
+    for (long Lcur = c->L; Lcur >= 2; Lcur >>= 12) {
+        const int BL = (int)std::min<long>(Lcur, 4096);
+        launch(c, "tree_rebuild", st, [&] { misc::k_tree_rebuild<<<dim3((unsigned)(Lcur / BL)), 256, 0, st>>>(c->tree, Lcur, BL); });
+        if (Lcur <= 4096) break;
+    }
 }
 
 int uniform_replay(const dqn_ctx *c)
@@ -419,7 +433,7 @@ int32_t forward_trunk_f32(dqn_ctx *c, const Workspace &w, const Pass *pass, int 
         int first = 0;
         for (int i = 0; i < npass; ++i) {
             const float *theta = theta_of(c, pass[i].net);
-            A.seg[i] = c1::FwdSegF{c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift},
+            A.seg[i] = c1::FwdSegF{c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift, (int)c->sub},
                                    theta + net::C1W, theta + net::C1B, act1 + row0[i] * net::A1, pass[i].n, first,
                                    pass[i].stack, pass[i].stack_mode};
             first += pass[i].n;
@@ -507,7 +521,7 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Workspace &w, const Pass *pass, int
         A.nseg = npass;
         for (int i = 0; i < npass; ++i) {
             c12::Seg &S = A.seg[i];
-            S.src = c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift};
+            S.src = c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift, (int)c->sub};
             S.w1 = shadow_of(c, pass[i].net) + net::C1W;
             S.b1 = theta_of(c, pass[i].net) + net::C1B;
             // only the backward pass reads conv1's output, and only the rows of the first pass of a training step
@@ -528,7 +542,7 @@ int32_t forward_trunk_bf16(dqn_ctx *c, const Workspace &w, const Pass *pass, int
         int first = 0;
         for (int i = 0; i < npass; ++i) {
             c1::FwdSeg &S = A.seg[i];
-            S.src = c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift};
+            S.src = c1::Src{pass[i].x, pass[i].xs, pass[i].idx, (long)c->cfg.replay_capacity, pass[i].shift, (int)c->sub};
             S.w = shadow_of(c, pass[i].net) + net::C1W;
             S.bias = theta_of(c, pass[i].net) + net::C1B;
             S.y = act1 + row0[i] * net::A1;
@@ -923,7 +937,7 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     }
     {   // conv1: one workgroup per split of samples, frames staged in LDS
         *ns1 = std::min(B, MAX_WSPLIT1);
-        c1::WgradArgs G{c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift}, d1, w.gp1, B, *ns1};
+        c1::WgradArgs G{c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift, (int)c->sub}, d1, w.gp1, B, *ns1};
         launch(c, "conv1_wgrad", st, [&] { c1::k_conv1_wgrad<<<dim3(*ns1, 2), 256, 0, st>>>(G); });
     }
 }
@@ -990,6 +1004,7 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
     c->levels = 0;
     while ((1l << c->levels) < c->L) ++c->levels;
     c->stored = 0;
+    c->sub = (long)cfg->replay_capacity;
     if (cfg->replay_capacity > 0) {
         size_t stride = align_up((size_t)cfg->replay_capacity * 4, 256);
         c->meta_a = (int32_t *)b->replay_meta;
@@ -1209,8 +1224,10 @@ int32_t per_fill(dqn_ctx *c, const float *priorities, int64_t n, void *stream)
     launch(c, "tree_leaves", st, [&] {
         misc::k_tree_leaves<<<grid1(L, 256), 256, 0, st>>>(c->tree, L, priorities, n, c->cfg.per_alpha);
     });
-    for (long first = L >> 1; first >= 1; first >>= 1)
-        launch(c, "tree_level", st, [&] { misc::k_tree_level<<<grid1(first, 256), 256, 0, st>>>(c->tree, first, first); });
+    rebuild_tree(c, st);
+    c->envs = 0;
+    c->sub = (long)c->cfg.replay_capacity;
+    c->slot_limit = n;
     c->stored = n;
     c->seq = n;
     c->cursor = n % c->cfg.replay_capacity;
@@ -1229,7 +1246,7 @@ int32_t per_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed, int32_
     launch(c, "per_sample", st, [&] {
         misc::k_per_sample<<<(B + 3) / 4, 256, 0, st>>>(misc::SampleArgs{
             c->tree, c->L, c->levels, c->stored, B, beta, draw_seed, c->cfg.per_stratified, idx, is_w, misc::MetaGather{},
-            uniform_replay(c)});
+            uniform_replay(c), c->slot_limit});
     });
     launch(c, "per_normalise", st, [&] { misc::k_per_normalise<<<1, 1024, 0, st>>>(is_w, B); });
     return hip_status(c, "per_sample");
@@ -1244,7 +1261,7 @@ int32_t per_update(dqn_ctx *c, const int32_t *idx, const float *td_abs, int32_t 
     hipStream_t st = (hipStream_t)stream;
     launch(c, "per_update", st, [&] {
         misc::k_per_update<<<1, (n + 63) / 64 * 64, 0, st>>>(
-            misc::PerUpdateArgs{c->tree, c->L, c->levels, c->stored, idx, td_abs, n, c->cfg.per_alpha, c->cfg.per_eps, 0});
+            misc::PerUpdateArgs{c->tree, c->L, c->levels, c->slot_limit, idx, td_abs, n, c->cfg.per_alpha, c->cfg.per_eps, 0});
     });
     return hip_status(c, "per_update");
 }
@@ -1272,6 +1289,7 @@ int32_t dqn_replay_store(dqn_ctx *c, int64_t n, const uint8_t *frames, const int
     const int64_t cap = c->cfg.replay_capacity;
     if (cap <= 0) return fail(c, DQN_ERR_STATE, "dqn_replay_store: context has no replay");
     if (cap < 16) return fail(c, DQN_ERR_STATE, "dqn_replay_store: needs a ring of at least 16 slots");
+    if (c->envs > 0) return fail(c, DQN_ERR_STATE, "dqn_replay_store: the ring holds many environment streams (dqn_replay_store_envs); per_fill resets it");
     if (n < 1 || n > 1020 || n > cap - 8) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_store: n must be in 1..min(1020, capacity-8)");
     if (!frames || !aligned(frames, 16) || !a || !r || !done)
         return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_store: NULL argument or frames not 16-byte aligned");
@@ -1289,7 +1307,41 @@ int32_t dqn_replay_store(dqn_ctx *c, int64_t n, const uint8_t *frames, const int
     c->cursor = (h0 + n) % cap;
     c->seq += n;
     c->stored = std::min<int64_t>(c->seq, cap);
+    c->slot_limit = c->stored;
     return hip_status(c, "dqn_replay_store");
+}
+
+int32_t dqn_replay_store_envs(dqn_ctx *c, int32_t E, const uint8_t *frames, const int32_t *a, const float *r,
+                              const uint8_t *done, void *stream)
+{
+    if (!c) return DQN_ERR_INVALID_ARG;
+    const int64_t cap = c->cfg.replay_capacity;
+    if (cap <= 0) return fail(c, DQN_ERR_STATE, "dqn_replay_store_envs: context has no replay");
+    if (E < 1 || cap / E < 16) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_store_envs: E must be in 1..capacity/16");
+    if (!frames || !aligned(frames, 16) || !a || !r || !done)
+        return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_store_envs: NULL argument or frames not 16-byte aligned");
+    if (c->envs == 0 && c->seq != 0)
+        return fail(c, DQN_ERR_STATE, "dqn_replay_store_envs: the ring already holds one stream; start from an empty context");
+    if (c->envs != 0 && c->envs != E) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_store_envs: the number of streams is fixed by the first call");
+    hipStream_t st = (hipStream_t)stream;
+    const long C = (long)(cap / E);
+    const long t = (long)c->seq, l = t % C;
+    launch(c, "replay_write", st, [&] {
+        misc::k_replay_write_envs<<<dim3((unsigned)E), 256, 0, st>>>((uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r,
+                                                                     c->meta_done, C, l, frames, a, r, done);
+    });
+    launch(c, "store_leaves", st, [&] {
+        misc::k_store_leaves_envs<<<grid1(E, 256), 256, 0, st>>>(c->tree, c->L, C, l, t, E, c->meta_done, c->cfg.per_alpha);
+    });
+    rebuild_tree(c, st);
+    c->envs = E;
+    c->sub = C;
+    c->slot_limit = (long)E * C;
+    c->leaves_all_one = false;
+    c->seq += 1;
+    c->cursor = c->seq % C;
+    c->stored = (long)E * std::min<int64_t>(c->seq, C);
+    return hip_status(c, "dqn_replay_store_envs");
 }
 
 int32_t dqn_replay_state(const dqn_ctx *c, int64_t *cursor, int64_t *stored, int64_t *steps)
@@ -1346,7 +1398,7 @@ int32_t dqn_replay_gather(dqn_ctx *c, const int32_t *idx, int32_t n, uint8_t *s,
     if ((s && !aligned(s, 16)) || (s_next && !aligned(s_next, 16))) return fail(c, DQN_ERR_INVALID_ARG, "dqn_replay_gather: outputs must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     misc::GatherArgs G{(const uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r, c->meta_done,
-                       (long)c->cfg.replay_capacity, idx, nullptr, s, s_next, a, r, done};
+                       (long)c->cfg.replay_capacity, idx, nullptr, s, s_next, a, r, done, c->sub};
     launch(c, "gather", st, [&] { misc::k_gather<<<dim3(n, 5), 256, 0, st>>>(G); });
     return hip_status(c, "dqn_replay_gather");
 }
@@ -1418,7 +1470,8 @@ static misc::SampleArgs sample_args(dqn_ctx *c, int32_t B, float beta, uint64_t 
     // raw importance weights; the head kernel divides by their maximum
     return misc::SampleArgs{c->tree, c->L, c->levels, c->stored, B, beta, draw_seed, c->cfg.per_stratified,
                             w.b_idx, w.b_w,
-                            misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done}, uniform_replay(c)};
+                            misc::MetaGather{c->meta_a, c->meta_r, c->meta_done, w.b_a, w.b_r, w.b_done}, uniform_replay(c),
+                            c->slot_limit};
 }
 
 // The sampling kernel of a replay-mode step.  The fp32 path copies the drawn frame stacks next
@@ -1428,7 +1481,8 @@ static void enqueue_sample(dqn_ctx *c, int32_t B, float beta, uint64_t draw_seed
     const misc::SampleArgs S = sample_args(c, B, beta, draw_seed);
     if (c->cfg.precision == 0) {
         misc::GatherArgs G{(const uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r, c->meta_done,
-                           (long)c->cfg.replay_capacity, c->ws.b_idx, c->ws.stack5, nullptr, nullptr, nullptr, nullptr, nullptr};
+                           (long)c->cfg.replay_capacity, c->ws.b_idx, c->ws.stack5, nullptr, nullptr, nullptr, nullptr, nullptr,
+                           c->sub};
         launch(c, "sample_gather", st, [&] { misc::k_sample_gather<<<dim3(B, 5), 256, 0, st>>>(S, G); });
         return;
     }

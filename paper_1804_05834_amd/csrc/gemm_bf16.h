@@ -819,7 +819,15 @@ struct Src {                      // where the four frames of sample n come from
     const int32_t *idx;           // sampled slots (ring mode)
     long cap;                     // ring capacity
     int shift;                    // 0: frames i-3..i (s), 1: frames i-2..i+1 (s')
+    int sub;                      // length of the sub-ring a window wraps in: the capacity (one stream),
+                                  // or the share of one environment stream when the ring holds many
 };
+
+// First slot of the sub-ring that slot i lies in.
+__device__ __forceinline__ long sub_ring_base(const Src &S, long i)
+{
+    return (long)S.sub == S.cap ? 0 : (long)((uint32_t)i / (uint32_t)S.sub) * S.sub;
+}
 
 // The sampled slot of sample n (ring mode; 0 otherwise).  Fetched one sample ahead of the frame
 // loads that depend on it, so that the two memory latencies do not add up.
@@ -837,10 +845,11 @@ __device__ __forceinline__ const uint8_t *frame_ptr(const Src &S, int n, int slo
     if (!S.idx) return S.x + (long)n * S.xs + (long)k * FR;
     long i = __builtin_amdgcn_readfirstlane(slot_n);
     i = i < 0 ? 0 : (i >= S.cap ? S.cap - 1 : i);
-    long slot = i - 3 + k + S.shift;  // within [-3, cap+1]: one wrap at most (cap >= 5)
-    if (slot < 0) slot += S.cap;
-    if (slot >= S.cap) slot -= S.cap;
-    return S.x + slot * FR;
+    const long base = sub_ring_base(S, i);
+    long slot = i - base - 3 + k + S.shift;  // within [-3, sub+1]: one wrap at most (sub >= 5)
+    if (slot < 0) slot += S.sub;
+    if (slot >= S.sub) slot -= S.sub;
+    return S.x + (base + slot) * FR;
 }
 
 // Staging of frames k0 .. k0+NF-1 of sample n as bf16 into xin[(k-k0)*FR ...], in two halves so
@@ -936,15 +945,16 @@ __device__ __forceinline__ void strip_load(StripRaw &R, const Src &S, int g, int
 {
     const uint8_t *base;
     bool contig = true;
-    long b = 0;
+    long b = 0, rb = 0;                           // first frame's slot within its sub-ring; the sub-ring's first slot
     if (!S.idx) {
         base = S.x + (long)g * S.xs;
     } else {
         long i = __builtin_amdgcn_readfirstlane(slot_g);
         i = i < 0 ? 0 : (i >= S.cap ? S.cap - 1 : i);
-        b = i - 3 + S.shift;                      // slot of the first frame, within [-3, cap - 2]
-        contig = b >= 0 && b + 3 < S.cap;
-        base = S.x + b * FR;
+        rb = sub_ring_base(S, i);
+        b = i - rb - 3 + S.shift;                 // within [-3, sub - 2]
+        contig = b >= 0 && b + 3 < S.sub;
+        base = S.x + (rb + b) * FR;
     }
     if (contig) {   // one scalar base, per-lane offsets that never change
         base += strip * (16 * 84);
@@ -957,9 +967,9 @@ __device__ __forceinline__ void strip_load(StripRaw &R, const Src &S, int g, int
             const int t = lane + 64 * i;
             if (t < CHUNKS) {
                 long slot = b + t / (CHUNKS / 4);
-                if (slot < 0) slot += S.cap;
-                if (slot >= S.cap) slot -= S.cap;
-                R.raw[i] = *reinterpret_cast<const u32x4 *>(S.x + slot * FR + strip * (16 * 84) + (t % (CHUNKS / 4)) * 16);
+                if (slot < 0) slot += S.sub;
+                if (slot >= S.sub) slot -= S.sub;
+                R.raw[i] = *reinterpret_cast<const u32x4 *>(S.x + (rb + slot) * FR + strip * (16 * 84) + (t % (CHUNKS / 4)) * 16);
             }
         }
     }

@@ -580,6 +580,68 @@ __global__ void k_tree_level(float *tree, long first, long count)
     tree[node] = tree[2 * node] + tree[2 * node + 1];
 }
 
+// Rebuild of the internal nodes from the leaves, 12 levels per launch: the tree over Lcur leaves
+// (leaves at tree[Lcur, 2 Lcur)) is cut into blocks of BL = min(Lcur, 4096) leaves; a workgroup loads
+// its block's leaves, forms the block's sub-tree in LDS level by level (node = left + right in fp32,
+// so every node has the bits any other order of repair gives) and writes its BL - 1 internal
+// nodes.  The block roots are the leaves of the tree one launch up: Lcur >> 12 of them.
+__global__ __launch_bounds__(256) void k_tree_rebuild(float *tree, long Lcur, int BL)
+{
+    __shared__ float t[2 * 4096];             // local heap: t[1] block root, leaves at t[BL, 2 BL)
+    const long b = blockIdx.x;                // block number
+    const long root = Lcur / BL + b;          // heap index of the block root
+    for (int i = threadIdx.x; i < BL; i += 256) t[BL + i] = tree[Lcur + b * BL + i];
+    for (int first = BL >> 1; first >= 1; first >>= 1) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < first; i += 256) t[first + i] = t[2 * (first + i)] + t[2 * (first + i) + 1];
+    }
+    __syncthreads();
+    // local node p at depth d (p in [2^d, 2^(d+1))) is heap node (root << d) + (p - 2^d)
+    for (int p = 1 + threadIdx.x; p < BL; p += 256) {
+        const int d = 31 - __clz(p);
+        tree[(root << d) + (p - (1 << d))] = t[p];
+    }
+}
+
+// Store path for many environment streams (Alg.1 "store transition", one emulator per stream): the
+// ring is E sub-rings of C slots, stream e owns slots [eC, (e+1)C); every call appends one time step
+// to every stream at local slot l = t mod C (t: time steps stored so far, the same for all).
+// grid (E): frame and transition data of stream e.
+__global__ __launch_bounds__(256) void k_replay_write_envs(uint8_t *frames, int32_t *meta_a, float *meta_r,
+                                                           uint8_t *meta_done, long C, long l,
+                                                           const uint8_t *src, const int32_t *a,
+                                                           const float *r, const uint8_t *done)
+{
+    const long e = blockIdx.x, slot = e * C + l;
+    const uint4 *s = reinterpret_cast<const uint4 *>(src + e * net::FRAME);
+    uint4 *d = reinterpret_cast<uint4 *>(frames + slot * net::FRAME);
+    for (int t = threadIdx.x; t < net::FRAME / 16; t += 256) d[t] = s[t];
+    if (threadIdx.x == 0) {
+        meta_a[slot] = a[e];
+        meta_r[slot] = r[e];
+        meta_done[slot] = done[e];
+    }
+}
+// One thread per stream: the leaves the new time step settles, by the rules of the one-stream store
+// path applied to the stream's own sub-ring (see k_store_priorities): the transition at local slot
+// l - 1 has just become complete and enters with leaf = fp32(max_p^alpha) unless its state stack
+// would reach back before the stream's start (t - 1 < 3) or across an episode end; the slot just
+// written and the three after it get leaf 0.  The internal nodes are rebuilt afterwards.
+__global__ __launch_bounds__(256) void k_store_leaves_envs(float *tree, long L, long C, long l, long t, int E,
+                                                           const uint8_t *done, float alpha)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= E) return;
+    const long base = (long)e * C;
+    auto at = [&](long k) { long q = (l + k) % C; if (q < 0) q += C; return base + q; };
+    if (t >= 1) {
+        bool valid = t - 1 >= 3;
+        for (int k = 2; k <= 4; ++k)
+            if (done[at(-k)]) valid = false;
+        tree[L + at(-1)] = valid ? (float)pow((double)tree[2 * L], (double)alpha) : 0.f;
+    }
+    for (int k = 0; k < 4; ++k) tree[L + at(k)] = 0.f;
+}
 
 __global__ __launch_bounds__(256) void k_per_sample(SampleArgs A)
 {
@@ -887,6 +949,16 @@ __global__ __launch_bounds__(256) void k_copy_out(CopyOutArgs A)
 }
 
 // --------------------------------------------------------------- replay
+// Slot `off` frames away from slot i (off in [-3, 1]), wrapping inside the sub-ring that i lies in:
+// the whole ring (sub == cap: one stream), or one environment stream's share of it.
+__device__ __forceinline__ long ring_slot(long i, long off, long cap, long sub)
+{
+    const long base = sub == cap ? 0 : (i / sub) * sub;
+    long l = (i - base + off) % sub;
+    if (l < 0) l += sub;
+    return base + l;
+}
+
 struct GatherArgs {
     const uint8_t *frames;  // ring [cap][7056]
     const int32_t *meta_a;
@@ -899,6 +971,7 @@ struct GatherArgs {
     int32_t *a;
     float *r;
     uint8_t *done;
+    long sub;            // length of the sub-ring a window wraps in (the capacity for one stream)
 };
 
 // Frame-stack gather: transition i reads ring slots i-3 .. i+1 (mod cap);
@@ -908,8 +981,7 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs A)
     const int j = blockIdx.x, k = blockIdx.y;
     long i = A.idx[j];
     i = i < 0 ? 0 : (i >= A.cap ? A.cap - 1 : i);  // keeps every access inside the ring
-    long slot = (i - 3 + k) % A.cap;
-    if (slot < 0) slot += A.cap;
+    const long slot = ring_slot(i, k - 3, A.cap, A.sub);
     const uint4 *src = reinterpret_cast<const uint4 *>(A.frames + slot * net::FRAME);
     uint4 *d0 = A.stack5 ? reinterpret_cast<uint4 *>(A.stack5 + ((long)j * 5 + k) * net::FRAME) : nullptr;
     uint4 *d1 = (A.s && k < 4) ? reinterpret_cast<uint4 *>(A.s + ((long)j * 4 + k) * net::FRAME) : nullptr;
@@ -945,8 +1017,7 @@ __global__ __launch_bounds__(256) void k_sample_gather(SampleArgs S, GatherArgs 
     }
     __syncthreads();
     const long i = slot_sh;
-    long slot = (i - 3 + k) % A.cap;
-    if (slot < 0) slot += A.cap;
+    const long slot = ring_slot(i, k - 3, A.cap, A.sub);
     const uint4 *src = reinterpret_cast<const uint4 *>(A.frames + slot * net::FRAME);
     uint4 *d0 = reinterpret_cast<uint4 *>(A.stack5 + ((long)j * 5 + k) * net::FRAME);
     for (int t = threadIdx.x; t < net::FRAME / 16; t += 256) d0[t] = src[t];

@@ -58,6 +58,8 @@ struct SampleArgs {
     float *is_w;
     MetaGather G;
     int uniform;   // 1: every stored slot has leaf 1 (priority exponent 0, tree built by a bulk fill): no tree reads
+    long limit;    // slots that may hold a transition are [0, limit): `size` for one stream; with many
+                   // environment streams the stored transitions are not the first `size` slots
 };
 
 // The mass the draws are scaled by: the root of the tree; in uniform mode the number of stored slots
@@ -73,7 +75,7 @@ __device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, i
     if (A.uniform) {
         // a tree whose stored leaves are all 1 holds exact integers, and its descent returns floor(z)
         long slot = (long)z;
-        return slot > A.size - 1 ? A.size - 1 : slot;
+        return slot > A.limit - 1 ? A.limit - 1 : slot;
     }
     long node = 1;
     const int lj = lane >= 2 ? 31 - __clz(lane) : 0;  // level of local heap node `lane`
@@ -98,7 +100,7 @@ __device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, i
         done += r;
     }
     long slot = node - A.L;
-    if (slot > A.size - 1) slot = A.size - 1;
+    if (slot > A.limit - 1) slot = A.limit - 1;
     return slot;
 }
 
@@ -119,8 +121,8 @@ __device__ __forceinline__ void per_sample_descend2(const SampleArgs &A, int j0,
     if (A.uniform) {
         slot0 = (long)z[0];
         slot1 = (long)z[1];
-        if (slot0 > A.size - 1) slot0 = A.size - 1;
-        if (slot1 > A.size - 1) slot1 = A.size - 1;
+        if (slot0 > A.limit - 1) slot0 = A.limit - 1;
+        if (slot1 > A.limit - 1) slot1 = A.limit - 1;
         return;
     }
     const int lj = lane >= 2 ? 31 - __clz(lane) : 0;
@@ -152,8 +154,8 @@ __device__ __forceinline__ void per_sample_descend2(const SampleArgs &A, int j0,
     }
     slot0 = node[0] - A.L;
     slot1 = node[1] - A.L;
-    if (slot0 > A.size - 1) slot0 = A.size - 1;
-    if (slot1 > A.size - 1) slot1 = A.size - 1;
+    if (slot0 > A.limit - 1) slot0 = A.limit - 1;
+    if (slot1 > A.limit - 1) slot1 = A.limit - 1;
 }
 
 // What one lane writes for draw j once the slot is known: index, raw weight, transition data.

@@ -19,7 +19,7 @@ EXPORTS = ["dqn_query_sizes", "dqn_init", "dqn_act", "dqn_train_step", "per_samp
            "per_fill", "dqn_replay_write", "dqn_replay_gather", "dqn_sync_target", "dqn_get_params",
            "dqn_set_params", "dqn_profile_begin", "dqn_profile_end", "dqn_last_error", "dqn_destroy",
            "dqn_replay_store", "dqn_replay_state", "dqn_schedule_default", "dqn_schedule_at", "dqn_preprocess",
-           "dqn_get_activations", "dqn_act_static", "dqn_selftest_fused_conv_schedule"]
+           "dqn_get_activations", "dqn_act_static", "dqn_selftest_fused_conv_schedule", "dqn_replay_store_envs"]
 
 
 class DqnConfig(C.Structure):
@@ -105,6 +105,7 @@ def lib():
             "dqn_replay_write": [vp, i64, i64, vp, vp, vp, vp, vp],
             "dqn_replay_gather": [vp, vp, i32, vp, vp, vp, vp, vp, vp],
             "dqn_replay_store": [vp, i64, vp, vp, vp, vp, vp],
+            "dqn_replay_store_envs": [vp, i32, vp, vp, vp, vp, vp],
             "dqn_replay_state": [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)],
             "dqn_preprocess": [vp, i64, i32, i32, vp, vp, vp],
             "dqn_schedule_default": [C.POINTER(DqnSchedule)],
@@ -272,6 +273,11 @@ class Dqn:
     def replay_store(self, frames, a, r, done):
         self._check(lib().dqn_replay_store(self._h, frames.shape[0], _ptr(frames), _ptr(a), _ptr(r), _ptr(done),
                                            _stream()))
+
+    def replay_store_envs(self, frames, a, r, done):
+        """One time step for each of frames.shape[0] environment streams."""
+        self._check(lib().dqn_replay_store_envs(self._h, frames.shape[0], _ptr(frames), _ptr(a), _ptr(r), _ptr(done),
+                                                _stream()))
 
     def replay_state(self):
         """(next slot, stored count, time steps stored so far)"""

@@ -901,6 +901,95 @@ def test_store_path_parity(dq, orc):
     m.close()
 
 
+@pytest.mark.parametrize("prec,E,C,steps", [(0, 37, 40, 100), (1, 64, 16, 45), (1, 2048, 24, 30)])
+def test_store_path_many_environment_streams(dq, orc, prec, E, C, steps):
+    """Alg.1's store line with one emulator per stream: E sub-rings of C slots, one time step per
+    stream and call.  The oracle's one-stream store runs once per stream on a ring of C slots; the
+    leaves of stream e are slots eC .. eC+C-1 of the library's tree, whose every node is compared bit
+    for bit (node = left + right).  Draws return whole transitions of one stream (the five frames
+    read back are the ones that stream stored, also where the window wraps inside its sub-ring),
+    N of Eq.12 is the number of stored transitions, and a training step on the stored data is held
+    against the oracle like any other."""
+    print("case store many streams", prec, E, C, steps, flush=True)
+    K, B = 18, 48
+    cap = E * C + 7                      # the last 7 slots belong to no stream
+    cfgd = CONFIGS["dueling_ddqn"]
+    alpha = float(np.float32(0.6))
+    m = dq.Dqn(dq.make_config(replay_capacity=cap, max_batch=B, precision=prec, **cfgd))
+    refs = [orc.ReplayState(C, alpha) for _ in range(E)]
+    L = m.L
+    ee = torch.arange(E)
+
+    def frame_id(e, t):
+        return e * 4096 + t
+
+    def ref_tree():
+        t = np.zeros(2 * L, np.float32)
+        for e, r in enumerate(refs):
+            t[L + e * C:L + (e + 1) * C] = r.tree[r.L:r.L + C]
+        for i in range(L - 1, 0, -1):
+            t[i] = t[2 * i] + t[2 * i + 1]
+        return t
+
+    max_p = 1.0
+    for t in range(steps):
+        fr = synth.frames(21, (frame_id(ee, t)).cuda(), device="cuda")
+        a = synth.actions(40, E, K, "cuda", first=t * E)
+        r = synth.rewards(41, E, "cuda", first=t * E)
+        d = synth.dones(42, E, 0.07, "cuda", first=t * E)
+        m.replay_store_envs(fr, a, r, d)
+        dn = d.cpu().numpy()
+        for e, rf in enumerate(refs):
+            rf.max_p = max_p
+            rf.store(dn[e:e + 1])
+        if t in (0, 3, 4, 5, C - 1, C, C + 3, steps // 2, steps - 1):
+            assert np.array_equal(m.tree.cpu().numpy()[1:], ref_tree()[1:]), t
+        if t == steps // 2:   # priorities move; later stores enter with the raised maximum
+            tr = ref_tree()
+            n_st = E * min(t + 1, C)
+            idx_ref, w_ref, _ = orc.per_sample(tr, n_st, B, 0.4, 17, limit=E * C)
+            idx, w = m.per_sample(B, 0.4, 17)
+            assert np.array_equal(idx.cpu().numpy(), idx_ref) and relerr(w.cpu().numpy(), w_ref) <= TOL
+            td = (0.5 + 3.0 * synth.u24(77, torch.arange(B))).cuda()
+            m.per_update(idx, td)
+            max_p = orc.per_update(tr, E * C, idx_ref, td.cpu().numpy(), alpha, float(np.float32(1e-6)), max_p)
+            assert float(m.max_priority) == np.float32(max_p)
+            for e, rf in enumerate(refs):
+                rf.tree[rf.L:rf.L + C] = tr[L + e * C:L + (e + 1) * C]
+                for i in range(rf.L - 1, 0, -1):
+                    rf.tree[i] = rf.tree[2 * i] + rf.tree[2 * i + 1]
+    assert m.replay_state()[1] == E * min(steps, C) and m.replay_state()[2] == steps
+    # a training step on what was stored, drawn by the step itself
+    p = synth.he_uniform_params(1804, K, 1); pt = synth.he_uniform_params(5834, K, 1)
+    m.set_params(0, torch.from_numpy(p)); m.set_params(1, torch.from_numpy(pt)); m.set_params(3, torch.zeros(p.size))
+    tr = ref_tree()
+    n_st = E * min(steps, C)
+    for seed in (5, 6, 7):
+        idx_ref, w_ref, z = orc.per_sample(tr, n_st, B, 0.4, seed, limit=E * C)
+        _, dist = orc.per_sample_cumsum(tr, E * C, z)
+        if np.all(dist > TOL * tr[1]):
+            break
+    out = m.train_step(B, None, beta=0.4, draw_seed=seed)
+    assert np.array_equal(out["idx"].cpu().numpy(), idx_ref) and relerr(out["is_w"].cpu().numpy(), w_ref) <= TOL
+    # the stream position each drawn slot holds, and the frames its window must read
+    e_of, l_of = idx_ref // C, idx_ref % C
+    q = l_of + ((steps - 1 - l_of) // C) * C            # latest time step written to local slot l
+    assert np.all(q + 1 <= steps - 1) and np.all(q - 3 >= max(0, steps - C))
+    ids = (e_of[:, None].astype(np.int64) * 4096 + (q[:, None] - 3 + np.arange(5)[None, :])).reshape(-1)
+    want = synth.frames(21, torch.from_numpy(ids)).reshape(B, 5, 84, 84)
+    s_g, sn_g, a_g, r_g, d_g = m.replay_gather(out["idx"])
+    assert torch.equal(s_g.cpu(), want[:, :4]) and torch.equal(sn_g.cpu(), want[:, 1:])
+    assert (l_of < 3).any() or C > 30, "no drawn window wraps inside its sub-ring: lengthen the run"
+    bnp = (want[:, :4].contiguous().numpy(), want[:, 1:].contiguous().numpy(), a_g.cpu().numpy(), r_g.cpu().numpy(), d_g.cpu().numpy())
+    tol = TOL_BF16 if prec else TOL
+    ref = _oracle_step(orc, cfgd, p, pt, bnp, w_ref, quant=prec)
+    ref64 = _oracle_step(orc, cfgd, p, pt, bnp, w_ref) if prec else None
+    _check_step(orc, out, ref, p, m, K, 1, bnp, w_ref, tol, ref_full=ref64)
+    with pytest.raises(dq.DqnError):
+        m.replay_store_envs(fr[:E - 1], a, r, d)         # the number of streams is fixed
+    m.close()
+
+
 @pytest.mark.parametrize("H,W,use_lut", [(210, 160, True), (84, 84, False), (100, 333, True)])
 def test_preprocess_parity(dq, orc, H, W, use_lut):
     """Sec.3 preprocessing: bytes equal the oracle's, except where the oracle's unrounded value

@@ -170,6 +170,29 @@ def test_importance_weights(orc):
     assert np.all(np.diff(w[order]) <= 1e-7)
 
 
+def test_stored_transitions_need_not_be_the_first_slots(orc):
+    """Many environment streams keep their transitions in sub-rings: the N of Eq.12 (stored
+    transitions) and the range of slots that may hold one are then different numbers."""
+    L, beta = 64, 0.4
+    raw = np.zeros(64, np.float32)
+    raw[10:20] = synth.exp_priorities(1, 10).numpy()
+    raw[40:50] = synth.exp_priorities(2, 10).numpy()
+    tree = orc.tree_build(raw, L, 1.0)
+    idx, w, z = orc.per_sample(tree, 20, 256, beta, 5, limit=64)
+    assert np.all(((idx >= 10) & (idx < 20)) | ((idx >= 40) & (idx < 50))) and (idx >= 40).any() and (idx < 20).any()
+    P = tree[L + idx].astype(np.float64) / float(tree[1])
+    rawr = (20 * P) ** -beta
+    assert np.allclose(w, rawr / rawr.max(), rtol=1e-6)
+    ref, dist = orc.per_sample_cumsum(tree, 64, z)
+    far = dist > 1e-5 * tree[1]
+    assert np.array_equal(idx[far], ref[far])
+    # with limit = N (one stream) nothing changes
+    t2 = orc.tree_build(synth.exp_priorities(3, 20).numpy(), L, 1.0)
+    a = orc.per_sample(t2, 20, 64, beta, 6)
+    b = orc.per_sample(t2, 20, 64, beta, 6, limit=20)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
 def test_empty_tree_is_an_error(orc):
     t = orc.tree_build(np.zeros(0, np.float32), 8, 0.6)
     with pytest.raises(ValueError):
