@@ -46,12 +46,15 @@ class Catch:
 
 
 def run(env_steps, seed=0, capacity=20000, batch=32, precision=0, learning_start=1000, update_period=2,
-        target_period=500, eps_steps=15000, lr=2.5e-4, eval_episodes=100, log=None):
+        target_period=500, eps_steps=15000, lr=2.5e-4, eval_episodes=100, log=None, dueling=1, per_alpha=0.6,
+        curve=None):
     """Trains for env_steps environment steps; returns (mean reward per episode of a near-greedy
-    evaluation with Table 1's test epsilon 0.001, mean reward of the first 100 training episodes)."""
-    m = dqn.Dqn(dqn.make_config(num_actions=K, dueling=1, double_q=1, precision=precision, loss_kind=1,
+    evaluation with Table 1's test epsilon 0.001, mean reward of the first 100 training episodes).
+    dueling / per_alpha select the model setting (Sec.4: plain or dueling head, uniform replay =
+    exponent 0 or prioritized replay).  curve: a list that receives the reward of every training episode."""
+    m = dqn.Dqn(dqn.make_config(num_actions=K, dueling=dueling, double_q=1, precision=precision, loss_kind=1,
                                 lr=lr, max_batch=batch, max_act_batch=1, replay_capacity=capacity,
-                                per_alpha=0.6, per_eps=1e-3, seed=1804 + seed, target_seed=5834 + seed))
+                                per_alpha=per_alpha, per_eps=1e-3, seed=1804 + seed, target_seed=5834 + seed))
     m.sync_target()
     sc = dqn.schedule_default()
     sc.learning_start, sc.update_period, sc.target_period = learning_start, update_period, target_period
@@ -94,12 +97,44 @@ def run(env_steps, seed=0, capacity=20000, batch=32, precision=0, learning_start
                 break
             obs = torch.cat([obs[:, 1:], ev.frame()[None, None]], dim=1).contiguous()
     m.close()
+    if curve is not None:
+        curve.extend(returns)
     early = sum(returns[:100]) / max(1, len(returns[:100]))
     return total / eval_episodes, early
 
 
+SETTINGS = (("double DQN", 0, 0.0), ("dueling double DQN", 1, 0.0),
+            ("double DQN with prioritized replay", 0, 0.6),
+            ("dueling double DQN with prioritized replay", 1, 0.6))
+
+
+def sweep(env_steps=20000, seeds=(0, 1, 2), log=print):
+    """The four model settings of the paper's performance comparison (Sec.4) on the toy environment:
+    per setting and seed the near-greedy evaluation reward after env_steps steps and the mean reward
+    over all training episodes (the area under the learning curve, which separates settings that all
+    end near the ceiling)."""
+    table = []
+    for name, dueling, alpha in SETTINGS:
+        finals, areas = [], []
+        for seed in seeds:
+            curve = []
+            final, _ = run(env_steps, seed=seed, update_period=1, target_period=1000, dueling=dueling,
+                           per_alpha=alpha, curve=curve)
+            finals.append(final)
+            areas.append(sum(curve) / max(1, len(curve)))
+            log("%-44s seed %d: evaluation %.2f, mean training reward %.3f" % (name, seed, final, areas[-1]))
+        table.append((name, sum(finals) / len(finals), sum(areas) / len(areas), finals, areas))
+    log("setting | mean evaluation reward | mean training reward (area under the curve)")
+    for name, f, a, _, _ in table:
+        log("%-44s | %.3f | %.3f" % (name, f, a))
+    return table
+
+
 if __name__ == "__main__":
     import sys
-    steps = int(sys.argv[1]) if len(sys.argv) > 1 else 30000
-    final, early = run(steps, log=lambda s: print(s, flush=True))
-    print("evaluation: mean reward per episode %.2f (first 100 training episodes: %.2f)" % (final, early))
+    if len(sys.argv) > 1 and sys.argv[1] == "sweep":
+        sweep(int(sys.argv[2]) if len(sys.argv) > 2 else 20000)
+    else:
+        steps = int(sys.argv[1]) if len(sys.argv) > 1 else 30000
+        final, early = run(steps, log=lambda s: print(s, flush=True))
+        print("evaluation: mean reward per episode %.2f (first 100 training episodes: %.2f)" % (final, early))

@@ -20,3 +20,16 @@ def test_catch_is_learned(precision):
     print("  evaluation %.2f, first 100 training episodes %.2f" % (final, early), flush=True)
     assert early < 0.0
     assert final >= 0.5
+
+
+def test_every_model_setting_runs_the_agent_loop():
+    """The four settings of the paper's comparison (plain / dueling head, uniform / prioritized
+    replay) through the whole loop, store path included (with exponent 0 the store path's zero
+    leaves send the draws through the tree): a short run each, finite and above the floor."""
+    from paper_1804_05834_amd import dqn, toy_catch
+    dqn.lib()
+    for name, dueling, alpha in toy_catch.SETTINGS:
+        final, early = toy_catch.run(4000, seed=3, dueling=dueling, per_alpha=alpha, update_period=1,
+                                     target_period=500, eval_episodes=30)
+        print("  %s: evaluation %.2f" % (name, final), flush=True)
+        assert -1.0 <= final <= 1.0 and -1.0 <= early <= 1.0
