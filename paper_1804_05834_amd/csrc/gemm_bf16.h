@@ -95,7 +95,10 @@ __device__ __forceinline__ uint4 ld8(const uint8_t *p)  // 8 pixels -> 8 bf16 (e
 // across it (__syncthreads() would wait for all of them first).
 __device__ __forceinline__ void sync_lds()
 {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // written with the builtins so that the compiler's own wait counting knows that every LDS operation
+    // of the wave has completed here (behind an inline-asm barrier it waits for all of them again)
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
 }
 
 __device__ __forceinline__ v8bf frag_k(const bf16_t *p)  // 8 consecutive k of one row
