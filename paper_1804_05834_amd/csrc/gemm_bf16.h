@@ -431,20 +431,26 @@ __global__ __launch_bounds__(256, 2) void k_fc1_fwd(Args A)
         if (i + 1 < n) stage(i + 1, 1, R0);
     }
 
-    // acc[a][b][4g + j] = Y[row block a, lane li][column block b, 8g + 4h + j]
-    float *y = static_cast<float *>(S.y) + (long)bz * A.split_stride;
+    // acc[a][b][4g + j] = Y[row block a, lane li][column block b, 8g + 4h + j].  The tile leaves through LDS
+    // (the operand buffers are no longer read: the loop ends on a barrier), so that it is written as whole
+    // 512-byte rows, two per wave and instruction, instead of 32-byte pieces of 32 different rows.
+    constexpr int LDO = BN + 4;                   // fp32 row stride of the staged output tile
+    static_assert(BM * LDO * 4 <= LDS_BYTES, "the output tile is staged in the operand buffers");
+    float *ot = reinterpret_cast<float *>(lds);
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
-        const int m = m0 + (wm * 2 + a) * 32 + li;
-        if (m >= S.M) continue;
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = n0 + (wn * 2 + b) * 32 + 8 * g + 4 * h;
-                *reinterpret_cast<v4f *>(y + (long)m * GFc1::N + col) =
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<v4f *>(&ot[((wm * 2 + a) * 32 + li) * LDO + (wn * 2 + b) * 32 + 8 * g + 4 * h]) =
                     v4f{acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-            }
+    lds_barrier();
+    float *y = static_cast<float *>(S.y) + (long)bz * A.split_stride;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = (tid >> 5) + 8 * i, cq = (tid & 31) * 4, m = m0 + r;
+        if (m < S.M) *reinterpret_cast<v4f *>(y + (long)m * GFc1::N + n0 + cq) = *reinterpret_cast<const v4f *>(&ot[r * LDO + cq]);
     }
 }
 }  // namespace f1

@@ -295,13 +295,17 @@ CONFIGS = {
     "squared_centered": dict(num_actions=6, dueling=1, double_q=0, loss_kind=0, rms_centered=1),
     # Double DQN with the plain output layer (one of the settings of the paper's performance figure)
     "ddqn_plain": dict(num_actions=18, dueling=0, double_q=1, loss_kind=1),
+    # the most actions the library takes: 65 head rows, 195 dot products per training row
+    "wide": dict(num_actions=64, dueling=1, double_q=1, loss_kind=1),
+    "wide_plain": dict(num_actions=33, dueling=0, double_q=0, loss_kind=0),
 }
 
 
 @pytest.mark.parametrize("name,B,prec", [("dqn", 32, 0), ("dueling_ddqn", 32, 0), ("dueling_ddqn", 5, 0),
                                          ("dueling_ddqn", 67, 0), ("squared_centered", 33, 0), ("dqn", 1, 0),
                                          ("dueling_ddqn", 32, 1), ("dueling_ddqn", 67, 1), ("dqn", 130, 1),
-                                         ("squared_centered", 3, 1)])
+                                         ("squared_centered", 3, 1), ("wide", 9, 0), ("wide", 40, 1),
+                                         ("wide_plain", 6, 0)])
 def test_train_step_explicit_batch(dq, orc, name, B, prec):
     print("case train_step", name, B, prec, flush=True)
     cfgd = CONFIGS[name]
