@@ -1105,19 +1105,21 @@ __device__ __forceinline__ void conv1_fwd_units(const FwdSeg &S, int u0, int u1,
 __device__ __forceinline__ void draw_slots(const misc::SampleArgs &P, int n, int u0, int u1, int *slots, int lane,
                                            bool publish)
 {
-    const float total = misc::sample_total(P);
     const int gs0 = u0 / UNITS, gs1 = (u1 - 1) / UNITS;   // launch-wide sample numbers
 #pragma unroll 1
     for (int ga = gs0; ga <= gs1; ga += 2) {
         const int gb = ga + 1 <= gs1 ? ga + 1 : ga;
-        long s0, s1;
-        misc::per_sample_descend2(P, ga % n, gb % n, lane, total, s0, s1);
+        const int jj[2] = {ga % n, gb % n};
+        long sl[2];
+        float leaf[2];
+        const float total = misc::per_sample_walk<2>(P, jj, lane, sl, leaf);
         if (lane == 0) {
-            slots[ga - gs0] = (int)s0;
-            slots[gb - gs0] = (int)s1;
-            if (publish && ga < n && UNITS * ga >= u0) misc::per_sample_emit(P, ga, s0, total);
-            if (publish && gb < n && gb != ga) misc::per_sample_emit(P, gb, s1, total);
+            slots[ga - gs0] = (int)sl[0];
+            slots[gb - gs0] = (int)sl[1];
         }
+        // lanes 0 and 1 publish one draw each
+        if (lane == 0 && publish && ga < n && UNITS * ga >= u0) misc::per_sample_emit(P, ga, sl[0], total, leaf[0]);
+        if (lane == 1 && publish && gb < n && gb != ga) misc::per_sample_emit(P, gb, sl[1], total, leaf[1]);
     }
 }
 
@@ -1651,7 +1653,7 @@ constexpr int NRING = 3;                                    // conv1 images in L
 constexpr int MAX_PER_WG = 32;                              // samples one workgroup may own (slot table)
 constexpr int STRIPS_B = 4 * STRIP * 2;                     // 53,760 bytes: one strip per producer wave
 constexpr int RING_B = NRING * S2::SAMPLE;                  // 86,400 bytes
-constexpr int LDS_BYTES = STRIPS_B + RING_B + MAX_PER_WG * 4;
+constexpr int LDS_BYTES = STRIPS_B + RING_B + MAX_PER_WG * 8 + 16;   // + slot table, leaf values, total
 // The hand-over schedule, as functions the kernel's loops and the host-side check
 // (schedule_is_safe, behind dqn_selftest_fused_conv_schedule) both call.
 constexpr int PRODUCERS = 4;                                // producer waves: strips per interval
@@ -1858,28 +1860,38 @@ __global__ __launch_bounds__(512) void k_conv12_fwd(Args A)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    // The slots of the run: drawn here, two per wave and walk, or copied from the index list.
+    float *leafv = reinterpret_cast<float *>(slots + MAX_PER_WG);   // [MAX_PER_WG] leaf values, then the total
+
+    // The slots of the run: drawn here, two per wave and walk, or copied from the index list.  Nothing but
+    // the slot stands between a draw and the first pixel request, so the walk leaves the leaf's value and
+    // the total in LDS, and what is published per draw (publish_draws) is written after the barrier by a
+    // wave that has nothing else to do yet.
     auto fill_slots = [&]() {
         if (!S.src.idx) return;
         if (A.draw) {
-            const float total = misc::sample_total(A.samp);
 #pragma unroll 1
             for (int k = 2 * wave; k < ns; k += 16) {
                 const int kb = k + 1 < ns ? k + 1 : k;
-                long s0, s1;
-                misc::per_sample_descend2(A.samp, lo + k, lo + kb, lane, total, s0, s1);
+                const int jj[2] = {lo + k, lo + kb};
+                long sl[2];
+                float leaf[2];
+                const float total = misc::per_sample_walk<2>(A.samp, jj, lane, sl, leaf);
                 if (lane == 0) {
-                    slots[k] = (int)s0;
-                    slots[kb] = (int)s1;
-                    if (s == 0) {
-                        misc::per_sample_emit(A.samp, lo + k, s0, total);
-                        if (kb != k) misc::per_sample_emit(A.samp, lo + kb, s1, total);
-                    }
+                    slots[k] = (int)sl[0];
+                    slots[kb] = (int)sl[1];
+                    leafv[k] = leaf[0];
+                    leafv[kb] = leaf[1];
+                    if (k == 0) leafv[MAX_PER_WG] = total;
                 }
             }
         } else {
             for (int k = tid; k < ns; k += 512) slots[k] = S.src.idx[lo + k];
         }
+    };
+    // index, raw importance weight and transition data of the segment-0 draws, one draw per lane
+    auto publish_draws = [&]() {
+        if (S.src.idx && A.draw && s == 0 && lane < ns)
+            misc::per_sample_emit(A.samp, lo + lane, slots[lane], leafv[MAX_PER_WG], leafv[lane]);
     };
 
     if (wave >= 4) {
@@ -1896,6 +1908,7 @@ __global__ __launch_bounds__(512) void k_conv12_fwd(Args A)
             }
         fill_slots();
         sync_lds();   // the slot table is complete
+        if (wave == 4) publish_draws();   // the consumers wait for the first image anyway
         run_consumer(S, lo, hi, ring, wa, lane, ph, hh);
     } else {
         StripOff O;

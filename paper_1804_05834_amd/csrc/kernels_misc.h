@@ -648,9 +648,11 @@ __global__ __launch_bounds__(256) void k_per_sample(SampleArgs A)
     const int lane = threadIdx.x & 63;
     const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (j >= A.B) return;
-    const float total = sample_total(A);
-    const long slot = per_sample_descend(A, j, lane, total);
-    if (lane == 0) per_sample_emit(A, j, slot, total);
+    const int jj[1] = {j};
+    long slot[1];
+    float leaf[1];
+    const float total = per_sample_walk<1>(A, jj, lane, slot, leaf);
+    if (lane == 0) per_sample_emit(A, j, slot[0], total, leaf[0]);
 }
 
 // w_j <- w_j / max_j w_j over the minibatch (single workgroup)
@@ -1008,11 +1010,13 @@ __global__ __launch_bounds__(256) void k_sample_gather(SampleArgs S, GatherArgs 
     __shared__ long slot_sh;
     const int j = blockIdx.x, k = blockIdx.y;
     if (threadIdx.x < 64) {
-        const float total = sample_total(S);
-        const long slot = per_sample_descend(S, j, threadIdx.x, total);
+        const int jj[1] = {j};
+        long slot[1];
+        float leaf[1];
+        const float total = per_sample_walk<1>(S, jj, threadIdx.x, slot, leaf);
         if (threadIdx.x == 0) {
-            slot_sh = slot;
-            if (k == 0) per_sample_emit(S, j, slot, total);
+            slot_sh = slot[0];
+            if (k == 0) per_sample_emit(S, j, slot[0], total, leaf[0]);
         }
     }
     __syncthreads();

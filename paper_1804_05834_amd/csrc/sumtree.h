@@ -66,106 +66,95 @@ struct SampleArgs {
 // (the root of a tree of ones), without a memory access.
 __device__ __forceinline__ float sample_total(const SampleArgs &A) { return A.uniform ? (float)A.size : A.tree[1]; }
 
-// Draw j by one wave; every lane returns the slot.
-__device__ __forceinline__ long per_sample_descend(const SampleArgs &A, int j, int lane, float total)
+// Draws jj[0 .. ND) by one wave at once: the fetches of a round are issued together, so ND draws cost the
+// round trips of one.  Every lane returns the slots, the values of the leaves reached and (the function's
+// value) the mass the draws were scaled by.  Lane 1 of the first round reads the root along with the
+// subtree below it, and the leaf's value is the child chosen in the last step: neither the total nor the
+// leaf costs a memory round trip of its own.
+template <int ND>
+__device__ __forceinline__ float per_sample_walk(const SampleArgs &A, const int (&jj)[ND], int lane, long (&slot)[ND],
+                                                 float (&leaf)[ND])
 {
-    const float *tree = A.tree;
-    const float u = draw_u24(A.seed, (uint64_t)j);
-    float z = A.stratified ? __fmul_rn((float)j + u, total / (float)A.B) : __fmul_rn(u, total);
+    auto mass = [&](int j, float total) {
+        const float u = draw_u24(A.seed, (uint64_t)j);
+        return A.stratified ? __fmul_rn((float)j + u, total / (float)A.B) : __fmul_rn(u, total);
+    };
     if (A.uniform) {
         // a tree whose stored leaves are all 1 holds exact integers, and its descent returns floor(z)
-        long slot = (long)z;
-        return slot > A.limit - 1 ? A.limit - 1 : slot;
+        const float total = sample_total(A);
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+            const long sl = (long)mass(jj[d], total);
+            slot[d] = sl > A.limit - 1 ? A.limit - 1 : sl;
+            leaf[d] = 1.f;
+        }
+        return total;
     }
-    long node = 1;
-    const int lj = lane >= 2 ? 31 - __clz(lane) : 0;  // level of local heap node `lane`
+    const float *tree = A.tree;
+    float total = 0.f, z[ND];
+    long node[ND];
+#pragma unroll
+    for (int d = 0; d < ND; ++d) { node[d] = 1; z[d] = 0.f; leaf[d] = 0.f; }
+    if (A.levels == 0) {   // a tree of one leaf
+        total = tree[1];
+#pragma unroll
+        for (int d = 0; d < ND; ++d) leaf[d] = total;
+    }
+    const int lj = lane >= 1 ? 31 - __clz(lane) : 0;  // level of local heap node `lane`
     for (int done = 0; done < A.levels;) {
         const int r = min(6, A.levels - done);  // levels walked in this round
-        float va = 0.f, vb = 0.f;
-        if (lane >= 2 && lane < (2 << min(r, 5))) va = tree[(node << lj) + (lane - (1 << lj))];
-        if (r == 6) vb = tree[(node << 6) + lane];
-        int cur = 1;  // local heap index
-        for (int t = 0; t < r; ++t) {
-            const int c = 2 * cur;  // left child
-            const float left = c < 64 ? __shfl(va, c, 64) : __shfl(vb, c - 64, 64);
-            const float right = c < 64 ? __shfl(va, c + 1, 64) : __shfl(vb, c - 63, 64);
-            if (z < left || right == 0.f) {   // nothing on the right: a zero leaf is never drawn
-                cur = c;
-            } else {
-                z = z - left;
-                cur = c + 1;
-            }
-        }
-        node = (node << r) + (cur - (1 << r));
-        done += r;
-    }
-    long slot = node - A.L;
-    if (slot > A.limit - 1) slot = A.limit - 1;
-    return slot;
-}
-
-// Draws j0 and j1 by one wave at once: the same walk as above for each, with the two fetches of a
-// round issued together, so the pair costs the four round trips of one.
-__device__ __forceinline__ void per_sample_descend2(const SampleArgs &A, int j0, int j1, int lane, float total,
-                                                    long &slot0, long &slot1)
-{
-    const float *tree = A.tree;
-    const int jj[2] = {j0, j1};
-    float z[2];
-    long node[2] = {1, 1};
+        float va[ND], vb[ND];
 #pragma unroll
-    for (int d = 0; d < 2; ++d) {
-        const float u = draw_u24(A.seed, (uint64_t)jj[d]);
-        z[d] = A.stratified ? __fmul_rn((float)jj[d] + u, total / (float)A.B) : __fmul_rn(u, total);
-    }
-    if (A.uniform) {
-        slot0 = (long)z[0];
-        slot1 = (long)z[1];
-        if (slot0 > A.limit - 1) slot0 = A.limit - 1;
-        if (slot1 > A.limit - 1) slot1 = A.limit - 1;
-        return;
-    }
-    const int lj = lane >= 2 ? 31 - __clz(lane) : 0;
-    for (int done = 0; done < A.levels;) {
-        const int r = min(6, A.levels - done);
-        float va[2] = {0.f, 0.f}, vb[2] = {0.f, 0.f};
-#pragma unroll
-        for (int d = 0; d < 2; ++d) {
-            if (lane >= 2 && lane < (2 << min(r, 5))) va[d] = tree[(node[d] << lj) + (lane - (1 << lj))];
+        for (int d = 0; d < ND; ++d) {
+            va[d] = vb[d] = 0.f;
+            if (lane >= (done ? 2 : 1) && lane < (2 << min(r, 5))) va[d] = tree[(node[d] << lj) + (lane - (1 << lj))];
             if (r == 6) vb[d] = tree[(node[d] << 6) + lane];
         }
+        if (done == 0) {
+            total = __shfl(va[0], 1, 64);
 #pragma unroll
-        for (int d = 0; d < 2; ++d) {
-            int cur = 1;
+            for (int d = 0; d < ND; ++d) z[d] = mass(jj[d], total);
+        }
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+            int cur = 1;  // local heap index
             for (int t = 0; t < r; ++t) {
-                const int c = 2 * cur;
+                const int c = 2 * cur;  // left child
                 const float left = c < 64 ? __shfl(va[d], c, 64) : __shfl(vb[d], c - 64, 64);
                 const float right = c < 64 ? __shfl(va[d], c + 1, 64) : __shfl(vb[d], c - 63, 64);
-                if (z[d] < left || right == 0.f) {
+                if (z[d] < left || right == 0.f) {   // nothing on the right: a zero leaf is never drawn
                     cur = c;
+                    leaf[d] = left;
                 } else {
                     z[d] = z[d] - left;
                     cur = c + 1;
+                    leaf[d] = right;
                 }
             }
             node[d] = (node[d] << r) + (cur - (1 << r));
         }
         done += r;
     }
-    slot0 = node[0] - A.L;
-    slot1 = node[1] - A.L;
-    if (slot0 > A.limit - 1) slot0 = A.limit - 1;
-    if (slot1 > A.limit - 1) slot1 = A.limit - 1;
+#pragma unroll
+    for (int d = 0; d < ND; ++d) {
+        slot[d] = node[d] - A.L;
+        if (slot[d] > A.limit - 1) {   // not reached while the tree has mass: slots past the limit hold zero leaves
+            slot[d] = A.limit - 1;
+            leaf[d] = tree[A.L + slot[d]];
+        }
+    }
+    return total;
 }
 
-// What one lane writes for draw j once the slot is known: index, raw weight, transition data.
-__device__ __forceinline__ void per_sample_emit(const SampleArgs &A, int j, long slot, float total)
+// What one lane writes for draw j once the walk has ended: index, raw weight (from the leaf's value and
+// the total the walk returned), transition data.
+__device__ __forceinline__ void per_sample_emit(const SampleArgs &A, int j, long slot, float total, float leaf)
 {
     A.idx[j] = (int32_t)slot;
     if (A.uniform) {
         A.is_w[j] = 1.f;   // (N * 1/N)^-beta
     } else {
-        const double P = (double)A.tree[A.L + slot] / (double)total;
+        const double P = (double)leaf / (double)total;
         // a tree without mass (every stored transition has priority zero) has nothing to draw: weight 0
         A.is_w[j] = total > 0.f ? (float)pow((double)A.size * P, -(double)A.beta) : 0.f;
     }
