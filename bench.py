@@ -89,9 +89,9 @@ def gemm_bytes_per_launch(B, R, bf16):
 MEASURED_TRAFFIC = {
     ("conv12_fwd", 512, "bf16"): 46.0e6 + 28.7e6,
     ("conv3_fwd", 512, "bf16"): 16.8e6 + 9.5e6,
-    ("fc1_fwd", 512, "bf16"): 19.9e6 + 21.7e6,
-    ("head_train", 512, "bf16"): 22.4e6 + 1.6e6,
-    ("fc1_bwd", 512, "bf16"): 13.4e6 + 9.6e6,
+    ("fc1_fwd", 512, "bf16"): 19.6e6 + 12.4e6,
+    ("head_train", 512, "bf16"): 13.2e6 + 1.7e6,
+    ("fc1_bwd", 512, "bf16"): 13.5e6 + 9.6e6,
     ("conv3_bwd", 512, "bf16"): 9.9e6 + 11.2e6,
     ("conv2_bwd", 512, "bf16"): 36.2e6 + 20.6e6,
     ("conv1_wgrad", 512, "bf16"): 27.1e6 + 8.3e6,
