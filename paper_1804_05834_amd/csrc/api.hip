@@ -166,6 +166,7 @@ struct dqn_ctx {
     // INT_MAX: never (the launch needs 140 KB of LDS per workgroup, granted at initialisation)
     int conv12_min = INT32_MAX;
     // bf16: fc1 forward as 128 x 128 tiles (gbf::f1) from this many rows per launch on; needs 72 KB of LDS
+    bool fused_bwd = false;   // conv2's input gradient and conv1's weight gradient in one workgroup per sample
     bool fc1_big = false;
     int fc1_big_rows = 512, fc1_big_splits = 0;
     hipStream_t side = nullptr;
@@ -894,6 +895,20 @@ __global__ __launch_bounds__(256, 2) void k_conv2_bwd_pu(gbf::dps::Args PA, gbf:
     else wgrad_tile<GConv2, 64, 64, 1, 1, true>(WA, tile_of(id - nps, nw), wgx, wgy, wgz, reinterpret_cast<bf16_t *>(lds));
 }
 
+// conv2's launch with conv1's weight gradient inside the per-sample workgroups (dps::conv2_dgrad_conv1_wgrad_body):
+// workgroup 0 as above, nps workgroups of samples, nw weight-gradient tiles.  Dynamic LDS: dps::FUSED_LDS.
+__global__ __launch_bounds__(256, 2) void k_conv21_bwd_pu(gbf::dps::FusedArgs FA, gbf::WgradArgs WA, int nps, int nw, int wgx,
+                                                          int wgy, int wgz, SplitUpdate U)
+{
+    using namespace gbf;
+    static_assert(dps::FUSED_LDS >= wgrad_lds<64, 64, true>() * 2 && dps::FUSED_LDS >= misc::PU_LDS_WORDS * 4, "LDS");
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
+    if (U.on && blockIdx.x == 0) return update_part(U, 2, reinterpret_cast<int *>(lds_dyn));
+    const int id = (int)blockIdx.x - U.on;
+    if (id < nps) dps::conv2_dgrad_conv1_wgrad_body(FA, id, nps, lds_dyn);
+    else wgrad_tile<GConv2, 64, 64, 1, 1, true>(WA, tile_of(id - nps, nw), wgx, wgy, wgz, reinterpret_cast<bf16_t *>(lds_dyn));
+}
+
 // bf16: one stream and one launch per layer, the layer's input gradient and weight gradient side by
 // side in it (both read the layer's dY and nothing else that the backward pass computes).  Events
 // between streams cost more than they gain here: a record or a wait on the critical stream adds
@@ -932,7 +947,18 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
         dps::Args P{d2, sh + net::C2W, act1, d1, B};
         split_rows((long)B * 81, 8, MAX_WSPLIT, 64, &rps, ns2);
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
-        const int nps = std::min(B, c->num_cu), nw = 8 * *ns2, gz = *ns2;
+        const int nw = 8 * *ns2, gz = *ns2;
+        if (c->fused_bwd) {
+            // conv1's weight gradient inside the per-sample workgroups: one partial per workgroup
+            const int nps = std::min({B, c->num_cu, MAX_WSPLIT1});
+            dps::FusedArgs F{P, c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift, (int)c->sub}, w.gp1};
+            launch(c, "conv2_bwd", st, [&] {
+                k_conv21_bwd_pu<<<nps + nw + U.on, 256, dps::FUSED_LDS, st>>>(F, G, nps, nw, 8, 1, gz, U);
+            });
+            *ns1 = nps;
+            return;
+        }
+        const int nps = std::min(B, c->num_cu);
         launch(c, "conv2_bwd", st, [&] { k_conv2_bwd_pu<<<nps + nw + U.on, 256, 0, st>>>(P, G, nps, nw, 8, 1, gz, U); });
     }
     {   // conv1: one workgroup per split of samples, frames staged in LDS
@@ -1064,6 +1090,15 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
                             gbf::c12::LDS_BYTES) == hipSuccess) {
         const char *m = std::getenv("DQN_CONV12_MIN_SAMPLES");
         c->conv12_min = m && m[0] ? std::atoi(m) : 8;
+    } else {
+        (void)hipGetLastError();
+    }
+    // DQN_FUSED_BWD=0 in the environment keeps conv1's weight gradient a launch of its own
+    if (cfg->precision == 1 &&
+        hipFuncSetAttribute((const void *)k_conv21_bwd_pu, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            gbf::dps::FUSED_LDS) == hipSuccess) {
+        const char *m = std::getenv("DQN_FUSED_BWD");
+        c->fused_bwd = !(m && m[0] == '0');
     } else {
         (void)hipGetLastError();
     }

@@ -1343,7 +1343,7 @@ __device__ __forceinline__ void conv1_wgrad_block(const WgradArgs &A, int tile, 
     const int xoff = (kc >> 6) * FR + ((kc >> 3) & 7) * 84 + (kc & 7);
     const bf16_t *yp = dys + rsub * LDY1 + 16 * half + 4 * (s16 & 3);
 
-    v16f acc = {0}, acc2 = {0}, accb = {0};
+    v16f acc = {0}, accb = {0};
     v8bf ones;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
@@ -1376,9 +1376,9 @@ __device__ __forceinline__ void conv1_wgrad_block(const WgradArgs &A, int tile, 
             load_sample(n + A.nsplit, slot_next);  // in flight during the MFMA loop
             if (n + 2 * A.nsplit < A.B) slot_next = sample_slot(A.src, n + 2 * A.nsplit);
         }
-#pragma unroll 6
-        for (int t = 0; t < 25; ++t) {  // 16 output pixels per step
-            v8bf fa = frag_tr(yp + 16 * t * LDY1, LDY1);
+        // the operands of step t + 1 are requested before the matrix instruction of step t
+        auto operands = [&](int t, v8bf &fa, v8bf &fb) {   // 16 output pixels per step
+            fa = frag_tr(yp + 16 * t * LDY1, LDY1);
             const int m0 = 16 * t + rsub, m1 = m0 + 4;
             const bf16_t *x0 = xin + xoff + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20);
             const bf16_t *x1 = xin + xoff + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20);
@@ -1386,10 +1386,19 @@ __device__ __forceinline__ void conv1_wgrad_block(const WgradArgs &A, int tile, 
             v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x1);
             typedef short v8s __attribute__((ext_vector_type(8)));
             v8s xb = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            // two accumulators, alternating: consecutive MFMAs do not wait for each other's result
-            if (t & 1) acc2 = mfma(fa, __builtin_bit_cast(v8bf, xb), acc2);
-            else acc = mfma(fa, __builtin_bit_cast(v8bf, xb), acc);
+            fb = __builtin_bit_cast(v8bf, xb);
+        };
+        v8bf fa, fb, fan, fbn;
+        operands(0, fa, fb);
+#pragma unroll
+        for (int t = 0; t < 25; ++t) {
+            fan = fa; fbn = fb;
+            if (t + 1 < 25) operands(t + 1, fan, fbn);
+            __builtin_amdgcn_sched_barrier(0);
+            acc = mfma(fa, fb, acc);
             if (do_bias) accb = mfma(fa, ones, accb);
+            __builtin_amdgcn_sched_barrier(0);
+            fa = fan; fb = fbn;
         }
     }
 
@@ -1397,7 +1406,7 @@ __device__ __forceinline__ void conv1_wgrad_block(const WgradArgs &A, int tile, 
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int o = 8 * (r / 4) + 4 * h + (r % 4);
-        part[o * 256 + 128 * cp + 32 * wave + li] = (acc[r] + acc2[r]) * (1.0f / 255.0f);
+        part[o * 256 + 128 * cp + 32 * wave + li] = acc[r] * (1.0f / 255.0f);
         if (do_bias && li == 0) part[32 * 256 + o] = accb[r];
     }
 }
@@ -2070,5 +2079,159 @@ __device__ __forceinline__ void conv2_dgrad_ps_body(const Args &A, int bid, int 
     }
 }
 constexpr int PS_LDS = IMG + 32 * W2PITCH;   // bytes
+
+// conv2's input gradient AND conv1's weight gradient of a sample in one workgroup (Section 2.1 network,
+// backward pass of the Section 2.2 loss): conv1's dY is needed by nothing but conv1's weight gradient,
+// sample by sample, so the workgroup that forms it keeps it in LDS, in the layout the weight gradient
+// stages it in, and goes on to the weight gradient of the same sample (c1::conv1_wgrad_block's loop,
+// both channel pairs one after the other, the frames read from the ring or the explicit states while
+// the input gradient is computed).  conv1's dY is never written to memory, and the launch of conv1's
+// weight gradient, with its hand-over, is gone.  Workgroup b takes samples b, b + nblocks, ... and
+// writes ONE partial of conv1's weight gradient: the same samples in the same order as split b of
+// c1::k_conv1_wgrad with nblocks splits, so the partials have the same bits.
+struct FusedArgs {
+    Args d;           // dx is not used
+    c1::Src src;      // where the frames of sample n come from
+    float *part1;     // [nblocks][32*256 + 32]
+};
+constexpr int FUSED_DYS = 400 * c1::LDY1 * 2;             // 32,000 bytes: conv1's dY as the weight gradient reads it
+constexpr int FUSED_XIN = 2 * c1::FR * 2;                 // 28,224 bytes: two frames as bf16
+constexpr int FUSED_LDS = FUSED_DYS + FUSED_XIN + IMG;    // 77,648 bytes; conv2's weights in transit lie over the first two
+static_assert(32 * W2PITCH <= FUSED_DYS + FUSED_XIN, "the weights in transit fit");
+
+__device__ __forceinline__ void conv2_dgrad_conv1_wgrad_body(const FusedArgs &F, int bid, int nblocks, uint8_t *lds)
+{
+    using c1::FR;
+    using c1::LDY1;
+    const Args &A = F.d;
+    bf16_t *dys = reinterpret_cast<bf16_t *>(lds), *xin = reinterpret_cast<bf16_t *>(lds + FUSED_DYS);
+    uint8_t *img = lds + FUSED_DYS + FUSED_XIN, *wt = lds;
+    const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), py = wave >> 1, px = wave & 1;
+    if (bid >= A.B) return;
+    u32x4 r0, r1, r2;
+    auto load_dy = [&](int g) {
+        const u32x4 *p = reinterpret_cast<const u32x4 *>(A.dy + (long)g * (81 * 64));
+        r0 = p[tid]; r1 = p[tid + 256]; r2 = p[tid < 136 ? tid + 512 : 647];
+    };
+    load_dy(bid);
+    int slot_g = c1::sample_slot(F.src, bid);
+    for (int i = tid; i < IMG / 16; i += 256) *reinterpret_cast<u32x4 *>(img + i * 16) = u32x4{0, 0, 0, 0};
+    // conv2's weights: see conv2_dgrad_ps_body
+    v8bf wa[8][2];
+    for (int half = 0; half < 2; ++half) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(A.w + half * 32 * 512);
+        sync_lds();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = tid + 256 * i;
+            *reinterpret_cast<u32x4 *>(wt + (c >> 6) * W2PITCH + (c & 63) * 16) = src[c];
+        }
+        sync_lds();
+#pragma unroll
+        for (int tap = 0; tap < 4; ++tap)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                const int ky = py + 2 * (tap >> 1), kx = px + 2 * (tap & 1);
+                const int col = (ky * 4 + kx) * 32 + 8 * (n & 3) + 4 * cb;
+                wa[2 * tap + half][cb] = frag_tr16(wt, W2PITCH, lane, col * 2);
+            }
+    }
+    // position 16b + n of the wave's parity class (block b), clamped; its dY corner in the image; its pixel
+    auto pos_of = [&](int b) { const int p = 16 * b + n; return p > 99 ? 99 : p; };
+    auto base_of = [&](int p) { return (uint32_t)(((p / 10) * 11 + (p % 10)) * PIX + kg * 16); };
+    auto pixel_of = [&](int p) { return (2 * (p / 10) + py) * 20 + 2 * (p % 10) + px; };
+    // conv1's weight gradient: this lane's share as in c1::conv1_wgrad_block (wave = block of 32 im2col columns)
+    typedef __attribute__((address_space(3))) v4s *lds_v4s;
+    const int li = lane & 31, h = lane >> 5, s16 = lane & 15, half = (lane >> 4) & 1;
+    const int rsub = 8 * h + (s16 >> 2);
+    const int kc = 32 * wave + 16 * half + 4 * (s16 & 3);
+    const int xoff = (kc >> 6) * FR + ((kc >> 3) & 7) * 84 + (kc & 7);
+    const bf16_t *yp = dys + rsub * LDY1 + 16 * half + 4 * (s16 & 3);
+    v16f acc[2] = {v16f{0}, v16f{0}}, accb = {0};
+    v8bf ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+    c1::Staged<256, 2> R;
+
+    for (int g = bid; g < A.B; g += nblocks) {
+        sync_lds();   // the previous sample's image, dY tile and frames (the first time: the weights in transit) have been read
+#define DPS_ST(I, V) { const int t = tid + 256 * I; const int q = t >> 3; *reinterpret_cast<u32x4 *>(img + ((q / 9 + 1) * 11 + q % 9 + 1) * PIX + (t & 7) * 16) = V; }
+        DPS_ST(0, r0) DPS_ST(1, r1)
+        if (tid < 136) DPS_ST(2, r2)
+#undef DPS_ST
+        const int gn = g + nblocks;
+        if (gn < A.B) load_dy(gn);
+        const bf16_t *xg = A.xact + (long)g * (400 * 32) + 8 * kg;
+        // ReLU masks two blocks ahead of their use (all seven at once would cost 28 registers)
+        uint4 mk0 = *reinterpret_cast<const uint4 *>(xg + pixel_of(pos_of(0)) * 32);
+        uint4 mk1 = *reinterpret_cast<const uint4 *>(xg + pixel_of(pos_of(1)) * 32);
+        // the first channel pair's frames are on their way while the input gradient is computed
+        c1::stage_load<256, 2>(R, F.src, g, slot_g, 0, tid);
+        const int slot_n = gn < A.B ? c1::sample_slot(F.src, gn) : 0;
+        sync_lds();
+#pragma unroll
+        for (int b = 0; b < 7; ++b) {
+            const int p = pos_of(b);
+            const uint4 mk = mk0;
+            mk0 = mk1;
+            if (b + 2 < 7) mk1 = *reinterpret_cast<const uint4 *>(xg + pixel_of(pos_of(b + 2)) * 32);
+            const uint32_t bs = base_of(p);
+            v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+            for (int st = 0; st < 8; ++st) {
+                const int tap = st >> 1, ty = tap >> 1, tx = tap & 1;
+                const int off = ((1 - ty) * 11 + (1 - tx)) * PIX + (st & 1) * 64;
+                const v8bf bb = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(img + bs + off));
+                acc0 = mfma16(wa[st][0], bb, acc0);
+                acc1 = mfma16(wa[st][1], bb, acc1);
+            }
+            if (16 * b + n < 100) *reinterpret_cast<uint4 *>(dys + pixel_of(p) * LDY1 + 8 * kg) = masked8(mk, acc0, acc1);
+        }
+#pragma unroll
+        for (int cp = 0; cp < 2; ++cp) {
+            if (cp == 1) sync_lds();   // the first pair's frames have been read
+            c1::stage_store<256, 2>(xin, R, tid);
+            if (cp == 0) c1::stage_load<256, 2>(R, F.src, g, slot_g, 2, tid);
+            sync_lds();   // the dY tile and the pair's frames are complete
+            const bool do_bias = cp == 0 && wave == 0;
+            // the operands of step t + 1 are requested before the matrix instruction of step t
+            auto operands = [&](int t, v8bf &fa, v8bf &fb) {   // 16 output pixels per step
+                fa = frag_tr(yp + 16 * t * LDY1, LDY1);
+                const int m0 = 16 * t + rsub, m1 = m0 + 4;
+                const bf16_t *x0 = xin + xoff + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20);
+                const bf16_t *x1 = xin + xoff + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20);
+                v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x0);
+                v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x1);
+                typedef short v8s __attribute__((ext_vector_type(8)));
+                v8s xb = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                fb = __builtin_bit_cast(v8bf, xb);
+            };
+            v8bf fa, fb, fan, fbn;
+            operands(0, fa, fb);
+#pragma unroll
+            for (int t = 0; t < 25; ++t) {
+                fan = fa; fbn = fb;
+                if (t + 1 < 25) operands(t + 1, fan, fbn);
+                __builtin_amdgcn_sched_barrier(0);
+                acc[cp] = mfma(fa, fb, acc[cp]);
+                if (do_bias) accb = mfma(fa, ones, accb);
+                __builtin_amdgcn_sched_barrier(0);
+                fa = fan; fb = fbn;
+            }
+        }
+        slot_g = slot_n;
+    }
+
+    float *part = F.part1 + (long)bid * (32 * 256 + 32);
+#pragma unroll
+    for (int cp = 0; cp < 2; ++cp)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int o = 8 * (r / 4) + 4 * h + (r % 4);
+            part[o * 256 + 128 * cp + 32 * wave + li] = acc[cp][r] * (1.0f / 255.0f);
+            if (cp == 0 && wave == 0 && li == 0) part[32 * 256 + o] = accb[r];
+        }
+}
 }  // namespace dps
 }  // namespace gbf

@@ -709,6 +709,43 @@ def test_fused_and_separate_conv_launches_agree(dq, B):
         m.close()
 
 
+@pytest.mark.parametrize("B", [5, 33, 300, 512, 1024])
+def test_fused_and_separate_conv1_weight_gradient_agree(dq, B):
+    """bf16: conv1's weight gradient runs inside the per-sample workgroups of conv2's backward launch
+    (conv1's dY never leaves the CU), or as a launch of its own when DQN_FUSED_BWD=0 says so.  A workgroup
+    takes the same samples in the same order as a sample split of the separate kernel, so two contexts over
+    identical state, one on each path, must agree bit for bit: in replay mode (frames read from the ring,
+    wrapping windows included) and on an explicit batch.  B = 5, 33: one sample per workgroup; 300: one or
+    two; 512, 1024: two and four."""
+    import os
+    print("case fused conv2 dgrad + conv1 wgrad", B, flush=True)
+    cap = 3000
+    cfgd = dict(CONFIGS["dueling_ddqn"], max_batch=B, max_act_batch=8, precision=1, replay_capacity=cap)
+    ms = []
+    for fused in ("1", "0"):
+        os.environ["DQN_FUSED_BWD"] = fused
+        try:
+            m = dq.Dqn(dq.make_config(**cfgd))
+        finally:
+            os.environ.pop("DQN_FUSED_BWD", None)
+        _fill_replay(m, cap)
+        m.per_fill(synth.exp_priorities(9, cap, "cuda"))
+        ms.append(m)
+    batch = tuple(dev(t) for t in synth.batch(23, B, 18))
+    for step in range(3):
+        outs = [m.train_step(B, None, beta=0.5, draw_seed=170 + step) for m in ms]
+        for k in ("idx", "td", "loss"):
+            assert torch.equal(outs[0][k], outs[1][k]), (step, k)
+        for which in (0, 2, 3):   # theta, v, the gradient of the step
+            assert torch.equal(ms[0].get_params(which), ms[1].get_params(which)), (step, which)
+    outs = [m.train_step(B, batch) for m in ms]
+    assert torch.equal(outs[0]["td"], outs[1]["td"])
+    for which in (0, 2, 3):
+        assert torch.equal(ms[0].get_params(which), ms[1].get_params(which)), which
+    for m in ms:
+        m.close()
+
+
 @pytest.mark.parametrize("prec,B", [(0, 32), (1, 64), (1, 6), (1, 1024)])
 def test_recorded_step_replays_match_plain_launches(dq, prec, B):
     """With DQN_GRAPH=1 the replay-mode step is recorded into a HIP graph and replayed.  Two
