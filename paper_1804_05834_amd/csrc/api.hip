@@ -57,6 +57,7 @@ struct Workspace {
     int32_t *b_idx, *b_a;
     float *b_w, *b_r, *td_abs, *loss_j, *qmax_j, *loss_slot;
     int *pu_state;   // walkers of a priority update that is split over two launches
+    gbf::bf16_t *w2t;  // bf16 only: the online conv2 weights as [tap][channel in][channel out] (see misc::k_w2_transposed)
     uint8_t *b_done;
     // activations, channel-last, rows = samples of all passes (fp32 or bf16 by precision)
     void *act1, *act2, *act3;
@@ -106,6 +107,7 @@ Workspace carve(const dqn_config &c, uint8_t *base)
     w.qmax_j = (float *)take(MB * 4);
     w.loss_slot = (float *)take(256);
     w.pu_state = (int *)take(3 * misc::STATE_STRIDE * 4);
+    w.w2t = (gbf::bf16_t *)take(c.precision == 1 ? net::L2N * 2 : 0);
     w.b_done = take(MB);
     const size_t es = c.precision == 1 ? 2 : 4;  // bytes per activation element
     w.act1 = take(rows * net::A1 * es);
@@ -702,6 +704,7 @@ void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipS
     for (; k < 5; ++k) RA.seg[k].block_begin = 0x7fffffff;  // never selected
     RA.theta = c->theta; RA.v = c->rms_v; RA.m = c->rms_m; RA.g = c->grads;
     RA.shadow = cfg.precision == 1 ? (__hip_bfloat16 *)c->buf.shadow_bf16 : nullptr;
+    RA.w2t = cfg.precision == 1 ? (__hip_bfloat16 *)w.w2t : nullptr;
     RA.lr = cfg.lr; RA.rho = cfg.rms_decay; RA.eps = cfg.rms_eps;
     if (last_part && last_part->on) launch(c, "rmsprop", st, [&] { k_rmsprop_pu<<<blk + 1, 256, 0, st>>>(RA, *last_part); });
     else launch(c, "rmsprop", st, [&] { misc::k_rmsprop<<<blk, 256, 0, st>>>(RA); });
@@ -901,12 +904,12 @@ __global__ __launch_bounds__(256, 2) void k_conv21_bwd_pu(gbf::dps::FusedArgs FA
                                                           int wgy, int wgz, SplitUpdate U)
 {
     using namespace gbf;
-    static_assert(dps::FUSED_LDS >= wgrad_lds<64, 64, true>() * 2 && dps::FUSED_LDS >= misc::PU_LDS_WORDS * 4, "LDS");
+    static_assert(dps::FUSED_LDS >= wgrad_lds<64, 128, true>() * 2 && dps::FUSED_LDS >= misc::PU_LDS_WORDS * 4, "LDS");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     if (U.on && blockIdx.x == 0) return update_part(U, 2, reinterpret_cast<int *>(lds_dyn));
     const int id = (int)blockIdx.x - U.on;
     if (id < nps) dps::conv2_dgrad_conv1_wgrad_body(FA, id, nps, lds_dyn);
-    else wgrad_tile<GConv2, 64, 64, 1, 1, true>(WA, tile_of(id - nps, nw), wgx, wgy, wgz, reinterpret_cast<bf16_t *>(lds_dyn));
+    else wgrad_tile<GConv2, 64, 128, 1, 2, true>(WA, tile_of(id - nps, nw), wgx, wgy, wgz, reinterpret_cast<bf16_t *>(lds_dyn));
 }
 
 // bf16: one stream and one launch per layer, the layer's input gradient and weight gradient side by
@@ -949,11 +952,14 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
         WgradArgs G{d2, act1, w.gp2, B, rps, net::A1, net::L2N, 1.0f};
         const int nw = 8 * *ns2, gz = *ns2;
         if (c->fused_bwd) {
-            // conv1's weight gradient inside the per-sample workgroups: one partial per workgroup
+            // conv1's weight gradient inside the per-sample workgroups: one partial per workgroup.  Two workgroups
+            // of this launch fit one CU, so the weight-gradient tiles are 64 x 128: a quarter of the row splits'
+            // tiles fewer, and the launch runs in one round of workgroups at B = 512
             const int nps = std::min({B, c->num_cu, MAX_WSPLIT1});
-            dps::FusedArgs F{P, c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift, (int)c->sub}, w.gp1};
+            const int nw2 = 4 * gz;
+            dps::FusedArgs F{P, c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift, (int)c->sub}, w.gp1, w.w2t};
             launch(c, "conv2_bwd", st, [&] {
-                k_conv21_bwd_pu<<<nps + nw + U.on, 256, dps::FUSED_LDS, st>>>(F, G, nps, nw, 8, 1, gz, U);
+                k_conv21_bwd_pu<<<nps + nw2 + U.on, 256, dps::FUSED_LDS, st>>>(F, G, nps, nw2, 4, 1, gz, U);
             });
             *ns1 = nps;
             return;
@@ -1071,6 +1077,7 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
         size_t half = align_up((size_t)c->n * 2, 256) / 2;
         misc::k_to_bf16<<<grid1(c->n, 256), 256, 0, st>>>(c->theta, sh, c->n);
         misc::k_to_bf16<<<grid1(c->n, 256), 256, 0, st>>>(c->theta_t, sh + half, c->n);
+        misc::k_w2_transposed<<<grid1(64 * 512, 256), 256, 0, st>>>(c->theta + net::C2W, (__hip_bfloat16 *)c->ws.w2t);
     }
     if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
         delete c;
@@ -1208,6 +1215,7 @@ int32_t dqn_set_params(dqn_ctx *c, int32_t which, const float *src, void *stream
         __hip_bfloat16 *sh = (__hip_bfloat16 *)c->buf.shadow_bf16;
         size_t half = align_up((size_t)c->n * 2, 256) / 2;
         misc::k_to_bf16<<<grid1(c->n, 256), 256, 0, st>>>(dst, sh + (which ? half : 0), c->n);
+        if (which == 0) misc::k_w2_transposed<<<grid1(64 * 512, 256), 256, 0, st>>>(c->theta + net::C2W, (__hip_bfloat16 *)c->ws.w2t);
     }
     return hip_status(c, "dqn_set_params");
 }

@@ -668,7 +668,7 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int t, int gx, in
     constexpr int NY = (BK + YR - 1) / YR, NX = (BK + XR - 1) / XR;
     using in_t = typename in_type<G>::t;
     constexpr int NBUF = DB ? 2 : 1;
-    constexpr bool ACC2 = DB && WM * WN == 1;
+    constexpr bool ACC2 = DB && WM * WN <= 2;   // two alternating accumulators per output block
     bf16_t(*Ys2)[BK * LDY] = reinterpret_cast<bf16_t(*)[BK * LDY]>(lds);
     bf16_t(*Xs2)[BK * LDX] = reinterpret_cast<bf16_t(*)[BK * LDX]>(lds + NBUF * BK * LDY);
 
@@ -730,7 +730,11 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int t, int gx, in
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 
-    v16f acc2 = {0};   // second accumulator (ACC2 only)
+    v16f acc2[WM][WN];   // second accumulators (ACC2 only)
+#pragma unroll
+    for (int a = 0; a < WM; ++a)
+#pragma unroll
+        for (int b = 0; b < WN; ++b) acc2[a][b] = v16f{0};
     auto compute = [&](int buf) {
         const bf16_t *yp = Ys2[buf] + ypo, *xp = Xs2[buf] + xpo;
 #pragma unroll
@@ -744,7 +748,7 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int t, int gx, in
             for (int a = 0; a < WM; ++a) {
 #pragma unroll
                 for (int b = 0; b < WN; ++b) {
-                    if (ACC2 && (kk & 16)) acc2 = mfma(fa[a], fb[b], acc2);
+                    if (ACC2 && (kk & 16)) acc2[a][b] = mfma(fa[a], fb[b], acc2[a][b]);
                     else acc[a][b] = mfma(fa[a], fb[b], acc[a][b]);
                 }
                 if (do_bias) accb[a] = mfma(fa[a], ones, accb[a]);
@@ -760,7 +764,12 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int t, int gx, in
             sync_lds();   // buffer sb is complete; every wave is past the previous stage, which read buffer sb^1
             compute(sb);
         }
-        if (ACC2) acc[0][0] += acc2;
+        if (ACC2) {
+#pragma unroll
+            for (int a = 0; a < WM; ++a)
+#pragma unroll
+                for (int b = 0; b < WN; ++b) acc[a][b] += acc2[a][b];
+        }
     } else {
         if (mbeg < mend) {
             gload(mbeg);
@@ -1342,6 +1351,7 @@ __device__ __forceinline__ void conv1_wgrad_block(const WgradArgs &A, int tile, 
     const int kc = 32 * wave + 16 * half + 4 * (s16 & 3);       // column within the pair: (c, p, q0)
     const int xoff = (kc >> 6) * FR + ((kc >> 3) & 7) * 84 + (kc & 7);
     const bf16_t *yp = dys + rsub * LDY1 + 16 * half + 4 * (s16 & 3);
+    const bf16_t *xw = xin + xoff + 4 * rsub;   // the window of output pixel rsub
 
     v16f acc = {0}, accb = {0};
     v8bf ones;
@@ -1379,9 +1389,12 @@ __device__ __forceinline__ void conv1_wgrad_block(const WgradArgs &A, int tile, 
         // the operands of step t + 1 are requested before the matrix instruction of step t
         auto operands = [&](int t, v8bf &fa, v8bf &fb) {   // 16 output pixels per step
             fa = frag_tr(yp + 16 * t * LDY1, LDY1);
-            const int m0 = 16 * t + rsub, m1 = m0 + 4;
-            const bf16_t *x0 = xin + xoff + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20);
-            const bf16_t *x1 = xin + xoff + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20);
+            // pixel m = 16t + rsub (and m + 4) of the 20-wide output: its window starts at input row 4(m/20),
+            // column 4(m%20).  16t = 20q + r with q, r known at compile time, so the lane only has to see
+            // whether r + rsub runs over into the next row: no division
+            const int q = (16 * t) / 20, r = (16 * t) % 20;
+            const bf16_t *x0 = xw + (336 * q + 4 * r) + (rsub >= 20 - r ? 256 : 0);
+            const bf16_t *x1 = xw + (336 * q + 4 * r + 16) + (rsub + 4 >= 20 - r ? 256 : 0);
             v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x0);
             v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x1);
             typedef short v8s __attribute__((ext_vector_type(8)));
@@ -2093,11 +2106,11 @@ struct FusedArgs {
     Args d;           // dx is not used
     c1::Src src;      // where the frames of sample n come from
     float *part1;     // [nblocks][32*256 + 32]
+    const bf16_t *w2t;  // conv2's weights as [tap][channel in][channel out]
 };
 constexpr int FUSED_DYS = 400 * c1::LDY1 * 2;             // 32,000 bytes: conv1's dY as the weight gradient reads it
 constexpr int FUSED_XIN = 2 * c1::FR * 2;                 // 28,224 bytes: two frames as bf16
-constexpr int FUSED_LDS = FUSED_DYS + FUSED_XIN + IMG;    // 77,648 bytes; conv2's weights in transit lie over the first two
-static_assert(32 * W2PITCH <= FUSED_DYS + FUSED_XIN, "the weights in transit fit");
+constexpr int FUSED_LDS = FUSED_DYS + FUSED_XIN + IMG;    // 77,648 bytes
 
 __device__ __forceinline__ void conv2_dgrad_conv1_wgrad_body(const FusedArgs &F, int bid, int nblocks, uint8_t *lds)
 {
@@ -2105,7 +2118,7 @@ __device__ __forceinline__ void conv2_dgrad_conv1_wgrad_body(const FusedArgs &F,
     using c1::LDY1;
     const Args &A = F.d;
     bf16_t *dys = reinterpret_cast<bf16_t *>(lds), *xin = reinterpret_cast<bf16_t *>(lds + FUSED_DYS);
-    uint8_t *img = lds + FUSED_DYS + FUSED_XIN, *wt = lds;
+    uint8_t *img = lds + FUSED_DYS + FUSED_XIN;
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, kg = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), py = wave >> 1, px = wave & 1;
     if (bid >= A.B) return;
@@ -2117,26 +2130,20 @@ __device__ __forceinline__ void conv2_dgrad_conv1_wgrad_body(const FusedArgs &F,
     load_dy(bid);
     int slot_g = c1::sample_slot(F.src, bid);
     for (int i = tid; i < IMG / 16; i += 256) *reinterpret_cast<u32x4 *>(img + i * 16) = u32x4{0, 0, 0, 0};
-    // conv2's weights: see conv2_dgrad_ps_body
+    // conv2's weights, wa[2 tap + co half][ci block] as in conv2_dgrad_ps_body, straight from the copy that
+    // keeps the output channels next to each other: the eight reduction elements of a lane are 16 bytes
     v8bf wa[8][2];
-    for (int half = 0; half < 2; ++half) {
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(A.w + half * 32 * 512);
-        sync_lds();
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int c = tid + 256 * i;
-            *reinterpret_cast<u32x4 *>(wt + (c >> 6) * W2PITCH + (c & 63) * 16) = src[c];
-        }
-        sync_lds();
+    for (int tap = 0; tap < 4; ++tap)
 #pragma unroll
-        for (int tap = 0; tap < 4; ++tap)
+        for (int half = 0; half < 2; ++half)
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
                 const int ky = py + 2 * (tap >> 1), kx = px + 2 * (tap & 1);
-                const int col = (ky * 4 + kx) * 32 + 8 * (n & 3) + 4 * cb;
-                wa[2 * tap + half][cb] = frag_tr16(wt, W2PITCH, lane, col * 2);
+                const int ci = 8 * (n >> 2) + 4 * cb + (n & 3);
+                wa[2 * tap + half][cb] = __builtin_bit_cast(
+                    v8bf, *reinterpret_cast<const uint4 *>(F.w2t + (((ky * 4 + kx) * 32 + ci) * 64 + 32 * half + 8 * kg)));
             }
-    }
     // position 16b + n of the wave's parity class (block b), clamped; its dY corner in the image; its pixel
     auto pos_of = [&](int b) { const int p = 16 * b + n; return p > 99 ? 99 : p; };
     auto base_of = [&](int p) { return (uint32_t)(((p / 10) * 11 + (p % 10)) * PIX + kg * 16); };
@@ -2148,14 +2155,15 @@ __device__ __forceinline__ void conv2_dgrad_conv1_wgrad_body(const FusedArgs &F,
     const int kc = 32 * wave + 16 * half + 4 * (s16 & 3);
     const int xoff = (kc >> 6) * FR + ((kc >> 3) & 7) * 84 + (kc & 7);
     const bf16_t *yp = dys + rsub * LDY1 + 16 * half + 4 * (s16 & 3);
+    const bf16_t *xw = xin + xoff + 4 * rsub;   // the window of output pixel rsub
     v16f acc[2] = {v16f{0}, v16f{0}}, accb = {0};
     v8bf ones;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
-    c1::Staged<256, 2> R;
+    c1::Staged<256, 2> R, R2;   // the frames of the two channel pairs
 
     for (int g = bid; g < A.B; g += nblocks) {
-        sync_lds();   // the previous sample's image, dY tile and frames (the first time: the weights in transit) have been read
+        sync_lds();   // the previous sample's image, dY tile and frames have been read (the first time: the image is cleared)
 #define DPS_ST(I, V) { const int t = tid + 256 * I; const int q = t >> 3; *reinterpret_cast<u32x4 *>(img + ((q / 9 + 1) * 11 + q % 9 + 1) * PIX + (t & 7) * 16) = V; }
         DPS_ST(0, r0) DPS_ST(1, r1)
         if (tid < 136) DPS_ST(2, r2)
@@ -2166,8 +2174,9 @@ __device__ __forceinline__ void conv2_dgrad_conv1_wgrad_body(const FusedArgs &F,
         // ReLU masks two blocks ahead of their use (all seven at once would cost 28 registers)
         uint4 mk0 = *reinterpret_cast<const uint4 *>(xg + pixel_of(pos_of(0)) * 32);
         uint4 mk1 = *reinterpret_cast<const uint4 *>(xg + pixel_of(pos_of(1)) * 32);
-        // the first channel pair's frames are on their way while the input gradient is computed
+        // the sample's four frames are on their way while the input gradient is computed
         c1::stage_load<256, 2>(R, F.src, g, slot_g, 0, tid);
+        c1::stage_load<256, 2>(R2, F.src, g, slot_g, 2, tid);
         const int slot_n = gn < A.B ? c1::sample_slot(F.src, gn) : 0;
         sync_lds();
 #pragma unroll
@@ -2191,16 +2200,16 @@ __device__ __forceinline__ void conv2_dgrad_conv1_wgrad_body(const FusedArgs &F,
 #pragma unroll
         for (int cp = 0; cp < 2; ++cp) {
             if (cp == 1) sync_lds();   // the first pair's frames have been read
-            c1::stage_store<256, 2>(xin, R, tid);
-            if (cp == 0) c1::stage_load<256, 2>(R, F.src, g, slot_g, 2, tid);
+            c1::stage_store<256, 2>(xin, cp == 0 ? R : R2, tid);
             sync_lds();   // the dY tile and the pair's frames are complete
             const bool do_bias = cp == 0 && wave == 0;
             // the operands of step t + 1 are requested before the matrix instruction of step t
             auto operands = [&](int t, v8bf &fa, v8bf &fb) {   // 16 output pixels per step
                 fa = frag_tr(yp + 16 * t * LDY1, LDY1);
-                const int m0 = 16 * t + rsub, m1 = m0 + 4;
-                const bf16_t *x0 = xin + xoff + (4 * (m0 / 20)) * 84 + 4 * (m0 % 20);
-                const bf16_t *x1 = xin + xoff + (4 * (m1 / 20)) * 84 + 4 * (m1 % 20);
+                // see c1::conv1_wgrad_block: no division
+                const int q = (16 * t) / 20, r = (16 * t) % 20;
+                const bf16_t *x0 = xw + (336 * q + 4 * r) + (rsub >= 20 - r ? 256 : 0);
+                const bf16_t *x1 = xw + (336 * q + 4 * r + 16) + (rsub + 4 >= 20 - r ? 256 : 0);
                 v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x0);
                 v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)x1);
                 typedef short v8s __attribute__((ext_vector_type(8)));

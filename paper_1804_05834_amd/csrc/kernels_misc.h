@@ -460,6 +460,7 @@ struct RmsArgs {
     RmsSeg seg[5];
     float *theta, *v, *m, *g;
     __hip_bfloat16 *shadow;  // bf16 copy of theta (same order) or nullptr
+    __hip_bfloat16 *w2t;     // with it: conv2's weights once more, as [tap][channel in][channel out] (or nullptr)
     float lr, rho, eps;
 };
 
@@ -479,6 +480,10 @@ __device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g)
     A.theta[i] = th;
     A.g[i] = g;
     if (A.shadow) A.shadow[i] = __float2bfloat16(th);
+    if (A.w2t && i >= net::C2W && i < net::C2W + 64 * 512) {
+        const int t = (int)(i - net::C2W);   // [channel out][tap][channel in]
+        A.w2t[(t & 511) * 64 + (t >> 9)] = __float2bfloat16(th);
+    }
 }
 
 // The segment that workgroup bx belongs to.  A macro, to be used on the KERNEL PARAMETER itself: picked
@@ -521,6 +526,15 @@ __global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
     __shared__ float red[4][64];
     RMS_SELECT_SEGMENT(A, (int)blockIdx.x, S)
     rmsprop_block(A, S, blockIdx.x, red);
+}
+
+// conv2's weights [channel out][tap][channel in] (fp32, internal order) as bf16 [tap][channel in][channel out]:
+// the layout in which the input gradient of conv2 finds the eight output channels of a matrix-instruction
+// operand next to each other (its reduction runs over the output channels)
+__global__ void k_w2_transposed(const float *w2, __hip_bfloat16 *w2t)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < 64 * 512) w2t[(t & 511) * 64 + (t >> 9)] = __float2bfloat16(w2[t]);
 }
 
 // fp32 -> bf16 copy (round to nearest even)
