@@ -577,13 +577,19 @@ __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, in
     v16f acc2 = {0};   // second accumulator (ACC2 only)
     auto compute = [&](int buf) {
         const bf16_t *ap = As2[buf] + apo, *bp = Bs2[buf] + bpo;
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            v8bf fa[WM], fb[WN];
+        // the fragments of a 16-deep step are requested before the matrix instructions of the step before it
+        auto frags = [&](int kk, v8bf (&fa)[WM], v8bf (&fb)[WN]) {
 #pragma unroll
             for (int a = 0; a < WM; ++a) fa[a] = frag_k(ap + a * 32 * LDK + kk);
 #pragma unroll
             for (int b = 0; b < WN; ++b) fb[b] = frag_tr(bp + kk * LDB + b * 32, LDB);
+        };
+        v8bf fa[WM], fb[WN], fan[WM], fbn[WN];
+        frags(0, fa, fb);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            if (kk + 16 < BK) frags(kk + 16, fan, fbn);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int a = 0; a < WM; ++a)
 #pragma unroll
@@ -591,6 +597,13 @@ __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, in
                     if (ACC2 && (kk & 16)) acc2 = mfma(fb[b], fa[a], acc2);
                     else acc[a][b] = mfma(fb[b], fa[a], acc[a][b]);
                 }
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk + 16 < BK) {
+#pragma unroll
+                for (int a = 0; a < WM; ++a) fa[a] = fan[a];
+#pragma unroll
+                for (int b = 0; b < WN; ++b) fb[b] = fbn[b];
+            }
         }
     };
     gload(0);
@@ -737,13 +750,19 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int t, int gx, in
         for (int b = 0; b < WN; ++b) acc2[a][b] = v16f{0};
     auto compute = [&](int buf) {
         const bf16_t *yp = Ys2[buf] + ypo, *xp = Xs2[buf] + xpo;
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            v8bf fa[WM], fb[WN];
+        // the fragments of a 16-deep step are requested before the matrix instructions of the step before it
+        auto frags = [&](int kk, v8bf (&fa)[WM], v8bf (&fb)[WN]) {
 #pragma unroll
             for (int a = 0; a < WM; ++a) fa[a] = frag_tr(yp + kk * LDY + a * 32, LDY);
 #pragma unroll
             for (int b = 0; b < WN; ++b) fb[b] = frag_tr(xp + kk * LDX + b * 32, LDX);
+        };
+        v8bf fa[WM], fb[WN], fan[WM], fbn[WN];
+        frags(0, fa, fb);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            if (kk + 16 < BK) frags(kk + 16, fan, fbn);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int a = 0; a < WM; ++a) {
 #pragma unroll
@@ -752,6 +771,13 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int t, int gx, in
                     else acc[a][b] = mfma(fa[a], fb[b], acc[a][b]);
                 }
                 if (do_bias) accb[a] = mfma(fa[a], ones, accb[a]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk + 16 < BK) {
+#pragma unroll
+                for (int a = 0; a < WM; ++a) fa[a] = fan[a];
+#pragma unroll
+                for (int b = 0; b < WN; ++b) fb[b] = fbn[b];
             }
         }
     };
@@ -2179,21 +2205,32 @@ __device__ __forceinline__ void conv2_dgrad_conv1_wgrad_body(const FusedArgs &F,
         c1::stage_load<256, 2>(R2, F.src, g, slot_g, 2, tid);
         const int slot_n = gn < A.B ? c1::sample_slot(F.src, gn) : 0;
         sync_lds();
+        // the operand of reduction step st + 1 (of the next block after a block's last step) is requested before
+        // the matrix instructions of step st
+        auto operand = [&](int b, int st) {
+            const int tap = st >> 1, ty = tap >> 1, tx = tap & 1;
+            const int off = ((1 - ty) * 11 + (1 - tx)) * PIX + (st & 1) * 64;
+            return *reinterpret_cast<const uint4 *>(img + base_of(pos_of(b)) + off);
+        };
+        uint4 cur = operand(0, 0);
 #pragma unroll
         for (int b = 0; b < 7; ++b) {
             const int p = pos_of(b);
             const uint4 mk = mk0;
             mk0 = mk1;
             if (b + 2 < 7) mk1 = *reinterpret_cast<const uint4 *>(xg + pixel_of(pos_of(b + 2)) * 32);
-            const uint32_t bs = base_of(p);
             v4f acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
 #pragma unroll
             for (int st = 0; st < 8; ++st) {
-                const int tap = st >> 1, ty = tap >> 1, tx = tap & 1;
-                const int off = ((1 - ty) * 11 + (1 - tx)) * PIX + (st & 1) * 64;
-                const v8bf bb = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(img + bs + off));
+                uint4 nxt = cur;
+                if (st < 7) nxt = operand(b, st + 1);
+                else if (b < 6) nxt = operand(b + 1, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                const v8bf bb = __builtin_bit_cast(v8bf, cur);
                 acc0 = mfma16(wa[st][0], bb, acc0);
                 acc1 = mfma16(wa[st][1], bb, acc1);
+                __builtin_amdgcn_sched_barrier(0);
+                cur = nxt;
             }
             if (16 * b + n < 100) *reinterpret_cast<uint4 *>(dys + pixel_of(p) * LDY1 + 8 * kg) = masked8(mk, acc0, acc1);
         }
