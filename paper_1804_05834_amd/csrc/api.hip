@@ -67,7 +67,7 @@ struct Workspace {
     float *dA;
     void *dh, *d3, *d2, *d1;
     // gradient partial sums per layer, [split][W..., b...]
-    float *gp1, *gp2, *gp3, *gp4, *gp5;
+    float *gp1, *gp2, *gp3;
     // step outputs staged here when the step is replayed from a recording
     float *o_loss, *o_q, *o_y, *o_td, *o_isw;  // o_q: [3][max_batch][K]
     int32_t *o_astar;
@@ -127,8 +127,6 @@ Workspace carve(const dqn_config &c, uint8_t *base)
     w.gp1 = (float *)take((size_t)MAX_WSPLIT1 * net::L1N * 4);
     w.gp2 = (float *)take((size_t)MAX_WSPLIT * net::L2N * 4);
     w.gp3 = (float *)take((size_t)MAX_WSPLIT * net::L3N * 4);
-    w.gp4 = (float *)take((size_t)net::L4N * 4);
-    w.gp5 = (float *)take((size_t)net::head_count(c.num_actions, c.dueling) * 4);
     w.o_loss = (float *)take(256);
     w.o_q = (float *)take(3 * MB * (size_t)c.num_actions * 4);
     w.o_y = (float *)take(MB * 4);
@@ -168,6 +166,7 @@ struct dqn_ctx {
     // INT_MAX: never (the launch needs 140 KB of LDS per workgroup, granted at initialisation)
     int conv12_min = INT32_MAX;
     // bf16: fc1 forward as 128 x 128 tiles (gbf::f1) from this many rows per launch on; needs 72 KB of LDS
+    float *gp4 = nullptr, *gp5 = nullptr;   // where fc1's and the head's weight gradients are written: inside `grads`
     bool fused_bwd = false;   // conv2's input gradient and conv1's weight gradient in one workgroup per sample
     bool fc1_big = false;
     int fc1_big_rows = 512, fc1_big_splits = 0;
@@ -691,7 +690,9 @@ void launch_rmsprop(dqn_ctx *c, unsigned layers, int ns1, int ns2, int ns3, hipS
     const Workspace &w = c->ws;
     const long cnt[5] = {net::L1N, net::L2N, net::L3N, net::L4N, net::head_count(cfg.num_actions, cfg.dueling)};
     const long beg[5] = {net::C1W, net::C2W, net::C3W, net::F1W, net::HEAD};
-    const float *part[5] = {w.gp1, w.gp2, w.gp3, w.gp4, w.gp5};
+    // fc1's and the head's weight gradients have a single partial: they are written straight into the
+    // gradient buffer (c->gp4, c->gp5), and RMSProp does not store them there once more
+    const float *part[5] = {w.gp1, w.gp2, w.gp3, c->gp4, c->gp5};
     const int nsp[5] = {ns1, ns2, ns3, 1, 1};
     misc::RmsArgs RA{};
     int blk = 0, k = 0;
@@ -774,7 +775,7 @@ void backward_f32(dqn_ctx *c, int B, const uint8_t *s, long xs, int *ns1, int *n
     const WgradArgs G1{d1, s, w.gp1, B, rps1, xs, net::L1N, 1.0f / 255.0f};
     const WgradArgs G2{d2, act1, w.gp2, B, rps2, net::A1, net::L2N, 1.0f};
     const WgradArgs G3{d3, act2, w.gp3, B, rps3, net::A2, net::L3N, 1.0f};
-    const WgradArgs G4{dh, act3, w.gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
+    const WgradArgs G4{dh, act3, c->gp4, B, (B + 31) / 32 * 32, net::A3, 0, 1.0f};
     if (sd == st) {
         // the priority update in three parts: few levels beside fc1's short launch, the rest in halves
         const int lv = c->levels;
@@ -928,7 +929,7 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
     int rps;
     {
         DgradArgs D{dh, sh + net::F1W, act3, d3, B};
-        WgradArgs G{dh, act3, w.gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
+        WgradArgs G{dh, act3, c->gp4, B, (B + 63) / 64 * 64, net::A3, 0, 1.0f};
         const int gx = (B + 63) / 64;
         PairGrid P{gx * 49, gx, 1, 49 * 8, 49, 8, 1};
         const int nh = c->R * 16;
@@ -1032,6 +1033,8 @@ int32_t dqn_init(dqn_ctx **out, const dqn_config *cfg, const dqn_buffers *b, voi
     c->rms_v = (float *)b->opt_state;
     c->rms_m = cfg->rms_centered ? (float *)((uint8_t *)b->opt_state + sz.params) : nullptr;
     c->grads = (float *)b->grads;
+    c->gp4 = c->grads + net::F1W;
+    c->gp5 = c->grads + net::HEAD;
     c->L = sz.tree_leaves;
     c->levels = 0;
     while ((1l << c->levels) < c->L) ++c->levels;
@@ -1607,7 +1610,7 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     if (sd != st || sp != st) (void)hipEventRecord(c->ev_fork, st);
     ev_wait(sd, c->ev_fork, st);
     if (sp != sd) ev_wait(sp, c->ev_fork, st);
-    misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, w.gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling,
+    misc::HeadWgradArgs HW{w.dA, w.h_s, w.loss_j, c->gp5, O.loss, w.loss_slot, B, cfg.num_actions, cfg.dueling,
                            w.td_abs, w.qmax_j, O.td_abs_mean, O.q_max_mean};
     // the indices come from the sampling kernel, so the ring capacity bounds them
     misc::PerUpdateArgs PU{c->tree, c->L, c->levels, (long)cfg.replay_capacity, w.b_idx, w.td_abs, B,

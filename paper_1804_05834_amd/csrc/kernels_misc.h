@@ -464,7 +464,8 @@ struct RmsArgs {
     float lr, rho, eps;
 };
 
-__device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g)
+// store_g: false where the gradient already stands in A.g (a single partial written there by its kernel)
+__device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g, bool store_g = true)
 {
     float v = A.rho * A.v[i] + (1.f - A.rho) * g * g;
     float denom;
@@ -478,7 +479,7 @@ __device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g)
     float th = A.theta[i] - A.lr * g / denom;
     A.v[i] = v;
     A.theta[i] = th;
-    A.g[i] = g;
+    if (store_g) A.g[i] = g;
     if (A.shadow) A.shadow[i] = __float2bfloat16(th);
     if (A.w2t && i >= net::C2W && i < net::C2W + 64 * 512) {
         const int t = (int)(i - net::C2W);   // [channel out][tap][channel in]
@@ -518,7 +519,7 @@ __device__ __forceinline__ void rmsprop_block(const RmsArgs &A, const RmsSeg &S,
             rms_update(A, S.begin + o, (red[0][pl] + red[1][pl]) + (red[2][pl] + red[3][pl]));
     } else {
         const long o = (long)(bx - S.block_begin) * 256 + tid;
-        if (o < S.count) rms_update(A, S.begin + o, S.part[o]);
+        if (o < S.count) rms_update(A, S.begin + o, S.part[o], S.part != A.g + S.begin);
     }
 }
 __global__ __launch_bounds__(256) void k_rmsprop(RmsArgs A)
