@@ -40,6 +40,8 @@ def flops_per_launch(B, R):
         "conv1_wgrad": B * F_CONV1,
         # bf16: a layer's input gradient and weight gradient share one launch
         "fc1_bwd": 2 * B * F_FC1, "conv3_bwd": 2 * B * F_CONV3, "conv2_bwd": 2 * B * F_CONV2,
+        # bf16: conv2's two gradients and conv1's weight gradient in one launch
+        "conv21_bwd": 2 * B * F_CONV2 + B * F_CONV1,
     }
 
 
@@ -79,6 +81,9 @@ def gemm_bytes_per_launch(B, R, bf16):
         "fc1_bwd": B * (512 * e + 2 * a3) + wf + 512 * 3136 * 4,
         "conv3_bwd": B * (a3 + 2 * a2) + w3 + 64 * 576 * 4,
         "conv2_bwd": B * (a2 + 2 * a1) + w2 + 64 * 512 * 4,
+        # conv1's dY stays on the CU: dY of conv2, conv1's activations (mask and conv2's weight-gradient operand),
+        # the four frames; the weights and the two weight gradients
+        "conv21_bwd": B * (a2 + a1 + 4 * 7056) + w2 + 64 * 512 * 4 + 32 * 256 * 4,
     }
 
 
@@ -93,9 +98,8 @@ MEASURED_TRAFFIC = {
     ("head_train", 512, "bf16"): 13.2e6 + 1.7e6,
     ("fc1_bwd", 512, "bf16"): 13.5e6 + 9.6e6,
     ("conv3_bwd", 512, "bf16"): 9.9e6 + 11.2e6,
-    ("conv2_bwd", 512, "bf16"): 36.2e6 + 20.6e6,
-    ("conv1_wgrad", 512, "bf16"): 27.1e6 + 8.3e6,
-    ("rmsprop", 512, "bf16"): 41.1e6 + 23.4e6,
+    ("conv21_bwd", 512, "bf16"): 50.3e6 + 16.0e6,
+    ("rmsprop", 512, "bf16"): 41.1e6 + 17.1e6,
 }
 
 

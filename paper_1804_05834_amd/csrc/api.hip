@@ -959,7 +959,7 @@ void backward_bf16(dqn_ctx *c, int B, const Pass &ps, int *ns1, int *ns2, int *n
             const int nps = std::min({B, c->num_cu, MAX_WSPLIT1});
             const int nw2 = 4 * gz;
             dps::FusedArgs F{P, c1::Src{ps.x, ps.xs, ps.idx, (long)c->cfg.replay_capacity, ps.shift, (int)c->sub}, w.gp1, w.w2t};
-            launch(c, "conv2_bwd", st, [&] {
+            launch(c, "conv21_bwd", st, [&] {
                 k_conv21_bwd_pu<<<nps + nw2 + U.on, 256, dps::FUSED_LDS, st>>>(F, G, nps, nw2, 4, 1, gz, U);
             });
             *ns1 = nps;
