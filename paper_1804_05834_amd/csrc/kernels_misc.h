@@ -210,11 +210,6 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         w0 = tid < A.B ? A.w[tid] : 0.f;
         w1 = tid + 512 < A.B ? A.w[tid + 512] : 0.f;
     }
-    // column tid of the online head, for the back-propagation into the hidden layer at the end
-    constexpr int HW_PRE = 24;
-    float hw[HW_PRE];
-#pragma unroll
-    for (int r = 0; r < HW_PRE; ++r) hw[r] = r < R ? A.head_on[head_w_off(r, K, A.dueling) + tid] : 0.f;
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- hidden layer: split sums in split order, bias, ReLU
@@ -233,6 +228,13 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
         A.h_s[(long)j * net::HID + tid] = hs;
     }
     __syncthreads();
+    // column tid of the online head, for the back-propagation into the hidden layer at the end: requested
+    // here, behind the operands the dot products wait for, and in flight until the last phase
+    constexpr int HW_PRE = 24;
+    float hw[HW_PRE];
+#pragma unroll
+    for (int r = 0; r < HW_PRE; ++r) hw[r] = r < R ? A.head_on[head_w_off(r, K, A.dueling) + tid] : 0.f;
+    __builtin_amdgcn_sched_barrier(0);
     head_rows3_dot(H0, hid, K, A.dueling, raw, tid);
     head_rows3_dot(H1, hid, K, A.dueling, raw, tid);
     for (int round = 2; 32 * round < 3 * R; ++round) {  // more than 64 dot products: K > 20
