@@ -41,8 +41,9 @@ struct MetaGather {
 // The memory side is batched: at a node x the wave fetches the whole 6-level subtree
 // below x in one round trip (lane l reads local heap node l of levels 1..5 and
 // node l of level 6), then walks those 6 levels out of registers with lane
-// shuffles.  20 levels cost 4 dependent round trips instead of 20, and every
-// fetch is a contiguous run of the heap array.
+// shuffles.  20 levels cost 3 dependent round trips instead of 20 (the round at the
+// root is wider where that saves one, see first_round_levels), and every fetch is a
+// contiguous run of the heap array.
 // is_w receives the RAW weight (N P(j))^-beta; k_per_normalise (or the consumer)
 // divides by the minibatch maximum.
 struct SampleArgs {
@@ -71,6 +72,15 @@ __device__ __forceinline__ float sample_total(const SampleArgs &A) { return A.un
 // value) the mass the draws were scaled by.  Lane 1 of the first round reads the root along with the
 // subtree below it, and the leaf's value is the child chosen in the last step: neither the total nor the
 // leaf costs a memory round trip of its own.
+// Levels of the walk's first round.  The top of the tree is ONE contiguous run of the heap array, so a round
+// that starts at the root can take 7 or 8 levels (255 / 511 nodes: four / eight loads per lane, issued
+// together) where that saves the walk a dependent round trip: 19 or 20 levels in three rounds, not four.
+__device__ __forceinline__ int first_round_levels(int levels)
+{
+    const int m = levels % 6;
+    return levels > 6 && (m == 1 || m == 2) ? 6 + m : min(6, levels);
+}
+
 template <int ND>
 __device__ __forceinline__ float per_sample_walk(const SampleArgs &A, const int (&jj)[ND], int lane, long (&slot)[ND],
                                                  float (&leaf)[ND])
@@ -101,7 +111,47 @@ __device__ __forceinline__ float per_sample_walk(const SampleArgs &A, const int 
         for (int d = 0; d < ND; ++d) leaf[d] = total;
     }
     const int lj = lane >= 1 ? 31 - __clz(lane) : 0;  // level of local heap node `lane`
-    for (int done = 0; done < A.levels;) {
+    int done = 0;
+    const int r0 = first_round_levels(A.levels);
+    if (r0 > 6) {
+        // the wide first round: lane l holds nodes l, 64 + l, ... of the top 2^(r0+1) nodes; the walk is the
+        // same in every lane, so each lane picks the register its own node of the wanted run sits in and
+        // the exchange takes the wanted lane's
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int n = 64 * q + lane;
+            v[q] = n >= 1 && n < (2 << r0) ? tree[n] : 0.f;
+        }
+        total = __shfl(v[0], 1, 64);
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+            z[d] = mass(jj[d], total);
+            int cur = 1;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                if (t >= r0) continue;
+                const int c = 2 * cur;  // left child, below 2^(t+1)... its run of 64 nodes: c >> 6
+                float m;
+                if (t < 5) m = v[0];
+                else if (t == 5) m = v[1];
+                else if (t == 6) m = (c & 64) ? v[3] : v[2];
+                else m = (c & 128) ? ((c & 64) ? v[7] : v[6]) : ((c & 64) ? v[5] : v[4]);
+                const float left = __shfl(m, c & 63, 64), right = __shfl(m, (c & 63) + 1, 64);
+                if (z[d] < left || right == 0.f) {
+                    cur = c;
+                    leaf[d] = left;
+                } else {
+                    z[d] = z[d] - left;
+                    cur = c + 1;
+                    leaf[d] = right;
+                }
+            }
+            node[d] = cur;
+        }
+        done = r0;
+    }
+    while (done < A.levels) {
         const int r = min(6, A.levels - done);  // levels walked in this round
         float va[ND], vb[ND];
 #pragma unroll

@@ -401,7 +401,9 @@ def _check_indices(orc, idx_gpu, tree_ref, size, B, beta, seed, stratified=False
 
 
 @pytest.mark.parametrize("cap,n,B,strat", [(1000, 1000, 32, 0), (1000, 613, 512, 0), (5000, 5000, 64, 1),
-                                           (37, 37, 1024, 0), (5, 1, 7, 0)])
+                                           (37, 37, 1024, 0), (5, 1, 7, 0),
+                                           # 8, 14 and 19 tree levels: the walk's first round takes 8, 8 and 7 of them
+                                           (200, 200, 64, 0), (10000, 10000, 64, 1), (300000, 300000, 128, 0)])
 def test_tree_fill_sample_update(dq, orc, cap, n, B, strat):
     print("case tree", cap, n, B, strat, flush=True)
     alpha, eps = np.float32(0.6), np.float32(1e-6)
