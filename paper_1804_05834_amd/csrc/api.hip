@@ -1627,7 +1627,8 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     int ns1, ns2, ns3;
     // bf16: the update in four parts: beside fc1's, conv3's and conv2's gradients and inside the RMSProp launch
     const int lv = c->levels;
-    const SplitUpdate U{PU, w.pu_state, {lv / 10, 3 * lv / 10, 6 * lv / 10}, batch ? 0 : 1};
+    // (of 20 levels: 2, 5, 7 and 6; the RMSProp launch is the one its part can outlast, fc1's the shortest)
+    const SplitUpdate U{PU, w.pu_state, {lv / 10, 7 * lv / 20, 7 * lv / 10}, batch ? 0 : 1};
     if (cfg.precision == 1) backward_bf16(c, B, passes[0], &ns1, &ns2, &ns3, st, HW, U);
     else backward_f32(c, B, stacking ? w.stack5 : s, stacking ? 5L * net::FRAME : xs, &ns1, &ns2, &ns3, st, sd,
                       fuse_tail ? &tail : nullptr);
