@@ -386,7 +386,7 @@ def time_replay_calls(m, torch, synth, capacity, reps=200):
     nb = capacity * 4 + 2 * m.L * 4          # priorities read, every node of the tree written
     out.append({"call": "per_fill", "slots": capacity, "us_per_call": t * 1e6, "algorithmic_bytes": nb,
                 "achieved_GBps": nb / t / 1e9, "frac_of_hbm_peak": nb / t / HBM_PEAK,
-                "launches": 1 + levels})
+                "launches": 1 + (levels + 11) // 12})   # the leaves, then twelve tree levels per launch
     return {"workload": "the replay calls of the boundary on their own, %d-slot ring" % capacity, "calls": out}
 
 
