@@ -1372,12 +1372,11 @@ int32_t dqn_replay_store_envs(dqn_ctx *c, int32_t E, const uint8_t *frames, cons
     hipStream_t st = (hipStream_t)stream;
     const long C = (long)(cap / E);
     const long t = (long)c->seq, l = t % C;
+    // two launches: the time steps with the leaves they settle, then the tree above the leaves
     launch(c, "replay_write", st, [&] {
         misc::k_replay_write_envs<<<dim3((unsigned)E), 256, 0, st>>>((uint8_t *)c->buf.replay_frames, c->meta_a, c->meta_r,
-                                                                     c->meta_done, C, l, frames, a, r, done);
-    });
-    launch(c, "store_leaves", st, [&] {
-        misc::k_store_leaves_envs<<<grid1(E, 256), 256, 0, st>>>(c->tree, c->L, C, l, t, E, c->meta_done, c->cfg.per_alpha);
+                                                                     c->meta_done, C, l, frames, a, r, done, c->tree, c->L,
+                                                                     t, c->cfg.per_alpha);
     });
     rebuild_tree(c, st);
     c->envs = E;

@@ -602,10 +602,9 @@ __global__ void k_tree_level(float *tree, long first, long count)
 // its block's leaves, forms the block's sub-tree in LDS level by level (node = left + right in fp32,
 // so every node has the bits any other order of repair gives) and writes its BL - 1 internal
 // nodes.  The block roots are the leaves of the tree one launch up: Lcur >> 12 of them.
-__global__ __launch_bounds__(256) void k_tree_rebuild(float *tree, long Lcur, int BL)
+// The block of BL leaves number b of the tree over Lcur leaves; t: 2 * 4096 floats of LDS
+__device__ __forceinline__ void tree_block(float *tree, long Lcur, int BL, long b, float *t)
 {
-    __shared__ float t[2 * 4096];             // local heap: t[1] block root, leaves at t[BL, 2 BL)
-    const long b = blockIdx.x;                // block number
     const long root = Lcur / BL + b;          // heap index of the block root
     for (int i = threadIdx.x; i < BL; i += 256) t[BL + i] = tree[Lcur + b * BL + i];
     for (int first = BL >> 1; first >= 1; first >>= 1) {
@@ -619,37 +618,21 @@ __global__ __launch_bounds__(256) void k_tree_rebuild(float *tree, long Lcur, in
         tree[(root << d) + (p - (1 << d))] = t[p];
     }
 }
-
-// Store path for many environment streams (Alg.1 "store transition", one emulator per stream): the
-// ring is E sub-rings of C slots, stream e owns slots [eC, (e+1)C); every call appends one time step
-// to every stream at local slot l = t mod C (t: time steps stored so far, the same for all).
-// grid (E): frame and transition data of stream e.
-__global__ __launch_bounds__(256) void k_replay_write_envs(uint8_t *frames, int32_t *meta_a, float *meta_r,
-                                                           uint8_t *meta_done, long C, long l,
-                                                           const uint8_t *src, const int32_t *a,
-                                                           const float *r, const uint8_t *done)
+__global__ __launch_bounds__(256) void k_tree_rebuild(float *tree, long Lcur, int BL)
 {
-    const long e = blockIdx.x, slot = e * C + l;
-    const uint4 *s = reinterpret_cast<const uint4 *>(src + e * net::FRAME);
-    uint4 *d = reinterpret_cast<uint4 *>(frames + slot * net::FRAME);
-    for (int t = threadIdx.x; t < net::FRAME / 16; t += 256) d[t] = s[t];
-    if (threadIdx.x == 0) {
-        meta_a[slot] = a[e];
-        meta_r[slot] = r[e];
-        meta_done[slot] = done[e];
-    }
+    __shared__ float t[2 * 4096];             // local heap: t[1] block root, leaves at t[BL, 2 BL)
+    tree_block(tree, Lcur, BL, blockIdx.x, t);
 }
 // One thread per stream: the leaves the new time step settles, by the rules of the one-stream store
 // path applied to the stream's own sub-ring (see k_store_priorities): the transition at local slot
 // l - 1 has just become complete and enters with leaf = fp32(max_p^alpha) unless its state stack
 // would reach back before the stream's start (t - 1 < 3) or across an episode end; the slot just
-// written and the three after it get leaf 0.  The internal nodes are rebuilt afterwards.
-__global__ __launch_bounds__(256) void k_store_leaves_envs(float *tree, long L, long C, long l, long t, int E,
-                                                           const uint8_t *done, float alpha)
+// written and the three after it get leaf 0.  Reads only transition data of earlier time steps.
+// The internal nodes are rebuilt afterwards.
+__device__ __forceinline__ void store_leaves_env(float *tree, long L, long C, long l, long t, long e,
+                                                 const uint8_t *done, float alpha)
 {
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= E) return;
-    const long base = (long)e * C;
+    const long base = e * C;
     auto at = [&](long k) { long q = (l + k) % C; if (q < 0) q += C; return base + q; };
     if (t >= 1) {
         bool valid = t - 1 >= 3;
@@ -658,6 +641,24 @@ __global__ __launch_bounds__(256) void k_store_leaves_envs(float *tree, long L, 
         tree[L + at(-1)] = valid ? (float)pow((double)tree[2 * L], (double)alpha) : 0.f;
     }
     for (int k = 0; k < 4; ++k) tree[L + at(k)] = 0.f;
+}
+// grid (E): frame and transition data of stream e (waves 0..3), and its leaves (one thread of the last wave)
+__global__ __launch_bounds__(256) void k_replay_write_envs(uint8_t *frames, int32_t *meta_a, float *meta_r,
+                                                           uint8_t *meta_done, long C, long l,
+                                                           const uint8_t *src, const int32_t *a,
+                                                           const float *r, const uint8_t *done,
+                                                           float *tree, long L, long t, float alpha)
+{
+    const long e = blockIdx.x, slot = e * C + l;
+    if (threadIdx.x == 192) store_leaves_env(tree, L, C, l, t, e, meta_done, alpha);
+    const uint4 *s = reinterpret_cast<const uint4 *>(src + e * net::FRAME);
+    uint4 *d = reinterpret_cast<uint4 *>(frames + slot * net::FRAME);
+    for (int t4 = threadIdx.x; t4 < net::FRAME / 16; t4 += 256) d[t4] = s[t4];
+    if (threadIdx.x == 0) {
+        meta_a[slot] = a[e];
+        meta_r[slot] = r[e];
+        meta_done[slot] = done[e];
+    }
 }
 
 __global__ __launch_bounds__(256) void k_per_sample(SampleArgs A)
