@@ -92,7 +92,7 @@ def gemm_bytes_per_launch(B, R, bf16):
 # run (fetch x1.949, write x0.9875).  Keyed by (kernel, batch, precision); the figures and the
 # commands are in profiles/train_step_b512_bf16_hbm_traffic.md.
 MEASURED_TRAFFIC = {
-    ("conv12_fwd", 512, "bf16"): 46.1e6 + 28.7e6,
+    ("conv12_fwd", 512, "bf16"): 46.2e6 + 28.7e6,
     ("conv3_fwd", 512, "bf16"): 16.8e6 + 9.5e6,
     ("fc1_fwd", 512, "bf16"): 19.6e6 + 12.4e6,
     ("head_train", 512, "bf16"): 13.2e6 + 1.7e6,
