@@ -1596,7 +1596,18 @@ static int32_t enqueue_step(dqn_ctx *c, int32_t B, const dqn_batch *batch, const
     H.qmax_j = w.qmax_j;
     H.q_s = O.q_s; H.q_no = O.q_next_online; H.q_nt = O.q_next_target; H.y = O.y; H.td = O.td;
     H.a_star = O.a_star; H.is_w = O.is_w;
-    launch(c, "head_train", st, [&] { misc::k_head_train<<<B, 512, 0, st>>>(H); });
+    if (ns < 1 || ns > misc::HEAD_MAX_SPLITS) return fail(c, DQN_ERR_STATE, "dqn_train_step: unexpected number of fc1 reduction splits");
+    launch(c, "head_train", st, [&] {
+        switch (ns) {
+        case 1: misc::k_head_train<1><<<B, 512, 0, st>>>(H); break;
+        case 2: misc::k_head_train<2><<<B, 512, 0, st>>>(H); break;
+        case 3: misc::k_head_train<3><<<B, 512, 0, st>>>(H); break;
+        case 4: misc::k_head_train<4><<<B, 512, 0, st>>>(H); break;
+        case 5: misc::k_head_train<5><<<B, 512, 0, st>>>(H); break;
+        case 6: misc::k_head_train<6><<<B, 512, 0, st>>>(H); break;
+        default: misc::k_head_train<7><<<B, 512, 0, st>>>(H); break;
+        }
+    });
 
     // large fp32 batches fork: the weight gradients of the trunk go to one side stream, the head
     // weight gradient and the priority update to another; they join again before the optimizer.

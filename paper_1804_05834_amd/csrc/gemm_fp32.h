@@ -186,6 +186,8 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_fwd(FwdArgs
     const float *ap = &As[(wm * 32 + li) * LD + ks * BK + 4 * h];
     const float *bp = &Bs[(wn * 32 + li) * LD + ks * BK + 4 * h];
     v16f acc = {0};
+    const int col = n0 + wn * 32 + li;
+    const float bias = S.bias ? S.bias[col] : 0.f;   // requested here, used in the epilogue
 
     gload(kbeg);
     sstore();
@@ -210,17 +212,20 @@ __global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_fwd(FwdArgs
     reduce_slices<NWT, KS>(acc, smem, ks, w2, lane);
     if (ks != 0) return;
 
+    // all values first, then the stores: a wait for the bias inside the bounds-checked branches would be
+    // repeated in every branch, and since stores count as outstanding memory operations too, each store
+    // would then wait for the one before it to be acknowledged
     float *y = S.y + (long)bz * A.split_stride;
-    const int col = n0 + wn * 32 + li;
-    const float bias = S.bias ? S.bias[col] : 0.f;
+    float v[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        v[r] = acc[r] * A.scale;
+        if (S.bias) v[r] = fmaxf(v[r] + bias, 0.f);
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         int m = m0 + wm * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-        if (m < S.M) {
-            float v = acc[r] * A.scale;
-            if (S.bias) v = fmaxf(v + bias, 0.f);
-            y[(long)m * G::N + col] = v;
-        }
+        if (m < S.M) y[(long)m * G::N + col] = v[r];
     }
 }
 
@@ -260,6 +265,9 @@ template <int BM, int BN, int KS> constexpr int dgrad_lds() { return BM * (BK * 
 // the workgroup (a launch may hold wider workgroups: the waves beyond leave at once; a barrier
 // counts only the waves that are still there).  Tile order: the parity classes of one row tile
 // together, then the row tiles of one column tile.
+// The whole reduction is requested before the first stage is staged where it is at most four stages long
+// (every layer at the tile shapes of the small-batch step): the tile is then one round trip to memory, not
+// one per stage; so are the stored activations the epilogue masks with (the ReLU of the layer below).
 template <class D, int BM, int BN, int KS>
 __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, int gz, float *smem)
 {
@@ -295,8 +303,11 @@ __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, in
         }
     }
     const int br = tid / (BN / 4), bc = (tid % (BN / 4)) * 4;
-    v4f ra[NA], rb[NBL];
-    auto gload = [&](int k0) {
+    constexpr int NST = D::K / BKS;             // reduction stages
+    constexpr bool ALLPRE = NST <= 4;           // all of them in flight at once
+    constexpr int NREG = ALLPRE ? NST : 1;
+    v4f ra[NREG][NA], rb[NREG][NBL];
+    auto gload = [&](int k0, v4f (&qa)[NA], v4f (&qb)[NBL]) {
         {   // a staged slab may span several kernel taps: each thread derives the tap of its chunk
             const int k = k0 + kq, tap = k / D::CO, o = k % D::CO;
             const int u = tap / D::TW, v = tap % D::TW;
@@ -304,7 +315,7 @@ __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, in
             for (int i = 0; i < NA; ++i) {
                 int ii = rh[i] - u, jj = rw[i] - v;
                 bool ok = rn[i] >= 0 && ii >= 0 && ii < D::OH && jj >= 0 && jj < D::OW;
-                ra[i] = ok ? ld4(A.dy + ((long)(rn[i] * D::OH + ii) * D::OW + jj) * D::CO + o)
+                qa[i] = ok ? ld4(A.dy + ((long)(rn[i] * D::OH + ii) * D::OW + jj) * D::CO + o)
                            : v4f{0, 0, 0, 0};
             }
         }
@@ -312,14 +323,14 @@ __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, in
         for (int i = 0; i < NBL; ++i) {
             const int k = k0 + br + i * BROWS, tap = k / D::CO, o = k % D::CO;
             const int p = ca + D::S * (tap / D::TW), q = cb + D::S * (tap % D::TW);
-            rb[i] = ld4(A.w + ((long)(o * D::KH + p) * D::KW + q) * D::CI + n0 + bc);
+            qb[i] = ld4(A.w + ((long)(o * D::KH + p) * D::KW + q) * D::CI + n0 + bc);
         }
     };
-    auto sstore = [&]() {
+    auto sstore = [&](const v4f (&qa)[NA], const v4f (&qb)[NBL]) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) *reinterpret_cast<v4f *>(&As[(lr + i * RPP) * LD + kq]) = ra[i];
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<v4f *>(&As[(lr + i * RPP) * LD + kq]) = qa[i];
 #pragma unroll
-        for (int i = 0; i < NBL; ++i) *reinterpret_cast<v4f *>(&Bs[(br + i * BROWS) * LDB + bc]) = rb[i];
+        for (int i = 0; i < NBL; ++i) *reinterpret_cast<v4f *>(&Bs[(br + i * BROWS) * LDB + bc]) = qb[i];
     };
 
     const int ks = wave / NWT, w2 = wave % NWT;
@@ -328,13 +339,7 @@ __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, in
     const float *ap = &As[(wm * 32 + li) * LD + ks * BK + 4 * h];
     const float *bp = &Bs[(ks * BK + 4 * h) * LDB + wn * 32 + li];
     v16f acc = {0};
-
-    gload(0);
-    sstore();
-    __syncthreads();
-    for (int k0 = 0; k0 < D::K; k0 += BKS) {
-        const bool more = k0 + BKS < D::K;
-        if (more) gload(k0 + BKS);
+    auto compute = [&]() {
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 8) {
             v4f a = ld4(ap + kk);
@@ -343,26 +348,68 @@ __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, in
             acc = mfma(a.z, bp[(kk + 2) * LDB], acc);
             acc = mfma(a.w, bp[(kk + 3) * LDB], acc);
         }
-        __syncthreads();
-        if (more) {
-            sstore();
+    };
+    // where this lane's results go (-1: no such row), and the stored activations there
+    const int col = n0 + wn * 32 + li;
+    int off[16];
+    float xm[16];
+    // (the loads are unconditional, from a clamped address: a value chosen between a loaded one and a
+    // constant would make the compiler wait for the load right here)
+    auto epilogue_loads = [&]() {
+        if (__builtin_amdgcn_readfirstlane(ks) != 0) return;   // only the waves of slice 0 write the tile
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int mg = m0 + wm * 32 + 8 * g + 4 * h;
+            int n = mg / D::PP, rr = mg % D::PP;
+            int ph = rr / D::WP, pw = rr % D::WP;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = 4 * g + j;
+                const int o = ((n * D::H + D::S * ph + ca) * D::W + D::S * pw + cb) * D::CI + col;
+                const bool valid = mg + j < Mc;
+                off[r] = valid ? o : -1;
+                xm[r] = A.xact[valid ? o : 0];
+                if (++pw == D::WP) {
+                    pw = 0;
+                    if (++ph == D::HP) { ph = 0; ++n; }
+                }
+            }
+        }
+    };
+
+    if constexpr (ALLPRE) {
+#pragma unroll
+        for (int st = 0; st < NST; ++st) gload(st * BKS, ra[st], rb[st]);
+        epilogue_loads();
+#pragma unroll
+        for (int st = 0; st < NST; ++st) {
+            if (st) __syncthreads();   // every wave has read the stage before
+            sstore(ra[st], rb[st]);
             __syncthreads();
+            compute();
+        }
+    } else {
+        gload(0, ra[0], rb[0]);
+        epilogue_loads();
+        sstore(ra[0], rb[0]);
+        __syncthreads();
+        for (int k0 = 0; k0 < D::K; k0 += BKS) {
+            const bool more = k0 + BKS < D::K;
+            if (more) gload(k0 + BKS, ra[0], rb[0]);
+            compute();
+            __syncthreads();
+            if (more) {
+                sstore(ra[0], rb[0]);
+                __syncthreads();
+            }
         }
     }
     reduce_slices<NWT, KS>(acc, smem, ks, w2, lane);
     if (ks != 0) return;
 
-    const int col = n0 + wn * 32 + li;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        int m = m0 + wm * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-        if (m < Mc) {
-            int n = m / D::PP, rr = m % D::PP;
-            int hh = D::S * (rr / D::WP) + ca, ww = D::S * (rr % D::WP) + cb;
-            long off = ((long)(n * D::H + hh) * D::W + ww) * D::CI + col;
-            A.dx[off] = A.xact[off] > 0.f ? acc[r] : 0.f;
-        }
-    }
+    for (int r = 0; r < 16; ++r)
+        if (off[r] >= 0) A.dx[off[r]] = xm[r] > 0.f ? acc[r] : 0.f;
 }
 template <class D, int BM, int BN, int KS = 1>
 __global__ __launch_bounds__((BM / 32) * (BN / 32) * KS * 64) void k_dgrad(DgradArgs A)

@@ -176,7 +176,11 @@ struct HeadArgs {
 // thread's column of the online head for the back-propagation, the raw importance weights, the
 // row's transition) is requested before anything is waited for, in the order of first use.  The
 // dueling combine (Eq.13) and the argmax run on one wave per pass with lane a holding action a.
-constexpr int HEAD_MAX_SPLITS = 7;   // reduction splits of fc1 that the kernel holds in registers
+// NS: the number of reduction splits of fc1 (A.nsplit), a template argument so that the loads of the
+// partial sums are unconditional: behind a run-time test the compiler adds a split to its sum right where
+// it is loaded, and the kernel then waits for its first load before it has requested the second.
+constexpr int HEAD_MAX_SPLITS = 7;   // most reduction splits of fc1
+template <int NS>
 __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
 {
     __shared__ float hid[3][net::HID];
@@ -190,13 +194,12 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
     const bool norm = A.w && A.w_raw;
 
     // ---- every global load, in the order of first use
-    float ps[3][HEAD_MAX_SPLITS];
+    float ps[3][NS];
     const long row[3] = {(long)j, (long)A.B + j, 2L * A.B + j};
 #pragma unroll
     for (int p = 0; p < 3; ++p)
 #pragma unroll
-        for (int sp = 0; sp < HEAD_MAX_SPLITS; ++sp)
-            ps[p][sp] = sp < A.nsplit ? A.part[sp * A.split_stride + row[p] * net::HID + tid] : 0.f;
+        for (int sp = 0; sp < NS; ++sp) ps[p][sp] = A.part[sp * A.split_stride + row[p] * net::HID + tid];
     const float b_on = A.f1b_on[tid], b_tg = A.f1b_tg[tid];
     HeadRound H0, H1;
     head_rows3_load(H0, 0, A.head_on, A.head_tg, K, A.dueling, tid);
@@ -218,8 +221,7 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
 #pragma unroll
-            for (int sp = 0; sp < HEAD_MAX_SPLITS; ++sp) acc[p] += ps[p][sp];
-            for (int sp = HEAD_MAX_SPLITS; sp < A.nsplit; ++sp) acc[p] += A.part[sp * A.split_stride + row[p] * net::HID + tid];
+            for (int sp = 0; sp < NS; ++sp) acc[p] += ps[p][sp];
         }
         const float hs = fmaxf(acc[0] + b_on, 0.f);
         hid[0][tid] = hs;
@@ -233,7 +235,9 @@ __global__ __launch_bounds__(512) void k_head_train(HeadArgs A)
     constexpr int HW_PRE = 24;
     float hw[HW_PRE];
 #pragma unroll
-    for (int r = 0; r < HW_PRE; ++r) hw[r] = r < R ? A.head_on[head_w_off(r, K, A.dueling) + tid] : 0.f;
+    // (unconditional, row index clamped: a value chosen between a loaded one and a constant would be waited
+    // for right here, in front of the dot products)
+    for (int r = 0; r < HW_PRE; ++r) hw[r] = A.head_on[head_w_off(r < R ? r : R - 1, K, A.dueling) + tid];
     __builtin_amdgcn_sched_barrier(0);
     head_rows3_dot(H0, hid, K, A.dueling, raw, tid);
     head_rows3_dot(H1, hid, K, A.dueling, raw, tid);
