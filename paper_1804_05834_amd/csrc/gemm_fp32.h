@@ -35,6 +35,20 @@ __device__ __forceinline__ v16f mfma(float a, float b, v16f c)
 }
 
 __device__ __forceinline__ v4f ld4(const float *p) { return *reinterpret_cast<const v4f *>(p); }
+// Four input elements as they lie in memory, and their conversion: a staging register holds the raw form,
+// so that nothing waits for a load before the tile of the stage before has been multiplied
+__device__ __forceinline__ v4f ld4raw(const float *p) { return *reinterpret_cast<const v4f *>(p); }
+__device__ __forceinline__ uint32_t ld4raw(const uint8_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
+__device__ __forceinline__ v4f cvt4(v4f v) { return v; }
+__device__ __forceinline__ v4f cvt4(uint32_t u)
+{
+    v4f r;
+    r.x = (float)(u & 0xFFu);
+    r.y = (float)((u >> 8) & 0xFFu);
+    r.z = (float)((u >> 16) & 0xFFu);
+    r.w = (float)(u >> 24);
+    return r;
+}
 __device__ __forceinline__ v4f ld4(const uint8_t *p)
 {
     uint32_t u = *reinterpret_cast<const uint32_t *>(p);
@@ -461,7 +475,9 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int bx, int by, i
     const int yr = tid / (BMO / 4), yc = (tid % (BMO / 4)) * 4;
     const int xr = tid / (BNK / 4), xc = (tid % (BNK / 4)) * 4;
     const int xko = G::k_off(kc0 + xc);
-    v4f ry[NY], rx[NX];
+    using raw_t = decltype(ld4raw(x));
+    v4f ry[NY];
+    raw_t rx[NX];
     auto gload = [&](int mb) {
 #pragma unroll
         for (int i = 0; i < NY; ++i) {
@@ -471,7 +487,7 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int bx, int by, i
 #pragma unroll
         for (int i = 0; i < NX; ++i) {
             int r = xr + i * XR, m = mb + r;
-            rx[i] = (r < BK && m < mend) ? ld4(x + G::row_off(m, A.xs) + xko) : v4f{0, 0, 0, 0};
+            rx[i] = (r < BK && m < mend) ? ld4raw(x + G::row_off(m, A.xs) + xko) : raw_t{};
         }
     };
     auto sstore = [&]() {
@@ -483,7 +499,7 @@ __device__ __forceinline__ void wgrad_tile(const WgradArgs &A, int bx, int by, i
 #pragma unroll
         for (int i = 0; i < NX; ++i) {
             int r = xr + i * XR;
-            if (r < BK) *reinterpret_cast<v4f *>(&Xs[r * LDX + xc]) = rx[i];
+            if (r < BK) *reinterpret_cast<v4f *>(&Xs[r * LDX + xc]) = cvt4(rx[i]);
         }
     };
 

@@ -473,16 +473,19 @@ struct RmsArgs {
 // store_g: false where the gradient already stands in A.g (a single partial written there by its kernel)
 __device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g, bool store_g = true)
 {
-    float v = A.rho * A.v[i] + (1.f - A.rho) * g * g;
+    // every operand is requested before the first store: the buffers may overlap as far as the compiler
+    // knows, so a load behind a store would wait for the arithmetic in front of that store
+    const float v_old = A.v[i], th_old = A.theta[i], m_old = A.m ? A.m[i] : 0.f;
+    float v = A.rho * v_old + (1.f - A.rho) * g * g;
     float denom;
     if (A.m) {
-        float m = A.rho * A.m[i] + (1.f - A.rho) * g;
+        float m = A.rho * m_old + (1.f - A.rho) * g;
         A.m[i] = m;
         denom = sqrtf(v - m * m + A.eps);
     } else {
         denom = sqrtf(v + A.eps);
     }
-    float th = A.theta[i] - A.lr * g / denom;
+    float th = th_old - A.lr * g / denom;
     A.v[i] = v;
     A.theta[i] = th;
     if (store_g) A.g[i] = g;
