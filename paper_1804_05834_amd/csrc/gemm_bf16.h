@@ -566,12 +566,13 @@ __device__ __forceinline__ void dgrad_tile(const DgradArgs &A, int t, int gx, in
             const int hh = D::S * (rr / D::WP) + ca, ww = D::S * (rr % D::WP) + cb;
             obase[a] = ((long)(n * D::H + hh) * D::W + ww) * D::CI + n0 + wn * WN * 32 + 4 * h;
         }
+        // (unconditional, from a clamped address: a value chosen between a loaded one and a constant would
+        // be waited for right here, in front of the first stage's loads)
+        const long ob = obase[a] >= 0 ? obase[a] : 0;
 #pragma unroll
         for (int b = 0; b < WN; ++b)
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                xa[a][b][g] = obase[a] >= 0 ? *reinterpret_cast<const uint2 *>(A.xact + obase[a] + b * 32 + 8 * g)
-                                            : uint2{0, 0};
+            for (int g = 0; g < 4; ++g) xa[a][b][g] = *reinterpret_cast<const uint2 *>(A.xact + ob + b * 32 + 8 * g);
     }
 
     v16f acc2 = {0};   // second accumulator (ACC2 only)
