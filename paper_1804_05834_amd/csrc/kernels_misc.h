@@ -470,22 +470,22 @@ struct RmsArgs {
     float lr, rho, eps;
 };
 
+// What the update reads of parameter i
+struct RmsOld { float v, th, m; };
+__device__ __forceinline__ RmsOld rms_load(const RmsArgs &A, long i) { return RmsOld{A.v[i], A.theta[i], A.m ? A.m[i] : 0.f}; }
 // store_g: false where the gradient already stands in A.g (a single partial written there by its kernel)
-__device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g, bool store_g = true)
+__device__ __forceinline__ void rms_apply(const RmsArgs &A, long i, float g, const RmsOld &old, bool store_g = true)
 {
-    // every operand is requested before the first store: the buffers may overlap as far as the compiler
-    // knows, so a load behind a store would wait for the arithmetic in front of that store
-    const float v_old = A.v[i], th_old = A.theta[i], m_old = A.m ? A.m[i] : 0.f;
-    float v = A.rho * v_old + (1.f - A.rho) * g * g;
+    float v = A.rho * old.v + (1.f - A.rho) * g * g;
     float denom;
     if (A.m) {
-        float m = A.rho * m_old + (1.f - A.rho) * g;
+        float m = A.rho * old.m + (1.f - A.rho) * g;
         A.m[i] = m;
         denom = sqrtf(v - m * m + A.eps);
     } else {
         denom = sqrtf(v + A.eps);
     }
-    float th = th_old - A.lr * g / denom;
+    float th = old.th - A.lr * g / denom;
     A.v[i] = v;
     A.theta[i] = th;
     if (store_g) A.g[i] = g;
@@ -494,6 +494,13 @@ __device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g, bo
         const int t = (int)(i - net::C2W);   // [channel out][tap][channel in]
         A.w2t[(t & 511) * 64 + (t >> 9)] = __float2bfloat16(th);
     }
+}
+// every operand is requested before the first store: the buffers may overlap as far as the compiler
+// knows, so a load behind a store would wait for the arithmetic in front of that store
+__device__ __forceinline__ void rms_update(const RmsArgs &A, long i, float g, bool store_g = true)
+{
+    const RmsOld old = rms_load(A, i);
+    rms_apply(A, i, g, old, store_g);
 }
 
 // The segment that workgroup bx belongs to.  A macro, to be used on the KERNEL PARAMETER itself: picked
@@ -517,15 +524,18 @@ __device__ __forceinline__ void rmsprop_block(const RmsArgs &A, const RmsSeg &S,
     if (S.nsplit > 1) {
         const int pl = tid & 63, sg = tid >> 6;
         const long o = (long)(bx - S.block_begin) * 64 + pl;
+        // what the update reads is requested along with the partial sums (by every thread, from a clamped
+        // index: no branch, no wait), not in a round trip of its own behind their sum
+        const RmsOld old = rms_load(A, S.begin + (o < S.count ? o : 0));
         float g = 0.f;
         if (o < S.count) {
-#pragma unroll 4
+#pragma unroll 8
             for (int t = sg; t < S.nsplit; t += 4) g += S.part[t * S.stride + o];
         }
         red[sg][pl] = g;
         __syncthreads();
         if (sg == 0 && o < S.count)
-            rms_update(A, S.begin + o, (red[0][pl] + red[1][pl]) + (red[2][pl] + red[3][pl]));
+            rms_apply(A, S.begin + o, (red[0][pl] + red[1][pl]) + (red[2][pl] + red[3][pl]), old);
     } else {
         const long o = (long)(bx - S.block_begin) * 256 + tid;
         if (o < S.count) rms_update(A, S.begin + o, S.part[o], S.part != A.g + S.begin);
