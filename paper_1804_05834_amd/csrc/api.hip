@@ -1464,7 +1464,8 @@ int32_t dqn_act(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon, uint64
     if (rc) return rc;
     misc::HeadActArgs H{c->ws.f1part, ns, ss, E, c->cfg.num_actions, c->cfg.dueling, c->theta + net::F1B,
                         c->theta + net::HEAD, epsilon, draw_seed, actions, q_opt};
-    launch(c, "head_act", st, [&] { misc::k_head_act<<<E, 256, 0, st>>>(H); });
+    if (ns < 1 || ns > misc::HEAD_MAX_SPLITS) return fail(c, DQN_ERR_STATE, "dqn_act: unexpected number of fc1 reduction splits");
+    launch(c, "head_act", st, [&] { misc::launch_head_act(H, st); });
     return hip_status(c, "dqn_act");
 }
 
@@ -1501,7 +1502,11 @@ int32_t dqn_act_static(dqn_ctx *c, const uint8_t *obs, int32_t E, float epsilon,
     if (rc == DQN_OK) {
         misc::HeadActArgs H{w.f1part, ns, ss, E, c->cfg.num_actions, c->cfg.dueling, c->theta + net::F1B,
                             c->theta + net::HEAD, epsilon, draw_seed, actions, q_opt};
-        misc::k_head_act<<<E, 256, 0, st>>>(H);
+        if (ns < 1 || ns > misc::HEAD_MAX_SPLITS) {
+            c->prof = prof;
+            return fail(c, DQN_ERR_STATE, "dqn_act_static: unexpected number of fc1 reduction splits");
+        }
+        misc::launch_head_act(H, st);
         rc = hip_status(c, "dqn_act_static");
     }
     c->prof = prof;

@@ -1625,12 +1625,14 @@ __device__ __forceinline__ void run(const Seg &S, int g0, int g1, uint8_t *lds, 
         bf16_t *y = S.y + (long)g * (H::NPOS * 64) + 32 * hh + 8 * kg;
 #pragma unroll
         for (int b = 0; b < H::NBLK; ++b) {
-            if (pos[b] < H::NPOS) {
-                const v4f a0 = acc[b][0], a1 = acc[b][1];
-                const uint2 lo = pack4(fmaxf(a0.x + b0.x, 0.f), fmaxf(a0.y + b0.y, 0.f), fmaxf(a0.z + b0.z, 0.f), fmaxf(a0.w + b0.w, 0.f));
-                const uint2 hi = pack4(fmaxf(a1.x + b1.x, 0.f), fmaxf(a1.y + b1.y, 0.f), fmaxf(a1.z + b1.z, 0.f), fmaxf(a1.w + b1.w, 0.f));
-                *reinterpret_cast<uint4 *>(y + pos[b] * 64) = uint4{lo.x, lo.y, hi.x, hi.y};
-            }
+            // unconditional: a lane past the last position has computed the last position once more (its
+            // operand address was clamped to that pixel) and stores the same bits there.  Without a branch
+            // the compiler can count these stores, and the wait for the next sample's pixels, requested
+            // before them, does not wait for their acknowledgement as well.
+            const v4f a0 = acc[b][0], a1 = acc[b][1];
+            const uint2 lo = pack4(fmaxf(a0.x + b0.x, 0.f), fmaxf(a0.y + b0.y, 0.f), fmaxf(a0.z + b0.z, 0.f), fmaxf(a0.w + b0.w, 0.f));
+            const uint2 hi = pack4(fmaxf(a1.x + b1.x, 0.f), fmaxf(a1.y + b1.y, 0.f), fmaxf(a1.z + b1.z, 0.f), fmaxf(a1.w + b1.w, 0.f));
+            *reinterpret_cast<uint4 *>(y + (pos[b] < H::NPOS ? pos[b] : H::NPOS - 1) * 64) = uint4{lo.x, lo.y, hi.x, hi.y};
         }
     }
 }

@@ -55,32 +55,7 @@ __device__ __forceinline__ int head_b_off(int r, int K, int dueling)
 
 constexpr int MAXR = 65;  // up to 64 actions + V
 
-// hidden[i] = relu(bias[i] + sum over reduction splits of the fc1 partial sums)
-__device__ __forceinline__ float hidden_unit(const float *part, int nsplit, long split_stride,
-                                             long row, int i, const float *bias)
-{
-    float acc = 0.f;
-#pragma unroll 7
-    for (int s = 0; s < nsplit; ++s) acc += part[s * split_stride + row * net::HID + i];
-    return fmaxf(acc + bias[i], 0.f);
-}
-
-// raw[r] = b[r] + <W[r], hid>, one wave per row in turn
-__device__ __forceinline__ void head_rows(const float *hid /*LDS*/, const float *head, int K,
-                                          int dueling, float *raw /*LDS*/, int tid, int nthreads)
-{
-    const int R = K + (dueling ? 1 : 0);
-    const int wave = tid >> 6, lane = tid & 63, nw = nthreads >> 6;
-    for (int r = wave; r < R; r += nw) {
-        const float *w = head + head_w_off(r, K, dueling);
-        float acc = 0.f;
-        for (int i = lane; i < net::HID; i += 64) acc += w[i] * hid[i];
-        acc = wave_sum(acc);
-        if (lane == 0) raw[r] = acc + head[head_b_off(r, K, dueling)];
-    }
-}
-
-// The same for the three passes of a training row at once: 3R dot products of length 512 spread
+// The dot products of the head for the three passes of a training row at once: 3R of length 512 spread
 // over groups of 16 lanes, so the whole head takes two rounds of a 512-thread workgroup instead
 // of one wave per row in turn.  The weights of a round do not depend on the hidden layer, so
 // head_rows3_load requests them while the fc1 partial sums are still being added up, and
@@ -119,26 +94,6 @@ __device__ __forceinline__ void head_rows3_dot(const HeadRound &H, const float (
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
     if (l == 0) raw[p][r] = acc + H.b;
-}
-
-// Q_a = V + (A_a - mean A) (Eq.13) or the raw outputs; serial, K <= 64
-__device__ __forceinline__ void combine_q(const float *raw, int K, int dueling, float *q)
-{
-    if (dueling) {
-        float mean = 0.f;
-        for (int a = 0; a < K; ++a) mean += raw[1 + a];
-        mean /= (float)K;
-        for (int a = 0; a < K; ++a) q[a] = raw[0] + (raw[1 + a] - mean);
-    } else {
-        for (int a = 0; a < K; ++a) q[a] = raw[a];
-    }
-}
-__device__ __forceinline__ int argmax_low(const float *q, int K)
-{
-    int best = 0;
-    for (int a = 1; a < K; ++a)
-        if (q[a] > q[best]) best = a;
-    return best;
 }
 
 struct HeadArgs {
@@ -420,32 +375,107 @@ struct HeadActArgs {
     float *q_out;  // optional [E][K]
 };
 
-// Acting (Alg.1 action lines): finish fc1, evaluate the head, pick the action.
+// Acting (Alg.1 action lines): finish fc1, evaluate the head, pick the action.  One workgroup per
+// observation, built like the training head: every global operand (the partial sums of the thread's two
+// hidden units, the biases, the head weights of the first 32 dot products, spread over groups of 16 lanes)
+// is requested before anything is waited for, the dueling combine (Eq.13) and the argmax run on one wave
+// with lane a holding action a, and the arithmetic is that of k_head_train, so Q(s, .) has the same bits
+// here and there.  NS: reduction splits of fc1 (A.nsplit), a template argument so that the loads are
+// unconditional.
+__device__ __forceinline__ void head_rows1_load(HeadRound &H, int round, const float *head, int K, int dueling, int tid)
+{
+    const int R = K + (dueling ? 1 : 0);
+    const int grp = tid >> 4, l = tid & 15;
+    const int d = grp + 16 * round;
+    H.d = d < R ? d : -1;
+    const int r = d < R ? d : R - 1;   // clamped: the loads are unconditional
+    const float *w = head + head_w_off(r, K, dueling);
+#pragma unroll
+    for (int k = 0; k < net::HID / 16; ++k) H.w[k] = w[l + 16 * k];
+    H.b = head[head_b_off(r, K, dueling)];
+}
+__device__ __forceinline__ void head_rows1_dot(const HeadRound &H, const float *hid /*LDS [512]*/, float *raw /*LDS*/, int tid)
+{
+    const int l = tid & 15;
+    float acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < net::HID / 16; ++k) acc += H.w[k] * hid[l + 16 * k];
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (l == 0 && H.d >= 0) raw[H.d] = acc + H.b;
+}
+template <int NS>
 __global__ __launch_bounds__(256) void k_head_act(HeadActArgs A)
 {
     __shared__ float hid[net::HID];
     __shared__ float raw[MAXR];
-    __shared__ float q[64];
     const int e = blockIdx.x, tid = threadIdx.x;
-    for (int i = tid; i < net::HID; i += 256)
-        hid[i] = hidden_unit(A.part, A.nsplit, A.split_stride, e, i, A.f1b);
-    __syncthreads();
-    head_rows(hid, A.head, A.K, A.dueling, raw, tid, 256);
-    __syncthreads();
-    if (tid == 0) {
-        combine_q(raw, A.K, A.dueling, q);
-        int act;
-        float u = draw_u24(A.seed, 2ull * (uint64_t)e);
-        if (u < A.epsilon) {
-            float u2 = draw_u24(A.seed, 2ull * (uint64_t)e + 1ull);
-            act = min((int)floorf(u2 * (float)A.K), A.K - 1);
-        } else {
-            act = argmax_low(q, A.K);
-        }
-        A.actions[e] = act;
+    const int K = A.K, R = K + (A.dueling ? 1 : 0);
+    float ps[2][NS];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int sp = 0; sp < NS; ++sp) ps[u][sp] = A.part[sp * A.split_stride + (long)e * net::HID + tid + 256 * u];
+    const float b0 = A.f1b[tid], b1 = A.f1b[tid + 256];
+    HeadRound H0, H1;
+    head_rows1_load(H0, 0, A.head, K, A.dueling, tid);
+    head_rows1_load(H1, 1, A.head, K, A.dueling, tid);
+    __builtin_amdgcn_sched_barrier(0);
+    {
+        float acc[2] = {0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int sp = 0; sp < NS; ++sp) acc[u] += ps[u][sp];
+        hid[tid] = fmaxf(acc[0] + b0, 0.f);
+        hid[tid + 256] = fmaxf(acc[1] + b1, 0.f);
     }
     __syncthreads();
-    if (A.q_out && tid < A.K) A.q_out[(long)e * A.K + tid] = q[tid];
+    head_rows1_dot(H0, hid, raw, tid);
+    head_rows1_dot(H1, hid, raw, tid);
+    for (int round = 2; 16 * round < R; ++round) {   // more than 32 dot products: K > 31
+        head_rows1_load(H0, round, A.head, K, A.dueling, tid);
+        head_rows1_dot(H0, hid, raw, tid);
+    }
+    __syncthreads();
+    if (tid < 64) {
+        const int a = tid;
+        const float v = a < K ? raw[A.dueling ? 1 + a : a] : 0.f;
+        float qa = v;
+        if (A.dueling) qa = raw[0] + (v - wave_sum(v) / (float)K);
+        // argmax with the lowest index winning ties; lanes past K never win
+        float bv = a < K ? qa : -3.4028234663852886e38f;
+        int bi = a < K ? a : 64;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (a == 0) {
+            int act = bi;
+            const float u = draw_u24(A.seed, 2ull * (uint64_t)e);
+            if (u < A.epsilon) {
+                const float u2 = draw_u24(A.seed, 2ull * (uint64_t)e + 1ull);
+                act = min((int)floorf(u2 * (float)K), K - 1);
+            }
+            A.actions[e] = act;
+        }
+        if (A.q_out && a < K) A.q_out[(long)e * K + a] = qa;
+    }
+}
+// the launch for a run-time number of splits
+inline void launch_head_act(const HeadActArgs &H, hipStream_t st)
+{
+    switch (H.nsplit) {
+    case 1: k_head_act<1><<<H.E, 256, 0, st>>>(H); break;
+    case 2: k_head_act<2><<<H.E, 256, 0, st>>>(H); break;
+    case 3: k_head_act<3><<<H.E, 256, 0, st>>>(H); break;
+    case 4: k_head_act<4><<<H.E, 256, 0, st>>>(H); break;
+    case 5: k_head_act<5><<<H.E, 256, 0, st>>>(H); break;
+    case 6: k_head_act<6><<<H.E, 256, 0, st>>>(H); break;
+    default: k_head_act<7><<<H.E, 256, 0, st>>>(H); break;
+    }
 }
 
 // --------------------------------------------------------------- RMSProp

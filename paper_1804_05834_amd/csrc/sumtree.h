@@ -208,10 +208,13 @@ __device__ __forceinline__ void per_sample_emit(const SampleArgs &A, int j, long
         // a tree without mass (every stored transition has priority zero) has nothing to draw: weight 0
         A.is_w[j] = total > 0.f ? (float)pow((double)A.size * P, -(double)A.beta) : 0.f;
     }
-    if (A.G.a) {
-        A.G.a[j] = A.G.meta_a[slot];
-        A.G.r[j] = A.G.meta_r[slot];
-        A.G.done[j] = A.G.meta_done[slot];
+    if (A.G.a) {   // the three loads first: behind a store the compiler would hold a load back
+        const int32_t a = A.G.meta_a[slot];
+        const float r = A.G.meta_r[slot];
+        const uint8_t d = A.G.meta_done[slot];
+        A.G.a[j] = a;
+        A.G.r[j] = r;
+        A.G.done[j] = d;
     }
 }
 
